@@ -1,0 +1,265 @@
+"""CPU oracle for the Sparse-Sketch Reducer codec (S2 Reducer, Algorithm 1 and Section 3.1).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what the
+GPU library has to compute.  It may be imported by the tests, by the smoke check
+and by the benchmark's CPU-baseline leg, and by nothing else.  It shares no code,
+table or constant generator with the HIP sources and imports nothing from the
+product package.
+
+Everything here follows the paper's order of steps:
+
+  compress   (Algorithm 1, the bitmap line and the insertion loops; Section 3.1
+              "Compressing Sparse Gradient")
+  aggregate  (Algorithm 1, the AllReduce line; Section 3.1 "Collecting
+              Sparse-Sketch with AllReduce")
+  decompress (Algorithm 1, the recovery line and the query loops; Section 3.1
+              "Decompressing Sparse Gradient")
+
+Notation: the paper writes r x c for the sketch; this code uses d rows and w
+columns, n for the gradient length and W for the number of workers.
+
+Accumulation is float64 throughout.  The sketch cells hold sums of float32 inputs
+converted exactly to float64, so the oracle's rounding error is ~1e-16 relative to
+the absolute mass of a cell, far below the float32 tolerance it is used to judge.
+
+Points the paper leaves open and the reading taken here (each also listed in the
+design notes of the repository):
+
+  * one bitmap bit per gradient element (the paper speaks of blocks; the loops
+    of Algorithm 1 run over element indices, and a block of one element is the
+    case both agree on);
+  * "non-zero" is decided on the float32 bit pattern: every pattern except +0.0
+    and -0.0 is non-zero (denormals, infinities and NaNs included);
+  * bitmap words are 64 bits, element i is bit (i mod 64), least significant
+    first, of word floor(i / 64); unused high bits of the last word are zero;
+  * hash family: the paper only says "hash function" and "random sign".  Row j
+    uses four 64-bit parameters a_j, b_j, c_j, e_j taken in that order from a
+    SplitMix64 stream started at `seed` (a_j and c_j made odd);
+        bucket  h_j(i) = ((a_j * i + b_j) mod 2^64) >> (64 - log2 w)
+        sign    s_j(i) = +1 if bit 63 of ((c_j * i + e_j) mod 2^64) is 0 else -1
+    w must be a power of two;
+  * the bitmap is aggregated with bitwise OR;
+  * median: middle order statistic for odd d, mean of the two middle ones for
+    even d;
+  * the decoder returns the estimate of the SUM over workers (Algorithm 1 has no
+    division by W).
+
+Parity pins: see tests/test_oracle_*.py.  No function in this file is unpinned,
+but the hash family itself is a reading (the paper names none); it is pinned to a
+big-integer re-statement and to the published SplitMix64 reference outputs.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+_U64 = np.uint64
+_MASK64 = (1 << 64) - 1
+
+
+# --------------------------------------------------------------------------
+# hash family (Section 3.1: "randomly mapped to a bucket by a hash function h",
+# "vector of random sign"; Algorithm 1 initialisation: {s_ij}, {h_ij})
+# --------------------------------------------------------------------------
+
+def splitmix64_stream(seed: int, count: int) -> list[int]:
+    """`count` successive outputs of the SplitMix64 generator (Steele, Lea, Flood
+    2014) whose state starts at `seed`.  Python integers, reduced mod 2^64."""
+    state = seed & _MASK64
+    out = []
+    for _ in range(count):
+        state = (state + 0x9E3779B97F4A7C15) & _MASK64
+        z = state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+        out.append(z ^ (z >> 31))
+    return out
+
+
+def hash_params(seed: int, d: int) -> list[tuple[int, int, int, int]]:
+    """Per-row parameters (a_j, b_j, c_j, e_j), j = 0..d-1, as Python integers."""
+    s = splitmix64_stream(seed, 4 * d)
+    rows = []
+    for j in range(d):
+        a, b, c, e = s[4 * j: 4 * j + 4]
+        rows.append((a | 1, b, c | 1, e))
+    return rows
+
+
+def _log2_exact(w: int) -> int:
+    if w < 1 or (w & (w - 1)) != 0:
+        raise ValueError("sketch width w must be a power of two")
+    return w.bit_length() - 1
+
+
+def bucket_hash(idx: np.ndarray, a: int, b: int, w: int) -> np.ndarray:
+    """h_j(i) for an array of indices (any unsigned integer dtype) -> int64."""
+    L = _log2_exact(w)
+    i = idx.astype(_U64)
+    with np.errstate(over="ignore"):
+        u = i * _U64(a) + _U64(b)          # wraps mod 2^64
+    if L == 0:
+        return np.zeros(i.shape, dtype=np.int64)
+    return (u >> _U64(64 - L)).astype(np.int64)
+
+
+def sign_hash(idx: np.ndarray, c: int, e: int) -> np.ndarray:
+    """s_j(i) in {+1.0, -1.0} (float64)."""
+    i = idx.astype(_U64)
+    with np.errstate(over="ignore"):
+        v = i * _U64(c) + _U64(e)
+    return np.where((v >> _U64(63)) == 0, 1.0, -1.0)
+
+
+# --------------------------------------------------------------------------
+# compress (Algorithm 1: bitmap line, insertion loops)
+# --------------------------------------------------------------------------
+
+def nonzero_mask(g: np.ndarray) -> np.ndarray:
+    """True where the float32 element is anything but +0.0 / -0.0."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    return (g.view(np.uint32) & np.uint32(0x7FFFFFFF)) != 0
+
+
+def pack_bitmap(mask: np.ndarray) -> np.ndarray:
+    """Boolean mask of length n -> ceil(n/64) little-endian 64-bit words, element
+    i in bit (i mod 64) of word i // 64."""
+    n = mask.shape[0]
+    words = (n + 63) // 64
+    by = np.packbits(mask.astype(np.uint8), bitorder="little")
+    buf = np.zeros(words * 8, dtype=np.uint8)
+    buf[: by.shape[0]] = by
+    return buf.view("<u8").astype(np.uint64)
+
+
+def unpack_bitmap(bitmap: np.ndarray, n: int) -> np.ndarray:
+    """Inverse of pack_bitmap: boolean mask of length n."""
+    by = np.ascontiguousarray(bitmap, dtype="<u8").view(np.uint8)
+    return np.unpackbits(by, bitorder="little")[:n].astype(bool)
+
+
+def sparse_of(g: np.ndarray) -> tuple[np.ndarray, np.ndarray]:
+    """Sparse(g): ascending indices of the non-zeros (uint32) and their values."""
+    idx = np.flatnonzero(nonzero_mask(g))
+    return idx.astype(np.uint32), np.ascontiguousarray(g, dtype=np.float32)[idx]
+
+
+def insert(idx: np.ndarray, val: np.ndarray, d: int, w: int, seed: int
+           ) -> tuple[np.ndarray, np.ndarray]:
+    """Insertion loops of Algorithm 1: for every i in Sparse(g) and every row j,
+    S[j, h_j(i)] += s_j(i) * g(i).  Returns (S, M), both float64 [d, w]; M is the
+    'mass' table that accumulates |g(i)| over the same insertions (used only to
+    scale test tolerances; it is not part of the method)."""
+    S = np.zeros((d, w), dtype=np.float64)
+    M = np.zeros((d, w), dtype=np.float64)
+    v = val.astype(np.float64)
+    for j, (a, b, c, e) in enumerate(hash_params(seed, d)):
+        h = bucket_hash(idx, a, b, w)
+        s = sign_hash(idx, c, e)
+        np.add.at(S[j], h, s * v)
+        np.add.at(M[j], h, np.abs(v))
+    return S, M
+
+
+def encode(g: np.ndarray, d: int, w: int, seed: int) -> dict:
+    """One worker's compress step on a dense-stored gradient g (float32[n])."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    mask = nonzero_mask(g)
+    idx = np.flatnonzero(mask).astype(np.uint32)
+    val = g[idx]
+    S, M = insert(idx, val, d, w, seed)
+    return {"bitmap": pack_bitmap(mask), "idx": idx, "val": val, "S": S, "M": M}
+
+
+def encode_sparse(idx: np.ndarray, val: np.ndarray, n: int, d: int, w: int, seed: int) -> dict:
+    """Same as encode() for a gradient given as (ascending distinct idx, val)
+    pairs, for lengths n whose dense form does not fit in host memory.  Pairs
+    whose value is +-0.0 are dropped, as the dense scan would drop them."""
+    idx = np.asarray(idx, dtype=np.uint32)
+    val = np.asarray(val, dtype=np.float32)
+    keep = nonzero_mask(val)
+    idx, val = idx[keep], val[keep]
+    words = (n + 63) // 64
+    bitmap = np.zeros(words, dtype=np.uint64)
+    np.bitwise_or.at(bitmap, (idx >> np.uint32(6)).astype(np.int64),
+                     _U64(1) << (idx & np.uint32(63)).astype(_U64))
+    S, M = insert(idx, val, d, w, seed)
+    return {"bitmap": bitmap, "idx": idx, "val": val, "S": S, "M": M}
+
+
+# --------------------------------------------------------------------------
+# aggregate (Algorithm 1: AllReduce(S, C))
+# --------------------------------------------------------------------------
+
+def merge(sketches: list[np.ndarray], bitmaps: list[np.ndarray]
+          ) -> tuple[np.ndarray, np.ndarray]:
+    """Sum of the workers' sketches, bitwise OR of their bitmaps."""
+    S = np.zeros_like(sketches[0], dtype=np.float64)
+    for Sk in sketches:
+        S = S + Sk
+    C = np.zeros_like(bitmaps[0], dtype=np.uint64)
+    for Ck in bitmaps:
+        C = C | Ck
+    return S, C
+
+
+# --------------------------------------------------------------------------
+# decompress (Algorithm 1: recover Sparse(g), estimates, median)
+# --------------------------------------------------------------------------
+
+def bitmap_indices(bitmap: np.ndarray, n: int) -> np.ndarray:
+    """Ascending indices of the set bits (uint32)."""
+    return np.flatnonzero(unpack_bitmap(bitmap, n)).astype(np.uint32)
+
+
+def median_rows(est: np.ndarray) -> np.ndarray:
+    """Median over axis 0 of a [d, k] table: the middle order statistic for odd
+    d, the mean of the two middle ones for even d."""
+    d = est.shape[0]
+    srt = np.sort(est, axis=0)
+    if d % 2 == 1:
+        return srt[d // 2]
+    return 0.5 * (srt[d // 2 - 1] + srt[d // 2])
+
+
+def estimates(S: np.ndarray, idx: np.ndarray, seed: int) -> np.ndarray:
+    """estimates[j, k] = s_j(i_k) * S[j, h_j(i_k)]  (float64 [d, len(idx)])."""
+    d, w = S.shape
+    est = np.empty((d, idx.shape[0]), dtype=np.float64)
+    for j, (a, b, c, e) in enumerate(hash_params(seed, d)):
+        est[j] = sign_hash(idx, c, e) * S[j, bucket_hash(idx, a, b, w)]
+    return est
+
+
+def decode(S: np.ndarray, bitmap: np.ndarray, n: int, seed: int, dense: bool = False) -> dict:
+    """Decompress: indices from the aggregated bitmap, median-of-rows estimate at
+    each.  With dense=True also the length-n vector with zeros at unset bits."""
+    idx = bitmap_indices(bitmap, n)
+    val = median_rows(estimates(S, idx, seed))
+    out = {"idx": idx, "val": val}
+    if dense:
+        gh = np.zeros(n, dtype=np.float64)
+        gh[idx] = val
+        out["dense"] = gh
+    return out
+
+
+def decode_tolerance_mass(M: np.ndarray, idx: np.ndarray, seed: int) -> np.ndarray:
+    """max_j M[j, h_j(i)] per index: the scale against which a decoded value's
+    float32 error is judged (the median moves by at most the largest per-row
+    perturbation)."""
+    d, w = M.shape
+    m = np.zeros(idx.shape[0], dtype=np.float64)
+    for j, (a, b, _c, _e) in enumerate(hash_params(seed, d)):
+        m = np.maximum(m, M[j, bucket_hash(idx, a, b, w)])
+    return m
+
+
+def reduce_workers(grads: list[np.ndarray], d: int, w: int, seed: int, dense: bool = False) -> dict:
+    """Whole of Algorithm 1 for W dense-stored worker gradients."""
+    enc = [encode(g, d, w, seed) for g in grads]
+    S, C = merge([e["S"] for e in enc], [e["bitmap"] for e in enc])
+    M = np.sum([e["M"] for e in enc], axis=0)
+    out = decode(S, C, grads[0].shape[0], seed, dense=dense)
+    out.update({"S": S, "M": M, "bitmap": C, "workers": enc})
+    return out

@@ -1,0 +1,138 @@
+"""The pins must bite: plant a plausible mistake in the oracle (on the CPU, by
+monkeypatching one of its functions) and check that at least one pin fails."""
+
+import numpy as np
+import pytest
+
+from oracle import s2r_oracle as orc
+from tests import test_oracle_pins as pins
+
+
+def _fails(fn, *args):
+    try:
+        fn(*args)
+    except AssertionError:
+        return True
+    except Exception:           # a crash also counts as "noticed"
+        return True
+    return False
+
+
+def _some_pin_fails():
+    checks = [
+        (pins.test_algorithm1_matches_pure_python, (3, 16, 1)),
+        (pins.test_algorithm1_matches_pure_python, (4, 32, 2)),
+        (pins.test_insert_and_query_equal_mapping_matrix_form, ()),
+        (pins.test_exact_recovery_when_collision_free, (3,)),
+        (pins.test_bitmap_and_sparse_match_elementwise_definition, (127,)),
+        (pins.test_median_brute_force_and_permutation_invariance, (5,)),
+        (pins.test_median_brute_force_and_permutation_invariance, (4,)),
+        (pins.test_bucket_and_sign_match_bigint, (1 << 14,)),
+        (pins.test_merged_bitmap_popcount_is_union_size, ()),
+        (pins.test_single_element_gradient, ()),
+        (pins.test_hash_params_order_and_oddness, ()),
+    ]
+    return any(_fails(fn, *a) for fn, a in checks)
+
+
+def test_unmutated_oracle_passes_the_same_checks():
+    assert not _some_pin_fails()
+
+
+def _mut_sign_dropped_in_query(monkeypatch):
+    real = orc.estimates
+
+    def bad(S, idx, seed):
+        d, w = S.shape
+        est = np.empty((d, idx.shape[0]))
+        for j, (a, b, c, e) in enumerate(orc.hash_params(seed, d)):
+            est[j] = S[j, orc.bucket_hash(idx, a, b, w)]
+        return est
+    monkeypatch.setattr(orc, "estimates", bad)
+    return real
+
+
+def _mut_msb_first_bitmap(monkeypatch):
+    def bad(mask):
+        n = mask.shape[0]
+        words = (n + 63) // 64
+        by = np.packbits(mask.astype(np.uint8), bitorder="big")
+        buf = np.zeros(words * 8, dtype=np.uint8)
+        buf[: by.shape[0]] = by
+        return buf.view("<u8").astype(np.uint64)
+    monkeypatch.setattr(orc, "pack_bitmap", bad)
+
+
+def _mut_median_off_by_one(monkeypatch):
+    def bad(est):
+        srt = np.sort(est, axis=0)
+        return srt[max(0, est.shape[0] // 2 - 1)]
+    monkeypatch.setattr(orc, "median_rows", bad)
+
+
+def _mut_low_bits_bucket(monkeypatch):
+    def bad(idx, a, b, w):
+        i = idx.astype(np.uint64)
+        with np.errstate(over="ignore"):
+            u = i * np.uint64(a) + np.uint64(b)
+        return (u & np.uint64(w - 1)).astype(np.int64)
+    monkeypatch.setattr(orc, "bucket_hash", bad)
+
+
+def _mut_sign_uses_bucket_multiplier(monkeypatch):
+    real = orc.hash_params
+
+    def bad(seed, d):
+        return [(a, b, a, b) for (a, b, c, e) in real(seed, d)]
+    monkeypatch.setattr(orc, "hash_params", bad)
+
+
+def _mut_merge_xor(monkeypatch):
+    def bad(sketches, bitmaps):
+        S = np.sum(sketches, axis=0)
+        C = np.zeros_like(bitmaps[0])
+        for Ck in bitmaps:
+            C = C ^ Ck
+        return S, C
+    monkeypatch.setattr(orc, "merge", bad)
+
+
+def _mut_merge_drops_last_worker(monkeypatch):
+    def bad(sketches, bitmaps):
+        S = np.sum(sketches[:-1], axis=0) if len(sketches) > 1 else sketches[0]
+        C = np.zeros_like(bitmaps[0])
+        for Ck in bitmaps:
+            C = C | Ck
+        return S, C
+    monkeypatch.setattr(orc, "merge", bad)
+
+
+def _mut_negative_zero_counts(monkeypatch):
+    def bad(g):
+        g = np.ascontiguousarray(g, dtype=np.float32)
+        return g.view(np.uint32) != 0
+    monkeypatch.setattr(orc, "nonzero_mask", bad)
+
+
+def _mut_insert_assign_not_accumulate(monkeypatch):
+    def bad(idx, val, d, w, seed):
+        S = np.zeros((d, w))
+        M = np.zeros((d, w))
+        v = val.astype(np.float64)
+        for j, (a, b, c, e) in enumerate(orc.hash_params(seed, d)):
+            h = orc.bucket_hash(idx, a, b, w)
+            S[j, h] += orc.sign_hash(idx, c, e) * v      # buffered: last write wins
+            M[j, h] += np.abs(v)
+        return S, M
+    monkeypatch.setattr(orc, "insert", bad)
+
+
+@pytest.mark.parametrize("mutant", [
+    _mut_sign_dropped_in_query, _mut_msb_first_bitmap, _mut_median_off_by_one,
+    _mut_low_bits_bucket, _mut_sign_uses_bucket_multiplier, _mut_merge_xor,
+    _mut_merge_drops_last_worker, _mut_negative_zero_counts,
+    _mut_insert_assign_not_accumulate,
+], ids=lambda f: f.__name__)
+def test_planted_mistake_is_caught(monkeypatch, mutant):
+    mutant(monkeypatch)
+    assert _some_pin_fails()
