@@ -1,0 +1,185 @@
+/*
+ * s2r.h -- C ABI of the MI355X (gfx950) sparse-sketch gradient codec.
+ *
+ * The library implements the data-parallel hot path of the Sparse-Sketch
+ * Reducer (S2 Reducer, Algorithm 1 and Section 3.1):
+ *
+ *   s2r_encode   one worker's compress step: non-zero bitmap C, Sparse(g), and
+ *                the count-sketch S of the non-zero values
+ *   s2r_merge    the aggregation AllReduce(S, C), carried out on one GPU over W
+ *                workers' buffers: S = sum_k S_k, C = OR_k C_k
+ *   s2r_decode   the decompress step: indices from the aggregated bitmap and,
+ *                at each, the median over rows of s_j(i) * S[j, h_j(i)]
+ *
+ * Notation.  n = gradient length (the paper's d in Section 3.1), d = sketch rows
+ * (the paper's r), w = sketch columns (the paper's c, m in Section 3.1), W =
+ * number of workers.
+ *
+ * Conventions common to all calls
+ *   - Every pointer named "dev" is a device pointer on the current HIP device;
+ *     the caller owns all memory.  The library allocates nothing, keeps no
+ *     pointer after the call returns and performs no host synchronisation: a
+ *     call validates its arguments on the host, enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and returns.
+ *     Results, including counts, are written to device memory in stream order.
+ *   - Return value: S2R_OK or a negative s2r_status.  Argument errors are
+ *     reported before anything is enqueued.  A launch failure reported by the
+ *     runtime gives S2R_ERR_LAUNCH.
+ *   - Bitmap layout: ceil(n/64) 64-bit little-endian words; element i is bit
+ *     (i mod 64), least significant first, of word floor(i/64); the unused high
+ *     bits of the last word are written as 0.  (The paper does not fix a
+ *     layout; Section 3.1 only says one flag per block.  A block is one
+ *     element here.)
+ *   - "Non-zero" is decided on the float32 bit pattern: everything except +0.0
+ *     and -0.0, i.e. (bits & 0x7fffffff) != 0.
+ *   - Sketch layout: d rows of w float32 cells, row-major, S[j*w + b].
+ *   - Hash family (the paper names none; Section 3.1, Algorithm 1
+ *     initialisation): row j has 64-bit parameters a_j, b_j, c_j, e_j, the
+ *     outputs number 4j .. 4j+3 of a SplitMix64 generator whose state starts at
+ *     `seed`, with a_j and c_j made odd.  Arithmetic mod 2^64:
+ *         h_j(i) = (a_j * i + b_j) >> (64 - log2 w)        (0 when w == 1)
+ *         s_j(i) = +1 if bit 63 of (c_j * i + e_j) is 0, else -1
+ *   - Limits: 1 <= n <= 2^32 (indices are uint32), 1 <= d <= S2R_MAX_ROWS,
+ *     w a power of two with 1 <= w <= 2^31 and d*w <= 2^32,
+ *     1 <= W <= S2R_MAX_WORKERS.
+ *   - Determinism: bitmaps, index lists and counts are bit-exact and identical
+ *     from run to run.  Sketch cells are float32 sums formed by hardware
+ *     atomics in arbitrary order, so they (and the decoded values that read
+ *     them) are reproducible only up to float32 summation order; the hardware
+ *     float32 atomic add may flush denormal operands and results to zero.
+ *   - Workspace: s2r_encode and s2r_decode need a device scratch buffer of at
+ *     least s2r_workspace_bytes(n, d, w) bytes, 256-byte aligned.  Its contents
+ *     on entry are irrelevant and on exit unspecified.  Two calls that overlap
+ *     in time (different streams) must not share a workspace.
+ *   - A count written by the library equal to S2R_COUNT_POISON means a kernel's
+ *     internal bounded wait gave up (it cannot happen unless the device stops
+ *     scheduling resident workgroups); the outputs of that call are invalid.
+ */
+#ifndef S2R_H
+#define S2R_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t s2r_status;
+
+#define S2R_OK               0
+#define S2R_ERR_NULL        -1   /* a required pointer is NULL                         */
+#define S2R_ERR_SIZE        -2   /* n, d, w, W or cap outside the documented limits     */
+#define S2R_ERR_WIDTH       -3   /* w is not a power of two                            */
+#define S2R_ERR_WORKSPACE   -4   /* workspace NULL, misaligned or too small            */
+#define S2R_ERR_LAUNCH      -5   /* the HIP runtime refused a kernel launch            */
+#define S2R_ERR_ALIGN       -6   /* a buffer is not aligned as documented              */
+
+#define S2R_MAX_ROWS        16
+#define S2R_MAX_WORKERS     64
+#define S2R_COUNT_POISON    0xFFFFFFFFFFFFFFFFull
+
+/* Library version as major*10000 + minor*100 + patch.  Host only. */
+int32_t s2r_version(void);
+
+/* Static, NUL-terminated description of a status code.  Host only. */
+const char* s2r_status_string(s2r_status status);
+
+/* Bytes of device scratch s2r_encode / s2r_decode need for these sizes (the
+ * larger of the two).  Host only; returns 0 for sizes outside the limits. */
+size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w);
+
+/* The four hash parameters of each of the d rows, as the kernels use them:
+ * params_out[4*j + 0..3] = a_j, b_j, c_j, e_j.  Host pointer, host only.
+ * (Section 3.1 "hash function h", "random sign s"; the family is this
+ * library's reading, stated at the top of this file.) */
+s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out /* host, 4*d */);
+
+/*
+ * Compress one worker's gradient (Algorithm 1: the bitmap line and the two
+ * insertion loops; Section 3.1 "Compressing Sparse Gradient").
+ *
+ *   grad     dev, in : n float32, dense-stored, mostly zero; 4-byte aligned
+ *   sketch   dev, out: d*w float32, OVERWRITTEN (zeroed, then
+ *                      S[j, h_j(i)] += s_j(i) * g(i) for every non-zero i);
+ *                      16-byte aligned
+ *   bitmap   dev, out: ceil(n/64) uint64, OVERWRITTEN; 8-byte aligned
+ *   nz_idx   dev, out: Sparse(g): the non-zero indices in ascending order,
+ *   nz_val   dev, out: and the values at them; capacity `cap` entries each.
+ *                      Both NULL (then cap is ignored) or both non-NULL.
+ *                      Entries at positions >= cap are not written.
+ *   nnz_out  dev, out: one uint64, the true number of non-zeros (also when it
+ *                      exceeds cap: the caller compares).  Required.
+ */
+s2r_status s2r_encode(const float* grad, uint64_t n,
+                      uint32_t d, uint32_t w, uint64_t seed,
+                      float* sketch, uint64_t* bitmap,
+                      uint32_t* nz_idx, float* nz_val, uint64_t cap,
+                      uint64_t* nnz_out,
+                      void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
+ * Aggregate W workers' sketches and bitmaps (Algorithm 1: AllReduce(S, C);
+ * Section 3.1 "Collecting Sparse-Sketch with AllReduce": sketches add, and the
+ * set bits of the aggregated bitmap mark the union of the non-zero blocks).
+ * On one GPU the collective is an elementwise float32 sum taken in ascending
+ * worker order and a bitwise OR.
+ *
+ *   sketches   HOST array of W dev pointers, each d*w float32, 16-byte aligned
+ *   bitmaps    HOST array of W dev pointers, each ceil(n/64) uint64
+ *   sketch_out dev, out: d*w float32; may be the same buffer as sketches[k]
+ *   bitmap_out dev, out: ceil(n/64) uint64; may be the same as bitmaps[k]
+ *   seed       accepted for uniformity of the three signatures; unused (the
+ *              aggregation does not depend on the hashes)
+ * The host arrays are read before the call returns.
+ */
+s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmaps,
+                     uint32_t W, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                     float* sketch_out, uint64_t* bitmap_out,
+                     void* stream);
+
+/*
+ * Decompress (Algorithm 1: "Recover Sparse(g) from aggregated bitmap", the
+ * estimates loop and the median; Section 3.1 "Decompressing Sparse Gradient").
+ *
+ *   sketch    dev, in : d*w float32 (aggregated)
+ *   bitmap    dev, in : ceil(n/64) uint64 (aggregated); bits at positions >= n
+ *                       in the last word must be 0
+ *   idx_out   dev, out: ascending indices of the set bits, capacity cap
+ *   val_out   dev, out: g^(i) = median_j s_j(i) * S[j, h_j(i)] at each of them
+ *                       (middle order statistic for odd d; mean of the two
+ *                       middle ones, in float32, for even d).  idx_out and
+ *                       val_out are both NULL or both non-NULL.
+ *   count_out dev, out: one uint64, the number of set bits.  Required.
+ *   dense_out dev, out: NULL, or n float32 that are fully written: the
+ *                       estimate at set bits, +0.0 elsewhere.  16-byte aligned.
+ * The estimate is of the SUM over workers (Algorithm 1 does not divide by W).
+ */
+s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
+                      uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                      uint32_t* idx_out, float* val_out, uint64_t cap,
+                      uint64_t* count_out,
+                      float* dense_out,
+                      void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
+ * Instrumentation for benchmarks.  While a pair of hipEvent_t is installed for
+ * a slot, the corresponding kernel launch made by the calling thread is
+ * bracketed by hipEventRecord(begin) / hipEventRecord(end) on the launch
+ * stream.  Passing NULLs removes the pair.  State is per host thread.
+ *   slot S2R_KERNEL_ENCODE_SCAN : the dense scan kernel of s2r_encode
+ *   slot S2R_KERNEL_MERGE       : the kernel of s2r_merge
+ *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel of s2r_decode
+ */
+#define S2R_KERNEL_ENCODE_SCAN 0
+#define S2R_KERNEL_MERGE       1
+#define S2R_KERNEL_DECODE      2
+#define S2R_KERNEL_SLOTS       3
+s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S2R_H */

@@ -1,0 +1,195 @@
+"""Thin ctypes binding of libs2r.so (the C ABI declared in include/s2r.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch tensors supply device memory and the stream handle; nothing is
+computed with torch ops here.  There is no CPU fallback: if the shared library
+has not been built, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_int32, c_size_t, c_uint32, c_uint64, c_void_p
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libs2r.so")
+
+S2R_OK = 0
+S2R_ERR_NULL = -1
+S2R_ERR_SIZE = -2
+S2R_ERR_WIDTH = -3
+S2R_ERR_WORKSPACE = -4
+S2R_ERR_LAUNCH = -5
+S2R_ERR_ALIGN = -6
+S2R_MAX_ROWS = 16
+S2R_MAX_WORKERS = 64
+S2R_COUNT_POISON = 0xFFFFFFFFFFFFFFFF
+S2R_KERNEL_ENCODE_SCAN = 0
+S2R_KERNEL_MERGE = 1
+S2R_KERNEL_DECODE = 2
+
+# every symbol include/s2r.h declares: name -> (restype, argtypes)
+SIGNATURES = {
+    "s2r_version": (c_int32, []),
+    "s2r_status_string": (c_char_p, [c_int32]),
+    "s2r_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32]),
+    "s2r_hash_params": (c_int32, [c_uint64, c_uint32, ctypes.POINTER(c_uint64)]),
+    "s2r_encode": (c_int32, [c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
+                             c_void_p, c_void_p, c_void_p, c_void_p, c_uint64,
+                             c_void_p, c_void_p, c_size_t, c_void_p]),
+    "s2r_merge": (c_int32, [ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
+                            c_uint32, c_uint64, c_uint32, c_uint32, c_uint64,
+                            c_void_p, c_void_p, c_void_p]),
+    "s2r_decode": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
+                             c_void_p, c_void_p, c_uint64, c_void_p, c_void_p,
+                             c_void_p, c_size_t, c_void_p]),
+    "s2r_set_kernel_events": (c_int32, [c_int32, c_void_p, c_void_p]),
+}
+
+_lib = None
+
+
+class S2RError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def load():
+    """Load libs2r.so (once).  Raises if it is not built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2110_02140_amd.build` "
+                "(the codec has no CPU fallback)")
+        # torch ships its own HIP runtime (same SONAME as the system one): import it
+        # first so that libs2r.so binds to the runtime that owns torch's memory and
+        # streams instead of loading a second copy.
+        import torch  # noqa: F401
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().s2r_status_string(status).decode()
+
+
+def version() -> int:
+    return load().s2r_version()
+
+
+def workspace_bytes(n: int, d: int, w: int) -> int:
+    return load().s2r_workspace_bytes(n, d, w)
+
+
+def hash_params(seed: int, d: int) -> list[tuple[int, int, int, int]]:
+    buf = (c_uint64 * (4 * d))()
+    st = load().s2r_hash_params(seed, d, buf)
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_hash_params")
+    return [tuple(int(buf[4 * j + q]) for q in range(4)) for j in range(d)]
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return getattr(stream, "cuda_stream", stream)
+
+
+def encode(grad, d, w, seed, sketch, bitmap, nz_idx, nz_val, nnz_out, workspace, stream=None, n=None):
+    """s2r_encode on torch device tensors.  grad float32[n]; sketch float32[d*w];
+    bitmap int64/uint64[ceil(n/64)]; nz_idx int32[cap] / nz_val float32[cap] or
+    both None; nnz_out int64[1]; workspace uint8[>= workspace_bytes]."""
+    n = grad.numel() if n is None else n
+    cap = 0 if nz_idx is None else nz_idx.numel()
+    st = load().s2r_encode(_ptr(grad), n, d, w, seed, _ptr(sketch), _ptr(bitmap), _ptr(nz_idx), _ptr(nz_val),
+                           cap, _ptr(nnz_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                           _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_encode")
+
+
+def merge(sketches, bitmaps, n, d, w, seed, sketch_out, bitmap_out, stream=None):
+    """s2r_merge: sketches / bitmaps are lists of W device tensors."""
+    W = len(sketches)
+    sp = (c_void_p * W)(*[t.data_ptr() for t in sketches])
+    bp = (c_void_p * W)(*[t.data_ptr() for t in bitmaps])
+    st = load().s2r_merge(sp, bp, W, n, d, w, seed, _ptr(sketch_out), _ptr(bitmap_out), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_merge")
+
+
+def decode(sketch, bitmap, n, d, w, seed, idx_out, val_out, count_out, dense_out, workspace, stream=None):
+    """s2r_decode on torch device tensors (idx_out/val_out both None or both
+    given; dense_out None or float32[n])."""
+    cap = 0 if idx_out is None else idx_out.numel()
+    st = load().s2r_decode(_ptr(sketch), _ptr(bitmap), n, d, w, seed, _ptr(idx_out), _ptr(val_out), cap,
+                           _ptr(count_out), _ptr(dense_out), _ptr(workspace),
+                           workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_decode")
+
+
+def set_kernel_events(slot: int, ev_begin, ev_end):
+    """Install (or, with None, remove) raw hipEvent_t handles around a kernel."""
+    st = load().s2r_set_kernel_events(slot, ev_begin, ev_end)
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_set_kernel_events")
+
+
+# ---------------------------------------------------------------- raw HIP events
+_hip = None
+
+
+def _hiprt():
+    global _hip
+    if _hip is None:
+        load()
+        _hip = ctypes.CDLL("libamdhip64.so.7")      # already loaded: same runtime as libs2r.so
+        _hip.hipEventCreate.argtypes = [ctypes.POINTER(c_void_p)]
+        _hip.hipEventDestroy.argtypes = [c_void_p]
+        _hip.hipEventSynchronize.argtypes = [c_void_p]
+        _hip.hipEventRecord.argtypes = [c_void_p, c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), c_void_p, c_void_p]
+    return _hip
+
+
+class HipEvent:
+    """A raw hipEvent_t, usable with set_kernel_events."""
+
+    def __init__(self):
+        self.handle = c_void_p()
+        if _hiprt().hipEventCreate(ctypes.byref(self.handle)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+
+    def record(self, stream=None):
+        if _hiprt().hipEventRecord(self.handle, _stream(stream)) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def synchronize(self):
+        if _hiprt().hipEventSynchronize(self.handle) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+
+    def elapsed_ms(self, end: "HipEvent") -> float:
+        ms = ctypes.c_float()
+        if _hiprt().hipEventElapsedTime(ctypes.byref(ms), self.handle, end.handle) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            _hiprt().hipEventDestroy(self.handle)
+        except Exception:
+            pass

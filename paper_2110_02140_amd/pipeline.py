@@ -1,0 +1,91 @@
+"""Device buffers for one workload and the call sequence of the hot path:
+W x s2r_encode -> s2r_merge -> s2r_decode, all on one stream.
+
+torch is used for device memory only (allocation, host<->device copies of test
+data).  Every step of the path itself is a call into libs2r.so.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding
+
+
+def words_of(n: int) -> int:
+    return (n + 63) // 64
+
+
+def upload_dense(idx: np.ndarray, val: np.ndarray, n: int, device) -> torch.Tensor:
+    """Dense float32[n] on the device with val at idx, zero elsewhere (input
+    staging, not part of the timed path)."""
+    g = torch.zeros(n, dtype=torch.float32, device=device)
+    if idx.shape[0]:
+        ti = torch.from_numpy(idx.astype(np.int64)).to(device)
+        tv = torch.from_numpy(np.ascontiguousarray(val, dtype=np.float32)).to(device)
+        g.index_put_((ti,), tv)
+    return g
+
+
+class Buffers:
+    """All device memory the path touches for a (W, n, d, w) problem."""
+
+    def __init__(self, W: int, n: int, d: int, w: int, seed: int, nz_cap: int, union_cap: int,
+                 device="cuda:0", dense_out: bool = False):
+        self.W, self.n, self.d, self.w, self.seed = W, n, d, w, seed
+        self.device = torch.device(device)
+        dev = self.device
+        nw = words_of(n)
+        self.grads: list[torch.Tensor] = []
+        self.sketch = [torch.empty(d * w, dtype=torch.float32, device=dev) for _ in range(W)]
+        self.bitmap = [torch.empty(nw, dtype=torch.int64, device=dev) for _ in range(W)]
+        self.nz_idx = [torch.empty(max(nz_cap, 1), dtype=torch.int32, device=dev) for _ in range(W)]
+        self.nz_val = [torch.empty(max(nz_cap, 1), dtype=torch.float32, device=dev) for _ in range(W)]
+        self.nnz = torch.zeros(W, dtype=torch.int64, device=dev)
+        self.sketch_sum = torch.empty(d * w, dtype=torch.float32, device=dev)
+        self.bitmap_or = torch.empty(nw, dtype=torch.int64, device=dev)
+        self.out_idx = torch.empty(max(union_cap, 1), dtype=torch.int32, device=dev)
+        self.out_val = torch.empty(max(union_cap, 1), dtype=torch.float32, device=dev)
+        self.out_count = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.dense_out = torch.empty(n, dtype=torch.float32, device=dev) if dense_out else None
+        ws = binding.workspace_bytes(n, d, w)
+        if ws == 0:
+            raise ValueError("sizes outside the library's limits")
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+
+    # ------------------------------------------------------------ the path
+    def encode(self, k: int, stream=None):
+        binding.encode(self.grads[k], self.d, self.w, self.seed, self.sketch[k], self.bitmap[k],
+                       self.nz_idx[k], self.nz_val[k], self.nnz[k:k + 1], self.workspace, stream, n=self.n)
+
+    def merge(self, stream=None):
+        binding.merge(self.sketch, self.bitmap, self.n, self.d, self.w, self.seed,
+                      self.sketch_sum, self.bitmap_or, stream)
+
+    def decode(self, stream=None):
+        binding.decode(self.sketch_sum, self.bitmap_or, self.n, self.d, self.w, self.seed,
+                       self.out_idx, self.out_val, self.out_count, self.dense_out, self.workspace, stream)
+
+    def step(self, stream=None):
+        """One pass of the whole hot path over the resident gradients."""
+        for k in range(self.W):
+            self.encode(k, stream)
+        self.merge(stream)
+        self.decode(stream)
+
+
+def buffers_for(wl, device="cuda:0", dense_out: bool = False, slack: int = 0) -> Buffers:
+    """Buffers sized for a workloads.Workload, with its gradients uploaded."""
+    nz_cap = max(len(i) for i in wl.idx) + slack
+    union_cap = min(wl.n, sum(len(i) for i in wl.idx)) + slack
+    b = Buffers(wl.W, wl.n, wl.d, wl.w, wl.seed, nz_cap, union_cap, device, dense_out)
+    for k in range(wl.W):
+        b.grads.append(upload_dense(wl.idx[k], wl.val[k], wl.n, b.device))
+    return b
+
+
+def u64(t: torch.Tensor) -> np.ndarray:
+    """Device int64 words -> host uint64 array."""
+    return t.cpu().numpy().view(np.uint64)

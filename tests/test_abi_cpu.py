@@ -1,0 +1,115 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol that
+include/s2r.h declares, and its host-only entry points and argument checks
+behave as documented.  No kernel is launched here."""
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import s2r_oracle as orc
+from paper_2110_02140_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "s2r.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(s2r_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = b.load()
+    names = _declared_symbols()
+    assert {"s2r_encode", "s2r_merge", "s2r_decode", "s2r_workspace_bytes"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(b.SIGNATURES), "binding and header disagree on the symbol list"
+
+
+def test_version_and_status_strings():
+    assert b.version() >= 100
+    seen = set()
+    for st in range(0, -7, -1):
+        s = b.status_string(st)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert b.status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("seed", [0, 1, 12345, 2**64 - 1])
+def test_host_hash_params_equal_oracle(seed):
+    assert b.hash_params(seed, 16) == orc.hash_params(seed, 16)
+
+
+def test_workspace_bytes_limits():
+    assert b.workspace_bytes(0, 3, 16) == 0
+    assert b.workspace_bytes(2**32 + 1, 3, 16) == 0
+    assert b.workspace_bytes(100, 0, 16) == 0
+    assert b.workspace_bytes(100, 17, 16) == 0
+    assert b.workspace_bytes(100, 3, 12) == 0          # not a power of two
+    assert b.workspace_bytes(100, 16, 1 << 29) == 0    # d*w > 2^32
+    small = b.workspace_bytes(1, 1, 1)
+    big = b.workspace_bytes(2**32, 5, 1 << 22)
+    assert small >= 256 + 8 and small % 256 == 0
+    assert big > small and big % 256 == 0
+
+
+def _call_encode(**kw):
+    lib = b.load()
+    a = dict(grad=0x1000, n=1000, d=3, w=64, seed=0, sketch=0x2000, bitmap=0x3000, idx=0x4000, val=0x5000,
+             cap=10, nnz=0x6000, ws=0x10000, wsb=1 << 20, stream=None)
+    a.update(kw)
+    return lib.s2r_encode(a["grad"], a["n"], a["d"], a["w"], a["seed"], a["sketch"], a["bitmap"], a["idx"],
+                          a["val"], a["cap"], a["nnz"], a["ws"], a["wsb"], a["stream"])
+
+
+def test_encode_rejects_bad_arguments_before_touching_the_device():
+    # (pointers are never dereferenced: every case below fails validation first)
+    assert _call_encode(grad=None) == b.S2R_ERR_NULL
+    assert _call_encode(sketch=None) == b.S2R_ERR_NULL
+    assert _call_encode(bitmap=None) == b.S2R_ERR_NULL
+    assert _call_encode(nnz=None) == b.S2R_ERR_NULL
+    assert _call_encode(idx=None) == b.S2R_ERR_NULL            # idx without val
+    assert _call_encode(n=0) == b.S2R_ERR_SIZE
+    assert _call_encode(n=2**32 + 1) == b.S2R_ERR_SIZE
+    assert _call_encode(d=0) == b.S2R_ERR_SIZE
+    assert _call_encode(d=17) == b.S2R_ERR_SIZE
+    assert _call_encode(w=0) == b.S2R_ERR_SIZE
+    assert _call_encode(w=48) == b.S2R_ERR_WIDTH
+    assert _call_encode(ws=None) == b.S2R_ERR_WORKSPACE
+    assert _call_encode(ws=0x10010) == b.S2R_ERR_WORKSPACE      # not 256-byte aligned
+    assert _call_encode(wsb=8) == b.S2R_ERR_WORKSPACE
+    assert _call_encode(sketch=0x2004) == b.S2R_ERR_ALIGN
+    assert _call_encode(grad=0x1002) == b.S2R_ERR_ALIGN
+
+
+def test_merge_and_decode_reject_bad_arguments():
+    lib = b.load()
+    two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    one_null = (ctypes.c_void_p * 2)(0x1000, None)
+    assert lib.s2r_merge(None, two, 2, 100, 3, 64, 0, 0x3000, 0x4000, None) == b.S2R_ERR_NULL
+    assert lib.s2r_merge(two, two, 0, 100, 3, 64, 0, 0x3000, 0x4000, None) == b.S2R_ERR_SIZE
+    assert lib.s2r_merge(two, two, 65, 100, 3, 64, 0, 0x3000, 0x4000, None) == b.S2R_ERR_SIZE
+    assert lib.s2r_merge(one_null, two, 2, 100, 3, 64, 0, 0x3000, 0x4000, None) == b.S2R_ERR_NULL
+    assert lib.s2r_merge(two, two, 2, 100, 3, 65, 0, 0x3000, 0x4000, None) == b.S2R_ERR_WIDTH
+    assert lib.s2r_merge(two, two, 2, 100, 3, 64, 0, 0x3004, 0x4000, None) == b.S2R_ERR_ALIGN
+    dec = lambda **k: lib.s2r_decode(k.get("S", 0x1000), k.get("C", 0x2000), k.get("n", 100), k.get("d", 3),
+                                     k.get("w", 64), 0, k.get("idx", 0x3000), k.get("val", 0x4000), 10,
+                                     k.get("cnt", 0x5000), None, k.get("ws", 0x10000), k.get("wsb", 1 << 20), None)
+    assert dec(S=None) == b.S2R_ERR_NULL
+    assert dec(cnt=None) == b.S2R_ERR_NULL
+    assert dec(val=None) == b.S2R_ERR_NULL
+    assert dec(n=0) == b.S2R_ERR_SIZE
+    assert dec(w=3) == b.S2R_ERR_WIDTH
+    assert dec(wsb=0) == b.S2R_ERR_WORKSPACE
+
+
+def test_set_kernel_events_argument_checks():
+    assert b.load().s2r_set_kernel_events(7, None, None) == b.S2R_ERR_SIZE
+    assert b.load().s2r_set_kernel_events(0, 0x10, None) == b.S2R_ERR_NULL
+    assert b.load().s2r_set_kernel_events(0, None, None) == b.S2R_OK
