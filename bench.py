@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: W x s2r_encode + s2r_merge +
+s2r_decode over one batch of synthetic worker gradients resident in HBM.
+
+Prints ONE JSON line.  `value` is dense-gradient GB/s = W*n*4 bytes per step /
+time per step.  `roofline` is for the dominant kernel (the dense scan of
+s2r_encode), timed with HIP events on the launch stream.  `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="which BASELINE config to time (default: the largest single-GPU one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=0, help="override the oracle sample length")
+    return ap.parse_args()
+
+
+def scan_kernel_bytes(n: int, nnz: float, d: int) -> float:
+    """Algorithmic bytes of one launch of the encode scan kernel: the dense read
+    (4 B per element), the bitmap (1 bit per element), the compacted index+value
+    list (8 B per non-zero) and the sketch insertions (d cells read and written,
+    4 B each way, per non-zero)."""
+    return 4.0 * n + n / 8.0 + 8.0 * nnz + 8.0 * d * nnz
+
+
+def cpu_baseline(wl, sample_elems: int):
+    """The oracle, as it stands, on the first `sample_elems` elements of each of
+    up to 4 workers: dense scan + insert per worker, merge, decode."""
+    import numpy as np
+    from oracle import s2r_oracle as orc
+    Ws = min(wl.W, 4)
+    ns = min(wl.n, sample_elems)
+    dense = []
+    for k in range(Ws):
+        cut = int(np.searchsorted(wl.idx[k], ns))
+        g = np.zeros(ns, dtype=np.float32)
+        g[wl.idx[k][:cut]] = wl.val[k][:cut]
+        dense.append(g)
+    t0 = time.perf_counter()
+    out = orc.reduce_workers(dense, wl.d, wl.w, wl.seed)
+    dt = time.perf_counter() - t0
+    gbs = Ws * ns * 4 / dt / 1e9
+    return {"value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{Ws} workers x first {ns} elements of {wl.name} (dense scan+insert, merge, decode; "
+                      f"{len(out['idx'])} union indices), {dt:.1f} s on 1 thread"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (W workers are simulated in one GPU's HBM); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2110_02140_amd import binding, pipeline, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the codec has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    binding.load()
+
+    cfg = int(args.workload[3:])
+    t_gen = time.perf_counter()
+    wl = workloads.make(cfg)
+    t_gen = time.perf_counter() - t_gen
+    b = pipeline.buffers_for(wl)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        b.step(stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = binding.HipEvent(), binding.HipEvent()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        b.step(stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_ms(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = wl.dense_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel timing of the dominant kernel, same call sequence, HIP events on the launch stream
+    reps = max(1, min(args.steps, 10))
+    pairs = [[(binding.HipEvent(), binding.HipEvent()) for _ in range(wl.W)] for _ in range(reps)]
+    phase = {}
+    for r in range(reps):
+        for k in range(wl.W):
+            e0, e1 = pairs[r][k]
+            binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SCAN, e0.handle, e1.handle)
+            b.encode(k, stream)
+        binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SCAN, None, None)
+        m0, m1, d0, d1 = (binding.HipEvent() for _ in range(4))
+        binding.set_kernel_events(binding.S2R_KERNEL_MERGE, m0.handle, m1.handle)
+        b.merge(stream)
+        binding.set_kernel_events(binding.S2R_KERNEL_MERGE, None, None)
+        binding.set_kernel_events(binding.S2R_KERNEL_DECODE, d0.handle, d1.handle)
+        b.decode(stream)
+        binding.set_kernel_events(binding.S2R_KERNEL_DECODE, None, None)
+        phase.setdefault("merge", []).append((m0, m1))
+        phase.setdefault("decode", []).append((d0, d1))
+    torch.cuda.synchronize()
+    scan_ms = float(np.mean([e0.elapsed_ms(e1) for row in pairs for (e0, e1) in row]))
+    merge_ms = float(np.mean([a.elapsed_ms(c) for a, c in phase["merge"]]))
+    decode_ms = float(np.mean([a.elapsed_ms(c) for a, c in phase["decode"]]))
+
+    nnz = b.nnz.cpu().numpy().astype(np.float64)
+    union = int(b.out_count.cpu()[0])
+    assert int(nnz.max()) != binding.S2R_COUNT_POISON and union != binding.S2R_COUNT_POISON
+    assert [int(x) for x in nnz] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
+    alg_bytes = scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d)
+    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "dense-gradient GB/s for encode+merge+decode on 1 MI355X",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "W": wl.W, "n": wl.n, "d": wl.d, "w": wl.w, "seed": wl.seed,
+                   "nnz_per_worker": int(nnz.mean()), "union_nnz": union,
+                   "dense_bytes_per_step": wl.dense_bytes},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "event_ms_per_step": round(ev_ms / args.steps, 4),
+        "kernel_ms": {"encode_scan_avg": round(scan_ms, 4), "merge": round(merge_ms, 4),
+                      "decode": round(decode_ms, 4)},
+        "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "algorithmic_bytes_per_launch": int(alg_bytes)},
+        "setup_s": {"generate": round(t_gen, 1)},
+    }
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample_elems or {1: 1 << 20, 2: 21_630_700, 3: 25_600_000}.get(cfg, 64_000_000)
+        out["cpu_baseline"] = cpu_baseline(wl, sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -145,10 +145,11 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeArgs A,
   const uint32_t d = A.d;
 #pragma unroll
   for (int k = 0; k < EPL; ++k) {
-    const uint64_t wk = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(myword >> 32), k) << 32) |
-                        (uint64_t)__builtin_amdgcn_readlane((uint32_t)myword, k);
+    // (readlane returns a signed int: go through uint32_t so that bit 31 does not sign-extend)
+    const uint64_t wk = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(myword >> 32), k) << 32) |
+                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)myword, k);
     if (wk == 0) continue;             // uniform over the wave
-    const uint32_t pk = __builtin_amdgcn_readlane(word_excl, k);
+    const uint32_t pk = (uint32_t)__builtin_amdgcn_readlane(word_excl, k);
     if ((v[k] << 1) != 0u) {
       const uint64_t pos = base + pk + bits_below_lane(wk);
       const uint32_t i = (uint32_t)(chunk0 + k * kWave + lane);
