@@ -130,7 +130,6 @@ def main():
 
     nnz = b.nnz.cpu().numpy().astype(np.float64)
     union = int(b.out_count.cpu()[0])
-    assert int(nnz.max()) != binding.S2R_COUNT_POISON and union != binding.S2R_COUNT_POISON
     assert [int(x) for x in nnz] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
     alg_bytes = scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d)
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9

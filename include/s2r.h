@@ -48,12 +48,12 @@
  *     them) are reproducible only up to float32 summation order; the hardware
  *     float32 atomic add may flush denormal operands and results to zero.
  *   - Workspace: s2r_encode and s2r_decode need a device scratch buffer of at
- *     least s2r_workspace_bytes(n, d, w) bytes, 256-byte aligned.  Its contents
- *     on entry are irrelevant and on exit unspecified.  Two calls that overlap
- *     in time (different streams) must not share a workspace.
- *   - A count written by the library equal to S2R_COUNT_POISON means a kernel's
- *     internal bounded wait gave up (it cannot happen unless the device stops
- *     scheduling resident workgroups); the outputs of that call are invalid.
+ *     least s2r_workspace_bytes(n, d, w) bytes, 256-byte aligned (per-tile
+ *     counts and their prefix sums).  Its contents on entry are irrelevant and
+ *     on exit unspecified.  Two calls that overlap in time (different streams)
+ *     must not share a workspace.
+ *   - No kernel of the library waits for another workgroup: every launch
+ *     finishes whatever the order in which the hardware schedules workgroups.
  */
 #ifndef S2R_H
 #define S2R_H
@@ -77,7 +77,6 @@ typedef int32_t s2r_status;
 
 #define S2R_MAX_ROWS        16
 #define S2R_MAX_WORKERS     64
-#define S2R_COUNT_POISON    0xFFFFFFFFFFFFFFFFull
 
 /* Library version as major*10000 + minor*100 + patch.  Host only. */
 int32_t s2r_version(void);

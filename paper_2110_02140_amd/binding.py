@@ -24,7 +24,6 @@ S2R_ERR_LAUNCH = -5
 S2R_ERR_ALIGN = -6
 S2R_MAX_ROWS = 16
 S2R_MAX_WORKERS = 64
-S2R_COUNT_POISON = 0xFFFFFFFFFFFFFFFF
 S2R_KERNEL_ENCODE_SCAN = 0
 S2R_KERNEL_MERGE = 1
 S2R_KERNEL_DECODE = 2

@@ -1,8 +1,6 @@
 // Device-side building blocks shared by the gfx950 kernels of the sparse-sketch
-// codec: the row hashes (Section 3.1: bucket hash h, sign hash s), wave64
-// helpers, and the single-pass chained prefix ("decoupled look-back") that gives
-// every tile the number of selected items before it, so that index lists come
-// out ascending without a second pass over the input.
+// codec: the row hashes (Section 3.1: bucket hash h, sign hash s) and wave64
+// helpers.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -44,9 +42,19 @@ __device__ __forceinline__ uint32_t bits_below_lane(uint64_t m) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t x) {
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x += (uint64_t)__shfl_xor((unsigned long long)x, off, kWave);
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, kWave);
+  return x;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x, uint32_t lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t t = __shfl_up(x, off, kWave);
+    if (lane >= (uint32_t)off) x += t;
+  }
   return x;
 }
 
@@ -61,69 +69,6 @@ __device__ __forceinline__ uint32_t select_bit(uint64_t m, uint32_t r) {
     if (r >= c) { x >>= sh; r -= c; pos += sh; }
   }
   return pos;
-}
-
-// ---------------------------------------------------------------------------
-// Chained prefix over tiles.
-//
-// status[t] packs a 2-bit flag (bits 63..62) and a 62-bit value in one word, so
-// one relaxed 64-bit atomic carries both and no ordering between two locations
-// is needed.  A tile first publishes AGGREGATE(its own count), then walks back
-// over its predecessors, a wave-wide window of 64 tiles at a time, summing
-// aggregates until it meets a PREFIX (inclusive count up to and including that
-// tile), and finally publishes its own PREFIX.  Tile ids are handed out by an
-// atomic counter in launch order, so every predecessor of a running tile has
-// itself started and publishes its aggregate without waiting for anybody: the
-// waits below end.  As a second line of defence each wait is bounded; if the
-// bound is ever hit the caller poisons its count output instead of hanging.
-// ---------------------------------------------------------------------------
-constexpr uint64_t kFlagEmpty = 0, kFlagAggregate = 1, kFlagPrefix = 2;
-constexpr uint64_t kValueMask = (1ull << 62) - 1;
-constexpr uint32_t kSpinLimit = 1u << 22;
-
-__device__ __forceinline__ void status_store(uint64_t* p, uint64_t flag, uint64_t value) {
-  __hip_atomic_store(p, (flag << 62) | value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t status_load(const uint64_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Called by all 64 lanes of one wave.  Publishes the tile's aggregate, returns
-// the exclusive prefix (same value in every lane), publishes the inclusive
-// prefix.  *timed_out is set (by any lane) if a bounded wait gave up.
-__device__ __forceinline__ uint64_t chained_exclusive_prefix(uint64_t* status, uint32_t tile,
-                                                             uint64_t aggregate, bool* timed_out) {
-  const uint32_t lane = lane_id();
-  if (tile == 0) {
-    if (lane == 0) status_store(&status[0], kFlagPrefix, aggregate);
-    return 0;
-  }
-  if (lane == 0) status_store(&status[tile], kFlagAggregate, aggregate);
-  uint64_t excl = 0;
-  int64_t window_end = (int64_t)tile - 1;          // newest tile of the current window
-  bool bad = false;
-  while (true) {
-    const int64_t t = window_end - (int64_t)lane;  // lane 0 looks at the nearest predecessor
-    uint64_t s = (kFlagPrefix << 62);              // tiles before 0: prefix 0
-    if (t >= 0) {
-      uint32_t spins = 0;
-      s = status_load(&status[t]);
-      while ((s >> 62) == kFlagEmpty) {
-        if (++spins > kSpinLimit) { bad = true; s = (kFlagPrefix << 62); break; }
-        __builtin_amdgcn_s_sleep(1);
-        s = status_load(&status[t]);
-      }
-    }
-    const uint64_t has_prefix = __ballot((s >> 62) == kFlagPrefix);
-    // lanes up to and including the nearest PREFIX contribute
-    const uint32_t first = has_prefix ? (uint32_t)__ffsll((unsigned long long)has_prefix) - 1u : 63u;
-    excl += wave_sum_u64(lane <= first ? (s & kValueMask) : 0ull);
-    if (has_prefix) break;
-    window_end -= kWave;
-  }
-  if (__ballot(bad)) *timed_out = true;
-  if (lane == 0) status_store(&status[tile], kFlagPrefix, excl + aggregate);
-  return excl;
 }
 
 }  // namespace s2r

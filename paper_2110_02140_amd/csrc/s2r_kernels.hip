@@ -2,16 +2,24 @@
 // (S2 Reducer, Algorithm 1 and Section 3.1).  See include/s2r.h for the
 // contract of every entry point.
 //
-// Kernels
-//   prep_kernel          zero the sketch, the tile status words and the counters
-//   encode_scan_kernel   one pass over the dense gradient: bitmap words from
-//                        wave ballots, ascending Sparse(g) through a chained
-//                        tile prefix, and the sketch insertions
-//                        S[j, h_j(i)] += s_j(i) g(i) as float32 atomics
-//   merge_kernel         S = sum_k S_k (ascending k), C = OR_k C_k
-//   decode_kernel        one pass over the aggregated bitmap: ascending index
-//                        list through the same chained prefix, per index the
-//                        d signed bucket reads and their median
+// The gradient, the bitmaps and the index lists are cut into tiles of
+// kTileWords bitmap words (= 64 * kTileWords elements).  No kernel waits for
+// another workgroup: ascending index lists come from per-tile counts, a small
+// prefix kernel, and a second kernel that expands the bitmap at known offsets.
+//
+//   s2r_encode : zero_kernel           zero the sketch
+//                encode_scan_kernel    the one pass over the dense gradient:
+//                                      bitmap words from wave ballots, per-tile
+//                                      non-zero counts, and the insertions
+//                                      S[j, h_j(i)] += s_j(i) g(i) as float32 atomics
+//                tile_prefix_kernel    exclusive prefix of the tile counts, total
+//                encode_compact_kernel Sparse(g): expands the bitmap (n/8 bytes)
+//                                      and gathers the values at the set bits
+//   s2r_merge  : merge_kernel          S = sum_k S_k (ascending k), C = OR_k C_k
+//   s2r_decode : bitmap_count_kernel   per-tile popcounts of the aggregated bitmap
+//                tile_prefix_kernel
+//                decode_kernel         expands the bitmap; per index the d signed
+//                                      bucket reads and their median
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -21,39 +29,28 @@
 
 namespace s2r {
 
-constexpr int kBlock = 256;                 // threads per workgroup (4 waves)
+constexpr int kBlock = 256;                       // threads per workgroup (4 waves)
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kEncodeEPL = 8;               // elements per lane in the dense scan
-constexpr int kEncodeTile = kBlock * kEncodeEPL;
-constexpr int kDecodeWordsPerThread = 2;
-constexpr int kDecodeTileWords = kBlock * kDecodeWordsPerThread;
-constexpr size_t kHeaderBytes = 256;
+constexpr int kTileWords = 512;                   // bitmap words per tile
+constexpr int kTileElems = kTileWords * 64;       // 32768 gradient elements per tile
+constexpr int kWordsPerWave = kTileWords / kWavesPerBlock;   // 128
+constexpr int kWordsPerThread = kTileWords / kBlock;         // 2
+constexpr int kScanEPL = 16;                      // dense scan: loads in flight per lane
+constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
 
-struct WorkHeader {
-  uint32_t tile_counter;
-  uint32_t pad[63];
-};
-static_assert(sizeof(WorkHeader) == kHeaderBytes, "header is one 256-byte block");
+static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
-// ------------------------------------------------------------------ prep
-// Zeroes `nvec` 16-byte units at `sketch16` (may be 0), `nstatus` status words,
-// the header, and the 8-byte count output.
-__global__ __launch_bounds__(kBlock) void prep_kernel(uint4* __restrict__ sketch16, uint64_t nvec,
-                                                      float* __restrict__ sketch_tail, uint32_t ntail,
-                                                      uint64_t* __restrict__ status, uint64_t nstatus,
-                                                      WorkHeader* __restrict__ hdr,
-                                                      uint64_t* __restrict__ count_out) {
+// ------------------------------------------------------------------ zero
+__global__ __launch_bounds__(kBlock) void zero_kernel(uint4* __restrict__ p16, uint64_t nvec,
+                                                      float* __restrict__ tail, uint32_t ntail) {
   const uint64_t tid = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t i = tid; i < nvec; i += stride) sketch16[i] = make_uint4(0u, 0u, 0u, 0u);
-  for (uint64_t i = tid; i < nstatus; i += stride) status[i] = 0ull;
-  if (tid < ntail) sketch_tail[tid] = 0.0f;
-  if (tid < 64) reinterpret_cast<uint32_t*>(hdr)[tid] = 0u;
-  if (tid == 0) *count_out = 0ull;
+  for (uint64_t i = tid; i < nvec; i += stride) p16[i] = make_uint4(0u, 0u, 0u, 0u);
+  if (tid < ntail) tail[tid] = 0.0f;
 }
 
-// ------------------------------------------------------------------ encode
-struct EncodeArgs {
+// ------------------------------------------------------------------ encode: dense scan
+struct ScanArgs {
   const uint32_t* grad;      // dense gradient as bit patterns
   uint64_t n;
   uint64_t nwords;
@@ -61,109 +58,217 @@ struct EncodeArgs {
   uint32_t log2w;
   float* sketch;
   uint64_t* bitmap;
-  uint32_t* nz_idx;          // may be null
-  float* nz_val;             // may be null
-  uint64_t cap;
-  uint64_t* nnz_out;
-  WorkHeader* hdr;
-  uint64_t* status;
-  uint32_t ntiles;
+  uint32_t* tile_count;      // [ntiles]
 };
 
-template <int EPL>
-__global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeArgs A, const HashRows hp) {
-  constexpr int TILE = kBlock * EPL;
-  __shared__ uint32_t s_tile;
-  __shared__ uint32_t s_wave_count[kWavesPerBlock];
-  __shared__ uint64_t s_base;
+__device__ __forceinline__ void sketch_insert(const ScanArgs& A, const HashRows& hp, uint32_t i, uint32_t vbits) {
+  for (uint32_t j = 0; j < A.d; ++j) {
+    const uint32_t h = bucket_of(i, hp.a[j], hp.b[j], A.log2w);
+    const uint32_t sv = vbits ^ signbit_of(i, hp.c[j], hp.e[j]);
+    __hip_atomic_fetch_add(&A.sketch[((uint64_t)j << A.log2w) + h], __uint_as_float(sv),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 
-  if (threadIdx.x == 0) s_tile = atomicAdd(&A.hdr->tile_counter, 1u);
-  __syncthreads();
-  const uint32_t tile = s_tile;
+// One workgroup per tile; wave q scans words [128q, 128q+128) of the tile, EPL
+// words (64*EPL elements) per iteration.  Lane l reads element 64k + l of the
+// iteration's chunk for k = 0..EPL-1: every load instruction is one coalesced
+// 256-byte row and its ballot is bitmap word k.  The words are parked one per
+// lane and leave as one coalesced 512-byte store per 64 words.
+template <int EPL>
+__global__ __launch_bounds__(kBlock) void encode_scan_kernel(const ScanArgs A, const HashRows hp) {
+  static_assert(kWave % EPL == 0 && kWordsPerWave % kWave == 0, "word parking assumes EPL | 64 | words per wave");
+  constexpr int kIters = kWordsPerWave / EPL;
+  __shared__ uint32_t s_wave_count[kWavesPerBlock];
+
+  const uint32_t tile = blockIdx.x;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
-  // first element of the 64*EPL-element chunk this wave scans
-  const uint64_t chunk0 = (uint64_t)tile * TILE + (uint64_t)wv * (kWave * EPL);
+  const uint64_t wave_word0 = (uint64_t)tile * kTileWords + (uint64_t)wv * kWordsPerWave;
+  const bool full = ((uint64_t)tile + 1) * kTileElems <= A.n;    // uniform over the workgroup
 
-  // Lane l reads element chunk0 + 64k + l for k = 0..EPL-1: each load is one
-  // fully coalesced 256-byte row, and the ballot of load k is bitmap word k.
-  uint32_t v[EPL];
-  if (chunk0 + (uint64_t)kWave * EPL <= A.n) {
+  uint32_t count = 0;          // non-zeros seen by this wave (uniform)
+  uint64_t parked = 0;         // lane l holds word (64*m + l) of the wave's range until stored
+#pragma unroll 2
+  for (int it = 0; it < kIters; ++it) {
+    const uint64_t e0 = (wave_word0 + (uint64_t)it * EPL) * 64;   // first element of the chunk
+    uint32_t v[EPL];
+    if (full) {
 #pragma unroll
-    for (int k = 0; k < EPL; ++k) v[k] = __builtin_nontemporal_load(&A.grad[chunk0 + k * kWave + lane]);
-  } else {
+      for (int k = 0; k < EPL; ++k) v[k] = __builtin_nontemporal_load(&A.grad[e0 + k * kWave + lane]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < EPL; ++k) {
+        const uint64_t i = e0 + k * kWave + lane;
+        v[k] = i < A.n ? A.grad[i] : 0u;
+      }
+    }
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
-      const uint64_t i = chunk0 + k * kWave + lane;
-      v[k] = i < A.n ? A.grad[i] : 0u;
-    }
-  }
-
-  uint64_t myword = 0;                 // lane k (< EPL) keeps word k of this wave's chunk
-#pragma unroll
-  for (int k = 0; k < EPL; ++k) {
-    const uint64_t b = __ballot((v[k] << 1) != 0u);     // non-zero: anything but +-0.0
-    if (lane == (uint32_t)k) myword = b;
-  }
-  const uint64_t word0 = chunk0 >> 6;
-  if (lane < (uint32_t)EPL && word0 + lane < A.nwords) A.bitmap[word0 + lane] = myword;
-
-  // non-zeros in the words before word k of this wave, and in the whole wave
-  const uint32_t cnt = (uint32_t)__popcll(myword);
-  uint32_t incl = cnt;
-#pragma unroll
-  for (int off = 1; off < EPL; off <<= 1) {
-    const uint32_t t = __shfl_up(incl, off, kWave);
-    if (lane >= (uint32_t)off) incl += t;
-  }
-  const uint32_t word_excl = incl - cnt;
-  const uint32_t wave_total = __shfl(incl, EPL - 1, kWave);
-  if (lane == 0) s_wave_count[wv] = wave_total;
-  __syncthreads();
-
-  uint32_t tile_total = 0, wave_off = 0;
-#pragma unroll
-  for (int q = 0; q < kWavesPerBlock; ++q) {
-    const uint32_t c = s_wave_count[q];
-    if ((uint32_t)q < wv) wave_off += c;
-    tile_total += c;
-  }
-
-  if (wv == 0) {
-    bool timed_out = false;
-    const uint64_t excl = chained_exclusive_prefix(A.status, tile, tile_total, &timed_out);
-    if (lane == 0) {
-      s_base = excl;
-      if (tile == A.ntiles - 1) atomicMax((unsigned long long*)A.nnz_out, (unsigned long long)(excl + tile_total));
-      if (timed_out) atomicMax((unsigned long long*)A.nnz_out, (unsigned long long)S2R_COUNT_POISON);
-    }
-  }
-  __syncthreads();
-  if (tile_total == 0) return;         // uniform over the workgroup
-
-  const uint64_t base = s_base + wave_off;
-  const uint32_t d = A.d;
-#pragma unroll
-  for (int k = 0; k < EPL; ++k) {
-    // (readlane returns a signed int: go through uint32_t so that bit 31 does not sign-extend)
-    const uint64_t wk = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(myword >> 32), k) << 32) |
-                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)myword, k);
-    if (wk == 0) continue;             // uniform over the wave
-    const uint32_t pk = (uint32_t)__builtin_amdgcn_readlane(word_excl, k);
-    if ((v[k] << 1) != 0u) {
-      const uint64_t pos = base + pk + bits_below_lane(wk);
-      const uint32_t i = (uint32_t)(chunk0 + k * kWave + lane);
-      if (A.nz_idx != nullptr && pos < A.cap) {
-        A.nz_idx[pos] = i;
-        A.nz_val[pos] = __uint_as_float(v[k]);
-      }
-      for (uint32_t j = 0; j < d; ++j) {
-        const uint32_t h = bucket_of(i, hp.a[j], hp.b[j], A.log2w);
-        const uint32_t sv = v[k] ^ signbit_of(i, hp.c[j], hp.e[j]);
-        __hip_atomic_fetch_add(&A.sketch[((uint64_t)j << A.log2w) + h], __uint_as_float(sv),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const bool nz = (v[k] << 1) != 0u;                 // anything but +0.0 / -0.0
+      const uint64_t b = __ballot(nz);
+      if (lane == (uint32_t)((it * EPL + k) & (kWave - 1))) parked = b;
+      if (b != 0) {                                      // uniform: most words are empty
+        count += (uint32_t)__popcll(b);
+        if (nz) sketch_insert(A, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
       }
     }
+    if (((it + 1) * EPL) % kWave == 0) {                 // 64 words parked: store them
+      const uint64_t w = wave_word0 + (uint64_t)((it + 1) * EPL - kWave) + lane;
+      if (w < A.nwords) A.bitmap[w] = parked;
+    }
+  }
+  if (lane == 0) s_wave_count[wv] = count;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) t += s_wave_count[q];
+    A.tile_count[tile] = t;
+  }
+}
+
+// ------------------------------------------------------------------ per-tile popcounts (decode)
+// One wave per tile: lane l reads words l, l+64, ... of the tile.
+__global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
+                                                              uint32_t ntiles, uint32_t* __restrict__ tile_count) {
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t tile = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (tile >= ntiles) return;
+  const uint64_t w0 = (uint64_t)tile * kTileWords;
+  uint32_t c = 0;
+#pragma unroll
+  for (int q = 0; q < kTileWords / kWave; ++q) {
+    const uint64_t w = w0 + q * kWave + lane;
+    c += w < nwords ? (uint32_t)__popcll(bitmap[w]) : 0u;
+  }
+  c = wave_sum_u32(c);
+  if (lane == 0) tile_count[tile] = c;
+}
+
+// ------------------------------------------------------------------ prefix of the tile counts
+// Single workgroup.  prefix[t] = sum of count[0..t), prefix[ntiles] = total, also
+// written to *total_out.  At most 2^17 tiles (n <= 2^32), 4 per thread per round.
+__global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_t* __restrict__ count, uint32_t ntiles,
+                                                                   uint64_t* __restrict__ prefix,
+                                                                   uint64_t* __restrict__ total_out) {
+  constexpr int kPer = 4;
+  constexpr int kWaves = kPrefixBlock / kWave;
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  uint64_t carry = 0;
+  for (uint32_t base = 0; base < ntiles; base += kPrefixBlock * kPer) {
+    const uint32_t i0 = base + threadIdx.x * kPer;
+    uint32_t c[kPer];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      c[q] = i0 + q < ntiles ? count[i0 + q] : 0u;
+      mine += c[q];
+    }
+    const uint32_t incl = wave_inclusive_scan_u32(mine, lane);
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    uint32_t wave_off = 0, round_total = 0;
+#pragma unroll
+    for (int q = 0; q < kWaves; ++q) {
+      const uint32_t x = s_wave[q];
+      if ((uint32_t)q < wv) wave_off += x;
+      round_total += x;
+    }
+    uint64_t run = carry + wave_off + (incl - mine);
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      if (i0 + q < ntiles) prefix[i0 + q] = run;
+      run += c[q];
+    }
+    carry += round_total;
+    __syncthreads();               // s_wave is rewritten in the next round
+  }
+  if (threadIdx.x == 0) {
+    prefix[ntiles] = carry;
+    *total_out = carry;
+  }
+}
+
+// ------------------------------------------------------------------ bitmap tile in LDS
+// Loads the tile's words, leaves them in s_words and the exclusive prefix of
+// their popcounts in s_prefix (s_prefix[kTileWords] = tile total).  All threads
+// of the workgroup call it; it ends with a barrier.
+struct TileBits {
+  uint64_t words[kTileWords];
+  uint32_t prefix[kTileWords + 1];
+  uint32_t wave_count[kWavesPerBlock];
+};
+
+__device__ __forceinline__ void load_tile_bits(TileBits& T, const uint64_t* __restrict__ bitmap, uint64_t nwords,
+                                               uint64_t word0) {
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  uint64_t wd[kWordsPerThread];
+  uint32_t pc[kWordsPerThread];
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int q = 0; q < kWordsPerThread; ++q) {        // thread t owns words 2t, 2t+1
+    const uint64_t wi = word0 + (uint64_t)threadIdx.x * kWordsPerThread + q;
+    wd[q] = wi < nwords ? bitmap[wi] : 0ull;
+    pc[q] = (uint32_t)__popcll(wd[q]);
+    cnt += pc[q];
+  }
+  const uint32_t incl = wave_inclusive_scan_u32(cnt, lane);
+  if (lane == kWave - 1) T.wave_count[wv] = incl;
+  __syncthreads();
+  uint32_t run = incl - cnt;
+#pragma unroll
+  for (int q = 0; q < kWavesPerBlock; ++q) run += (uint32_t)q < wv ? T.wave_count[q] : 0u;
+#pragma unroll
+  for (int q = 0; q < kWordsPerThread; ++q) {
+    T.words[threadIdx.x * kWordsPerThread + q] = wd[q];
+    T.prefix[threadIdx.x * kWordsPerThread + q] = run;
+    run += pc[q];
+  }
+  if (threadIdx.x == kBlock - 1) T.prefix[kTileWords] = run;
+  __syncthreads();
+}
+
+// Element index (relative to the tile) of the t-th set bit of the tile, t < total.
+__device__ __forceinline__ uint32_t locate_set_bit(const TileBits& T, uint32_t t) {
+  static_assert(kTileWords == 512, "the search below takes log2(kTileWords) = 9 steps");
+  uint32_t lo = 0, hi = kTileWords;               // invariant: prefix[lo] <= t < prefix[hi]
+#pragma unroll
+  for (int step = 0; step < 9; ++step) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (T.prefix[mid] <= t) lo = mid; else hi = mid;
+  }
+  return lo * 64 + select_bit(T.words[lo], t - T.prefix[lo]);
+}
+
+// ------------------------------------------------------------------ encode: Sparse(g)
+struct CompactArgs {
+  const uint32_t* grad;
+  const uint64_t* bitmap;
+  uint64_t nwords;
+  const uint64_t* prefix;    // [ntiles + 1]
+  uint32_t* nz_idx;
+  uint32_t* nz_val;          // float bit patterns
+  uint64_t cap;
+};
+
+__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArgs A) {
+  __shared__ TileBits T;
+  const uint32_t tile = blockIdx.x;
+  const uint64_t base = A.prefix[tile];
+  const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
+  if (total == 0 || base >= A.cap) return;         // uniform over the workgroup
+  const uint64_t word0 = (uint64_t)tile * kTileWords;
+  load_tile_bits(T, A.bitmap, A.nwords, word0);
+  for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
+    const uint64_t pos = base + t;
+    if (pos >= A.cap) break;
+    const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
+    A.nz_idx[pos] = i;
+    A.nz_val[pos] = A.grad[i];
   }
 }
 
@@ -217,19 +322,17 @@ struct DecodeArgs {
   uint64_t nwords;
   uint32_t d;
   uint32_t log2w;
+  const uint64_t* prefix;    // [ntiles + 1]
   uint32_t* idx_out;         // may be null
   float* val_out;            // may be null
   uint64_t cap;
-  uint64_t* count_out;
   float* dense_out;          // may be null
-  WorkHeader* hdr;
-  uint64_t* status;
-  uint32_t ntiles;
 };
 
+// Median of D values by a fully unrolled exchange network: every output is one
+// of the inputs (odd D); even D averages the two middle ones in float32.
 template <int D>
 __device__ __forceinline__ float median_fixed(float (&x)[D]) {
-  // selection by a fully unrolled exchange network; every output is one of the inputs
 #pragma unroll
   for (int a = 0; a < D - 1; ++a) {
 #pragma unroll
@@ -245,7 +348,7 @@ __device__ __forceinline__ float median_fixed(float (&x)[D]) {
 }
 
 template <int D>
-__device__ __forceinline__ float query_fixed(const DecodeArgs& A, const HashRows& hp, uint32_t i) {
+__device__ __forceinline__ float query(const DecodeArgs& A, const HashRows& hp, uint32_t i) {
   float est[D];
 #pragma unroll
   for (int j = 0; j < D; ++j) {
@@ -256,114 +359,30 @@ __device__ __forceinline__ float query_fixed(const DecodeArgs& A, const HashRows
   return median_fixed<D>(est);
 }
 
-// any d up to kMaxRows: estimates kept in a local array, insertion sort
-__device__ __noinline__ float query_any(const DecodeArgs& A, const HashRows& hp, uint32_t i) {
-  float est[kMaxRows];
-  const uint32_t d = A.d;
-  for (uint32_t j = 0; j < d; ++j) {
-    const uint32_t h = bucket_of(i, hp.a[j], hp.b[j], A.log2w);
-    const uint32_t raw = __float_as_uint(A.sketch[((uint64_t)j << A.log2w) + h]);
-    const float x = __uint_as_float(raw ^ signbit_of(i, hp.c[j], hp.e[j]));
-    uint32_t p = j;
-    while (p > 0 && est[p - 1] > x) { est[p] = est[p - 1]; --p; }
-    est[p] = x;
-  }
-  if (d & 1u) return est[d / 2];
-  return 0.5f * (est[d / 2 - 1] + est[d / 2]);
-}
-
-template <int D>   // D == 0: runtime d
+template <int D>
 __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, const HashRows hp) {
-  __shared__ uint32_t s_tile;
-  __shared__ uint64_t s_words[kDecodeTileWords];
-  __shared__ uint32_t s_prefix[kDecodeTileWords + 1];   // exclusive prefix of popcounts, [last] = total
-  __shared__ uint32_t s_wave_count[kWavesPerBlock];
-  __shared__ uint64_t s_base;
+  __shared__ TileBits T;
+  const uint32_t tile = blockIdx.x;
+  const uint64_t word0 = (uint64_t)tile * kTileWords;
+  const uint64_t base = A.prefix[tile];
+  const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
 
-  if (threadIdx.x == 0) s_tile = atomicAdd(&A.hdr->tile_counter, 1u);
-  __syncthreads();
-  const uint32_t tile = s_tile;
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wv = threadIdx.x / kWave;
-  const uint64_t word0 = (uint64_t)tile * kDecodeTileWords;
-
-  // thread t owns words 2t and 2t+1 of the tile
-  uint64_t wd[kDecodeWordsPerThread];
-  uint32_t pc[kDecodeWordsPerThread];
-  uint32_t cnt = 0;
-#pragma unroll
-  for (int q = 0; q < kDecodeWordsPerThread; ++q) {
-    const uint64_t wi = word0 + (uint64_t)threadIdx.x * kDecodeWordsPerThread + q;
-    wd[q] = wi < A.nwords ? A.bitmap[wi] : 0ull;
-    pc[q] = (uint32_t)__popcll(wd[q]);
-    cnt += pc[q];
-  }
-  uint32_t incl = cnt;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t t = __shfl_up(incl, off, kWave);
-    if (lane >= (uint32_t)off) incl += t;
-  }
-  if (lane == kWave - 1) s_wave_count[wv] = incl;
-  __syncthreads();
-  uint32_t tile_total = 0, wave_off = 0;
-#pragma unroll
-  for (int q = 0; q < kWavesPerBlock; ++q) {
-    const uint32_t c = s_wave_count[q];
-    if ((uint32_t)q < wv) wave_off += c;
-    tile_total += c;
-  }
-  {
-    uint32_t run = wave_off + incl - cnt;
-#pragma unroll
-    for (int q = 0; q < kDecodeWordsPerThread; ++q) {
-      s_words[threadIdx.x * kDecodeWordsPerThread + q] = wd[q];
-      s_prefix[threadIdx.x * kDecodeWordsPerThread + q] = run;
-      run += pc[q];
-    }
-    if (threadIdx.x == kBlock - 1) s_prefix[kDecodeTileWords] = run;
-  }
-
-  if (wv == 0) {
-    bool timed_out = false;
-    const uint64_t excl = chained_exclusive_prefix(A.status, tile, tile_total, &timed_out);
-    if (lane == 0) {
-      s_base = excl;
-      if (tile == A.ntiles - 1) atomicMax((unsigned long long*)A.count_out, (unsigned long long)(excl + tile_total));
-      if (timed_out) atomicMax((unsigned long long*)A.count_out, (unsigned long long)S2R_COUNT_POISON);
-    }
-  }
-
-  // dense output: this workgroup owns elements [64*word0, 64*(word0 + tile words)):
-  // clear them first, the estimates are written over the zeros after the barrier
+  // dense output: this workgroup owns the tile's elements; clear them first, the
+  // estimates are written over the zeros after the barrier in load_tile_bits
   if (A.dense_out != nullptr) {
     const uint64_t e0 = word0 * 64;
-    const uint64_t e1 = min(A.n, e0 + (uint64_t)kDecodeTileWords * 64);
-    if (e1 > e0) {
-      float4* p4 = reinterpret_cast<float4*>(A.dense_out + e0);   // e0 is a multiple of 64 elements
-      const uint64_t n4 = (e1 - e0) / 4;
-      for (uint64_t q = threadIdx.x; q < n4; q += kBlock) p4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-      const uint64_t r = e0 + n4 * 4 + threadIdx.x;
-      if (r < e1) A.dense_out[r] = 0.0f;
-    }
+    const uint64_t e1 = min(A.n, e0 + (uint64_t)kTileElems);
+    float4* p4 = reinterpret_cast<float4*>(A.dense_out + e0);     // e0 is a multiple of 64 elements
+    const uint64_t n4 = (e1 - e0) / 4;
+    for (uint64_t q = threadIdx.x; q < n4; q += kBlock) p4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const uint64_t r = e0 + n4 * 4 + threadIdx.x;
+    if (r < e1) A.dense_out[r] = 0.0f;
   }
-  __syncthreads();
-  if (tile_total == 0) return;
-
-  const uint64_t base = s_base;
-  for (uint32_t t = threadIdx.x; t < tile_total; t += kBlock) {
-    // the word holding the t-th set bit of the tile: last w with prefix[w] <= t
-    uint32_t lo = 0, hi = kDecodeTileWords;     // invariant: prefix[lo] <= t < prefix[hi]
-#pragma unroll
-    for (int step = 0; step < 9; ++step) {      // 2^9 = 512 words per tile
-      const uint32_t mid = (lo + hi) >> 1;
-      if (s_prefix[mid] <= t) lo = mid; else hi = mid;
-    }
-    const uint32_t bit = select_bit(s_words[lo], t - s_prefix[lo]);
-    const uint32_t i = (uint32_t)((word0 + lo) * 64 + bit);
-    float g;
-    if (D == 0) g = query_any(A, hp, i);
-    else g = query_fixed<(D == 0 ? 1 : D)>(A, hp, i);
+  if (total == 0) return;                          // uniform over the workgroup
+  load_tile_bits(T, A.bitmap, A.nwords, word0);
+  for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
+    const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
+    const float g = query<D>(A, hp, i);
     const uint64_t pos = base + t;
     if (A.idx_out != nullptr && pos < A.cap) {
       A.idx_out[pos] = i;
@@ -372,7 +391,6 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
     if (A.dense_out != nullptr) A.dense_out[i] = g;
   }
 }
-static_assert(kDecodeTileWords == 512, "the word search in decode_kernel takes log2(tile words) = 9 steps");
 
 // ------------------------------------------------------------------ host side
 struct EventPair { hipEvent_t begin, end; };
@@ -402,7 +420,7 @@ static void make_hash_rows(uint64_t seed, uint32_t d, HashRows* hp) {
 
 static inline bool is_pow2(uint32_t w) { return w != 0 && (w & (w - 1)) == 0; }
 static inline uint32_t log2_of(uint32_t w) { uint32_t l = 0; while ((1u << l) < w) ++l; return l; }
-static inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
   if (n == 0 || n > (1ull << 32)) return S2R_ERR_SIZE;
@@ -414,16 +432,34 @@ static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
   return S2R_OK;
 }
 
-static inline uint32_t encode_tiles(uint64_t n) { return (uint32_t)ceil_div(n, kEncodeTile); }
-static inline uint32_t decode_tiles(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kDecodeTileWords); }
+static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kTileWords); }
+
+// workspace: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]], each part 256-byte aligned
+struct Workspace {
+  uint32_t* count;
+  uint64_t* prefix;
+};
+static inline size_t workspace_need(uint64_t n) {
+  const size_t t = tiles_of(n);
+  return align256(t * sizeof(uint32_t)) + align256((t + 1) * sizeof(uint64_t));
+}
+static inline Workspace carve(void* ws, uint64_t n) {
+  Workspace w;
+  w.count = reinterpret_cast<uint32_t*>(ws);
+  w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)tiles_of(n) * sizeof(uint32_t)));
+  return w;
+}
 
 static inline void record(int slot, bool end, hipStream_t st) {
   hipEvent_t ev = end ? g_events[slot].end : g_events[slot].begin;
   if (ev != nullptr) (void)hipEventRecord(ev, st);
 }
 
-static inline s2r_status launch_status() {
-  return hipGetLastError() == hipSuccess ? S2R_OK : S2R_ERR_LAUNCH;
+static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+template <int D>
+static void launch_decode(dim3 grid, hipStream_t st, const DecodeArgs& A, const HashRows& hp) {
+  hipLaunchKernelGGL(decode_kernel<D>, grid, dim3(kBlock), 0, st, A, hp);
 }
 
 }  // namespace s2r
@@ -432,7 +468,7 @@ using namespace s2r;
 
 extern "C" {
 
-int32_t s2r_version(void) { return 100; }
+int32_t s2r_version(void) { return 200; }
 
 const char* s2r_status_string(s2r_status status) {
   switch (status) {
@@ -449,9 +485,7 @@ const char* s2r_status_string(s2r_status status) {
 
 size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w) {
   if (check_sizes(n, d, w) != S2R_OK) return 0;
-  const uint64_t tiles = encode_tiles(n) > decode_tiles(n) ? encode_tiles(n) : decode_tiles(n);
-  const uint64_t bytes = kHeaderBytes + tiles * sizeof(uint64_t);
-  return (size_t)((bytes + 255) & ~(uint64_t)255);
+  return workspace_need(n);
 }
 
 s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out) {
@@ -483,45 +517,56 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 ||
-      workspace_bytes < s2r_workspace_bytes(n, d, w)) return S2R_ERR_WORKSPACE;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_need(n))
+    return S2R_ERR_WORKSPACE;
   if (((uintptr_t)grad & 3u) || ((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) ||
       ((uintptr_t)nz_idx & 3u) || ((uintptr_t)nz_val & 3u) || ((uintptr_t)nnz_out & 7u)) return S2R_ERR_ALIGN;
 
   hipStream_t st = (hipStream_t)stream;
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-
-  EncodeArgs A;
-  A.grad = reinterpret_cast<const uint32_t*>(grad);
-  A.n = n;
-  A.nwords = ceil_div(n, 64);
-  A.d = d;
-  A.log2w = log2_of(w);
-  A.sketch = sketch;
-  A.bitmap = bitmap;
-  A.nz_idx = nz_idx;
-  A.nz_val = nz_val;
-  A.cap = nz_idx ? cap : 0;
-  A.nnz_out = nnz_out;
-  A.hdr = reinterpret_cast<WorkHeader*>(workspace);
-  A.status = reinterpret_cast<uint64_t*>((char*)workspace + kHeaderBytes);
-  A.ntiles = encode_tiles(n);
+  const Workspace ws = carve(workspace, n);
+  const uint32_t ntiles = tiles_of(n);
 
   const uint64_t cells = (uint64_t)d * w;
   const uint64_t nvec = cells / 4;
   const uint32_t ntail = (uint32_t)(cells - nvec * 4);
-  uint64_t work = nvec > A.ntiles ? nvec : A.ntiles;
-  uint32_t pblocks = (uint32_t)(ceil_div(work, kBlock) < 2048 ? ceil_div(work, kBlock) : 2048);
-  if (pblocks == 0) pblocks = 1;
-  hipLaunchKernelGGL(prep_kernel, dim3(pblocks), dim3(kBlock), 0, st, reinterpret_cast<uint4*>(sketch), nvec,
-                     sketch + nvec * 4, ntail, A.status, (uint64_t)A.ntiles, A.hdr, nnz_out);
-  if (launch_status() != S2R_OK) return S2R_ERR_LAUNCH;
+  uint64_t zb = ceil_div(nvec > 0 ? nvec : 1, kBlock);
+  if (zb > 2048) zb = 2048;
+  hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb), dim3(kBlock), 0, st, reinterpret_cast<uint4*>(sketch), nvec,
+                     sketch + nvec * 4, ntail);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
 
+  ScanArgs S;
+  S.grad = reinterpret_cast<const uint32_t*>(grad);
+  S.n = n;
+  S.nwords = ceil_div(n, 64);
+  S.d = d;
+  S.log2w = log2_of(w);
+  S.sketch = sketch;
+  S.bitmap = bitmap;
+  S.tile_count = ws.count;
   record(S2R_KERNEL_ENCODE_SCAN, false, st);
-  hipLaunchKernelGGL(encode_scan_kernel<kEncodeEPL>, dim3(A.ntiles), dim3(kBlock), 0, st, A, hp);
+  hipLaunchKernelGGL(encode_scan_kernel<kScanEPL>, dim3(ntiles), dim3(kBlock), 0, st, S, hp);
   record(S2R_KERNEL_ENCODE_SCAN, true, st);
-  return launch_status();
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, nnz_out);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+
+  if (nz_idx != nullptr && cap > 0) {
+    CompactArgs C;
+    C.grad = S.grad;
+    C.bitmap = bitmap;
+    C.nwords = S.nwords;
+    C.prefix = ws.prefix;
+    C.nz_idx = nz_idx;
+    C.nz_val = reinterpret_cast<uint32_t*>(nz_val);
+    C.cap = cap;
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(ntiles), dim3(kBlock), 0, st, C);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+  return S2R_OK;
 }
 
 s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
@@ -558,7 +603,7 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
   record(S2R_KERNEL_MERGE, false, st);
   hipLaunchKernelGGL(merge_kernel, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
   record(S2R_KERNEL_MERGE, true, st);
-  return launch_status();
+  return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
 s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
@@ -568,50 +613,60 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   if ((idx_out == nullptr) != (val_out == nullptr)) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 ||
-      workspace_bytes < s2r_workspace_bytes(n, d, w)) return S2R_ERR_WORKSPACE;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_need(n))
+    return S2R_ERR_WORKSPACE;
   if (((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) || ((uintptr_t)idx_out & 3u) ||
       ((uintptr_t)val_out & 3u) || ((uintptr_t)count_out & 7u) || ((uintptr_t)dense_out & 15u)) return S2R_ERR_ALIGN;
 
   hipStream_t st = (hipStream_t)stream;
   HashRows hp;
   make_hash_rows(seed, d, &hp);
+  const Workspace ws = carve(workspace, n);
+  const uint32_t ntiles = tiles_of(n);
+  const uint64_t nwords = ceil_div(n, 64);
+
+  hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
+                     bitmap, nwords, ntiles, ws.count);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, count_out);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+  if ((idx_out == nullptr || cap == 0) && dense_out == nullptr) return S2R_OK;   // only the count was asked for
 
   DecodeArgs A;
   A.sketch = sketch;
   A.bitmap = bitmap;
   A.n = n;
-  A.nwords = ceil_div(n, 64);
+  A.nwords = nwords;
   A.d = d;
   A.log2w = log2_of(w);
+  A.prefix = ws.prefix;
   A.idx_out = idx_out;
   A.val_out = val_out;
   A.cap = idx_out ? cap : 0;
-  A.count_out = count_out;
   A.dense_out = dense_out;
-  A.hdr = reinterpret_cast<WorkHeader*>(workspace);
-  A.status = reinterpret_cast<uint64_t*>((char*)workspace + kHeaderBytes);
-  A.ntiles = decode_tiles(n);
-
-  uint32_t pblocks = (uint32_t)(ceil_div(A.ntiles, kBlock) < 2048 ? ceil_div(A.ntiles, kBlock) : 2048);
-  hipLaunchKernelGGL(prep_kernel, dim3(pblocks), dim3(kBlock), 0, st, (uint4*)nullptr, (uint64_t)0, (float*)nullptr,
-                     0u, A.status, (uint64_t)A.ntiles, A.hdr, count_out);
-  if (launch_status() != S2R_OK) return S2R_ERR_LAUNCH;
 
   record(S2R_KERNEL_DECODE, false, st);
-  const dim3 grid(A.ntiles), block(kBlock);
+  const dim3 grid(ntiles);
   switch (d) {
-    case 1: hipLaunchKernelGGL(decode_kernel<1>, grid, block, 0, st, A, hp); break;
-    case 2: hipLaunchKernelGGL(decode_kernel<2>, grid, block, 0, st, A, hp); break;
-    case 3: hipLaunchKernelGGL(decode_kernel<3>, grid, block, 0, st, A, hp); break;
-    case 4: hipLaunchKernelGGL(decode_kernel<4>, grid, block, 0, st, A, hp); break;
-    case 5: hipLaunchKernelGGL(decode_kernel<5>, grid, block, 0, st, A, hp); break;
-    case 6: hipLaunchKernelGGL(decode_kernel<6>, grid, block, 0, st, A, hp); break;
-    case 7: hipLaunchKernelGGL(decode_kernel<7>, grid, block, 0, st, A, hp); break;
-    default: hipLaunchKernelGGL(decode_kernel<0>, grid, block, 0, st, A, hp); break;
+    case 1: launch_decode<1>(grid, st, A, hp); break;
+    case 2: launch_decode<2>(grid, st, A, hp); break;
+    case 3: launch_decode<3>(grid, st, A, hp); break;
+    case 4: launch_decode<4>(grid, st, A, hp); break;
+    case 5: launch_decode<5>(grid, st, A, hp); break;
+    case 6: launch_decode<6>(grid, st, A, hp); break;
+    case 7: launch_decode<7>(grid, st, A, hp); break;
+    case 8: launch_decode<8>(grid, st, A, hp); break;
+    case 9: launch_decode<9>(grid, st, A, hp); break;
+    case 10: launch_decode<10>(grid, st, A, hp); break;
+    case 11: launch_decode<11>(grid, st, A, hp); break;
+    case 12: launch_decode<12>(grid, st, A, hp); break;
+    case 13: launch_decode<13>(grid, st, A, hp); break;
+    case 14: launch_decode<14>(grid, st, A, hp); break;
+    case 15: launch_decode<15>(grid, st, A, hp); break;
+    default: launch_decode<16>(grid, st, A, hp); break;
   }
   record(S2R_KERNEL_DECODE, true, st);
-  return launch_status();
+  return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
 }  // extern "C"
