@@ -164,6 +164,23 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
                       void* stream);
 
 /*
+ * How s2r_encode carries out the insertion loops of Algorithm 1
+ * (S[j, h_j(i)] += s_j(i) g(i)); the result is the same sketch either way.
+ *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued
+ *                      from the dense scan (the sketch is zeroed first)
+ *   S2R_INSERT_SLICE   workgroups that each own a slice of one sketch row in
+ *                      LDS and read Sparse(g); needs nz_idx / nz_val (with NULL
+ *                      lists s2r_encode uses atomics whatever is set here)
+ *   S2R_INSERT_AUTO    (default) chosen from n, d, w and cap, the caller's bound
+ *                      on the number of non-zeros
+ * State is per host thread.  Returns S2R_ERR_SIZE for any other value.
+ */
+#define S2R_INSERT_AUTO   0
+#define S2R_INSERT_ATOMIC 1
+#define S2R_INSERT_SLICE  2
+s2r_status s2r_set_insert_strategy(int32_t strategy);
+
+/*
  * Instrumentation for benchmarks.  While a pair of hipEvent_t is installed for
  * a slot, the corresponding kernel launch made by the calling thread is
  * bracketed by hipEventRecord(begin) / hipEventRecord(end) on the launch
@@ -171,11 +188,13 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
  *   slot S2R_KERNEL_ENCODE_SCAN : the dense scan kernel of s2r_encode
  *   slot S2R_KERNEL_MERGE       : the kernel of s2r_merge
  *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel of s2r_decode
+ *   slot S2R_KERNEL_ENCODE_SLICE: the LDS-slice sketch kernel of s2r_encode
  */
-#define S2R_KERNEL_ENCODE_SCAN 0
-#define S2R_KERNEL_MERGE       1
-#define S2R_KERNEL_DECODE      2
-#define S2R_KERNEL_SLOTS       3
+#define S2R_KERNEL_ENCODE_SCAN  0
+#define S2R_KERNEL_MERGE        1
+#define S2R_KERNEL_DECODE       2
+#define S2R_KERNEL_ENCODE_SLICE 3
+#define S2R_KERNEL_SLOTS        4
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end);
 
 #ifdef __cplusplus

@@ -27,6 +27,10 @@ S2R_MAX_WORKERS = 64
 S2R_KERNEL_ENCODE_SCAN = 0
 S2R_KERNEL_MERGE = 1
 S2R_KERNEL_DECODE = 2
+S2R_KERNEL_ENCODE_SLICE = 3
+S2R_INSERT_AUTO = 0
+S2R_INSERT_ATOMIC = 1
+S2R_INSERT_SLICE = 2
 
 # every symbol include/s2r.h declares: name -> (restype, argtypes)
 SIGNATURES = {
@@ -44,6 +48,7 @@ SIGNATURES = {
                              c_void_p, c_void_p, c_uint64, c_void_p, c_void_p,
                              c_void_p, c_size_t, c_void_p]),
     "s2r_set_kernel_events": (c_int32, [c_int32, c_void_p, c_void_p]),
+    "s2r_set_insert_strategy": (c_int32, [c_int32]),
 }
 
 _lib = None
@@ -139,6 +144,13 @@ def decode(sketch, bitmap, n, d, w, seed, idx_out, val_out, count_out, dense_out
                            workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_decode")
+
+
+def set_insert_strategy(strategy: int):
+    """S2R_INSERT_AUTO / _ATOMIC / _SLICE for the calling thread's s2r_encode calls."""
+    st = load().s2r_set_insert_strategy(strategy)
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_set_insert_strategy")
 
 
 def set_kernel_events(slot: int, ev_begin, ev_end):

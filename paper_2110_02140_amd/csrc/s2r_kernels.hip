@@ -7,14 +7,23 @@
 // another workgroup: ascending index lists come from per-tile counts, a small
 // prefix kernel, and a second kernel that expands the bitmap at known offsets.
 //
-//   s2r_encode : zero_kernel           zero the sketch
+//   s2r_encode : zero_kernel           zero the tile counts (and the sketch when the
+//                                      insertions are atomics)
 //                encode_scan_kernel    the one pass over the dense gradient:
 //                                      bitmap words from wave ballots, per-tile
-//                                      non-zero counts, and the insertions
-//                                      S[j, h_j(i)] += s_j(i) g(i) as float32 atomics
+//                                      non-zero counts, and (INSERT variant) the
+//                                      insertions S[j, h_j(i)] += s_j(i) g(i) as
+//                                      float32 atomics
 //                tile_prefix_kernel    exclusive prefix of the tile counts, total
 //                encode_compact_kernel Sparse(g): expands the bitmap (n/8 bytes)
 //                                      and gathers the values at the set bits
+//                sketch_slice_kernel   (slice variant) every workgroup owns a slice
+//                                      of one sketch row in LDS, streams Sparse(g)
+//                                      and accumulates the items that hash into its
+//                                      slice, then stores the slice: no global
+//                                      atomics, no zeroing
+//                sketch_overflow_kernel (slice variant) inserts, with atomics, the
+//                                      non-zeros that did not fit the caller's list
 //   s2r_merge  : merge_kernel          S = sum_k S_k (ascending k), C = OR_k C_k
 //   s2r_decode : bitmap_count_kernel   per-tile popcounts of the aggregated bitmap
 //                tile_prefix_kernel
@@ -33,19 +42,28 @@ constexpr int kBlock = 256;                       // threads per workgroup (4 wa
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kTileWords = 512;                   // bitmap words per tile
 constexpr int kTileElems = kTileWords * 64;       // 32768 gradient elements per tile
-constexpr int kWordsPerWave = kTileWords / kWavesPerBlock;   // 128
 constexpr int kWordsPerThread = kTileWords / kBlock;         // 2
-constexpr int kScanEPL = 16;                      // dense scan: loads in flight per lane
+constexpr int kScanEPL = 8;                       // dense scan: bitmap words (loads in flight) per wave
+constexpr int kScanWords = kWavesPerBlock * kScanEPL;        // 32 words = 2048 elements per scan workgroup
+constexpr int kScansPerTile = kTileWords / kScanWords;       // 16
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
+constexpr int kPrefixPer = 32;                    // tile counts per thread per round
+constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice workgroup
+constexpr int kSliceLog2Max = 15;                 // at most 2^15 cells = 128 KiB of LDS per slice
+static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
 
 static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 // ------------------------------------------------------------------ zero
+// Zeroes nvec 16-byte units at p16 plus ntail floats at tail (the sketch; both may
+// be empty) and ncount tile counters.
 __global__ __launch_bounds__(kBlock) void zero_kernel(uint4* __restrict__ p16, uint64_t nvec,
-                                                      float* __restrict__ tail, uint32_t ntail) {
+                                                      float* __restrict__ tail, uint32_t ntail,
+                                                      uint32_t* __restrict__ count, uint32_t ncount) {
   const uint64_t tid = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
   for (uint64_t i = tid; i < nvec; i += stride) p16[i] = make_uint4(0u, 0u, 0u, 0u);
+  for (uint64_t i = tid; i < ncount; i += stride) count[i] = 0u;
   if (tid < ntail) tail[tid] = 0.0f;
 }
 
@@ -70,71 +88,68 @@ __device__ __forceinline__ void sketch_insert(const ScanArgs& A, const HashRows&
   }
 }
 
-// One workgroup per tile; wave q scans words [128q, 128q+128) of the tile, EPL
-// words (64*EPL elements) per iteration.  Lane l reads element 64k + l of the
-// iteration's chunk for k = 0..EPL-1: every load instruction is one coalesced
-// 256-byte row and its ballot is bitmap word k.  The words are parked one per
-// lane and leave as one coalesced 512-byte store per 64 words.
-template <int EPL>
+// One workgroup scans kScanWords bitmap words (2048 elements), each wave EPL of
+// them in one shot.  Lane l reads element 64k + l of the wave's chunk for
+// k = 0..EPL-1: every load instruction is one coalesced 256-byte row and its
+// ballot is bitmap word k.  Consecutive workgroups read consecutive 8 KiB, so the
+// workgroups resident at any time sweep one compact window of memory.  The
+// workgroup's non-zero count is added to its tile's counter (zeroed beforehand).
+template <int EPL, bool INSERT>
 __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const ScanArgs A, const HashRows hp) {
-  static_assert(kWave % EPL == 0 && kWordsPerWave % kWave == 0, "word parking assumes EPL | 64 | words per wave");
-  constexpr int kIters = kWordsPerWave / EPL;
   __shared__ uint32_t s_wave_count[kWavesPerBlock];
 
-  const uint32_t tile = blockIdx.x;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
-  const uint64_t wave_word0 = (uint64_t)tile * kTileWords + (uint64_t)wv * kWordsPerWave;
-  const bool full = ((uint64_t)tile + 1) * kTileElems <= A.n;    // uniform over the workgroup
+  const uint64_t word0 = (uint64_t)blockIdx.x * kScanWords + (uint64_t)wv * EPL;   // this wave's first word
+  const uint64_t e0 = word0 * 64;
 
-  uint32_t count = 0;          // non-zeros seen by this wave (uniform)
-  uint64_t parked = 0;         // lane l holds word (64*m + l) of the wave's range until stored
-#pragma unroll 2
-  for (int it = 0; it < kIters; ++it) {
-    const uint64_t e0 = (wave_word0 + (uint64_t)it * EPL) * 64;   // first element of the chunk
-    uint32_t v[EPL];
-    if (full) {
+  uint32_t v[EPL];
+  if (e0 + (uint64_t)EPL * kWave <= A.n) {               // uniform over the wave
 #pragma unroll
-      for (int k = 0; k < EPL; ++k) v[k] = __builtin_nontemporal_load(&A.grad[e0 + k * kWave + lane]);
-    } else {
-#pragma unroll
-      for (int k = 0; k < EPL; ++k) {
-        const uint64_t i = e0 + k * kWave + lane;
-        v[k] = i < A.n ? A.grad[i] : 0u;
-      }
-    }
+    for (int k = 0; k < EPL; ++k) v[k] = __builtin_nontemporal_load(&A.grad[e0 + k * kWave + lane]);
+  } else {
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
-      const bool nz = (v[k] << 1) != 0u;                 // anything but +0.0 / -0.0
-      const uint64_t b = __ballot(nz);
-      if (lane == (uint32_t)((it * EPL + k) & (kWave - 1))) parked = b;
-      if (b != 0) {                                      // uniform: most words are empty
-        count += (uint32_t)__popcll(b);
-        if (nz) sketch_insert(A, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
-      }
-    }
-    if (((it + 1) * EPL) % kWave == 0) {                 // 64 words parked: store them
-      const uint64_t w = wave_word0 + (uint64_t)((it + 1) * EPL - kWave) + lane;
-      if (w < A.nwords) A.bitmap[w] = parked;
+      const uint64_t i = e0 + k * kWave + lane;
+      v[k] = i < A.n ? A.grad[i] : 0u;
     }
   }
+
+  uint32_t count = 0;          // non-zeros seen by this wave (uniform)
+  uint64_t parked = 0;         // lane k keeps word k until the store below
+#pragma unroll
+  for (int k = 0; k < EPL; ++k) {
+    const bool nz = (v[k] << 1) != 0u;                   // anything but +0.0 / -0.0
+    const uint64_t b = __ballot(nz);
+    if (lane == (uint32_t)k) parked = b;
+    if (b != 0) {                                        // uniform: most words are empty
+      count += (uint32_t)__popcll(b);
+      if (INSERT && nz) sketch_insert(A, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
+    }
+  }
+  if (lane < (uint32_t)EPL && word0 + lane < A.nwords) A.bitmap[word0 + lane] = parked;
+
   if (lane == 0) s_wave_count[wv] = count;
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t t = 0;
 #pragma unroll
     for (int q = 0; q < kWavesPerBlock; ++q) t += s_wave_count[q];
-    A.tile_count[tile] = t;
+    if (t != 0) atomicAdd(&A.tile_count[blockIdx.x / kScansPerTile], t);
   }
 }
 
 // ------------------------------------------------------------------ per-tile popcounts (decode)
 // One wave per tile: lane l reads words l, l+64, ... of the tile.
 __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
-                                                              uint32_t ntiles, uint32_t* __restrict__ tile_count) {
+                                                              uint32_t ntiles, uint32_t padded_tiles,
+                                                              uint32_t* __restrict__ tile_count) {
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t tile = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  if (tile >= ntiles) return;
+  if (tile >= ntiles) {        // counters up to the next multiple of kPrefixPer are read by the prefix kernel
+    if (lane == 0 && tile < padded_tiles) tile_count[tile] = 0u;
+    return;
+  }
   const uint64_t w0 = (uint64_t)tile * kTileWords;
   uint32_t c = 0;
 #pragma unroll
@@ -148,29 +163,38 @@ __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __
 
 // ------------------------------------------------------------------ prefix of the tile counts
 // Single workgroup.  prefix[t] = sum of count[0..t), prefix[ntiles] = total, also
-// written to *total_out.  At most 2^17 tiles (n <= 2^32), 4 per thread per round.
+// written to *total_out.  Thread t of a round owns kPrefixPer consecutive counts
+// (128 contiguous bytes, loaded as eight 16-byte vectors that are all in flight
+// together); count[] is readable and zero up to the next multiple of kPrefixPer.
+// n <= 2^32 gives at most 2^17 tiles: four rounds.
 __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_t* __restrict__ count, uint32_t ntiles,
                                                                    uint64_t* __restrict__ prefix,
                                                                    uint64_t* __restrict__ total_out) {
-  constexpr int kPer = 4;
   constexpr int kWaves = kPrefixBlock / kWave;
   __shared__ uint32_t s_wave[kWaves];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
   uint64_t carry = 0;
-  for (uint32_t base = 0; base < ntiles; base += kPrefixBlock * kPer) {
-    const uint32_t i0 = base + threadIdx.x * kPer;
-    uint32_t c[kPer];
+  for (uint32_t base = 0; base < ntiles; base += kPrefixBlock * kPrefixPer) {
+    const uint32_t i0 = base + threadIdx.x * kPrefixPer;
+    uint32_t c[kPrefixPer];
     uint32_t mine = 0;
+    if (i0 < ntiles) {
 #pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-      c[q] = i0 + q < ntiles ? count[i0 + q] : 0u;
-      mine += c[q];
+      for (int q = 0; q < kPrefixPer / 4; ++q) {
+        const uint4 x = reinterpret_cast<const uint4*>(count + i0)[q];
+        c[4 * q + 0] = x.x; c[4 * q + 1] = x.y; c[4 * q + 2] = x.z; c[4 * q + 3] = x.w;
+      }
+#pragma unroll
+      for (int q = 0; q < kPrefixPer; ++q) mine += c[q];
+    } else {
+#pragma unroll
+      for (int q = 0; q < kPrefixPer; ++q) c[q] = 0u;
     }
     const uint32_t incl = wave_inclusive_scan_u32(mine, lane);
     if (lane == kWave - 1) s_wave[wv] = incl;
     __syncthreads();
-    uint32_t wave_off = 0, round_total = 0;
+    uint64_t wave_off = 0, round_total = 0;        // a round can hold 2^15 tiles of 2^15 non-zeros
 #pragma unroll
     for (int q = 0; q < kWaves; ++q) {
       const uint32_t x = s_wave[q];
@@ -179,7 +203,7 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_
     }
     uint64_t run = carry + wave_off + (incl - mine);
 #pragma unroll
-    for (int q = 0; q < kPer; ++q) {
+    for (int q = 0; q < kPrefixPer; ++q) {
       if (i0 + q < ntiles) prefix[i0 + q] = run;
       run += c[q];
     }
@@ -269,6 +293,114 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArg
     const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
     A.nz_idx[pos] = i;
     A.nz_val[pos] = A.grad[i];
+  }
+}
+
+// ------------------------------------------------------------------ encode: sketch by LDS slices
+// Workgroup (j, s) owns cells [s * 2^slice_log2, (s+1) * 2^slice_log2) of sketch
+// row j in LDS.  It streams the whole index list (coalesced, cache resident: every
+// slice of every row reads the same list), keeps the items whose bucket falls in
+// its slice, accumulates them with LDS atomics and finally stores the slice.  Each
+// cell of the sketch is written exactly once, by plain coalesced stores.
+struct SliceArgs {
+  const uint32_t* nz_idx;
+  const uint32_t* nz_val;    // float bit patterns
+  const uint64_t* nnz;       // device: true number of non-zeros
+  uint64_t cap;              // entries of the lists that exist
+  float* sketch;
+  uint32_t log2w;
+  uint32_t slice_log2;       // log2 of cells per slice (<= log2w)
+};
+
+__device__ __forceinline__ void slice_accumulate(float* s_slice, const SliceArgs& A, uint32_t s, uint32_t mask,
+                                                 uint64_t a, uint64_t b, uint64_t c, uint64_t e, uint32_t i, uint64_t t) {
+  const uint32_t h = bucket_of(i, a, b, A.log2w);
+  if ((h >> A.slice_log2) == s) {
+    const uint32_t sv = A.nz_val[t] ^ signbit_of(i, c, e);
+    __hip_atomic_fetch_add(&s_slice[h & mask], __uint_as_float(sv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+}
+
+__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const SliceArgs A, const HashRows hp) {
+  extern __shared__ float s_slice[];
+  constexpr int kVecs = 8;                                     // 16-byte index loads in flight per thread
+  const uint32_t spr_log2 = A.log2w - A.slice_log2;            // log2 of slices per row
+  const uint32_t j = blockIdx.x >> spr_log2;
+  const uint32_t s = blockIdx.x & ((1u << spr_log2) - 1u);
+  const uint32_t cells = 1u << A.slice_log2;
+  for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0f;
+  __syncthreads();
+
+  const uint64_t have = *A.nnz < A.cap ? *A.nnz : A.cap;
+  const uint64_t a = hp.a[j], b = hp.b[j], cc = hp.c[j], e = hp.e[j];
+  const uint32_t mask = cells - 1u;
+
+  // items before the first 16-byte boundary of the index list, then whole vectors, then the rest
+  uint64_t head = ((16u - (uint32_t)((uintptr_t)A.nz_idx & 15u)) & 15u) / 4u;
+  if (head > have) head = have;
+  if (threadIdx.x < head) slice_accumulate(s_slice, A, s, mask, a, b, cc, e, A.nz_idx[threadIdx.x], threadIdx.x);
+  const uint4* idx4 = reinterpret_cast<const uint4*>(A.nz_idx + head);
+  const uint64_t nvec = (have - head) / 4;
+  for (uint64_t q0 = threadIdx.x; q0 < nvec; q0 += (uint64_t)kSliceBlock * kVecs) {
+    // three phases so that the loads of each phase are all in flight together:
+    // indices; buckets and the values of the items that fall in this slice; LDS adds
+    uint4 x[kVecs];
+#pragma unroll
+    for (int u = 0; u < kVecs; ++u) {
+      const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
+      x[u] = q < nvec ? idx4[q] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    uint32_t cell[kVecs * 4];       // cell within the slice, or ~0u when the item is not ours
+    uint32_t val[kVecs * 4];
+#pragma unroll
+    for (int u = 0; u < kVecs; ++u) {
+      const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
+      const uint32_t i4[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t h = bucket_of(i4[r], a, b, A.log2w);
+        const bool ours = q < nvec && (h >> A.slice_log2) == s;
+        cell[4 * u + r] = ours ? (h & mask) : ~0u;
+        val[4 * u + r] = ours ? A.nz_val[head + q * 4 + r] ^ signbit_of(i4[r], cc, e) : 0u;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kVecs * 4; ++k) {
+      if (cell[k] != ~0u)
+        __hip_atomic_fetch_add(&s_slice[cell[k]], __uint_as_float(val[k]), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+  }
+  const uint64_t t_tail = head + nvec * 4 + threadIdx.x;
+  if (t_tail < have) slice_accumulate(s_slice, A, s, mask, a, b, cc, e, A.nz_idx[t_tail], t_tail);
+
+  __syncthreads();
+  float* out = A.sketch + ((uint64_t)j << A.log2w) + ((uint64_t)s << A.slice_log2);
+  for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = s_slice[c];
+}
+
+// Non-zeros at list positions >= cap are not in the caller's lists; this kernel
+// finds them in the bitmap and inserts them with atomics after the slices were
+// stored, so the sketch is complete whatever cap is.  Tiles that lie entirely
+// below cap (all of them, normally) leave at once.
+struct OverflowArgs {
+  ScanArgs scan;
+  const uint64_t* prefix;    // [ntiles + 1]
+  uint64_t cap;
+};
+
+__global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const OverflowArgs A, const HashRows hp) {
+  __shared__ TileBits T;
+  const uint32_t tile = blockIdx.x;
+  const uint64_t base = A.prefix[tile];
+  const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
+  if (base + total <= A.cap) return;               // uniform over the workgroup
+  const uint64_t word0 = (uint64_t)tile * kTileWords;
+  load_tile_bits(T, A.scan.bitmap, A.scan.nwords, word0);
+  const uint32_t first = base >= A.cap ? 0u : (uint32_t)(A.cap - base);
+  for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
+    const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
+    sketch_insert(A.scan, hp, i, A.scan.grad[i]);
   }
 }
 
@@ -395,6 +527,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
 // ------------------------------------------------------------------ host side
 struct EventPair { hipEvent_t begin, end; };
 static thread_local EventPair g_events[S2R_KERNEL_SLOTS] = {};
+static thread_local int32_t g_strategy = S2R_INSERT_AUTO;
 
 static inline uint64_t splitmix_next(uint64_t& state) {
   state += 0x9E3779B97F4A7C15ull;
@@ -439,15 +572,34 @@ struct Workspace {
   uint32_t* count;
   uint64_t* prefix;
 };
+static inline uint32_t padded_tiles_of(uint64_t n) {      // the prefix kernel reads whole groups of kPrefixPer
+  return (uint32_t)(ceil_div(tiles_of(n), kPrefixPer) * kPrefixPer);
+}
 static inline size_t workspace_need(uint64_t n) {
-  const size_t t = tiles_of(n);
-  return align256(t * sizeof(uint32_t)) + align256((t + 1) * sizeof(uint64_t));
+  return align256((size_t)padded_tiles_of(n) * sizeof(uint32_t)) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
 }
 static inline Workspace carve(void* ws, uint64_t n) {
   Workspace w;
   w.count = reinterpret_cast<uint32_t*>(ws);
-  w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)tiles_of(n) * sizeof(uint32_t)));
+  w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)padded_tiles_of(n) * sizeof(uint32_t)));
   return w;
+}
+
+// How s2r_encode forms the sketch.  Measured on MI355X: scattered float32 atomics
+// retire at about 21e9 per second over the whole chip whatever their scope, and
+// cost little extra while they hide under the dense read; a slice workgroup
+// filters about 3.5e9 list items per second, and (d*w / slice cells) of them run
+// at most 256 at a time.  `cap` is the caller's bound on the number of non-zeros.
+static int32_t choose_strategy(uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap) {
+  (void)n;
+  if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice kernel reads Sparse(g)
+  if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
+  const uint32_t log2w = log2_of(w);
+  const uint32_t slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+  const double slices = (double)d * (double)(1u << (log2w - slice_log2));
+  const double t_slice = (double)ceil_div((uint64_t)slices, 256) * (double)cap / 3.5e9;
+  const double t_atomic = (double)cap * d / 21.0e9;
+  return t_slice < t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
 }
 
 static inline void record(int slot, bool end, hipStream_t st) {
@@ -502,6 +654,12 @@ s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out) {
   return S2R_OK;
 }
 
+s2r_status s2r_set_insert_strategy(int32_t strategy) {
+  if (strategy != S2R_INSERT_AUTO && strategy != S2R_INSERT_ATOMIC && strategy != S2R_INSERT_SLICE) return S2R_ERR_SIZE;
+  g_strategy = strategy;
+  return S2R_OK;
+}
+
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
   if (slot < 0 || slot >= S2R_KERNEL_SLOTS) return S2R_ERR_SIZE;
   if ((ev_begin == nullptr) != (ev_end == nullptr)) return S2R_ERR_NULL;
@@ -528,13 +686,18 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   const Workspace ws = carve(workspace, n);
   const uint32_t ntiles = tiles_of(n);
 
+  const int32_t strategy = choose_strategy(n, d, w, nz_idx != nullptr, cap);
+  const uint32_t log2w = log2_of(w);
+
+  // tile counters, and the sketch when the scan inserts into it with atomics
   const uint64_t cells = (uint64_t)d * w;
-  const uint64_t nvec = cells / 4;
-  const uint32_t ntail = (uint32_t)(cells - nvec * 4);
-  uint64_t zb = ceil_div(nvec > 0 ? nvec : 1, kBlock);
+  const uint64_t nvec = strategy == S2R_INSERT_ATOMIC ? cells / 4 : 0;
+  const uint32_t ntail = strategy == S2R_INSERT_ATOMIC ? (uint32_t)(cells - nvec * 4) : 0u;
+  const uint32_t ncount = padded_tiles_of(n);
+  uint64_t zb = ceil_div(nvec > ncount ? nvec : ncount, kBlock);
   if (zb > 2048) zb = 2048;
   hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb), dim3(kBlock), 0, st, reinterpret_cast<uint4*>(sketch), nvec,
-                     sketch + nvec * 4, ntail);
+                     sketch + nvec * 4, ntail, ws.count, ncount);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
   ScanArgs S;
@@ -542,12 +705,16 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   S.n = n;
   S.nwords = ceil_div(n, 64);
   S.d = d;
-  S.log2w = log2_of(w);
+  S.log2w = log2w;
   S.sketch = sketch;
   S.bitmap = bitmap;
   S.tile_count = ws.count;
+  const dim3 scan_grid((uint32_t)ceil_div(S.nwords, kScanWords));
   record(S2R_KERNEL_ENCODE_SCAN, false, st);
-  hipLaunchKernelGGL(encode_scan_kernel<kScanEPL>, dim3(ntiles), dim3(kBlock), 0, st, S, hp);
+  if (strategy == S2R_INSERT_ATOMIC)
+    hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true>), scan_grid, dim3(kBlock), 0, st, S, hp);
+  else
+    hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false>), scan_grid, dim3(kBlock), 0, st, S, hp);
   record(S2R_KERNEL_ENCODE_SCAN, true, st);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
@@ -564,6 +731,37 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
     C.nz_val = reinterpret_cast<uint32_t*>(nz_val);
     C.cap = cap;
     hipLaunchKernelGGL(encode_compact_kernel, dim3(ntiles), dim3(kBlock), 0, st, C);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+
+  if (strategy == S2R_INSERT_SLICE) {
+    SliceArgs L;
+    L.nz_idx = nz_idx;
+    L.nz_val = reinterpret_cast<const uint32_t*>(nz_val);
+    L.nnz = nnz_out;
+    L.cap = cap;
+    L.sketch = sketch;
+    L.log2w = log2w;
+    L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+    const size_t lds = sizeof(float) << L.slice_log2;
+    static thread_local bool lds_raised = false;
+    if (!lds_raised) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(sizeof(float) << kSliceLog2Max)) != hipSuccess) return S2R_ERR_LAUNCH;
+      lds_raised = true;
+    }
+    const uint32_t slices = d << (log2w - L.slice_log2);
+    record(S2R_KERNEL_ENCODE_SLICE, false, st);
+    hipLaunchKernelGGL(sketch_slice_kernel, dim3(slices), dim3(kSliceBlock), lds, st, L, hp);
+    record(S2R_KERNEL_ENCODE_SLICE, true, st);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+
+    OverflowArgs O;
+    O.scan = S;
+    O.prefix = ws.prefix;
+    O.cap = cap;
+    hipLaunchKernelGGL(sketch_overflow_kernel, dim3(ntiles), dim3(kBlock), 0, st, O, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
   return S2R_OK;
@@ -625,8 +823,9 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   const uint32_t ntiles = tiles_of(n);
   const uint64_t nwords = ceil_div(n, 64);
 
-  hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
-                     bitmap, nwords, ntiles, ws.count);
+  const uint32_t padded = padded_tiles_of(n);
+  hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(padded, kWavesPerBlock)), dim3(kBlock), 0, st,
+                     bitmap, nwords, ntiles, padded, ws.count);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;

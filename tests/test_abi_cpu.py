@@ -109,6 +109,13 @@ def test_merge_and_decode_reject_bad_arguments():
     assert dec(wsb=0) == b.S2R_ERR_WORKSPACE
 
 
+def test_set_insert_strategy_argument_checks():
+    assert b.load().s2r_set_insert_strategy(3) == b.S2R_ERR_SIZE
+    assert b.load().s2r_set_insert_strategy(-1) == b.S2R_ERR_SIZE
+    for st in (b.S2R_INSERT_SLICE, b.S2R_INSERT_ATOMIC, b.S2R_INSERT_AUTO):
+        assert b.load().s2r_set_insert_strategy(st) == b.S2R_OK
+
+
 def test_set_kernel_events_argument_checks():
     assert b.load().s2r_set_kernel_events(7, None, None) == b.S2R_ERR_SIZE
     assert b.load().s2r_set_kernel_events(0, 0x10, None) == b.S2R_ERR_NULL

@@ -19,6 +19,16 @@ from paper_2110_02140_amd import binding, pipeline, workloads
 
 pytestmark = pytest.mark.gpu
 
+STRATEGIES = {"auto": binding.S2R_INSERT_AUTO, "atomic": binding.S2R_INSERT_ATOMIC, "slice": binding.S2R_INSERT_SLICE}
+
+
+@pytest.fixture(params=["atomic", "slice"])
+def strategy(request):
+    """Run the test once per way of forming the sketch in s2r_encode."""
+    binding.set_insert_strategy(STRATEGIES[request.param])
+    yield request.param
+    binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+
 REL = 1e-5
 DENORM_SLACK = 64 * float(np.finfo(np.float32).tiny)
 
@@ -73,16 +83,16 @@ def _run_and_check(wl, dense_out=False):
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
-def test_small_recipes_match_oracle(cfg):
+def test_small_recipes_match_oracle(cfg, strategy):
     _run_and_check(workloads.make_small(cfg), dense_out=True)
 
 
-def test_recipe1_full_size():
+def test_recipe1_full_size(strategy):
     _run_and_check(workloads.make(1), dense_out=True)
 
 
 @pytest.mark.parametrize("cfg", [2, 3, 4])
-def test_full_size_recipes_match_oracle(cfg):
+def test_full_size_recipes_match_oracle(cfg, strategy):
     _run_and_check(workloads.make(cfg))
 
 
@@ -95,7 +105,7 @@ def _custom(n, idx, val, d=3, w=64, W=1, seed=0):
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 2047, 2048, 2049, 4096 + 64, 32768, 32769, 100003])
-def test_ragged_lengths_dense_gradient(n):
+def test_ragged_lengths_dense_gradient(n, strategy):
     """Every element non-zero: maximal counts, every tile boundary crossed."""
     rng = np.random.default_rng(n)
     idx = [np.arange(n)]
@@ -103,7 +113,7 @@ def test_ragged_lengths_dense_gradient(n):
     _run_and_check(_custom(n, idx, val, d=3, w=1 << 8), dense_out=True)
 
 
-def test_all_zero_gradient():
+def test_all_zero_gradient(strategy):
     wl = _custom(5000, [np.empty(0, dtype=np.uint32)] * 2, [np.empty(0, dtype=np.float32)] * 2, W=2)
     b, dec = _run_and_check(wl, dense_out=True)
     assert int(b.out_count.cpu()[0]) == 0 and not b.sketch_sum.cpu().numpy().any()
@@ -130,7 +140,7 @@ def test_special_values_follow_the_bit_pattern_rule():
 
 
 @pytest.mark.parametrize("d,w", [(1, 1), (1, 64), (2, 2), (4, 128), (5, 1 << 12), (6, 32), (7, 64), (8, 64), (16, 16)])
-def test_rows_and_widths(d, w):
+def test_rows_and_widths(d, w, strategy):
     rng = np.random.default_rng(d * 1000 + w)
     n, W = 20011, 3
     idx = [np.sort(rng.choice(n, 700, replace=False)) for _ in range(W)]
@@ -138,7 +148,7 @@ def test_rows_and_widths(d, w):
     _run_and_check(_custom(n, idx, val, d=d, w=w, W=W, seed=d), dense_out=True)
 
 
-def test_capacity_overflow_reports_true_count_and_keeps_prefix():
+def test_capacity_overflow_reports_true_count_and_keeps_prefix(strategy):
     rng = np.random.default_rng(77)
     n = 50000
     idx = np.sort(rng.choice(n, 3000, replace=False))
@@ -173,7 +183,7 @@ def test_null_lists_and_in_place_merge():
     assert int(b.out_count.cpu()[0]) == len(dec["idx"])
 
 
-def test_linearity_on_device():
+def test_linearity_on_device(strategy):
     """Sum of the workers' sketches == sketch of the summed gradient."""
     wl = workloads.make_small(2)
     b = pipeline.buffers_for(wl)
@@ -208,3 +218,14 @@ def test_runs_are_repeatable_bit_exact_in_the_integer_outputs():
     for k, (a, c) in enumerate(zip(first[3], b.nz_idx)):
         m = int(b.nnz[k])
         assert torch.equal(a[:m], c[:m])
+
+
+def test_auto_strategy_matches_oracle_on_every_small_recipe():
+    binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+    for cfg in (1, 2, 3, 4, 5):
+        _run_and_check(workloads.make_small(cfg))
+
+
+def test_strategy_argument_check():
+    assert binding.load().s2r_set_insert_strategy(7) == binding.S2R_ERR_SIZE
+    assert binding.load().s2r_set_insert_strategy(binding.S2R_INSERT_AUTO) == binding.S2R_OK
