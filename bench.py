@@ -32,6 +32,9 @@ def parse_args():
                     help="which BASELINE config to time (default: the largest single-GPU one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=0, help="override the oracle sample length")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a kernel of known traffic, for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -127,6 +130,14 @@ def main():
     scan_ms = float(np.mean([e0.elapsed_ms(e1) for row in pairs for (e0, e1) in row]))
     merge_ms = float(np.mean([a.elapsed_ms(c) for a, c in phase["merge"]]))
     decode_ms = float(np.mean([a.elapsed_ms(c) for a, c in phase["decode"]]))
+
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=b.device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     nnz = b.nnz.cpu().numpy().astype(np.float64)
     union = int(b.out_count.cpu()[0])

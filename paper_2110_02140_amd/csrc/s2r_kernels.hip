@@ -52,6 +52,8 @@ constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice w
 constexpr int kSliceLog2Max = 15;                 // at most 2^15 cells = 128 KiB of LDS per slice
 static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));      // a 16-byte vector the nontemporal builtins accept
+
 static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 // ------------------------------------------------------------------ zero
@@ -142,14 +144,10 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const ScanArgs A, c
 // ------------------------------------------------------------------ per-tile popcounts (decode)
 // One wave per tile: lane l reads words l, l+64, ... of the tile.
 __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
-                                                              uint32_t ntiles, uint32_t padded_tiles,
-                                                              uint32_t* __restrict__ tile_count) {
+                                                              uint32_t ntiles, uint32_t* __restrict__ tile_count) {
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t tile = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  if (tile >= ntiles) {        // counters up to the next multiple of kPrefixPer are read by the prefix kernel
-    if (lane == 0 && tile < padded_tiles) tile_count[tile] = 0u;
-    return;
-  }
+  if (tile >= ntiles) return;
   const uint64_t w0 = (uint64_t)tile * kTileWords;
   uint32_t c = 0;
 #pragma unroll
@@ -163,52 +161,53 @@ __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __
 
 // ------------------------------------------------------------------ prefix of the tile counts
 // Single workgroup.  prefix[t] = sum of count[0..t), prefix[ntiles] = total, also
-// written to *total_out.  Thread t of a round owns kPrefixPer consecutive counts
-// (128 contiguous bytes, loaded as eight 16-byte vectors that are all in flight
-// together); count[] is readable and zero up to the next multiple of kPrefixPer.
-// n <= 2^32 gives at most 2^17 tiles: four rounds.
+// written to *total_out.  A round covers kPrefixPer rows of 1024 consecutive
+// counts; thread t owns column t of every row, so all loads and stores are
+// coalesced and the kPrefixPer loads of a thread are in flight together.  Each row
+// is scanned inside its waves, the 32 x 16 wave totals are scanned by wave 0, and
+// every element adds the offset of its (row, wave).  n <= 2^32 gives at most 2^17
+// tiles: four rounds.
 __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_t* __restrict__ count, uint32_t ntiles,
                                                                    uint64_t* __restrict__ prefix,
                                                                    uint64_t* __restrict__ total_out) {
-  constexpr int kWaves = kPrefixBlock / kWave;
-  __shared__ uint32_t s_wave[kWaves];
+  constexpr int kWaves = kPrefixBlock / kWave;               // 16
+  constexpr int kCells = kPrefixPer * kWaves;                // 512 (row, wave) totals per round
+  __shared__ uint32_t s_tot[kCells + 1];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
   uint64_t carry = 0;
   for (uint32_t base = 0; base < ntiles; base += kPrefixBlock * kPrefixPer) {
-    const uint32_t i0 = base + threadIdx.x * kPrefixPer;
-    uint32_t c[kPrefixPer];
-    uint32_t mine = 0;
-    if (i0 < ntiles) {
-#pragma unroll
-      for (int q = 0; q < kPrefixPer / 4; ++q) {
-        const uint4 x = reinterpret_cast<const uint4*>(count + i0)[q];
-        c[4 * q + 0] = x.x; c[4 * q + 1] = x.y; c[4 * q + 2] = x.z; c[4 * q + 3] = x.w;
-      }
-#pragma unroll
-      for (int q = 0; q < kPrefixPer; ++q) mine += c[q];
-    } else {
-#pragma unroll
-      for (int q = 0; q < kPrefixPer; ++q) c[q] = 0u;
-    }
-    const uint32_t incl = wave_inclusive_scan_u32(mine, lane);
-    if (lane == kWave - 1) s_wave[wv] = incl;
-    __syncthreads();
-    uint64_t wave_off = 0, round_total = 0;        // a round can hold 2^15 tiles of 2^15 non-zeros
-#pragma unroll
-    for (int q = 0; q < kWaves; ++q) {
-      const uint32_t x = s_wave[q];
-      if ((uint32_t)q < wv) wave_off += x;
-      round_total += x;
-    }
-    uint64_t run = carry + wave_off + (incl - mine);
+    uint32_t c[kPrefixPer], incl[kPrefixPer];
 #pragma unroll
     for (int q = 0; q < kPrefixPer; ++q) {
-      if (i0 + q < ntiles) prefix[i0 + q] = run;
-      run += c[q];
+      const uint32_t i = base + q * kPrefixBlock + threadIdx.x;
+      c[q] = i < ntiles ? count[i] : 0u;
     }
-    carry += round_total;
-    __syncthreads();               // s_wave is rewritten in the next round
+#pragma unroll
+    for (int q = 0; q < kPrefixPer; ++q) {
+      incl[q] = wave_inclusive_scan_u32(c[q], lane);
+      if (lane == kWave - 1) s_tot[q * kWaves + wv] = incl[q];
+    }
+    __syncthreads();
+    if (wv == 0) {             // exclusive scan of the 512 totals, 8 per lane; a round holds < 2^31 non-zeros
+      constexpr int kPerLane = kCells / kWave;
+      uint32_t t[kPerLane], sum = 0;
+#pragma unroll
+      for (int r = 0; r < kPerLane; ++r) { t[r] = s_tot[lane * kPerLane + r]; sum += t[r]; }
+      const uint32_t lane_incl = wave_inclusive_scan_u32(sum, lane);
+      uint32_t run = lane_incl - sum;
+#pragma unroll
+      for (int r = 0; r < kPerLane; ++r) { s_tot[lane * kPerLane + r] = run; run += t[r]; }
+      if (lane == kWave - 1) s_tot[kCells] = lane_incl;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kPrefixPer; ++q) {
+      const uint32_t i = base + q * kPrefixBlock + threadIdx.x;
+      if (i < ntiles) prefix[i] = carry + s_tot[q * kWaves + wv] + (incl[q] - c[q]);
+    }
+    carry += s_tot[kCells];
+    __syncthreads();               // s_tot is rewritten in the next round
   }
   if (threadIdx.x == 0) {
     prefix[ntiles] = carry;
@@ -217,26 +216,33 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_
 }
 
 // ------------------------------------------------------------------ bitmap tile in LDS
-// Loads the tile's words, leaves them in s_words and the exclusive prefix of
-// their popcounts in s_prefix (s_prefix[kTileWords] = tile total).  All threads
-// of the workgroup call it; it ends with a barrier.
+// read_tile_words issues the loads of the tile's words (two per thread);
+// scan_tile_words leaves them in T.words and the exclusive prefix of their
+// popcounts in T.prefix (T.prefix[kTileWords] = tile total).  All threads of the
+// workgroup call both; the second ends with a barrier.  They are separate so
+// that a kernel can have its other loads in flight together with the words'.
 struct TileBits {
   uint64_t words[kTileWords];
   uint32_t prefix[kTileWords + 1];
   uint32_t wave_count[kWavesPerBlock];
 };
 
-__device__ __forceinline__ void load_tile_bits(TileBits& T, const uint64_t* __restrict__ bitmap, uint64_t nwords,
-                                               uint64_t word0) {
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wv = threadIdx.x / kWave;
-  uint64_t wd[kWordsPerThread];
-  uint32_t pc[kWordsPerThread];
-  uint32_t cnt = 0;
+__device__ __forceinline__ void read_tile_words(uint64_t (&wd)[kWordsPerThread], const uint64_t* __restrict__ bitmap,
+                                                uint64_t nwords, uint64_t word0) {
 #pragma unroll
   for (int q = 0; q < kWordsPerThread; ++q) {        // thread t owns words 2t, 2t+1
     const uint64_t wi = word0 + (uint64_t)threadIdx.x * kWordsPerThread + q;
     wd[q] = wi < nwords ? bitmap[wi] : 0ull;
+  }
+}
+
+__device__ __forceinline__ void scan_tile_words(TileBits& T, const uint64_t (&wd)[kWordsPerThread]) {
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  uint32_t pc[kWordsPerThread];
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int q = 0; q < kWordsPerThread; ++q) {
     pc[q] = (uint32_t)__popcll(wd[q]);
     cnt += pc[q];
   }
@@ -282,11 +288,13 @@ struct CompactArgs {
 __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArgs A) {
   __shared__ TileBits T;
   const uint32_t tile = blockIdx.x;
+  const uint64_t word0 = (uint64_t)tile * kTileWords;
+  uint64_t wd[kWordsPerThread];
+  read_tile_words(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
   const uint64_t base = A.prefix[tile];
   const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
   if (total == 0 || base >= A.cap) return;         // uniform over the workgroup
-  const uint64_t word0 = (uint64_t)tile * kTileWords;
-  load_tile_bits(T, A.bitmap, A.nwords, word0);
+  scan_tile_words(T, wd);
   for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
     const uint64_t pos = base + t;
     if (pos >= A.cap) break;
@@ -396,7 +404,9 @@ __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const OverflowA
   const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
   if (base + total <= A.cap) return;               // uniform over the workgroup
   const uint64_t word0 = (uint64_t)tile * kTileWords;
-  load_tile_bits(T, A.scan.bitmap, A.scan.nwords, word0);
+  uint64_t wd[kWordsPerThread];
+  read_tile_words(wd, A.scan.bitmap, A.scan.nwords, word0);
+  scan_tile_words(T, wd);
   const uint32_t first = base >= A.cap ? 0u : (uint32_t)(A.cap - base);
   for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
     const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
@@ -417,30 +427,46 @@ struct MergeArgs {
   uint32_t sketch_blocks;   // blocks [0, sketch_blocks) sum the sketch, the rest OR the bitmap
 };
 
+// One thread per 16 bytes of sketch (blocks [0, sketch_blocks)) or per bitmap word
+// (the remaining blocks).  The W inputs of a position are independent streams:
+// they are read eight at a time so that eight loads are in flight per thread, and
+// added in ascending worker order.
 __global__ __launch_bounds__(kBlock) void merge_kernel(const MergeArgs A) {
+  constexpr uint32_t kDepth = 8;
   if (blockIdx.x < A.sketch_blocks) {
-    const uint64_t stride = (uint64_t)A.sketch_blocks * kBlock;
-    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < A.ncell4; i += stride) {
-      float4 acc = reinterpret_cast<const float4*>(A.sketch[0])[i];
-      for (uint32_t k = 1; k < A.W; ++k) {
-        const float4 x = reinterpret_cast<const float4*>(A.sketch[k])[i];
-        acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < A.ncell4) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (uint32_t k0 = 0; k0 < A.W; k0 += kDepth) {
+        f32x4 x[kDepth];
+#pragma unroll
+        for (uint32_t u = 0; u < kDepth; ++u)
+          if (k0 + u < A.W) x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(A.sketch[k0 + u]) + i);
+#pragma unroll
+        for (uint32_t u = 0; u < kDepth; ++u) {
+          if (k0 + u < A.W) acc = (k0 + u == 0) ? x[0] : acc + x[u];      // worker 0 starts the sum: no 0 + x
+        }
       }
-      reinterpret_cast<float4*>(A.sketch_out)[i] = acc;
+      reinterpret_cast<f32x4*>(A.sketch_out)[i] = acc;
     }
     // cells beyond the last full group of four (only when d*w is not a multiple of 4)
-    const uint64_t t = A.ncell4 * 4 + (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t t = A.ncell4 * 4 + i;
     if (t < A.ncells) {
       float acc = A.sketch[0][t];
       for (uint32_t k = 1; k < A.W; ++k) acc += A.sketch[k][t];
       A.sketch_out[t] = acc;
     }
   } else {
-    const uint64_t nb = gridDim.x - A.sketch_blocks;
-    const uint64_t stride = nb * kBlock;
-    for (uint64_t i = (uint64_t)(blockIdx.x - A.sketch_blocks) * kBlock + threadIdx.x; i < A.nwords; i += stride) {
-      uint64_t acc = A.bitmap[0][i];
-      for (uint32_t k = 1; k < A.W; ++k) acc |= A.bitmap[k][i];
+    const uint64_t i = (uint64_t)(blockIdx.x - A.sketch_blocks) * kBlock + threadIdx.x;
+    if (i < A.nwords) {
+      uint64_t acc = 0;
+      for (uint32_t k0 = 0; k0 < A.W; k0 += kDepth) {
+        uint64_t x[kDepth];
+#pragma unroll
+        for (uint32_t u = 0; u < kDepth; ++u) x[u] = k0 + u < A.W ? __builtin_nontemporal_load(A.bitmap[k0 + u] + i) : 0ull;
+#pragma unroll
+        for (uint32_t u = 0; u < kDepth; ++u) acc |= x[u];
+      }
       A.bitmap_out[i] = acc;
     }
   }
@@ -475,8 +501,8 @@ __device__ __forceinline__ float median_fixed(float (&x)[D]) {
       x[b + 1] = hi;
     }
   }
-  if (D & 1) return x[D / 2];
-  return 0.5f * (x[D / 2 - 1] + x[D / 2]);
+  if constexpr ((D & 1) != 0) return x[D / 2];
+  else return 0.5f * (x[D / 2 - 1] + x[D / 2]);
 }
 
 template <int D>
@@ -496,11 +522,13 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
   __shared__ TileBits T;
   const uint32_t tile = blockIdx.x;
   const uint64_t word0 = (uint64_t)tile * kTileWords;
+  uint64_t wd[kWordsPerThread];
+  read_tile_words(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
   const uint64_t base = A.prefix[tile];
   const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
 
   // dense output: this workgroup owns the tile's elements; clear them first, the
-  // estimates are written over the zeros after the barrier in load_tile_bits
+  // estimates are written over the zeros after the barrier in scan_tile_words
   if (A.dense_out != nullptr) {
     const uint64_t e0 = word0 * 64;
     const uint64_t e1 = min(A.n, e0 + (uint64_t)kTileElems);
@@ -511,7 +539,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
     if (r < e1) A.dense_out[r] = 0.0f;
   }
   if (total == 0) return;                          // uniform over the workgroup
-  load_tile_bits(T, A.bitmap, A.nwords, word0);
+  scan_tile_words(T, wd);
   for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
     const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
     const float g = query<D>(A, hp, i);
@@ -572,16 +600,13 @@ struct Workspace {
   uint32_t* count;
   uint64_t* prefix;
 };
-static inline uint32_t padded_tiles_of(uint64_t n) {      // the prefix kernel reads whole groups of kPrefixPer
-  return (uint32_t)(ceil_div(tiles_of(n), kPrefixPer) * kPrefixPer);
-}
 static inline size_t workspace_need(uint64_t n) {
-  return align256((size_t)padded_tiles_of(n) * sizeof(uint32_t)) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
+  return align256((size_t)tiles_of(n) * sizeof(uint32_t)) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
 }
 static inline Workspace carve(void* ws, uint64_t n) {
   Workspace w;
   w.count = reinterpret_cast<uint32_t*>(ws);
-  w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)padded_tiles_of(n) * sizeof(uint32_t)));
+  w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)tiles_of(n) * sizeof(uint32_t)));
   return w;
 }
 
@@ -693,7 +718,7 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   const uint64_t cells = (uint64_t)d * w;
   const uint64_t nvec = strategy == S2R_INSERT_ATOMIC ? cells / 4 : 0;
   const uint32_t ntail = strategy == S2R_INSERT_ATOMIC ? (uint32_t)(cells - nvec * 4) : 0u;
-  const uint32_t ncount = padded_tiles_of(n);
+  const uint32_t ncount = ntiles;
   uint64_t zb = ceil_div(nvec > ncount ? nvec : ncount, kBlock);
   if (zb > 2048) zb = 2048;
   hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb), dim3(kBlock), 0, st, reinterpret_cast<uint4*>(sketch), nvec,
@@ -791,11 +816,9 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
   A.ncell4 = A.ncells / 4;
   A.nwords = ceil_div(n, 64);
   A.W = W;
-  // one thread per 16 bytes of sketch / 8 bytes of bitmap, capped so that the grid stays a few waves deep
-  uint64_t sb = ceil_div(A.ncell4 > 0 ? A.ncell4 : 1, kBlock);
-  uint64_t bb = ceil_div(A.nwords, kBlock);
-  if (sb > 4096) sb = 4096;
-  if (bb > 4096) bb = 4096;
+  // one thread per 16 bytes of sketch / 8 bytes of bitmap (d*w <= 2^32 and n <= 2^32 keep the grid below 2^23)
+  const uint64_t sb = ceil_div(A.ncell4 > 0 ? A.ncell4 : 1, kBlock);
+  const uint64_t bb = ceil_div(A.nwords, kBlock);
   A.sketch_blocks = (uint32_t)sb;
   hipStream_t st = (hipStream_t)stream;
   record(S2R_KERNEL_MERGE, false, st);
@@ -823,9 +846,8 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   const uint32_t ntiles = tiles_of(n);
   const uint64_t nwords = ceil_div(n, 64);
 
-  const uint32_t padded = padded_tiles_of(n);
-  hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(padded, kWavesPerBlock)), dim3(kBlock), 0, st,
-                     bitmap, nwords, ntiles, padded, ws.count);
+  hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
+                     bitmap, nwords, ntiles, ws.count);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
