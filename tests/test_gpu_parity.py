@@ -229,3 +229,41 @@ def test_auto_strategy_matches_oracle_on_every_small_recipe():
 def test_strategy_argument_check():
     assert binding.load().s2r_set_insert_strategy(7) == binding.S2R_ERR_SIZE
     assert binding.load().s2r_set_insert_strategy(binding.S2R_INSERT_AUTO) == binding.S2R_OK
+
+
+def test_recipe5_full_size_in_the_benchmarked_configuration():
+    """The workload bench.py times (W=16, n=1e9, 64 GB of dense input), default
+    strategy: every worker's count, bitmap and index list; the sketches of the
+    first and last worker; the merged bitmap and sketch; every decoded index and
+    value."""
+    binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+    wl = workloads.make(5)
+    print(f"[case] {wl.name} full size", flush=True)
+    b = pipeline.buffers_for(wl)
+    b.step()
+    torch.cuda.synchronize()
+    nnz = b.nnz.cpu().numpy()
+    S = np.zeros((wl.d, wl.w))
+    M = np.zeros((wl.d, wl.w))
+    C = np.zeros((wl.n + 63) // 64, dtype=np.uint64)
+    for k in range(wl.W):
+        e = orc.encode_sparse(wl.idx[k], wl.val[k], wl.n, wl.d, wl.w, wl.seed)
+        assert nnz[k] == len(e["idx"]), f"worker {k} nnz"
+        assert np.array_equal(pipeline.u64(b.bitmap[k]), e["bitmap"]), f"worker {k} bitmap"
+        assert np.array_equal(b.nz_idx[k][: nnz[k]].cpu().numpy().view(np.uint32), e["idx"]), f"worker {k} idx"
+        assert np.array_equal(b.nz_val[k][: nnz[k]].cpu().numpy(), e["val"]), f"worker {k} val"
+        if k in (0, wl.W - 1):
+            _check_sketch(b.sketch[k].cpu().numpy(), e["S"], e["M"], f"worker {k} sketch")
+        S += e["S"]
+        M += e["M"]
+        C |= e["bitmap"]
+        print(f"  worker {k} ok", flush=True)
+    assert np.array_equal(pipeline.u64(b.bitmap_or), C), "merged bitmap"
+    _check_sketch(b.sketch_sum.cpu().numpy(), S, M, "merged sketch")
+    dec = orc.decode(S, C, wl.n, wl.seed)
+    cnt = int(b.out_count.cpu()[0])
+    assert cnt == len(dec["idx"])
+    assert np.array_equal(b.out_idx[:cnt].cpu().numpy().view(np.uint32), dec["idx"])
+    tol = REL * orc.decode_tolerance_mass(M, dec["idx"], wl.seed) + DENORM_SLACK
+    err = np.abs(b.out_val[:cnt].cpu().numpy().astype(np.float64) - dec["val"])
+    assert np.all(err <= tol), f"decoded values: worst {err.max():.3e}"
