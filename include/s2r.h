@@ -88,6 +88,12 @@ const char* s2r_status_string(s2r_status status);
  * larger of the two).  Host only; returns 0 for sizes outside the limits. */
 size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w);
 
+/* Bytes of device scratch with which s2r_encode can also use the LDS-slice
+ * strategy for lists of capacity cap (s2r_workspace_bytes plus d bytes per list
+ * entry).  With a smaller workspace (but at least s2r_workspace_bytes) it
+ * inserts with atomics.  Host only; returns 0 outside the limits or if cap > n. */
+size_t s2r_encode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
+
 /* The four hash parameters of each of the d rows, as the kernels use them:
  * params_out[4*j + 0..3] = a_j, b_j, c_j, e_j.  Host pointer, host only.
  * (Section 3.1 "hash function h", "random sign s"; the family is this
@@ -169,8 +175,9 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued
  *                      from the dense scan (the sketch is zeroed first)
  *   S2R_INSERT_SLICE   workgroups that each own a slice of one sketch row in
- *                      LDS and read Sparse(g); needs nz_idx / nz_val (with NULL
- *                      lists s2r_encode uses atomics whatever is set here)
+ *                      LDS and read Sparse(g); needs nz_idx / nz_val, a workspace
+ *                      of s2r_encode_workspace_bytes and w <= 2^23 (otherwise
+ *                      s2r_encode uses atomics whatever is set here)
  *   S2R_INSERT_AUTO    (default) chosen from n, d, w and cap, the caller's bound
  *                      on the number of non-zeros
  * State is per host thread.  Returns S2R_ERR_SIZE for any other value.

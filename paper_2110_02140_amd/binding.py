@@ -37,6 +37,7 @@ SIGNATURES = {
     "s2r_version": (c_int32, []),
     "s2r_status_string": (c_char_p, [c_int32]),
     "s2r_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32]),
+    "s2r_encode_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint64]),
     "s2r_hash_params": (c_int32, [c_uint64, c_uint32, ctypes.POINTER(c_uint64)]),
     "s2r_encode": (c_int32, [c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
                              c_void_p, c_void_p, c_void_p, c_void_p, c_uint64,
@@ -91,6 +92,10 @@ def version() -> int:
 
 def workspace_bytes(n: int, d: int, w: int) -> int:
     return load().s2r_workspace_bytes(n, d, w)
+
+
+def encode_workspace_bytes(n: int, d: int, w: int, cap: int) -> int:
+    return load().s2r_encode_workspace_bytes(n, d, w, cap)
 
 
 def hash_params(seed: int, d: int) -> list[tuple[int, int, int, int]]:

@@ -283,9 +283,16 @@ struct CompactArgs {
   uint32_t* nz_idx;
   uint32_t* nz_val;          // float bit patterns
   uint64_t cap;
+  // SLICE_IDS only: for every listed item and row j, the sketch slice h_j(i) >> slice_log2
+  uint8_t* slice_id;         // [d][sid_stride]
+  uint64_t sid_stride;
+  uint32_t d;
+  uint32_t log2w;
+  uint32_t slice_log2;
 };
 
-__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArgs A) {
+template <bool SLICE_IDS>
+__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArgs A, const HashRows hp) {
   __shared__ TileBits T;
   const uint32_t tile = blockIdx.x;
   const uint64_t word0 = (uint64_t)tile * kTileWords;
@@ -295,24 +302,56 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArg
   const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
   if (total == 0 || base >= A.cap) return;         // uniform over the workgroup
   scan_tile_words(T, wd);
-  for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
-    const uint64_t pos = base + t;
-    if (pos >= A.cap) break;
-    const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
-    A.nz_idx[pos] = i;
-    A.nz_val[pos] = A.grad[i];
+  // four output slots per thread and trip, so that the four value gathers are in flight together
+  constexpr int kSlots = 4;
+  for (uint32_t t0 = threadIdx.x; t0 < total; t0 += kBlock * kSlots) {
+    uint32_t i[kSlots], v[kSlots];
+    bool live[kSlots];
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      const uint32_t t = t0 + u * kBlock;
+      live[u] = t < total && base + t < A.cap;
+      i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) v[u] = live[u] ? A.grad[i[u]] : 0u;
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      if (!live[u]) continue;
+      const uint64_t pos = base + t0 + u * kBlock;
+      A.nz_idx[pos] = i[u];
+      A.nz_val[pos] = v[u];
+      if (SLICE_IDS) {
+        for (uint32_t j = 0; j < A.d; ++j)
+          A.slice_id[j * A.sid_stride + pos] = (uint8_t)(bucket_of(i[u], hp.a[j], hp.b[j], A.log2w) >> A.slice_log2);
+      }
+    }
   }
 }
 
 // ------------------------------------------------------------------ encode: sketch by LDS slices
 // Workgroup (j, s) owns cells [s * 2^slice_log2, (s+1) * 2^slice_log2) of sketch
-// row j in LDS.  It streams the whole index list (coalesced, cache resident: every
-// slice of every row reads the same list), keeps the items whose bucket falls in
-// its slice, accumulates them with LDS atomics and finally stores the slice.  Each
-// cell of the sketch is written exactly once, by plain coalesced stores.
+// row j in LDS.  It streams row j's slice ids (one byte per listed item, written
+// by the compaction kernel; 16 items per 16-byte load, cache resident because
+// every slice of the row reads the same bytes), and finds the items whose id is s
+// with a four-bytes-at-a-time equality test.  Matches are rare in a wave (one
+// item in slices-per-row), so they are not handled where they are found: each
+// wave pushes their list positions into a queue of its own in LDS and, when the
+// queue fills, drains it with all lanes busy: index and value loads, the bucket
+// and sign hashes, one LDS float add per item.  Finally the slice is stored: each
+// cell of the sketch is written exactly once, by plain coalesced stores, with no
+// global atomics and no zeroing of the sketch beforehand.
+constexpr int kQueue = 384;                          // queue entries per wave
+constexpr int kQueueBatches = kQueue / kWave;        // 6
+constexpr int kSliceWaves = kSliceBlock / kWave;     // 16
+constexpr size_t kSliceLdsMax = (sizeof(float) << kSliceLog2Max) + sizeof(uint32_t) * kQueue * kSliceWaves;
+static_assert(kSliceLdsMax <= 160 * 1024, "slice + queues must fit the 160 KiB of LDS of a CU");
+
 struct SliceArgs {
   const uint32_t* nz_idx;
   const uint32_t* nz_val;    // float bit patterns
+  const uint8_t* slice_id;   // [d][sid_stride], rows 16-byte aligned
+  uint64_t sid_stride;
   const uint64_t* nnz;       // device: true number of non-zeros
   uint64_t cap;              // entries of the lists that exist
   float* sketch;
@@ -320,67 +359,106 @@ struct SliceArgs {
   uint32_t slice_log2;       // log2 of cells per slice (<= log2w)
 };
 
-__device__ __forceinline__ void slice_accumulate(float* s_slice, const SliceArgs& A, uint32_t s, uint32_t mask,
-                                                 uint64_t a, uint64_t b, uint64_t c, uint64_t e, uint32_t i, uint64_t t) {
-  const uint32_t h = bucket_of(i, a, b, A.log2w);
-  if ((h >> A.slice_log2) == s) {
-    const uint32_t sv = A.nz_val[t] ^ signbit_of(i, c, e);
-    __hip_atomic_fetch_add(&s_slice[h & mask], __uint_as_float(sv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+struct SliceRow {            // what a drain needs, all uniform
+  const uint32_t* nz_idx;
+  const uint32_t* nz_val;
+  uint64_t a, b, c, e;
+  uint32_t log2w, mask;
+};
+
+__device__ __forceinline__ void drain_queue(float* s_slice, const uint32_t* queue, uint32_t qcount, uint32_t lane,
+                                            const SliceRow& R) {
+  __builtin_amdgcn_wave_barrier();                   // the pushes of this wave are in program order before the reads
+  uint32_t t[kQueueBatches], idx[kQueueBatches], val[kQueueBatches];
+#pragma unroll
+  for (int q = 0; q < kQueueBatches; ++q) t[q] = (uint32_t)q * kWave + lane < qcount ? queue[q * kWave + lane] : ~0u;
+#pragma unroll
+  for (int q = 0; q < kQueueBatches; ++q) {            // all loads of the drain in flight together
+    idx[q] = (uint32_t)q * kWave + lane < qcount ? R.nz_idx[t[q]] : 0u;
+    val[q] = (uint32_t)q * kWave + lane < qcount ? R.nz_val[t[q]] : 0u;
+  }
+#pragma unroll
+  for (int q = 0; q < kQueueBatches; ++q) {
+    if ((uint32_t)q * kWave + lane < qcount) {
+      const uint32_t h = bucket_of(idx[q], R.a, R.b, R.log2w);
+      const uint32_t sv = val[q] ^ signbit_of(idx[q], R.c, R.e);
+      __hip_atomic_fetch_add(&s_slice[h & R.mask], __uint_as_float(sv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
+// Pushes the list position `item` of every lane with has == true; drains when a
+// further push of 64 might not fit.  qcount is uniform over the wave.
+__device__ __forceinline__ void push_matches(float* s_slice, uint32_t* queue, uint32_t& qcount, uint32_t lane, bool has,
+                                             uint32_t item, const SliceRow& R) {
+  const uint64_t m = __ballot(has);
+  if (m == 0) return;
+  if (has) queue[qcount + bits_below_lane(m)] = item;
+  qcount += (uint32_t)__popcll(m);
+  if (qcount > (uint32_t)(kQueue - kWave)) {
+    drain_queue(s_slice, queue, qcount, lane, R);
+    qcount = 0;
   }
 }
 
 __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const SliceArgs A, const HashRows hp) {
   extern __shared__ float s_slice[];
-  constexpr int kVecs = 8;                                     // 16-byte index loads in flight per thread
-  const uint32_t spr_log2 = A.log2w - A.slice_log2;            // log2 of slices per row
+  constexpr int kVecs = 4;                                     // 16-byte id loads in flight per thread
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t spr_log2 = A.log2w - A.slice_log2;            // log2 of slices per row (<= 8)
   const uint32_t j = blockIdx.x >> spr_log2;
   const uint32_t s = blockIdx.x & ((1u << spr_log2) - 1u);
   const uint32_t cells = 1u << A.slice_log2;
+  uint32_t* queue = reinterpret_cast<uint32_t*>(s_slice + cells) + wv * kQueue;
   for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0f;
   __syncthreads();
 
   const uint64_t have = *A.nnz < A.cap ? *A.nnz : A.cap;
-  const uint64_t a = hp.a[j], b = hp.b[j], cc = hp.c[j], e = hp.e[j];
-  const uint32_t mask = cells - 1u;
+  SliceRow R;
+  R.nz_idx = A.nz_idx; R.nz_val = A.nz_val;
+  R.a = hp.a[j]; R.b = hp.b[j]; R.c = hp.c[j]; R.e = hp.e[j];
+  R.log2w = A.log2w; R.mask = cells - 1u;
+  const uint8_t* ids = A.slice_id + (uint64_t)j * A.sid_stride;
+  const uint32_t sb = s * 0x01010101u;                         // s in every byte
+  uint32_t qcount = 0;
 
-  // items before the first 16-byte boundary of the index list, then whole vectors, then the rest
-  uint64_t head = ((16u - (uint32_t)((uintptr_t)A.nz_idx & 15u)) & 15u) / 4u;
-  if (head > have) head = have;
-  if (threadIdx.x < head) slice_accumulate(s_slice, A, s, mask, a, b, cc, e, A.nz_idx[threadIdx.x], threadIdx.x);
-  const uint4* idx4 = reinterpret_cast<const uint4*>(A.nz_idx + head);
-  const uint64_t nvec = (have - head) / 4;
-  for (uint64_t q0 = threadIdx.x; q0 < nvec; q0 += (uint64_t)kSliceBlock * kVecs) {
-    // three phases so that the loads of each phase are all in flight together:
-    // indices; buckets and the values of the items that fall in this slice; LDS adds
+  const uint64_t nvec = have / 16;
+  const uint4* ids16 = reinterpret_cast<const uint4*>(ids);
+  // the loop variable is the wave's first vector, so the trip count is the same in
+  // all lanes of a wave and qcount stays uniform; lanes past the end read a filler
+  for (uint64_t qw = (uint64_t)wv * kWave; qw < nvec; qw += (uint64_t)kSliceBlock * kVecs) {
+    const uint64_t q0 = qw + lane;
     uint4 x[kVecs];
 #pragma unroll
     for (int u = 0; u < kVecs; ++u) {
       const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
-      x[u] = q < nvec ? idx4[q] : make_uint4(0u, 0u, 0u, 0u);
+      x[u] = q < nvec ? ids16[q] : make_uint4(~sb, ~sb, ~sb, ~sb);       // a filler that matches nothing
     }
-    uint32_t cell[kVecs * 4];       // cell within the slice, or ~0u when the item is not ours
-    uint32_t val[kVecs * 4];
 #pragma unroll
     for (int u = 0; u < kVecs; ++u) {
       const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
-      const uint32_t i4[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+      const uint32_t wds[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t h = bucket_of(i4[r], a, b, A.log2w);
-        const bool ours = q < nvec && (h >> A.slice_log2) == s;
-        cell[4 * u + r] = ours ? (h & mask) : ~0u;
-        val[4 * u + r] = ours ? A.nz_val[head + q * 4 + r] ^ signbit_of(i4[r], cc, e) : 0u;
+        const uint32_t v = wds[r] ^ sb;                       // a zero byte where the id equals s
+        uint32_t z = ~(((v & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | v | 0x7F7F7F7Fu);   // 0x80 in exactly those bytes
+        while (__ballot(z != 0) != 0) {                       // uniform; almost always 0 or 1 rounds
+          const bool has = z != 0;
+          const uint32_t byte = has ? ((uint32_t)__ffs((int)z) - 1u) >> 3 : 0u;
+          push_matches(s_slice, queue, qcount, lane, has, (uint32_t)(q * 16 + r * 4 + byte), R);
+          z &= z - 1u;
+        }
       }
     }
-#pragma unroll
-    for (int k = 0; k < kVecs * 4; ++k) {
-      if (cell[k] != ~0u)
-        __hip_atomic_fetch_add(&s_slice[cell[k]], __uint_as_float(val[k]), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
-    }
   }
-  const uint64_t t_tail = head + nvec * 4 + threadIdx.x;
-  if (t_tail < have) slice_accumulate(s_slice, A, s, mask, a, b, cc, e, A.nz_idx[t_tail], t_tail);
+  {                                                           // the last have % 16 items, one per thread
+    const uint64_t t = nvec * 16 + threadIdx.x;
+    const bool has = t < have && ids[t] == (uint8_t)s;
+    push_matches(s_slice, queue, qcount, lane, has, (uint32_t)t, R);
+  }
+  if (qcount != 0) drain_queue(s_slice, queue, qcount, lane, R);
 
   __syncthreads();
   float* out = A.sketch + ((uint64_t)j << A.log2w) + ((uint64_t)s << A.slice_log2);
@@ -595,35 +673,53 @@ static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
 
 static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kTileWords); }
 
-// workspace: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]], each part 256-byte aligned
+// workspace: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]] [slice ids u8[d][stride]], each part
+// 256-byte aligned; the slice ids exist only when the caller's workspace is large enough for its cap
 struct Workspace {
   uint32_t* count;
   uint64_t* prefix;
+  uint8_t* slice_id;
+  uint64_t sid_stride;
 };
-static inline size_t workspace_need(uint64_t n) {
+static inline size_t workspace_base(uint64_t n) {
   return align256((size_t)tiles_of(n) * sizeof(uint32_t)) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
 }
-static inline Workspace carve(void* ws, uint64_t n) {
+static inline uint64_t sid_stride_of(uint64_t cap) { return (cap + 255) & ~(uint64_t)255; }
+static inline size_t workspace_with_ids(uint64_t n, uint32_t d, uint64_t cap) {
+  return workspace_base(n) + (size_t)d * sid_stride_of(cap);
+}
+static inline Workspace carve(void* ws, uint64_t n, uint64_t cap) {
   Workspace w;
   w.count = reinterpret_cast<uint32_t*>(ws);
   w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)tiles_of(n) * sizeof(uint32_t)));
+  w.slice_id = reinterpret_cast<uint8_t*>((char*)ws + workspace_base(n));
+  w.sid_stride = sid_stride_of(cap);
   return w;
 }
 
-// How s2r_encode forms the sketch.  Measured on MI355X: scattered float32 atomics
-// retire at about 21e9 per second over the whole chip whatever their scope, and
-// cost little extra while they hide under the dense read; a slice workgroup
-// filters about 3.5e9 list items per second, and (d*w / slice cells) of them run
-// at most 256 at a time.  `cap` is the caller's bound on the number of non-zeros.
-static int32_t choose_strategy(uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap) {
-  (void)n;
+// How s2r_encode forms the sketch.  Cost models from measurements on MI355X:
+//  - scattered float32 atomics retire at about 21e9 per second over the whole chip
+//    whatever their scope; issued from the dense scan, about half of the scan's own
+//    time hides them (when the non-zeros are spread over many workgroups);
+//  - a slice workgroup costs about 15 us (clearing and storing 128 KiB of LDS) plus
+//    its share of the list at 16e9 items per second, plus about 3 us per queue drain
+//    of a wave; (d*w / slice cells) workgroups run at most 256 at a time; the slice
+//    ids and the overflow pass add about 10 us.
+// `cap` is the caller's bound on the number of non-zeros.
+static int32_t choose_strategy(uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap, size_t workspace_bytes) {
   if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice kernel reads Sparse(g)
-  if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
   const uint32_t log2w = log2_of(w);
   const uint32_t slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
-  const double slices = (double)d * (double)(1u << (log2w - slice_log2));
-  const double t_slice = (double)ceil_div((uint64_t)slices, 256) * (double)cap / 3.5e9;
-  const double t_atomic = (double)cap * d / 21.0e9;
+  if (log2w - slice_log2 > 8) return S2R_INSERT_ATOMIC;      // a slice id is one byte
+  if (workspace_bytes < workspace_with_ids(n, d, cap)) return S2R_INSERT_ATOMIC;
+  if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
+  const double per_row = (double)(1u << (log2w - slice_log2));
+  const double rounds = (double)ceil_div((uint64_t)(d * per_row), 256);
+  const double drains = (double)cap / per_row / kSliceWaves / (kQueue - kWave);
+  const double t_slice = rounds * (15e-6 + (double)cap / 16e9 + drains * 3e-6) + 10e-6;
+  const double t_stream = 4.0 * (double)n / 6.0e12;
+  double t_atomic = (double)cap * d / 21.0e9 - 0.5 * t_stream;
+  if (t_atomic < 0) t_atomic = 0;
   return t_slice < t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
 }
 
@@ -662,7 +758,12 @@ const char* s2r_status_string(s2r_status status) {
 
 size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w) {
   if (check_sizes(n, d, w) != S2R_OK) return 0;
-  return workspace_need(n);
+  return workspace_base(n);
+}
+
+size_t s2r_encode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
+  if (check_sizes(n, d, w) != S2R_OK || cap > n) return 0;
+  return workspace_with_ids(n, d, cap);
 }
 
 s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out) {
@@ -700,7 +801,7 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_need(n))
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_base(n))
     return S2R_ERR_WORKSPACE;
   if (((uintptr_t)grad & 3u) || ((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) ||
       ((uintptr_t)nz_idx & 3u) || ((uintptr_t)nz_val & 3u) || ((uintptr_t)nnz_out & 7u)) return S2R_ERR_ALIGN;
@@ -708,10 +809,11 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   hipStream_t st = (hipStream_t)stream;
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-  const Workspace ws = carve(workspace, n);
+  if (nz_idx != nullptr && cap > n) cap = n;                  // there cannot be more non-zeros than elements
+  const Workspace ws = carve(workspace, n, cap);
   const uint32_t ntiles = tiles_of(n);
 
-  const int32_t strategy = choose_strategy(n, d, w, nz_idx != nullptr, cap);
+  const int32_t strategy = choose_strategy(n, d, w, nz_idx != nullptr, cap, workspace_bytes);
   const uint32_t log2w = log2_of(w);
 
   // tile counters, and the sketch when the scan inserts into it with atomics
@@ -746,6 +848,7 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, nnz_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
+  const uint32_t slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
   if (nz_idx != nullptr && cap > 0) {
     CompactArgs C;
     C.grad = S.grad;
@@ -755,7 +858,15 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
     C.nz_idx = nz_idx;
     C.nz_val = reinterpret_cast<uint32_t*>(nz_val);
     C.cap = cap;
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(ntiles), dim3(kBlock), 0, st, C);
+    C.slice_id = ws.slice_id;
+    C.sid_stride = ws.sid_stride;
+    C.d = d;
+    C.log2w = log2w;
+    C.slice_log2 = slice_log2;
+    if (strategy == S2R_INSERT_SLICE)
+      hipLaunchKernelGGL(encode_compact_kernel<true>, dim3(ntiles), dim3(kBlock), 0, st, C, hp);
+    else
+      hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(ntiles), dim3(kBlock), 0, st, C, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
 
@@ -766,14 +877,16 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
     L.nnz = nnz_out;
     L.cap = cap;
     L.sketch = sketch;
+    L.slice_id = ws.slice_id;
+    L.sid_stride = ws.sid_stride;
     L.log2w = log2w;
-    L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
-    const size_t lds = sizeof(float) << L.slice_log2;
+    L.slice_log2 = slice_log2;
+    const size_t lds = (sizeof(float) << slice_log2) + sizeof(uint32_t) * kQueue * kSliceWaves;
     static thread_local bool lds_raised = false;
     if (!lds_raised) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)(sizeof(float) << kSliceLog2Max)) != hipSuccess) return S2R_ERR_LAUNCH;
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess)
+        return S2R_ERR_LAUNCH;
       lds_raised = true;
     }
     const uint32_t slices = d << (log2w - L.slice_log2);
@@ -834,7 +947,7 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   if ((idx_out == nullptr) != (val_out == nullptr)) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_need(n))
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_base(n))
     return S2R_ERR_WORKSPACE;
   if (((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) || ((uintptr_t)idx_out & 3u) ||
       ((uintptr_t)val_out & 3u) || ((uintptr_t)count_out & 7u) || ((uintptr_t)dense_out & 15u)) return S2R_ERR_ALIGN;
@@ -842,7 +955,7 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   hipStream_t st = (hipStream_t)stream;
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-  const Workspace ws = carve(workspace, n);
+  const Workspace ws = carve(workspace, n, 0);
   const uint32_t ntiles = tiles_of(n);
   const uint64_t nwords = ceil_div(n, 64);
 

@@ -49,7 +49,7 @@ class Buffers:
         self.out_val = torch.empty(max(union_cap, 1), dtype=torch.float32, device=dev)
         self.out_count = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dense_out = torch.empty(n, dtype=torch.float32, device=dev) if dense_out else None
-        ws = binding.workspace_bytes(n, d, w)
+        ws = binding.encode_workspace_bytes(n, d, w, min(max(nz_cap, 1), n))
         if ws == 0:
             raise ValueError("sizes outside the library's limits")
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
