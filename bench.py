@@ -30,6 +30,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="which BASELINE config to time (default: the largest single-GPU one)")
+    ap.add_argument("--per-worker-calls", action="store_true",
+                    help="encode with W s2r_encode calls instead of one s2r_encode_batch call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=0, help="override the oracle sample length")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -39,10 +41,10 @@ def parse_args():
 
 
 def scan_kernel_bytes(n: int, nnz: float, d: int) -> float:
-    """Algorithmic bytes of one launch of the encode scan kernel: the dense read
+    """Algorithmic bytes the encode scan kernel moves per worker: the dense read
     (4 B per element), the bitmap (1 bit per element), the compacted index+value
     list (8 B per non-zero) and the sketch insertions (d cells read and written,
-    4 B each way, per non-zero)."""
+    4 B each way, per non-zero).  One launch covers `workers` of these."""
     return 4.0 * n + n / 8.0 + 8.0 * nnz + 8.0 * d * nnz
 
 
@@ -102,14 +104,15 @@ def main():
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
 
+    batched = not args.per_worker_calls
     for _ in range(args.warmup):
-        b.step(stream)
+        b.step(stream, batched)
     torch.cuda.synchronize()
     ev0, ev1 = binding.HipEvent(), binding.HipEvent()
     t0 = time.perf_counter()
     ev0.record(stream)
     for _ in range(args.steps):
-        b.step(stream)
+        b.step(stream, batched)
     ev1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -117,29 +120,31 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = wl.dense_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---- per-kernel timing of the dominant kernel, same call sequence, HIP events on the launch stream
+    # ---- per-kernel timing, same call sequence, HIP events recorded by the library around its own launches
     reps = max(1, min(args.steps, 10))
-    pairs = [[(binding.HipEvent(), binding.HipEvent()) for _ in range(wl.W)] for _ in range(reps)]
-    phase = {}
+    slots = {"scan": binding.S2R_KERNEL_ENCODE_SCAN, "merge": binding.S2R_KERNEL_MERGE,
+             "decode": binding.S2R_KERNEL_DECODE}
+    timed = {k: [] for k in slots}
+
+    def bracket(name, call):
+        e0, e1 = binding.HipEvent(), binding.HipEvent()
+        binding.set_kernel_events(slots[name], e0.handle, e1.handle)
+        call()
+        binding.set_kernel_events(slots[name], None, None)
+        timed[name].append((e0, e1))
+
     for r in range(reps):
-        for k in range(wl.W):
-            e0, e1 = pairs[r][k]
-            binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SCAN, e0.handle, e1.handle)
-            b.encode(k, stream)
-        binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SCAN, None, None)
-        m0, m1, d0, d1 = (binding.HipEvent() for _ in range(4))
-        binding.set_kernel_events(binding.S2R_KERNEL_MERGE, m0.handle, m1.handle)
-        b.merge(stream)
-        binding.set_kernel_events(binding.S2R_KERNEL_MERGE, None, None)
-        binding.set_kernel_events(binding.S2R_KERNEL_DECODE, d0.handle, d1.handle)
-        b.decode(stream)
-        binding.set_kernel_events(binding.S2R_KERNEL_DECODE, None, None)
-        phase.setdefault("merge", []).append((m0, m1))
-        phase.setdefault("decode", []).append((d0, d1))
+        if batched:
+            bracket("scan", lambda: b.encode_all(stream))
+        else:
+            for k in range(wl.W):
+                bracket("scan", lambda k=k: b.encode(k, stream))
+        bracket("merge", lambda: b.merge(stream))
+        bracket("decode", lambda: b.decode(stream))
     torch.cuda.synchronize()
-    scan_ms = float(np.mean([e0.elapsed_ms(e1) for row in pairs for (e0, e1) in row]))
-    merge_ms = float(np.mean([a.elapsed_ms(c) for a, c in phase["merge"]]))
-    decode_ms = float(np.mean([a.elapsed_ms(c) for a, c in phase["decode"]]))
+    scan_ms, merge_ms, decode_ms = (float(np.mean([a.elapsed_ms(c) for a, c in timed[k]]))
+                                    for k in ("scan", "merge", "decode"))
+    workers_per_launch = binding.scan_launch_workers()
 
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=b.device)
@@ -152,7 +157,7 @@ def main():
     nnz = b.nnz.cpu().numpy().astype(np.float64)
     union = int(b.out_count.cpu()[0])
     assert [int(x) for x in nnz] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
-    alg_bytes = scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d)
+    alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d)
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
 
     out = {
@@ -173,8 +178,9 @@ def main():
                    "dense_bytes_per_step": wl.dense_bytes},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "event_ms_per_step": round(ev_ms / args.steps, 4),
-        "kernel_ms": {"encode_scan_avg": round(scan_ms, 4), "merge": round(merge_ms, 4),
-                      "decode": round(decode_ms, 4)},
+        "encode_calls": "s2r_encode_batch" if batched else "s2r_encode x W",
+        "kernel_ms": {"encode_scan_per_launch": round(scan_ms, 4), "workers_per_scan_launch": workers_per_launch,
+                      "merge": round(merge_ms, 4), "decode": round(decode_ms, 4)},
         "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None, "algorithmic_bytes_per_launch": int(alg_bytes)},

@@ -125,6 +125,30 @@ s2r_status s2r_encode(const float* grad, uint64_t n,
                       void* stream);
 
 /*
+ * s2r_encode for W workers in one call: the same kernels, each launched once over
+ * all workers, which spares small gradients the per-worker launch overheads.
+ * Worker k's outputs are exactly those of s2r_encode on grads[k].
+ *
+ *   grads, sketches, bitmaps   HOST arrays of W dev pointers (as in s2r_encode)
+ *   nz_idx, nz_val             HOST arrays of W dev pointers, capacity cap each; both
+ *                              arrays NULL (no lists for any worker), or all 2W
+ *                              pointers non-NULL
+ *   nnz_out                    dev, out: W uint64
+ *   workspace                  dev scratch, 256-byte aligned, split evenly between
+ *                              the workers: at least W * s2r_workspace_bytes(n,d,w),
+ *                              or W * s2r_encode_workspace_bytes(n,d,w,cap) to
+ *                              allow the LDS-slice strategy
+ * The host arrays are read before the call returns.  1 <= W <= S2R_MAX_WORKERS.
+ */
+s2r_status s2r_encode_batch(const float* const* grads, uint32_t W, uint64_t n,
+                            uint32_t d, uint32_t w, uint64_t seed,
+                            float* const* sketches, uint64_t* const* bitmaps,
+                            uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap,
+                            uint64_t* nnz_out,
+                            void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
  * Aggregate W workers' sketches and bitmaps (Algorithm 1: AllReduce(S, C);
  * Section 3.1 "Collecting Sparse-Sketch with AllReduce": sketches add, and the
  * set bits of the aggregated bitmap mark the union of the non-zero blocks).
@@ -192,7 +216,8 @@ s2r_status s2r_set_insert_strategy(int32_t strategy);
  * a slot, the corresponding kernel launch made by the calling thread is
  * bracketed by hipEventRecord(begin) / hipEventRecord(end) on the launch
  * stream.  Passing NULLs removes the pair.  State is per host thread.
- *   slot S2R_KERNEL_ENCODE_SCAN : the dense scan kernel of s2r_encode
+ *   slot S2R_KERNEL_ENCODE_SCAN : the dense scan kernel of s2r_encode / s2r_encode_batch
+ *                                 (see s2r_scan_launch_workers)
  *   slot S2R_KERNEL_MERGE       : the kernel of s2r_merge
  *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel of s2r_decode
  *   slot S2R_KERNEL_ENCODE_SLICE: the LDS-slice sketch kernel of s2r_encode
@@ -203,6 +228,12 @@ s2r_status s2r_set_insert_strategy(int32_t strategy);
 #define S2R_KERNEL_ENCODE_SLICE 3
 #define S2R_KERNEL_SLOTS        4
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end);
+
+/* Number of workers covered by the dense-scan launch that the
+ * S2R_KERNEL_ENCODE_SCAN events of the calling thread's last encode call
+ * bracketed (a batch may be scanned in one launch or worker by worker; in the
+ * latter case the events bracket the last worker's launch).  Host only. */
+uint32_t s2r_scan_launch_workers(void);
 
 #ifdef __cplusplus
 }

@@ -42,6 +42,10 @@ SIGNATURES = {
     "s2r_encode": (c_int32, [c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
                              c_void_p, c_void_p, c_void_p, c_void_p, c_uint64,
                              c_void_p, c_void_p, c_size_t, c_void_p]),
+    "s2r_encode_batch": (c_int32, [ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32, c_uint32, c_uint64,
+                                   ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
+                                   ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p), c_uint64,
+                                   c_void_p, c_void_p, c_size_t, c_void_p]),
     "s2r_merge": (c_int32, [ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
                             c_uint32, c_uint64, c_uint32, c_uint32, c_uint64,
                             c_void_p, c_void_p, c_void_p]),
@@ -50,6 +54,7 @@ SIGNATURES = {
                              c_void_p, c_size_t, c_void_p]),
     "s2r_set_kernel_events": (c_int32, [c_int32, c_void_p, c_void_p]),
     "s2r_set_insert_strategy": (c_int32, [c_int32]),
+    "s2r_scan_launch_workers": (c_uint32, []),
 }
 
 _lib = None
@@ -130,6 +135,23 @@ def encode(grad, d, w, seed, sketch, bitmap, nz_idx, nz_val, nnz_out, workspace,
         raise S2RError(st, "s2r_encode")
 
 
+def _ptr_array(tensors):
+    return (c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def encode_batch(grads, n, d, w, seed, sketches, bitmaps, nz_idx, nz_val, nnz_out, workspace, stream=None):
+    """s2r_encode_batch: lists of W device tensors; nz_idx / nz_val lists or both
+    None; nnz_out int64[W]; workspace uint8[>= W * workspace bytes]."""
+    W = len(grads)
+    cap = 0 if nz_idx is None else min(t.numel() for t in nz_idx)
+    st = load().s2r_encode_batch(_ptr_array(grads), W, n, d, w, seed, _ptr_array(sketches), _ptr_array(bitmaps),
+                                 None if nz_idx is None else _ptr_array(nz_idx),
+                                 None if nz_val is None else _ptr_array(nz_val), cap, _ptr(nnz_out),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_encode_batch")
+
+
 def merge(sketches, bitmaps, n, d, w, seed, sketch_out, bitmap_out, stream=None):
     """s2r_merge: sketches / bitmaps are lists of W device tensors."""
     W = len(sketches)
@@ -156,6 +178,10 @@ def set_insert_strategy(strategy: int):
     st = load().s2r_set_insert_strategy(strategy)
     if st != S2R_OK:
         raise S2RError(st, "s2r_set_insert_strategy")
+
+
+def scan_launch_workers() -> int:
+    return load().s2r_scan_launch_workers()
 
 
 def set_kernel_events(slot: int, ev_begin, ev_end):

@@ -56,36 +56,69 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));      // a 16-byte vecto
 
 static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
+// ------------------------------------------------------------------ encode: arguments
+// s2r_encode is a batch of one: every encode kernel takes the whole batch and
+// blockIdx.y is the worker.  The per-worker pointers travel in the kernel
+// arguments and are read with scalar loads.
+struct WorkerPtrs {
+  const uint32_t* grad;      // dense gradient as bit patterns
+  float* sketch;
+  uint64_t* bitmap;
+  uint32_t* nz_idx;          // may be null
+  uint32_t* nz_val;          // float bit patterns; may be null
+};
+
+struct EncodeBatch {
+  WorkerPtrs w[S2R_MAX_WORKERS];
+  uint64_t* nnz_out;         // [W]
+  char* workspace;           // W chunks of ws_stride bytes: tile counts | tile prefix | slice ids
+  uint64_t ws_stride;
+  uint64_t prefix_off;       // byte offset of the tile prefix inside a chunk
+  uint64_t sid_off;          // byte offset of the slice ids inside a chunk
+  uint64_t sid_stride;       // bytes per row of slice ids
+  uint64_t n;
+  uint64_t nwords;
+  uint64_t cap;
+  uint32_t ntiles;
+  uint32_t d;
+  uint32_t log2w;
+  uint32_t slice_log2;       // log2 of cells per LDS slice (<= log2w)
+  uint32_t first_worker;     // zero and scan kernels: worker = first_worker + blockIdx.y
+  uint32_t nworkers;         // W; a workgroup whose worker is not below it leaves at once
+};
+
+__device__ __forceinline__ uint32_t* ws_count(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride);
+}
+__device__ __forceinline__ uint64_t* ws_prefix(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint64_t*>(B.workspace + k * B.ws_stride + B.prefix_off);
+}
+__device__ __forceinline__ uint8_t* ws_slice_ids(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint8_t*>(B.workspace + k * B.ws_stride + B.sid_off);
+}
+
 // ------------------------------------------------------------------ zero
-// Zeroes nvec 16-byte units at p16 plus ntail floats at tail (the sketch; both may
-// be empty) and ncount tile counters.
-__global__ __launch_bounds__(kBlock) void zero_kernel(uint4* __restrict__ p16, uint64_t nvec,
-                                                      float* __restrict__ tail, uint32_t ntail,
-                                                      uint32_t* __restrict__ count, uint32_t ncount) {
+// Per worker: zeroes the tile counters and, when nvec/ntail are non-zero, the
+// sketch (nvec 16-byte units plus ntail trailing floats).
+__global__ __launch_bounds__(kBlock) void zero_kernel(const EncodeBatch B, uint64_t nvec, uint32_t ntail) {
+  const uint32_t k = B.first_worker + blockIdx.y;
+  if (k >= B.nworkers) return;
   const uint64_t tid = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  uint4* p16 = reinterpret_cast<uint4*>(B.w[k].sketch);
   for (uint64_t i = tid; i < nvec; i += stride) p16[i] = make_uint4(0u, 0u, 0u, 0u);
-  for (uint64_t i = tid; i < ncount; i += stride) count[i] = 0u;
-  if (tid < ntail) tail[tid] = 0.0f;
+  if (tid < ntail) B.w[k].sketch[nvec * 4 + tid] = 0.0f;
+  uint32_t* count = ws_count(B, k);
+  for (uint64_t i = tid; i < B.ntiles; i += stride) count[i] = 0u;
 }
 
 // ------------------------------------------------------------------ encode: dense scan
-struct ScanArgs {
-  const uint32_t* grad;      // dense gradient as bit patterns
-  uint64_t n;
-  uint64_t nwords;
-  uint32_t d;
-  uint32_t log2w;
-  float* sketch;
-  uint64_t* bitmap;
-  uint32_t* tile_count;      // [ntiles]
-};
-
-__device__ __forceinline__ void sketch_insert(const ScanArgs& A, const HashRows& hp, uint32_t i, uint32_t vbits) {
-  for (uint32_t j = 0; j < A.d; ++j) {
-    const uint32_t h = bucket_of(i, hp.a[j], hp.b[j], A.log2w);
+__device__ __forceinline__ void sketch_insert(float* sketch, uint32_t d, uint32_t log2w, const HashRows& hp,
+                                              uint32_t i, uint32_t vbits) {
+  for (uint32_t j = 0; j < d; ++j) {
+    const uint32_t h = bucket_of(i, hp.a[j], hp.b[j], log2w);
     const uint32_t sv = vbits ^ signbit_of(i, hp.c[j], hp.e[j]);
-    __hip_atomic_fetch_add(&A.sketch[((uint64_t)j << A.log2w) + h], __uint_as_float(sv),
+    __hip_atomic_fetch_add(&sketch[((uint64_t)j << log2w) + h], __uint_as_float(sv),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
@@ -97,23 +130,26 @@ __device__ __forceinline__ void sketch_insert(const ScanArgs& A, const HashRows&
 // workgroups resident at any time sweep one compact window of memory.  The
 // workgroup's non-zero count is added to its tile's counter (zeroed beforehand).
 template <int EPL, bool INSERT>
-__global__ __launch_bounds__(kBlock) void encode_scan_kernel(const ScanArgs A, const HashRows hp) {
+__global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_wave_count[kWavesPerBlock];
 
+  const uint32_t worker = B.first_worker + blockIdx.y;
+  if (worker >= B.nworkers) return;                      // uniform over the workgroup
+  const WorkerPtrs P = B.w[worker];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
   const uint64_t word0 = (uint64_t)blockIdx.x * kScanWords + (uint64_t)wv * EPL;   // this wave's first word
   const uint64_t e0 = word0 * 64;
 
   uint32_t v[EPL];
-  if (e0 + (uint64_t)EPL * kWave <= A.n) {               // uniform over the wave
+  if (e0 + (uint64_t)EPL * kWave <= B.n) {               // uniform over the wave
 #pragma unroll
-    for (int k = 0; k < EPL; ++k) v[k] = __builtin_nontemporal_load(&A.grad[e0 + k * kWave + lane]);
+    for (int k = 0; k < EPL; ++k) v[k] = __builtin_nontemporal_load(&P.grad[e0 + k * kWave + lane]);
   } else {
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
       const uint64_t i = e0 + k * kWave + lane;
-      v[k] = i < A.n ? A.grad[i] : 0u;
+      v[k] = i < B.n ? P.grad[i] : 0u;
     }
   }
 
@@ -126,10 +162,10 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const ScanArgs A, c
     if (lane == (uint32_t)k) parked = b;
     if (b != 0) {                                        // uniform: most words are empty
       count += (uint32_t)__popcll(b);
-      if (INSERT && nz) sketch_insert(A, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
+      if (INSERT && nz) sketch_insert(P.sketch, B.d, B.log2w, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
     }
   }
-  if (lane < (uint32_t)EPL && word0 + lane < A.nwords) A.bitmap[word0 + lane] = parked;
+  if (lane < (uint32_t)EPL && word0 + lane < B.nwords) P.bitmap[word0 + lane] = parked;
 
   if (lane == 0) s_wave_count[wv] = count;
   __syncthreads();
@@ -137,7 +173,7 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const ScanArgs A, c
     uint32_t t = 0;
 #pragma unroll
     for (int q = 0; q < kWavesPerBlock; ++q) t += s_wave_count[q];
-    if (t != 0) atomicAdd(&A.tile_count[blockIdx.x / kScansPerTile], t);
+    if (t != 0) atomicAdd(&ws_count(B, worker)[blockIdx.x / kScansPerTile], t);
   }
 }
 
@@ -167,9 +203,15 @@ __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __
 // is scanned inside its waves, the 32 x 16 wave totals are scanned by wave 0, and
 // every element adds the offset of its (row, wave).  n <= 2^32 gives at most 2^17
 // tiles: four rounds.
-__global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_t* __restrict__ count, uint32_t ntiles,
-                                                                   uint64_t* __restrict__ prefix,
+// blockIdx.y selects one of several independent problems (the workers of an
+// encode batch): its counts are at ws + y*ws_stride, its prefix at prefix_off
+// bytes after them, its total at total_out[y].
+__global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const char* __restrict__ ws, uint64_t ws_stride,
+                                                                   uint64_t prefix_off, uint32_t ntiles,
                                                                    uint64_t* __restrict__ total_out) {
+  const uint32_t* __restrict__ count = reinterpret_cast<const uint32_t*>(ws + blockIdx.y * ws_stride);
+  uint64_t* __restrict__ prefix =
+      reinterpret_cast<uint64_t*>(const_cast<char*>(ws) + blockIdx.y * ws_stride + prefix_off);
   constexpr int kWaves = kPrefixBlock / kWave;               // 16
   constexpr int kCells = kPrefixPer * kWaves;                // 512 (row, wave) totals per round
   __shared__ uint32_t s_tot[kCells + 1];
@@ -211,7 +253,7 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const uint32_
   }
   if (threadIdx.x == 0) {
     prefix[ntiles] = carry;
-    *total_out = carry;
+    total_out[blockIdx.y] = carry;
   }
 }
 
@@ -275,33 +317,24 @@ __device__ __forceinline__ uint32_t locate_set_bit(const TileBits& T, uint32_t t
 }
 
 // ------------------------------------------------------------------ encode: Sparse(g)
-struct CompactArgs {
-  const uint32_t* grad;
-  const uint64_t* bitmap;
-  uint64_t nwords;
-  const uint64_t* prefix;    // [ntiles + 1]
-  uint32_t* nz_idx;
-  uint32_t* nz_val;          // float bit patterns
-  uint64_t cap;
-  // SLICE_IDS only: for every listed item and row j, the sketch slice h_j(i) >> slice_log2
-  uint8_t* slice_id;         // [d][sid_stride]
-  uint64_t sid_stride;
-  uint32_t d;
-  uint32_t log2w;
-  uint32_t slice_log2;
-};
-
+// SLICE_IDS: also writes, for every listed item and row j, the sketch slice
+// h_j(i) >> slice_log2 as one byte (read by sketch_slice_kernel).
 template <bool SLICE_IDS>
-__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArgs A, const HashRows hp) {
+__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ TileBits T;
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const WorkerPtrs P = B.w[k];
+  const uint64_t* prefix = ws_prefix(B, k);
   const uint32_t tile = blockIdx.x;
   const uint64_t word0 = (uint64_t)tile * kTileWords;
   uint64_t wd[kWordsPerThread];
-  read_tile_words(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
-  const uint64_t base = A.prefix[tile];
-  const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
-  if (total == 0 || base >= A.cap) return;         // uniform over the workgroup
+  read_tile_words(wd, P.bitmap, B.nwords, word0);      // in flight together with the two prefix loads
+  const uint64_t base = prefix[tile];
+  const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
+  if (total == 0 || base >= B.cap) return;         // uniform over the workgroup
   scan_tile_words(T, wd);
+  uint8_t* slice_id = ws_slice_ids(B, k);
   // four output slots per thread and trip, so that the four value gathers are in flight together
   constexpr int kSlots = 4;
   for (uint32_t t0 = threadIdx.x; t0 < total; t0 += kBlock * kSlots) {
@@ -310,20 +343,20 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const CompactArg
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
       const uint32_t t = t0 + u * kBlock;
-      live[u] = t < total && base + t < A.cap;
+      live[u] = t < total && base + t < B.cap;
       i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
 #pragma unroll
-    for (int u = 0; u < kSlots; ++u) v[u] = live[u] ? A.grad[i[u]] : 0u;
+    for (int u = 0; u < kSlots; ++u) v[u] = live[u] ? P.grad[i[u]] : 0u;
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
       if (!live[u]) continue;
       const uint64_t pos = base + t0 + u * kBlock;
-      A.nz_idx[pos] = i[u];
-      A.nz_val[pos] = v[u];
+      P.nz_idx[pos] = i[u];
+      P.nz_val[pos] = v[u];
       if (SLICE_IDS) {
-        for (uint32_t j = 0; j < A.d; ++j)
-          A.slice_id[j * A.sid_stride + pos] = (uint8_t)(bucket_of(i[u], hp.a[j], hp.b[j], A.log2w) >> A.slice_log2);
+        for (uint32_t j = 0; j < B.d; ++j)
+          slice_id[j * B.sid_stride + pos] = (uint8_t)(bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
       }
     }
   }
@@ -346,18 +379,6 @@ constexpr int kQueueBatches = kQueue / kWave;        // 6
 constexpr int kSliceWaves = kSliceBlock / kWave;     // 16
 constexpr size_t kSliceLdsMax = (sizeof(float) << kSliceLog2Max) + sizeof(uint32_t) * kQueue * kSliceWaves;
 static_assert(kSliceLdsMax <= 160 * 1024, "slice + queues must fit the 160 KiB of LDS of a CU");
-
-struct SliceArgs {
-  const uint32_t* nz_idx;
-  const uint32_t* nz_val;    // float bit patterns
-  const uint8_t* slice_id;   // [d][sid_stride], rows 16-byte aligned
-  uint64_t sid_stride;
-  const uint64_t* nnz;       // device: true number of non-zeros
-  uint64_t cap;              // entries of the lists that exist
-  float* sketch;
-  uint32_t log2w;
-  uint32_t slice_log2;       // log2 of cells per slice (<= log2w)
-};
 
 struct SliceRow {            // what a drain needs, all uniform
   const uint32_t* nz_idx;
@@ -402,25 +423,29 @@ __device__ __forceinline__ void push_matches(float* s_slice, uint32_t* queue, ui
   }
 }
 
-__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const SliceArgs A, const HashRows hp) {
+__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B, const HashRows hp) {
   extern __shared__ float s_slice[];
   constexpr int kVecs = 4;                                     // 16-byte id loads in flight per thread
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const WorkerPtrs P = B.w[k];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
-  const uint32_t spr_log2 = A.log2w - A.slice_log2;            // log2 of slices per row (<= 8)
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;            // log2 of slices per row (<= 8)
   const uint32_t j = blockIdx.x >> spr_log2;
   const uint32_t s = blockIdx.x & ((1u << spr_log2) - 1u);
-  const uint32_t cells = 1u << A.slice_log2;
+  const uint32_t cells = 1u << B.slice_log2;
   uint32_t* queue = reinterpret_cast<uint32_t*>(s_slice + cells) + wv * kQueue;
   for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0f;
   __syncthreads();
 
-  const uint64_t have = *A.nnz < A.cap ? *A.nnz : A.cap;
+  const uint64_t nnz = B.nnz_out[k];
+  const uint64_t have = nnz < B.cap ? nnz : B.cap;
   SliceRow R;
-  R.nz_idx = A.nz_idx; R.nz_val = A.nz_val;
+  R.nz_idx = P.nz_idx; R.nz_val = P.nz_val;
   R.a = hp.a[j]; R.b = hp.b[j]; R.c = hp.c[j]; R.e = hp.e[j];
-  R.log2w = A.log2w; R.mask = cells - 1u;
-  const uint8_t* ids = A.slice_id + (uint64_t)j * A.sid_stride;
+  R.log2w = B.log2w; R.mask = cells - 1u;
+  const uint8_t* ids = ws_slice_ids(B, k) + (uint64_t)j * B.sid_stride;
   const uint32_t sb = s * 0x01010101u;                         // s in every byte
   uint32_t qcount = 0;
 
@@ -461,7 +486,7 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const SliceAr
   if (qcount != 0) drain_queue(s_slice, queue, qcount, lane, R);
 
   __syncthreads();
-  float* out = A.sketch + ((uint64_t)j << A.log2w) + ((uint64_t)s << A.slice_log2);
+  float* out = P.sketch + ((uint64_t)j << B.log2w) + ((uint64_t)s << B.slice_log2);
   for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = s_slice[c];
 }
 
@@ -469,26 +494,24 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const SliceAr
 // finds them in the bitmap and inserts them with atomics after the slices were
 // stored, so the sketch is complete whatever cap is.  Tiles that lie entirely
 // below cap (all of them, normally) leave at once.
-struct OverflowArgs {
-  ScanArgs scan;
-  const uint64_t* prefix;    // [ntiles + 1]
-  uint64_t cap;
-};
-
-__global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const OverflowArgs A, const HashRows hp) {
+__global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ TileBits T;
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const WorkerPtrs P = B.w[k];
+  const uint64_t* prefix = ws_prefix(B, k);
   const uint32_t tile = blockIdx.x;
-  const uint64_t base = A.prefix[tile];
-  const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
-  if (base + total <= A.cap) return;               // uniform over the workgroup
+  const uint64_t base = prefix[tile];
+  const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
+  if (base + total <= B.cap) return;               // uniform over the workgroup
   const uint64_t word0 = (uint64_t)tile * kTileWords;
   uint64_t wd[kWordsPerThread];
-  read_tile_words(wd, A.scan.bitmap, A.scan.nwords, word0);
+  read_tile_words(wd, P.bitmap, B.nwords, word0);
   scan_tile_words(T, wd);
-  const uint32_t first = base >= A.cap ? 0u : (uint32_t)(A.cap - base);
+  const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
   for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
     const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
-    sketch_insert(A.scan, hp, i, A.scan.grad[i]);
+    sketch_insert(P.sketch, B.d, B.log2w, hp, i, P.grad[i]);
   }
 }
 
@@ -634,6 +657,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
 struct EventPair { hipEvent_t begin, end; };
 static thread_local EventPair g_events[S2R_KERNEL_SLOTS] = {};
 static thread_local int32_t g_strategy = S2R_INSERT_AUTO;
+static thread_local uint32_t g_scan_launch_workers = 0;     // workers covered by the scan launch the events bracket
 
 static inline uint64_t splitmix_next(uint64_t& state) {
   state += 0x9E3779B97F4A7C15ull;
@@ -673,28 +697,15 @@ static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
 
 static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kTileWords); }
 
-// workspace: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]] [slice ids u8[d][stride]], each part
-// 256-byte aligned; the slice ids exist only when the caller's workspace is large enough for its cap
-struct Workspace {
-  uint32_t* count;
-  uint64_t* prefix;
-  uint8_t* slice_id;
-  uint64_t sid_stride;
-};
+// workspace of one worker: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]] [slice ids u8[d][stride]],
+// each part 256-byte aligned; the slice ids exist only when the caller's workspace is large enough for its cap
+static inline size_t workspace_prefix_off(uint64_t n) { return align256((size_t)tiles_of(n) * sizeof(uint32_t)); }
 static inline size_t workspace_base(uint64_t n) {
-  return align256((size_t)tiles_of(n) * sizeof(uint32_t)) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
+  return workspace_prefix_off(n) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
 }
 static inline uint64_t sid_stride_of(uint64_t cap) { return (cap + 255) & ~(uint64_t)255; }
 static inline size_t workspace_with_ids(uint64_t n, uint32_t d, uint64_t cap) {
   return workspace_base(n) + (size_t)d * sid_stride_of(cap);
-}
-static inline Workspace carve(void* ws, uint64_t n, uint64_t cap) {
-  Workspace w;
-  w.count = reinterpret_cast<uint32_t*>(ws);
-  w.prefix = reinterpret_cast<uint64_t*>((char*)ws + align256((size_t)tiles_of(n) * sizeof(uint32_t)));
-  w.slice_id = reinterpret_cast<uint8_t*>((char*)ws + workspace_base(n));
-  w.sid_stride = sid_stride_of(cap);
-  return w;
 }
 
 // How s2r_encode forms the sketch.  Cost models from measurements on MI355X:
@@ -786,6 +797,8 @@ s2r_status s2r_set_insert_strategy(int32_t strategy) {
   return S2R_OK;
 }
 
+uint32_t s2r_scan_launch_workers(void) { return g_scan_launch_workers; }
+
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
   if (slot < 0 || slot >= S2R_KERNEL_SLOTS) return S2R_ERR_SIZE;
   if ((ev_begin == nullptr) != (ev_end == nullptr)) return S2R_ERR_NULL;
@@ -794,94 +807,107 @@ s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
   return S2R_OK;
 }
 
-s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
-                      float* sketch, uint64_t* bitmap, uint32_t* nz_idx, float* nz_val, uint64_t cap,
-                      uint64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (grad == nullptr || sketch == nullptr || bitmap == nullptr || nnz_out == nullptr) return S2R_ERR_NULL;
-  if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
+// The encode of W workers (W = 1 for s2r_encode): every kernel is launched once
+// with the worker in blockIdx.y.  workspace_bytes is the size of the whole
+// workspace, split evenly between the workers.
+static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t n, uint32_t d, uint32_t w,
+                                 uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
+                                 uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
+                                 void* workspace, size_t workspace_bytes, hipStream_t st) {
+  if (grads == nullptr || sketches == nullptr || bitmaps == nullptr || nnz_out == nullptr) return S2R_ERR_NULL;
+  if (W == 0 || W > S2R_MAX_WORKERS) return S2R_ERR_SIZE;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_base(n))
-    return S2R_ERR_WORKSPACE;
-  if (((uintptr_t)grad & 3u) || ((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) ||
-      ((uintptr_t)nz_idx & 3u) || ((uintptr_t)nz_val & 3u) || ((uintptr_t)nnz_out & 7u)) return S2R_ERR_ALIGN;
+  const bool lists = nz_idx != nullptr && nz_idx[0] != nullptr;
+  if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
+  if (((uintptr_t)nnz_out & 7u) != 0) return S2R_ERR_ALIGN;
 
-  hipStream_t st = (hipStream_t)stream;
+  EncodeBatch E;
+  for (uint32_t k = 0; k < W; ++k) {
+    if (grads[k] == nullptr || sketches[k] == nullptr || bitmaps[k] == nullptr) return S2R_ERR_NULL;
+    uint32_t* ik = nz_idx ? nz_idx[k] : nullptr;
+    float* vk = nz_val ? nz_val[k] : nullptr;
+    if ((ik == nullptr) != (vk == nullptr) || (ik != nullptr) != lists) return S2R_ERR_NULL;
+    if (((uintptr_t)grads[k] & 3u) || ((uintptr_t)sketches[k] & 15u) || ((uintptr_t)bitmaps[k] & 7u) ||
+        ((uintptr_t)ik & 3u) || ((uintptr_t)vk & 3u)) return S2R_ERR_ALIGN;
+    E.w[k].grad = reinterpret_cast<const uint32_t*>(grads[k]);
+    E.w[k].sketch = sketches[k];
+    E.w[k].bitmap = bitmaps[k];
+    E.w[k].nz_idx = ik;
+    E.w[k].nz_val = reinterpret_cast<uint32_t*>(vk);
+  }
+  if (!lists) cap = 0;
+  if (cap > n) cap = n;                                       // there cannot be more non-zeros than elements
+  const size_t ws_each = (workspace_bytes / W) & ~(size_t)255;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_base(n))
+    return S2R_ERR_WORKSPACE;
+
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-  if (nz_idx != nullptr && cap > n) cap = n;                  // there cannot be more non-zeros than elements
-  const Workspace ws = carve(workspace, n, cap);
   const uint32_t ntiles = tiles_of(n);
-
-  const int32_t strategy = choose_strategy(n, d, w, nz_idx != nullptr, cap, workspace_bytes);
   const uint32_t log2w = log2_of(w);
+  const int32_t strategy = choose_strategy(n, d, w, lists, cap, ws_each);
 
-  // tile counters, and the sketch when the scan inserts into it with atomics
+  E.nworkers = W;
+  E.nnz_out = nnz_out;
+  E.workspace = reinterpret_cast<char*>(workspace);
+  E.ws_stride = ws_each;
+  E.prefix_off = workspace_prefix_off(n);
+  E.sid_off = workspace_base(n);
+  E.sid_stride = sid_stride_of(cap);
+  E.n = n;
+  E.nwords = ceil_div(n, 64);
+  E.cap = cap;
+  E.ntiles = ntiles;
+  E.d = d;
+  E.log2w = log2w;
+  E.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+
+  // Tile counters, and the sketch when the scan inserts into it with atomics; then the scan.  Measured on
+  // config 5 (4 GB per worker, 84 MB sketches): a scan whose sketch was zeroed just before it takes 760 us,
+  // against 820 us when all 16 sketches were zeroed first and 800 us in groups of three, so gradients of
+  // 1 GiB and more, for which two extra launches per worker cost nothing, are zeroed and scanned worker by
+  // worker.  Smaller ones gain more from single launches over the whole batch.
   const uint64_t cells = (uint64_t)d * w;
   const uint64_t nvec = strategy == S2R_INSERT_ATOMIC ? cells / 4 : 0;
   const uint32_t ntail = strategy == S2R_INSERT_ATOMIC ? (uint32_t)(cells - nvec * 4) : 0u;
-  const uint32_t ncount = ntiles;
-  uint64_t zb = ceil_div(nvec > ncount ? nvec : ncount, kBlock);
+  uint64_t zb = ceil_div(nvec > ntiles ? nvec : ntiles, kBlock);
   if (zb > 2048) zb = 2048;
-  hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb), dim3(kBlock), 0, st, reinterpret_cast<uint4*>(sketch), nvec,
-                     sketch + nvec * 4, ntail, ws.count, ncount);
-  if (!launch_ok()) return S2R_ERR_LAUNCH;
-
-  ScanArgs S;
-  S.grad = reinterpret_cast<const uint32_t*>(grad);
-  S.n = n;
-  S.nwords = ceil_div(n, 64);
-  S.d = d;
-  S.log2w = log2w;
-  S.sketch = sketch;
-  S.bitmap = bitmap;
-  S.tile_count = ws.count;
-  const dim3 scan_grid((uint32_t)ceil_div(S.nwords, kScanWords));
-  record(S2R_KERNEL_ENCODE_SCAN, false, st);
-  if (strategy == S2R_INSERT_ATOMIC)
-    hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true>), scan_grid, dim3(kBlock), 0, st, S, hp);
-  else
-    hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false>), scan_grid, dim3(kBlock), 0, st, S, hp);
-  record(S2R_KERNEL_ENCODE_SCAN, true, st);
-  if (!launch_ok()) return S2R_ERR_LAUNCH;
-
-  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, nnz_out);
-  if (!launch_ok()) return S2R_ERR_LAUNCH;
-
-  const uint32_t slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
-  if (nz_idx != nullptr && cap > 0) {
-    CompactArgs C;
-    C.grad = S.grad;
-    C.bitmap = bitmap;
-    C.nwords = S.nwords;
-    C.prefix = ws.prefix;
-    C.nz_idx = nz_idx;
-    C.nz_val = reinterpret_cast<uint32_t*>(nz_val);
-    C.cap = cap;
-    C.slice_id = ws.slice_id;
-    C.sid_stride = ws.sid_stride;
-    C.d = d;
-    C.log2w = log2w;
-    C.slice_log2 = slice_log2;
-    if (strategy == S2R_INSERT_SLICE)
-      hipLaunchKernelGGL(encode_compact_kernel<true>, dim3(ntiles), dim3(kBlock), 0, st, C, hp);
+  const uint32_t group = (strategy == S2R_INSERT_ATOMIC && n * sizeof(float) >= (1ull << 30)) ? 1u : W;
+  const uint32_t scan_blocks = (uint32_t)ceil_div(E.nwords, kScanWords);
+  uint32_t last_group = 0;
+  for (uint32_t k0 = 0; k0 < W; k0 += group) {
+    const uint32_t gy = W - k0 < group ? W - k0 : group;      // workers k0 .. k0 + gy - 1, all < W
+    const bool last = k0 + gy == W;                           // the events bracket the last scan launch
+    E.first_worker = k0;
+    hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, gy), dim3(kBlock), 0, st, E, nvec, ntail);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    if (last) record(S2R_KERNEL_ENCODE_SCAN, false, st);
+    if (strategy == S2R_INSERT_ATOMIC)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true>), dim3(scan_blocks, gy), dim3(kBlock), 0, st, E, hp);
     else
-      hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(ntiles), dim3(kBlock), 0, st, C, hp);
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false>), dim3(scan_blocks, gy), dim3(kBlock), 0, st, E, hp);
+    if (last) record(S2R_KERNEL_ENCODE_SCAN, true, st);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    last_group = gy;
+  }
+  g_scan_launch_workers = last_group;
+  E.first_worker = 0;
+
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1, W), dim3(kPrefixBlock), 0, st, E.workspace, E.ws_stride,
+                     E.prefix_off, ntiles, nnz_out);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+
+  if (lists && cap > 0) {
+    if (strategy == S2R_INSERT_SLICE)
+      hipLaunchKernelGGL(encode_compact_kernel<true>, dim3(ntiles, W), dim3(kBlock), 0, st, E, hp);
+    else
+      hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(ntiles, W), dim3(kBlock), 0, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
 
   if (strategy == S2R_INSERT_SLICE) {
-    SliceArgs L;
-    L.nz_idx = nz_idx;
-    L.nz_val = reinterpret_cast<const uint32_t*>(nz_val);
-    L.nnz = nnz_out;
-    L.cap = cap;
-    L.sketch = sketch;
-    L.slice_id = ws.slice_id;
-    L.sid_stride = ws.sid_stride;
-    L.log2w = log2w;
-    L.slice_log2 = slice_log2;
-    const size_t lds = (sizeof(float) << slice_log2) + sizeof(uint32_t) * kQueue * kSliceWaves;
+    const size_t lds = (sizeof(float) << E.slice_log2) + sizeof(uint32_t) * kQueue * kSliceWaves;
     static thread_local bool lds_raised = false;
     if (!lds_raised) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
@@ -889,20 +915,32 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
         return S2R_ERR_LAUNCH;
       lds_raised = true;
     }
-    const uint32_t slices = d << (log2w - L.slice_log2);
+    const uint32_t slices = d << (log2w - E.slice_log2);
     record(S2R_KERNEL_ENCODE_SLICE, false, st);
-    hipLaunchKernelGGL(sketch_slice_kernel, dim3(slices), dim3(kSliceBlock), lds, st, L, hp);
+    hipLaunchKernelGGL(sketch_slice_kernel, dim3(slices, W), dim3(kSliceBlock), lds, st, E, hp);
     record(S2R_KERNEL_ENCODE_SLICE, true, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
 
-    OverflowArgs O;
-    O.scan = S;
-    O.prefix = ws.prefix;
-    O.cap = cap;
-    hipLaunchKernelGGL(sketch_overflow_kernel, dim3(ntiles), dim3(kBlock), 0, st, O, hp);
+    hipLaunchKernelGGL(sketch_overflow_kernel, dim3(ntiles, W), dim3(kBlock), 0, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
   return S2R_OK;
+}
+
+s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                      float* sketch, uint64_t* bitmap, uint32_t* nz_idx, float* nz_val, uint64_t cap,
+                      uint64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
+  return encode_workers(&grad, 1, n, d, w, seed, &sketch, &bitmap, nz_idx ? &nz_idx : nullptr,
+                        nz_val ? &nz_val : nullptr, cap, nnz_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+s2r_status s2r_encode_batch(const float* const* grads, uint32_t W, uint64_t n, uint32_t d, uint32_t w,
+                            uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
+                            uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  return encode_workers(grads, W, n, d, w, seed, sketches, bitmaps, nz_idx, nz_val, cap, nnz_out, workspace,
+                        workspace_bytes, (hipStream_t)stream);
 }
 
 s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
@@ -955,14 +993,16 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   hipStream_t st = (hipStream_t)stream;
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-  const Workspace ws = carve(workspace, n, 0);
   const uint32_t ntiles = tiles_of(n);
   const uint64_t nwords = ceil_div(n, 64);
 
+  uint32_t* tile_count = reinterpret_cast<uint32_t*>(workspace);
+  uint64_t* tile_prefix = reinterpret_cast<uint64_t*>((char*)workspace + workspace_prefix_off(n));
   hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
-                     bitmap, nwords, ntiles, ws.count);
+                     bitmap, nwords, ntiles, tile_count);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
-  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, ws.count, ntiles, ws.prefix, count_out);
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, (const char*)workspace, (uint64_t)0,
+                     (uint64_t)workspace_prefix_off(n), ntiles, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if ((idx_out == nullptr || cap == 0) && dense_out == nullptr) return S2R_OK;   // only the count was asked for
 
@@ -973,7 +1013,7 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   A.nwords = nwords;
   A.d = d;
   A.log2w = log2_of(w);
-  A.prefix = ws.prefix;
+  A.prefix = tile_prefix;
   A.idx_out = idx_out;
   A.val_out = val_out;
   A.cap = idx_out ? cap : 0;

@@ -52,13 +52,18 @@ class Buffers:
         ws = binding.encode_workspace_bytes(n, d, w, min(max(nz_cap, 1), n))
         if ws == 0:
             raise ValueError("sizes outside the library's limits")
-        self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(ws * W, dtype=torch.uint8, device=dev)     # W shares for encode_batch
         assert self.workspace.data_ptr() % 256 == 0
 
     # ------------------------------------------------------------ the path
     def encode(self, k: int, stream=None):
         binding.encode(self.grads[k], self.d, self.w, self.seed, self.sketch[k], self.bitmap[k],
                        self.nz_idx[k], self.nz_val[k], self.nnz[k:k + 1], self.workspace, stream, n=self.n)
+
+    def encode_all(self, stream=None):
+        """All W workers through one s2r_encode_batch call."""
+        binding.encode_batch(self.grads, self.n, self.d, self.w, self.seed, self.sketch, self.bitmap,
+                             self.nz_idx, self.nz_val, self.nnz, self.workspace, stream)
 
     def merge(self, stream=None):
         binding.merge(self.sketch, self.bitmap, self.n, self.d, self.w, self.seed,
@@ -68,10 +73,14 @@ class Buffers:
         binding.decode(self.sketch_sum, self.bitmap_or, self.n, self.d, self.w, self.seed,
                        self.out_idx, self.out_val, self.out_count, self.dense_out, self.workspace, stream)
 
-    def step(self, stream=None):
-        """One pass of the whole hot path over the resident gradients."""
-        for k in range(self.W):
-            self.encode(k, stream)
+    def step(self, stream=None, batched: bool = True):
+        """One pass of the whole hot path over the resident gradients: the W
+        encodes (one s2r_encode_batch call, or W s2r_encode calls), merge, decode."""
+        if batched:
+            self.encode_all(stream)
+        else:
+            for k in range(self.W):
+                self.encode(k, stream)
         self.merge(stream)
         self.decode(stream)
 

@@ -109,6 +109,27 @@ def test_merge_and_decode_reject_bad_arguments():
     assert dec(wsb=0) == b.S2R_ERR_WORKSPACE
 
 
+def test_encode_batch_rejects_bad_arguments():
+    lib = b.load()
+    two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    sk = (ctypes.c_void_p * 2)(0x10000, 0x20000)
+    one_null = (ctypes.c_void_p * 2)(0x1000, None)
+    call = lambda **k: lib.s2r_encode_batch(k.get("g", two), k.get("W", 2), k.get("n", 1000), 3, k.get("w", 64), 0,
+                                            k.get("S", sk), k.get("C", two), k.get("idx", None), k.get("val", None),
+                                            10, k.get("nnz", 0x6000), k.get("ws", 0x100000), k.get("wsb", 1 << 20), None)
+    assert call(g=None) == b.S2R_ERR_NULL
+    assert call(g=one_null) == b.S2R_ERR_NULL
+    assert call(nnz=None) == b.S2R_ERR_NULL
+    assert call(idx=two) == b.S2R_ERR_NULL                  # idx without val
+    assert call(idx=one_null, val=two) == b.S2R_ERR_NULL    # lists for some workers only
+    assert call(W=0) == b.S2R_ERR_SIZE
+    assert call(W=65) == b.S2R_ERR_SIZE
+    assert call(w=100) == b.S2R_ERR_WIDTH
+    assert call(wsb=300) == b.S2R_ERR_WORKSPACE
+    assert call(ws=0x100010) == b.S2R_ERR_WORKSPACE
+    assert call(S=(ctypes.c_void_p * 2)(0x10000, 0x20004)) == b.S2R_ERR_ALIGN
+
+
 def test_set_insert_strategy_argument_checks():
     assert b.load().s2r_set_insert_strategy(3) == b.S2R_ERR_SIZE
     assert b.load().s2r_set_insert_strategy(-1) == b.S2R_ERR_SIZE

@@ -49,11 +49,11 @@ def _check_sketch(got, S, M, what):
     assert np.all(got[M == 0] == 0.0), f"{what}: untouched cells must be zero"
 
 
-def _run_and_check(wl, dense_out=False):
-    print(f"[case] {wl.name} W={wl.W} n={wl.n} d={wl.d} w={wl.w}", flush=True)
+def _run_and_check(wl, dense_out=False, batched=True):
+    print(f"[case] {wl.name} W={wl.W} n={wl.n} d={wl.d} w={wl.w} batched={batched}", flush=True)
     enc, S, C, M, dec = _oracle_for(wl)
     b = pipeline.buffers_for(wl, dense_out=dense_out)
-    b.step()
+    b.step(batched=batched)
     torch.cuda.synchronize()
     nnz = b.nnz.cpu().numpy()
     for k in range(wl.W):
@@ -82,9 +82,10 @@ def _run_and_check(wl, dense_out=False):
     return b, dec
 
 
+@pytest.mark.parametrize("batched", [True, False], ids=["batch", "per_worker"])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
-def test_small_recipes_match_oracle(cfg, strategy):
-    _run_and_check(workloads.make_small(cfg), dense_out=True)
+def test_small_recipes_match_oracle(cfg, strategy, batched):
+    _run_and_check(workloads.make_small(cfg), dense_out=True, batched=batched)
 
 
 def test_recipe1_full_size(strategy):
@@ -93,7 +94,7 @@ def test_recipe1_full_size(strategy):
 
 @pytest.mark.parametrize("cfg", [2, 3, 4])
 def test_full_size_recipes_match_oracle(cfg, strategy):
-    _run_and_check(workloads.make(cfg))
+    _run_and_check(workloads.make(cfg), batched=(cfg != 3))
 
 
 def _custom(n, idx, val, d=3, w=64, W=1, seed=0):
@@ -267,3 +268,34 @@ def test_recipe5_full_size_in_the_benchmarked_configuration():
     tol = REL * orc.decode_tolerance_mass(M, dec["idx"], wl.seed) + DENORM_SLACK
     err = np.abs(b.out_val[:cnt].cpu().numpy().astype(np.float64) - dec["val"])
     assert np.all(err <= tol), f"decoded values: worst {err.max():.3e}"
+
+
+def test_batch_with_null_lists_and_argument_checks():
+    wl = workloads.make_small(1)
+    enc, S, C, M, dec = _oracle_for(wl)
+    b = pipeline.buffers_for(wl)
+    binding.encode_batch(b.grads, wl.n, wl.d, wl.w, wl.seed, b.sketch, b.bitmap, None, None, b.nnz, b.workspace)
+    torch.cuda.synchronize()
+    assert b.nnz.cpu().numpy().tolist() == [len(e["idx"]) for e in enc]
+    for k in range(wl.W):
+        assert np.array_equal(pipeline.u64(b.bitmap[k]), enc[k]["bitmap"])
+        _check_sketch(b.sketch[k].cpu().numpy(), enc[k]["S"], enc[k]["M"], f"worker {k} sketch")
+    small = b.workspace[: binding.workspace_bytes(wl.n, wl.d, wl.w)]        # enough for one worker only
+    with pytest.raises(binding.S2RError) as ei:
+        binding.encode_batch(b.grads, wl.n, wl.d, wl.w, wl.seed, b.sketch, b.bitmap, None, None, b.nnz, small)
+    assert ei.value.status == binding.S2R_ERR_WORKSPACE
+
+
+def test_large_gradients_are_scanned_worker_by_worker():
+    """n*4 >= 1 GiB with atomics: the batch is zeroed and scanned one worker per
+    launch (first_worker advances), everything else in single launches."""
+    binding.set_insert_strategy(binding.S2R_INSERT_ATOMIC)
+    try:
+        rng = np.random.default_rng(5)
+        n, W, d, w = (1 << 28) + 77, 3, 3, 1 << 12
+        idx = [np.sort(rng.choice(n, 2000, replace=False)) for _ in range(W)]
+        val = [rng.normal(0, 0.01, 2000).astype(np.float32) for _ in range(W)]
+        _run_and_check(_custom(n, idx, val, d=d, w=w, W=W, seed=3))
+        assert binding.scan_launch_workers() == 1
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
