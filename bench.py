@@ -40,12 +40,14 @@ def parse_args():
     return ap.parse_args()
 
 
-def scan_kernel_bytes(n: int, nnz: float, d: int) -> float:
+def scan_kernel_bytes(n: int, nnz: float, d: int, inserts: bool) -> float:
     """Algorithmic bytes the encode scan kernel moves per worker: the dense read
     (4 B per element), the bitmap (1 bit per element), the compacted index+value
     list (8 B per non-zero) and the sketch insertions (d cells read and written,
-    4 B each way, per non-zero).  One launch covers `workers` of these."""
-    return 4.0 * n + n / 8.0 + 8.0 * nnz + 8.0 * d * nnz
+    4 B each way, per non-zero) when this kernel makes them; without them (LDS
+    slice strategy) the list and the sketch are written by other kernels.  One
+    launch covers one or more workers."""
+    return 4.0 * n + n / 8.0 + (8.0 * nnz + 8.0 * d * nnz if inserts else 0.0)
 
 
 def cpu_baseline(wl, first_sample: int, budget_s: float = 12.0):
@@ -145,6 +147,7 @@ def main():
     scan_ms, merge_ms, decode_ms = (float(np.mean([a.elapsed_ms(c) for a, c in timed[k]]))
                                     for k in ("scan", "merge", "decode"))
     workers_per_launch = binding.scan_launch_workers()
+    atomic = binding.last_insert_strategy() == binding.S2R_INSERT_ATOMIC
 
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=b.device)
@@ -157,7 +160,7 @@ def main():
     nnz = b.nnz.cpu().numpy().astype(np.float64)
     union = int(b.out_count.cpu()[0])
     assert [int(x) for x in nnz] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
-    alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d)
+    alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d, atomic)
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
 
     out = {
@@ -179,6 +182,7 @@ def main():
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "event_ms_per_step": round(ev_ms / args.steps, 4),
         "encode_calls": "s2r_encode_batch" if batched else "s2r_encode x W",
+        "insert_strategy": "atomic" if atomic else "lds_slice",
         "kernel_ms": {"encode_scan_per_launch": round(scan_ms, 4), "workers_per_scan_launch": workers_per_launch,
                       "merge": round(merge_ms, 4), "decode": round(decode_ms, 4)},
         "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),

@@ -211,6 +211,11 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
 #define S2R_INSERT_SLICE  2
 s2r_status s2r_set_insert_strategy(int32_t strategy);
 
+/* S2R_INSERT_ATOMIC or S2R_INSERT_SLICE: what the calling thread's last
+ * s2r_encode / s2r_encode_batch call used (S2R_INSERT_AUTO before any call).
+ * Host only. */
+int32_t s2r_last_insert_strategy(void);
+
 /*
  * Instrumentation for benchmarks.  While a pair of hipEvent_t is installed for
  * a slot, the corresponding kernel launch made by the calling thread is

@@ -55,6 +55,7 @@ SIGNATURES = {
     "s2r_set_kernel_events": (c_int32, [c_int32, c_void_p, c_void_p]),
     "s2r_set_insert_strategy": (c_int32, [c_int32]),
     "s2r_scan_launch_workers": (c_uint32, []),
+    "s2r_last_insert_strategy": (c_int32, []),
 }
 
 _lib = None
@@ -178,6 +179,10 @@ def set_insert_strategy(strategy: int):
     st = load().s2r_set_insert_strategy(strategy)
     if st != S2R_OK:
         raise S2RError(st, "s2r_set_insert_strategy")
+
+
+def last_insert_strategy() -> int:
+    return load().s2r_last_insert_strategy()
 
 
 def scan_launch_workers() -> int:

@@ -657,6 +657,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
 struct EventPair { hipEvent_t begin, end; };
 static thread_local EventPair g_events[S2R_KERNEL_SLOTS] = {};
 static thread_local int32_t g_strategy = S2R_INSERT_AUTO;
+static thread_local int32_t g_last_strategy = S2R_INSERT_AUTO;   // what the last encode call used
 static thread_local uint32_t g_scan_launch_workers = 0;     // workers covered by the scan launch the events bracket
 
 static inline uint64_t splitmix_next(uint64_t& state) {
@@ -714,10 +715,11 @@ static inline size_t workspace_with_ids(uint64_t n, uint32_t d, uint64_t cap) {
 //    time hides them (when the non-zeros are spread over many workgroups);
 //  - a slice workgroup costs about 15 us (clearing and storing 128 KiB of LDS) plus
 //    its share of the list at 16e9 items per second, plus about 3 us per queue drain
-//    of a wave; (d*w / slice cells) workgroups run at most 256 at a time; the slice
-//    ids and the overflow pass add about 10 us.
+//    of a wave; the (d*w / slice cells) workgroups of every worker of the batch run
+//    at most 256 at a time; the slice ids and the overflow pass add about 10 us.
 // `cap` is the caller's bound on the number of non-zeros.
-static int32_t choose_strategy(uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap, size_t workspace_bytes) {
+static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap,
+                               size_t workspace_bytes) {
   if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice kernel reads Sparse(g)
   const uint32_t log2w = log2_of(w);
   const uint32_t slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
@@ -725,13 +727,13 @@ static int32_t choose_strategy(uint64_t n, uint32_t d, uint32_t w, bool have_lis
   if (workspace_bytes < workspace_with_ids(n, d, cap)) return S2R_INSERT_ATOMIC;
   if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
   const double per_row = (double)(1u << (log2w - slice_log2));
-  const double rounds = (double)ceil_div((uint64_t)(d * per_row), 256);
+  const double rounds = (double)ceil_div((uint64_t)(W * d * per_row), 256);       // all workers' slices share the CUs
   const double drains = (double)cap / per_row / kSliceWaves / (kQueue - kWave);
   const double t_slice = rounds * (15e-6 + (double)cap / 16e9 + drains * 3e-6) + 10e-6;
   const double t_stream = 4.0 * (double)n / 6.0e12;
   double t_atomic = (double)cap * d / 21.0e9 - 0.5 * t_stream;
   if (t_atomic < 0) t_atomic = 0;
-  return t_slice < t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
+  return t_slice < W * t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
 }
 
 static inline void record(int slot, bool end, hipStream_t st) {
@@ -799,6 +801,8 @@ s2r_status s2r_set_insert_strategy(int32_t strategy) {
 
 uint32_t s2r_scan_launch_workers(void) { return g_scan_launch_workers; }
 
+int32_t s2r_last_insert_strategy(void) { return g_last_strategy; }
+
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
   if (slot < 0 || slot >= S2R_KERNEL_SLOTS) return S2R_ERR_SIZE;
   if ((ev_begin == nullptr) != (ev_end == nullptr)) return S2R_ERR_NULL;
@@ -846,7 +850,8 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   make_hash_rows(seed, d, &hp);
   const uint32_t ntiles = tiles_of(n);
   const uint32_t log2w = log2_of(w);
-  const int32_t strategy = choose_strategy(n, d, w, lists, cap, ws_each);
+  const int32_t strategy = choose_strategy(W, n, d, w, lists, cap, ws_each);
+  g_last_strategy = strategy;
 
   E.nworkers = W;
   E.nnz_out = nnz_out;
