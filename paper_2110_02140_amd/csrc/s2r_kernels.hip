@@ -367,7 +367,8 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
 // row j in LDS.  It streams row j's slice ids (one byte per listed item, written
 // by the compaction kernel; 16 items per 16-byte load, cache resident because
 // every slice of the row reads the same bytes), and finds the items whose id is s
-// with a four-bytes-at-a-time equality test.  Matches are rare in a wave (one
+// with a branch-free four-bytes-at-a-time equality test that leaves one hit bit
+// per item in a 64-bit mask per lane.  Matches are rare in a wave (one
 // item in slices-per-row), so they are not handled where they are found: each
 // wave pushes their list positions into a queue of its own in LDS and, when the
 // queue fills, drains it with all lanes busy: index and value loads, the bucket
@@ -436,7 +437,12 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
   const uint32_t s = blockIdx.x & ((1u << spr_log2) - 1u);
   const uint32_t cells = 1u << B.slice_log2;
   uint32_t* queue = reinterpret_cast<uint32_t*>(s_slice + cells) + wv * kQueue;
-  for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0f;
+  if (cells >= 4u * kSliceBlock) {                             // (the LDS array and every slice are 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
+      reinterpret_cast<float4*>(s_slice)[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+  } else {
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0f;
+  }
   __syncthreads();
 
   const uint64_t nnz = B.nnz_out[k];
@@ -461,21 +467,27 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
       const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
       x[u] = q < nvec ? ids16[q] : make_uint4(~sb, ~sb, ~sb, ~sb);       // a filler that matches nothing
     }
+    // bit 16u + 4r + c of `hits`: byte c of word r of vector u equals s.  Branch-free: per word an exact
+    // zero-byte test of (word ^ s-in-every-byte), then a multiply that gathers the four flag bits.
+    uint64_t hits = 0;
 #pragma unroll
     for (int u = 0; u < kVecs; ++u) {
-      const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
       const uint32_t wds[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+      uint32_t h16 = 0;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t v = wds[r] ^ sb;                       // a zero byte where the id equals s
-        uint32_t z = ~(((v & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | v | 0x7F7F7F7Fu);   // 0x80 in exactly those bytes
-        while (__ballot(z != 0) != 0) {                       // uniform; almost always 0 or 1 rounds
-          const bool has = z != 0;
-          const uint32_t byte = has ? ((uint32_t)__ffs((int)z) - 1u) >> 3 : 0u;
-          push_matches(s_slice, queue, qcount, lane, has, (uint32_t)(q * 16 + r * 4 + byte), R);
-          z &= z - 1u;
-        }
+        const uint32_t v = wds[r] ^ sb;
+        const uint32_t z = ~(((v & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | v | 0x7F7F7F7Fu);   // 0x80 in exactly the zero bytes
+        h16 |= (((z >> 7) * 0x10204080u) >> 28) << (4 * r);      // bits 0, 8, 16, 24 -> one nibble
       }
+      hits |= (uint64_t)h16 << (16 * u);
+    }
+    while (__ballot(hits != 0) != 0) {                          // uniform; about as many rounds as the busiest lane has hits
+      const bool has = hits != 0;
+      const uint32_t p = has ? (uint32_t)__ffsll((unsigned long long)hits) - 1u : 0u;
+      const uint64_t q = q0 + (uint64_t)(p >> 4) * kSliceBlock;
+      push_matches(s_slice, queue, qcount, lane, has, (uint32_t)(q * 16 + (p & 15u)), R);
+      hits &= hits - 1ull;
     }
   }
   {                                                           // the last have % 16 items, one per thread
@@ -487,7 +499,12 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
 
   __syncthreads();
   float* out = P.sketch + ((uint64_t)j << B.log2w) + ((uint64_t)s << B.slice_log2);
-  for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = s_slice[c];
+  if (cells >= 4u * kSliceBlock) {
+    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
+      reinterpret_cast<float4*>(out)[c] = reinterpret_cast<const float4*>(s_slice)[c];
+  } else {
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = s_slice[c];
+  }
 }
 
 // Non-zeros at list positions >= cap are not in the caller's lists; this kernel
