@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the encode scan kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this file,
+# scaled by what the same counters read for a plain 1 GiB copy (profiles/hbm_traffic_<workload>.txt):
+# (workload, insert strategy, workers per launch) -> bytes.  Other combinations have not been counted.
+MEASURED_SCAN_TRAFFIC = {("cfg5_large_zipf", "atomic", 1): 4.299e9}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -187,7 +192,9 @@ def main():
                       "merge": round(merge_ms, 4), "decode": round(decode_ms, 4)},
         "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "algorithmic_bytes_per_launch": int(alg_bytes)},
+                     "traffic": MEASURED_SCAN_TRAFFIC.get((wl.name, "atomic" if atomic else "lds_slice",
+                                                           workers_per_launch)),
+                     "algorithmic_bytes_per_launch": int(alg_bytes)},
         "setup_s": {"generate": round(t_gen, 1)},
     }
     if not args.no_cpu_baseline:
