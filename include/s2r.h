@@ -89,9 +89,10 @@ const char* s2r_status_string(s2r_status status);
 size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w);
 
 /* Bytes of device scratch with which s2r_encode can also use the LDS-slice
- * strategy for lists of capacity cap (s2r_workspace_bytes plus d bytes per list
- * entry).  With a smaller workspace (but at least s2r_workspace_bytes) it
- * inserts with atomics.  Host only; returns 0 outside the limits or if cap > n. */
+ * strategy for lists of capacity cap (s2r_workspace_bytes plus 8*d bytes per
+ * list entry for the partitioned records, plus their histograms).  With a
+ * smaller workspace (but at least s2r_workspace_bytes) it inserts with atomics.
+ * Host only; returns 0 outside the limits or if cap > n. */
 size_t s2r_encode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
 
 /* The four hash parameters of each of the d rows, as the kernels use them:
@@ -199,9 +200,11 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued
  *                      from the dense scan (the sketch is zeroed first)
  *   S2R_INSERT_SLICE   workgroups that each own a slice of one sketch row in
- *                      LDS and read Sparse(g); needs nz_idx / nz_val, a workspace
- *                      of s2r_encode_workspace_bytes and w <= 2^23 (otherwise
- *                      s2r_encode uses atomics whatever is set here)
+ *                      LDS and add the entries of Sparse(g), which a counting
+ *                      sort has partitioned by slice; needs nz_idx / nz_val, a
+ *                      workspace of s2r_encode_workspace_bytes, d*w <= 2^27 and
+ *                      d*cap < 2^32 (otherwise s2r_encode uses atomics whatever
+ *                      is set here)
  *   S2R_INSERT_AUTO    (default) chosen from n, d, w and cap, the caller's bound
  *                      on the number of non-zeros
  * State is per host thread.  Returns S2R_ERR_SIZE for any other value.

@@ -17,11 +17,13 @@
 //                tile_prefix_kernel    exclusive prefix of the tile counts, total
 //                encode_compact_kernel Sparse(g): expands the bitmap (n/8 bytes)
 //                                      and gathers the values at the set bits
-//                sketch_slice_kernel   (slice variant) every workgroup owns a slice
-//                                      of one sketch row in LDS, streams Sparse(g)
-//                                      and accumulates the items that hash into its
-//                                      slice, then stores the slice: no global
-//                                      atomics, no zeroing
+//                bin_hist_kernel,      (slice variant) Sparse(g) x rows is partitioned by
+//                bin_scan_kernel,      sketch slice (counting sort: histogram per chunk,
+//                bin_scatter_kernel    offsets, scatter of (cell, signed value) records)
+//                sketch_slice_kernel   (slice variant) every workgroup owns a slice of
+//                                      one sketch row in LDS, adds the records of its
+//                                      bin and stores the slice: no global atomics, no
+//                                      zeroing of the sketch
 //                sketch_overflow_kernel (slice variant) inserts, with atomics, the
 //                                      non-zeros that did not fit the caller's list
 //   s2r_merge  : merge_kernel          S = sum_k S_k (ascending k), C = OR_k C_k
@@ -74,8 +76,9 @@ struct EncodeBatch {
   char* workspace;           // W chunks of ws_stride bytes: tile counts | tile prefix | slice ids
   uint64_t ws_stride;
   uint64_t prefix_off;       // byte offset of the tile prefix inside a chunk
-  uint64_t sid_off;          // byte offset of the slice ids inside a chunk
-  uint64_t sid_stride;       // bytes per row of slice ids
+  uint64_t hist_off;         // slice variant: byte offsets inside a chunk of the per-chunk bin histogram
+  uint64_t binstart_off;     //   [nchunks][nbins] u32, the bin starts [nbins + 1] u32,
+  uint64_t rec_off;          //   and the binned records [d * cap] of 8 bytes
   uint64_t n;
   uint64_t nwords;
   uint64_t cap;
@@ -83,6 +86,8 @@ struct EncodeBatch {
   uint32_t d;
   uint32_t log2w;
   uint32_t slice_log2;       // log2 of cells per LDS slice (<= log2w)
+  uint32_t nbins;            // d * slices per row
+  uint32_t nchunks;          // list chunks of kBinChunk items
   uint32_t first_worker;     // zero and scan kernels: worker = first_worker + blockIdx.y
   uint32_t nworkers;         // W; a workgroup whose worker is not below it leaves at once
 };
@@ -93,8 +98,14 @@ __device__ __forceinline__ uint32_t* ws_count(const EncodeBatch& B, uint32_t k) 
 __device__ __forceinline__ uint64_t* ws_prefix(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint64_t*>(B.workspace + k * B.ws_stride + B.prefix_off);
 }
-__device__ __forceinline__ uint8_t* ws_slice_ids(const EncodeBatch& B, uint32_t k) {
-  return reinterpret_cast<uint8_t*>(B.workspace + k * B.ws_stride + B.sid_off);
+__device__ __forceinline__ uint32_t* ws_bin_hist(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.hist_off);
+}
+__device__ __forceinline__ uint32_t* ws_bin_start(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.binstart_off);
+}
+__device__ __forceinline__ uint2* ws_records(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint2*>(B.workspace + k * B.ws_stride + B.rec_off);
 }
 
 // ------------------------------------------------------------------ zero
@@ -317,10 +328,7 @@ __device__ __forceinline__ uint32_t locate_set_bit(const TileBits& T, uint32_t t
 }
 
 // ------------------------------------------------------------------ encode: Sparse(g)
-// SLICE_IDS: also writes, for every listed item and row j, the sketch slice
-// h_j(i) >> slice_log2 as one byte (read by sketch_slice_kernel).
-template <bool SLICE_IDS>
-__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B, const HashRows hp) {
+__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B) {
   __shared__ TileBits T;
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
@@ -334,7 +342,6 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
   const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
   if (total == 0 || base >= B.cap) return;         // uniform over the workgroup
   scan_tile_words(T, wd);
-  uint8_t* slice_id = ws_slice_ids(B, k);
   // four output slots per thread and trip, so that the four value gathers are in flight together
   constexpr int kSlots = 4;
   for (uint32_t t0 = threadIdx.x; t0 < total; t0 += kBlock * kSlots) {
@@ -354,90 +361,164 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
       const uint64_t pos = base + t0 + u * kBlock;
       P.nz_idx[pos] = i[u];
       P.nz_val[pos] = v[u];
-      if (SLICE_IDS) {
-        for (uint32_t j = 0; j < B.d; ++j)
-          slice_id[j * B.sid_stride + pos] = (uint8_t)(bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
-      }
     }
   }
 }
 
 // ------------------------------------------------------------------ encode: sketch by LDS slices
-// Workgroup (j, s) owns cells [s * 2^slice_log2, (s+1) * 2^slice_log2) of sketch
-// row j in LDS.  It streams row j's slice ids (one byte per listed item, written
-// by the compaction kernel; 16 items per 16-byte load, cache resident because
-// every slice of the row reads the same bytes), and finds the items whose id is s
-// with a branch-free four-bytes-at-a-time equality test that leaves one hit bit
-// per item in a 64-bit mask per lane.  Matches are rare in a wave (one
-// item in slices-per-row), so they are not handled where they are found: each
-// wave pushes their list positions into a queue of its own in LDS and, when the
-// queue fills, drains it with all lanes busy: index and value loads, the bucket
-// and sign hashes, one LDS float add per item.  Finally the slice is stored: each
-// cell of the sketch is written exactly once, by plain coalesced stores, with no
-// global atomics and no zeroing of the sketch beforehand.
-constexpr int kQueue = 384;                          // queue entries per wave
-constexpr int kQueueBatches = kQueue / kWave;        // 6
-constexpr int kSliceWaves = kSliceBlock / kWave;     // 16
-constexpr size_t kSliceLdsMax = (sizeof(float) << kSliceLog2Max) + sizeof(uint32_t) * kQueue * kSliceWaves;
-static_assert(kSliceLdsMax <= 160 * 1024, "slice + queues must fit the 160 KiB of LDS of a CU");
+// The insertions S[j, h_j(i)] += s_j(i) g(i) without global atomics.  Row j of the
+// sketch is cut into slices of 2^slice_log2 cells (128 KiB of LDS); bin (j, s)
+// collects the pairs (item, row j) whose bucket falls in slice s.  A counting sort
+// over the listed items brings each bin's records together:
+//   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins
+//   bin_scan_kernel     offsets of every (chunk, bin) run and of every bin
+//   bin_scatter_kernel  writes each record (cell in the slice | sign bit, value)
+//                       into its run (order inside a run is arbitrary)
+//   sketch_slice_kernel workgroup (j, s) clears its slice in LDS, adds its bin's
+//                       records with LDS float atomics and stores the slice
+// Work is O(items x rows), whatever the number of slices, and every cell of the
+// sketch is written exactly once by plain coalesced stores.
+constexpr int kBinBlock = 1024;
+constexpr int kBinItems = 16;                          // list items per thread
+constexpr int kBinChunk = kBinBlock * kBinItems;       // 16384 items per workgroup
+constexpr int kMaxBins = 4096;                         // d * slices per row that the LDS histograms hold
+constexpr size_t kSliceLdsMax = sizeof(float) << kSliceLog2Max;
 
-struct SliceRow {            // what a drain needs, all uniform
-  const uint32_t* nz_idx;
-  const uint32_t* nz_val;
-  uint64_t a, b, c, e;
-  uint32_t log2w, mask;
-};
-
-__device__ __forceinline__ void drain_queue(float* s_slice, const uint32_t* queue, uint32_t qcount, uint32_t lane,
-                                            const SliceRow& R) {
-  __builtin_amdgcn_wave_barrier();                   // the pushes of this wave are in program order before the reads
-  uint32_t t[kQueueBatches], idx[kQueueBatches], val[kQueueBatches];
-#pragma unroll
-  for (int q = 0; q < kQueueBatches; ++q) t[q] = (uint32_t)q * kWave + lane < qcount ? queue[q * kWave + lane] : ~0u;
-#pragma unroll
-  for (int q = 0; q < kQueueBatches; ++q) {            // all loads of the drain in flight together
-    idx[q] = (uint32_t)q * kWave + lane < qcount ? R.nz_idx[t[q]] : 0u;
-    val[q] = (uint32_t)q * kWave + lane < qcount ? R.nz_val[t[q]] : 0u;
-  }
-#pragma unroll
-  for (int q = 0; q < kQueueBatches; ++q) {
-    if ((uint32_t)q * kWave + lane < qcount) {
-      const uint32_t h = bucket_of(idx[q], R.a, R.b, R.log2w);
-      const uint32_t sv = val[q] ^ signbit_of(idx[q], R.c, R.e);
-      __hip_atomic_fetch_add(&s_slice[h & R.mask], __uint_as_float(sv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    }
-  }
-  __builtin_amdgcn_wave_barrier();
+__device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t k) {
+  const uint64_t nnz = B.nnz_out[k];
+  return nnz < B.cap ? nnz : B.cap;
 }
 
-// Pushes the list position `item` of every lane with has == true; drains when a
-// further push of 64 might not fit.  qcount is uniform over the wave.
-__device__ __forceinline__ void push_matches(float* s_slice, uint32_t* queue, uint32_t& qcount, uint32_t lane, bool has,
-                                             uint32_t item, const SliceRow& R) {
-  const uint64_t m = __ballot(has);
-  if (m == 0) return;
-  if (has) queue[qcount + bits_below_lane(m)] = item;
-  qcount += (uint32_t)__popcll(m);
-  if (qcount > (uint32_t)(kQueue - kWave)) {
-    drain_queue(s_slice, queue, qcount, lane, R);
-    qcount = 0;
-  }
-}
-
-__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B, const HashRows hp) {
-  extern __shared__ float s_slice[];
-  constexpr int kVecs = 4;                                     // 16-byte id loads in flight per thread
+__global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
+  __shared__ uint32_t s_hist[kMaxBins];
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
-  const WorkerPtrs P = B.w[k];
+  const uint32_t chunk = blockIdx.x;
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
+  __syncthreads();
+  const uint64_t have = listed_items(B, k);
+  const uint32_t* __restrict__ idx = B.w[k].nz_idx;
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;
+  uint32_t i[kBinItems];
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+    i[u] = t < have ? idx[t] : 0u;
+  }
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+    if (t < have) {
+      for (uint32_t j = 0; j < B.d; ++j) {
+        const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
+        __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
+}
+
+// One workgroup per worker.  In place: hist[c][b] becomes the number of records of
+// bin b in chunks before c; bin_start[b] the number of records in bins before b
+// (bin_start[nbins] = all records).  Thread t owns bins t, t + 1024, ...: for a
+// fixed chunk the threads read consecutive counters.
+__global__ __launch_bounds__(kBinBlock) void bin_scan_kernel(const EncodeBatch B) {
+  constexpr int kPerThread = kMaxBins / kBinBlock;       // 4
+  constexpr int kWaves = kBinBlock / kWave;
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
-  const uint32_t spr_log2 = B.log2w - B.slice_log2;            // log2 of slices per row (<= 8)
-  const uint32_t j = blockIdx.x >> spr_log2;
-  const uint32_t s = blockIdx.x & ((1u << spr_log2) - 1u);
+  uint32_t* hist = ws_bin_hist(B, k);
+  uint32_t* bin_start = ws_bin_start(B, k);
+  uint32_t total[kPerThread];
+#pragma unroll
+  for (int r = 0; r < kPerThread; ++r) {
+    const uint32_t b = r * kBinBlock + threadIdx.x;
+    uint32_t run = 0;
+    if (b < B.nbins) {
+      constexpr uint32_t kAhead = 8;                      // counters in flight per thread
+      for (uint32_t c0 = 0; c0 < B.nchunks; c0 += kAhead) {
+        uint32_t v[kAhead];
+#pragma unroll
+        for (uint32_t q = 0; q < kAhead; ++q) v[q] = c0 + q < B.nchunks ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+#pragma unroll
+        for (uint32_t q = 0; q < kAhead; ++q) {
+          if (c0 + q < B.nchunks) hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
+          run += v[q];
+        }
+      }
+    }
+    total[r] = run;
+  }
+  uint32_t carry = 0;                                     // records in the bins of earlier rounds
+#pragma unroll
+  for (int r = 0; r < kPerThread; ++r) {                  // bins r*1024 .. r*1024+1023 in thread order
+    const uint32_t incl = wave_inclusive_scan_u32(total[r], lane);
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    uint32_t wave_off = 0, round_total = 0;
+#pragma unroll
+    for (int q = 0; q < kWaves; ++q) {
+      const uint32_t x = s_wave[q];
+      if ((uint32_t)q < wv) wave_off += x;
+      round_total += x;
+    }
+    const uint32_t b = r * kBinBlock + threadIdx.x;
+    if (b < B.nbins) bin_start[b] = carry + wave_off + incl - total[r];
+    carry += round_total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) bin_start[B.nbins] = carry;
+}
+
+__global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
+  __shared__ uint32_t s_cursor[kMaxBins];                 // next free record of each bin's run of this chunk
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const uint32_t chunk = blockIdx.x;
+  const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+  const uint32_t* bin_start = ws_bin_start(B, k);
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_cursor[b] = bin_start[b] + hist[b];
+  __syncthreads();
+  const uint64_t have = listed_items(B, k);
+  const WorkerPtrs P = B.w[k];
+  uint2* __restrict__ rec = ws_records(B, k);
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;
+  const uint32_t mask = (1u << B.slice_log2) - 1u;
+  uint32_t i[kBinItems], v[kBinItems];
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+    i[u] = t < have ? P.nz_idx[t] : 0u;
+    v[u] = t < have ? P.nz_val[t] : 0u;
+  }
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+    if (t < have) {
+      for (uint32_t j = 0; j < B.d; ++j) {
+        const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
+        const uint32_t bin = (j << spr_log2) + (h >> B.slice_log2);
+        const uint32_t pos = __hip_atomic_fetch_add(&s_cursor[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        rec[pos] = make_uint2((h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]), v[u]);
+      }
+    }
+  }
+}
+
+// Workgroup = bin (j, s) of worker blockIdx.y.
+__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B) {
+  extern __shared__ float s_slice[];
+  constexpr int kAhead = 4;                               // 8-byte record loads in flight per thread
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
   const uint32_t cells = 1u << B.slice_log2;
-  uint32_t* queue = reinterpret_cast<uint32_t*>(s_slice + cells) + wv * kQueue;
-  if (cells >= 4u * kSliceBlock) {                             // (the LDS array and every slice are 16-byte aligned)
+  if (cells >= 4u * kSliceBlock) {                        // (the LDS array and every slice are 16-byte aligned)
     for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
       reinterpret_cast<float4*>(s_slice)[c] = make_float4(0.f, 0.f, 0.f, 0.f);
   } else {
@@ -445,60 +526,23 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
   }
   __syncthreads();
 
-  const uint64_t nnz = B.nnz_out[k];
-  const uint64_t have = nnz < B.cap ? nnz : B.cap;
-  SliceRow R;
-  R.nz_idx = P.nz_idx; R.nz_val = P.nz_val;
-  R.a = hp.a[j]; R.b = hp.b[j]; R.c = hp.c[j]; R.e = hp.e[j];
-  R.log2w = B.log2w; R.mask = cells - 1u;
-  const uint8_t* ids = ws_slice_ids(B, k) + (uint64_t)j * B.sid_stride;
-  const uint32_t sb = s * 0x01010101u;                         // s in every byte
-  uint32_t qcount = 0;
-
-  const uint64_t nvec = have / 16;
-  const uint4* ids16 = reinterpret_cast<const uint4*>(ids);
-  // the loop variable is the wave's first vector, so the trip count is the same in
-  // all lanes of a wave and qcount stays uniform; lanes past the end read a filler
-  for (uint64_t qw = (uint64_t)wv * kWave; qw < nvec; qw += (uint64_t)kSliceBlock * kVecs) {
-    const uint64_t q0 = qw + lane;
-    uint4 x[kVecs];
+  const uint32_t* bin_start = ws_bin_start(B, k);
+  const uint32_t first = bin_start[bin], last = bin_start[bin + 1];
+  const uint2* __restrict__ rec = ws_records(B, k);
+  for (uint32_t r0 = first + threadIdx.x; r0 < last; r0 += kSliceBlock * kAhead) {
+    uint2 x[kAhead];
 #pragma unroll
-    for (int u = 0; u < kVecs; ++u) {
-      const uint64_t q = q0 + (uint64_t)u * kSliceBlock;
-      x[u] = q < nvec ? ids16[q] : make_uint4(~sb, ~sb, ~sb, ~sb);       // a filler that matches nothing
-    }
-    // bit 16u + 4r + c of `hits`: byte c of word r of vector u equals s.  Branch-free: per word an exact
-    // zero-byte test of (word ^ s-in-every-byte), then a multiply that gathers the four flag bits.
-    uint64_t hits = 0;
+    for (int u = 0; u < kAhead; ++u) x[u] = r0 + u * kSliceBlock < last ? rec[r0 + u * kSliceBlock] : make_uint2(0u, 0u);
 #pragma unroll
-    for (int u = 0; u < kVecs; ++u) {
-      const uint32_t wds[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-      uint32_t h16 = 0;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint32_t v = wds[r] ^ sb;
-        const uint32_t z = ~(((v & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | v | 0x7F7F7F7Fu);   // 0x80 in exactly the zero bytes
-        h16 |= (((z >> 7) * 0x10204080u) >> 28) << (4 * r);      // bits 0, 8, 16, 24 -> one nibble
-      }
-      hits |= (uint64_t)h16 << (16 * u);
-    }
-    while (__ballot(hits != 0) != 0) {                          // uniform; about as many rounds as the busiest lane has hits
-      const bool has = hits != 0;
-      const uint32_t p = has ? (uint32_t)__ffsll((unsigned long long)hits) - 1u : 0u;
-      const uint64_t q = q0 + (uint64_t)(p >> 4) * kSliceBlock;
-      push_matches(s_slice, queue, qcount, lane, has, (uint32_t)(q * 16 + (p & 15u)), R);
-      hits &= hits - 1ull;
+    for (int u = 0; u < kAhead; ++u) {
+      if (r0 + u * kSliceBlock < last)
+        __hip_atomic_fetch_add(&s_slice[x[u].x & 0x7FFFFFFFu], __uint_as_float(x[u].y ^ (x[u].x & 0x80000000u)),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
   }
-  {                                                           // the last have % 16 items, one per thread
-    const uint64_t t = nvec * 16 + threadIdx.x;
-    const bool has = t < have && ids[t] == (uint8_t)s;
-    push_matches(s_slice, queue, qcount, lane, has, (uint32_t)t, R);
-  }
-  if (qcount != 0) drain_queue(s_slice, queue, qcount, lane, R);
-
   __syncthreads();
-  float* out = P.sketch + ((uint64_t)j << B.log2w) + ((uint64_t)s << B.slice_log2);
+  // bin = j * slices-per-row + s, so the slice starts at cell bin * cells of the row-major sketch
+  float* out = B.w[k].sketch + (uint64_t)bin * cells;
   if (cells >= 4u * kSliceBlock) {
     for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
       reinterpret_cast<float4*>(out)[c] = reinterpret_cast<const float4*>(s_slice)[c];
@@ -715,38 +759,49 @@ static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
 
 static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kTileWords); }
 
-// workspace of one worker: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]] [slice ids u8[d][stride]],
-// each part 256-byte aligned; the slice ids exist only when the caller's workspace is large enough for its cap
+// workspace of one worker: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]], and for the slice
+// strategy [bin histogram u32[nchunks][nbins]] [bin starts u32[nbins + 1]] [records 8 B x d*cap]; each part
+// 256-byte aligned.  The slice parts exist only when the caller's workspace is large enough for its cap.
 static inline size_t workspace_prefix_off(uint64_t n) { return align256((size_t)tiles_of(n) * sizeof(uint32_t)); }
 static inline size_t workspace_base(uint64_t n) {
   return workspace_prefix_off(n) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
 }
-static inline uint64_t sid_stride_of(uint64_t cap) { return (cap + 255) & ~(uint64_t)255; }
-static inline size_t workspace_with_ids(uint64_t n, uint32_t d, uint64_t cap) {
-  return workspace_base(n) + (size_t)d * sid_stride_of(cap);
+struct SliceLayout {
+  bool possible;             // the bins fit the LDS histograms and record positions fit 32 bits
+  uint32_t slice_log2, nbins, nchunks;
+  size_t hist_off, binstart_off, rec_off, total;
+};
+static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
+  SliceLayout L;
+  const uint32_t log2w = log2_of(w);
+  L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+  const uint64_t nbins = (uint64_t)d << (log2w - L.slice_log2);
+  L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0;
+  L.nbins = (uint32_t)(L.possible ? nbins : 0);
+  L.nchunks = (uint32_t)(L.possible ? ceil_div(cap, kBinChunk) : 0);
+  L.hist_off = workspace_base(n);
+  L.binstart_off = L.hist_off + align256((size_t)L.nchunks * L.nbins * sizeof(uint32_t));
+  L.rec_off = L.binstart_off + align256(((size_t)L.nbins + 1) * sizeof(uint32_t));
+  L.total = L.rec_off + align256((size_t)(L.possible ? d * cap : 0) * 8);
+  return L;
 }
 
 // How s2r_encode forms the sketch.  Cost models from measurements on MI355X:
 //  - scattered float32 atomics retire at about 21e9 per second over the whole chip
 //    whatever their scope; issued from the dense scan, about half of the scan's own
 //    time hides them (when the non-zeros are spread over many workgroups);
-//  - a slice workgroup costs about 15 us (clearing and storing 128 KiB of LDS) plus
-//    its share of the list at 16e9 items per second, plus about 3 us per queue drain
-//    of a wave; the (d*w / slice cells) workgroups of every worker of the batch run
-//    at most 256 at a time; the slice ids and the overflow pass add about 10 us.
+//  - the slice strategy adds four kernels: about 30 us of launches,
+//    12 us per round of 256 slice workgroups (clearing and storing 128 KiB of LDS
+//    each), and the records at about 60e9 per second;
 // `cap` is the caller's bound on the number of non-zeros.
 static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap,
                                size_t workspace_bytes) {
-  if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice kernel reads Sparse(g)
-  const uint32_t log2w = log2_of(w);
-  const uint32_t slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
-  if (log2w - slice_log2 > 8) return S2R_INSERT_ATOMIC;      // a slice id is one byte
-  if (workspace_bytes < workspace_with_ids(n, d, cap)) return S2R_INSERT_ATOMIC;
+  if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice strategy reads Sparse(g)
+  const SliceLayout L = slice_layout(n, d, w, cap);
+  if (!L.possible || workspace_bytes < L.total) return S2R_INSERT_ATOMIC;
   if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
-  const double per_row = (double)(1u << (log2w - slice_log2));
-  const double rounds = (double)ceil_div((uint64_t)(W * d * per_row), 256);       // all workers' slices share the CUs
-  const double drains = (double)cap / per_row / kSliceWaves / (kQueue - kWave);
-  const double t_slice = rounds * (15e-6 + (double)cap / 16e9 + drains * 3e-6) + 10e-6;
+  const double rounds = (double)ceil_div((uint64_t)W * L.nbins, 256);       // all workers' slices share the CUs
+  const double t_slice = 30e-6 + rounds * 12e-6 + (double)W * cap * d / 60e9;
   const double t_stream = 4.0 * (double)n / 6.0e12;
   double t_atomic = (double)cap * d / 21.0e9 - 0.5 * t_stream;
   if (t_atomic < 0) t_atomic = 0;
@@ -793,7 +848,8 @@ size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w) {
 
 size_t s2r_encode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   if (check_sizes(n, d, w) != S2R_OK || cap > n) return 0;
-  return workspace_with_ids(n, d, cap);
+  const SliceLayout L = slice_layout(n, d, w, cap);
+  return L.possible ? L.total : workspace_base(n);
 }
 
 s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out) {
@@ -875,15 +931,19 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.workspace = reinterpret_cast<char*>(workspace);
   E.ws_stride = ws_each;
   E.prefix_off = workspace_prefix_off(n);
-  E.sid_off = workspace_base(n);
-  E.sid_stride = sid_stride_of(cap);
+  const SliceLayout L = slice_layout(n, d, w, cap);
+  E.hist_off = L.hist_off;
+  E.binstart_off = L.binstart_off;
+  E.rec_off = L.rec_off;
+  E.nbins = L.nbins;
+  E.nchunks = L.nchunks;
   E.n = n;
   E.nwords = ceil_div(n, 64);
   E.cap = cap;
   E.ntiles = ntiles;
   E.d = d;
   E.log2w = log2w;
-  E.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+  E.slice_log2 = L.slice_log2;
 
   // Tile counters, and the sketch when the scan inserts into it with atomics; then the scan.  Measured on
   // config 5 (4 GB per worker, 84 MB sketches): a scan whose sketch was zeroed just before it takes 760 us,
@@ -921,15 +981,12 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
   if (lists && cap > 0) {
-    if (strategy == S2R_INSERT_SLICE)
-      hipLaunchKernelGGL(encode_compact_kernel<true>, dim3(ntiles, W), dim3(kBlock), 0, st, E, hp);
-    else
-      hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(ntiles, W), dim3(kBlock), 0, st, E, hp);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(ntiles, W), dim3(kBlock), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
 
   if (strategy == S2R_INSERT_SLICE) {
-    const size_t lds = (sizeof(float) << E.slice_log2) + sizeof(uint32_t) * kQueue * kSliceWaves;
+    const size_t lds = sizeof(float) << E.slice_log2;
     static thread_local bool lds_raised = false;
     if (!lds_raised) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
@@ -937,9 +994,14 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
         return S2R_ERR_LAUNCH;
       lds_raised = true;
     }
-    const uint32_t slices = d << (log2w - E.slice_log2);
+    hipLaunchKernelGGL(bin_hist_kernel, dim3(E.nchunks, W), dim3(kBinBlock), 0, st, E, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_scan_kernel, dim3(1, W), dim3(kBinBlock), 0, st, E);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, W), dim3(kBinBlock), 0, st, E, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
     record(S2R_KERNEL_ENCODE_SLICE, false, st);
-    hipLaunchKernelGGL(sketch_slice_kernel, dim3(slices, W), dim3(kSliceBlock), lds, st, E, hp);
+    hipLaunchKernelGGL(sketch_slice_kernel, dim3(E.nbins, W), dim3(kSliceBlock), lds, st, E);
     record(S2R_KERNEL_ENCODE_SLICE, true, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
 
