@@ -133,12 +133,20 @@ def main():
              "decode": binding.S2R_KERNEL_DECODE}
     timed = {k: [] for k in slots}
 
+    slice_pairs = []
+
     def bracket(name, call):
         e0, e1 = binding.HipEvent(), binding.HipEvent()
         binding.set_kernel_events(slots[name], e0.handle, e1.handle)
+        if name == "scan":          # the LDS-slice kernel, when the encode uses it, is bracketed in the same call
+            s0, s1 = binding.HipEvent(), binding.HipEvent()
+            binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SLICE, s0.handle, s1.handle)
         call()
         binding.set_kernel_events(slots[name], None, None)
         timed[name].append((e0, e1))
+        if name == "scan":
+            binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SLICE, None, None)
+            slice_pairs.append((s0, s1))
 
     for r in range(reps):
         if batched:
@@ -153,6 +161,7 @@ def main():
                                     for k in ("scan", "merge", "decode"))
     workers_per_launch = binding.scan_launch_workers()
     atomic = binding.last_insert_strategy() == binding.S2R_INSERT_ATOMIC
+    slice_ms = None if atomic else float(np.mean([a.elapsed_ms(c) for a, c in slice_pairs]))
 
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=b.device)
@@ -189,6 +198,7 @@ def main():
         "encode_calls": "s2r_encode_batch" if batched else "s2r_encode x W",
         "insert_strategy": "atomic" if atomic else "lds_slice",
         "kernel_ms": {"encode_scan_per_launch": round(scan_ms, 4), "workers_per_scan_launch": workers_per_launch,
+                      "encode_slice_per_launch": None if slice_ms is None else round(slice_ms, 4),
                       "merge": round(merge_ms, 4), "decode": round(decode_ms, 4)},
         "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -51,7 +51,8 @@ constexpr int kScansPerTile = kTileWords / kScanWords;       // 16
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
 constexpr int kPrefixPer = 32;                    // tile counts per thread per round
 constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice workgroup
-constexpr int kSliceLog2Max = 15;                 // at most 2^15 cells = 128 KiB of LDS per slice
+constexpr int kSliceLog2Max = 15;                 // at most 2^15 cells = 128 KiB of LDS per slice (slices of
+                                                  // 2^12..2^14 cells with 256..1024 threads measured the same)
 static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));      // a 16-byte vector the nontemporal builtins accept
@@ -553,26 +554,37 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
 
 // Non-zeros at list positions >= cap are not in the caller's lists; this kernel
 // finds them in the bitmap and inserts them with atomics after the slices were
-// stored, so the sketch is complete whatever cap is.  Tiles that lie entirely
-// below cap (all of them, normally) leave at once.
+// stored, so the sketch is complete whatever cap is.  Normally there are none:
+// each thread checks one tile's range of list positions and the workgroup leaves
+// unless one of its kBlock tiles reaches beyond cap.
 __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ TileBits T;
+  __shared__ uint32_t s_any;
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const WorkerPtrs P = B.w[k];
   const uint64_t* prefix = ws_prefix(B, k);
-  const uint32_t tile = blockIdx.x;
-  const uint64_t base = prefix[tile];
-  const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
-  if (base + total <= B.cap) return;               // uniform over the workgroup
-  const uint64_t word0 = (uint64_t)tile * kTileWords;
-  uint64_t wd[kWordsPerThread];
-  read_tile_words(wd, P.bitmap, B.nwords, word0);
-  scan_tile_words(T, wd);
-  const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
-  for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
-    const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
-    sketch_insert(P.sketch, B.d, B.log2w, hp, i, P.grad[i]);
+  const uint32_t tile0 = blockIdx.x * kBlock;
+  if (threadIdx.x == 0) s_any = 0u;
+  __syncthreads();
+  const uint32_t mine = tile0 + threadIdx.x;
+  if (mine < B.ntiles && prefix[mine + 1] > B.cap) s_any = 1u;
+  __syncthreads();
+  if (s_any == 0u) return;                               // uniform over the workgroup
+  for (uint32_t tile = tile0; tile < tile0 + kBlock && tile < B.ntiles; ++tile) {
+    const uint64_t base = prefix[tile];
+    const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
+    if (base + total <= B.cap) continue;                 // uniform over the workgroup
+    const uint64_t word0 = (uint64_t)tile * kTileWords;
+    uint64_t wd[kWordsPerThread];
+    read_tile_words(wd, P.bitmap, B.nwords, word0);
+    __syncthreads();                                     // T may still be read by the previous tile's loop
+    scan_tile_words(T, wd);
+    const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
+    for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
+      const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
+      sketch_insert(P.sketch, B.d, B.log2w, hp, i, P.grad[i]);
+    }
   }
 }
 
@@ -1005,7 +1017,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
     record(S2R_KERNEL_ENCODE_SLICE, true, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
 
-    hipLaunchKernelGGL(sketch_overflow_kernel, dim3(ntiles, W), dim3(kBlock), 0, st, E, hp);
+    hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), W), dim3(kBlock), 0, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
   return S2R_OK;
