@@ -3,18 +3,20 @@
 // contract of every entry point.
 //
 // The gradient, the bitmaps and the index lists are cut into tiles of
-// kTileWords bitmap words (= 64 * kTileWords elements).  No kernel waits for
-// another workgroup: ascending index lists come from per-tile counts, a small
-// prefix kernel, and a second kernel that expands the bitmap at known offsets.
+// kTileWords bitmap words (= 64 * kTileWords elements), a tile into kScansPerTile
+// pieces of kScanWords words.  No kernel waits for another workgroup and none
+// shares a counter with another: ascending index lists come from per-piece counts
+// (one 16-bit store per scan workgroup), a small prefix kernel over the tiles,
+// and a second kernel that expands the bitmap at known offsets.
 //
-//   s2r_encode : zero_kernel           zero the tile counts (and the sketch when the
-//                                      insertions are atomics)
+//   s2r_encode : zero_kernel           (atomic variant) zero the sketch
 //                encode_scan_kernel    the one pass over the dense gradient:
-//                                      bitmap words from wave ballots, per-tile
+//                                      bitmap words from wave ballots, per-piece
 //                                      non-zero counts, and (INSERT variant) the
 //                                      insertions S[j, h_j(i)] += s_j(i) g(i) as
 //                                      float32 atomics
-//                tile_prefix_kernel    exclusive prefix of the tile counts, total
+//                tile_prefix_kernel    tile counts from the piece counts, their
+//                                      exclusive prefix, total
 //                encode_compact_kernel Sparse(g): expands the bitmap (n/8 bytes)
 //                                      and gathers the values at the set bits
 //                bin_hist_kernel,      (slice variant) Sparse(g) x rows is partitioned by
@@ -27,7 +29,7 @@
 //                sketch_overflow_kernel (slice variant) inserts, with atomics, the
 //                                      non-zeros that did not fit the caller's list
 //   s2r_merge  : merge_kernel          S = sum_k S_k (ascending k), C = OR_k C_k
-//   s2r_decode : bitmap_count_kernel   per-tile popcounts of the aggregated bitmap
+//   s2r_decode : bitmap_count_kernel   per-piece popcounts of the aggregated bitmap
 //                tile_prefix_kernel
 //                decode_kernel         expands the bitmap; per index the d signed
 //                                      bucket reads and their median
@@ -48,12 +50,15 @@ constexpr int kWordsPerThread = kTileWords / kBlock;         // 2
 constexpr int kScanEPL = 8;                       // dense scan: bitmap words (loads in flight) per wave
 constexpr int kScanWords = kWavesPerBlock * kScanEPL;        // 32 words = 2048 elements per scan workgroup
 constexpr int kScansPerTile = kTileWords / kScanWords;       // 16
+constexpr int kCompactThreads = 256;              // workgroup of the list compaction (64 and 128 measured the same)
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
-constexpr int kPrefixPer = 32;                    // tile counts per thread per round
+constexpr int kPrefixPer = 8;                     // tiles per thread per round
 constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice workgroup
 constexpr int kSliceLog2Max = 15;                 // at most 2^15 cells = 128 KiB of LDS per slice (slices of
                                                   // 2^12..2^14 cells with 256..1024 threads measured the same)
 static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
+static_assert(kScanWords * 64 <= 0xFFFF, "a piece count must fit 16 bits");
+static_assert(kScansPerTile == 16, "tile_prefix_kernel reads a tile's piece counts as two 16-byte loads");
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));      // a 16-byte vector the nontemporal builtins accept
 
@@ -74,7 +79,7 @@ struct WorkerPtrs {
 struct EncodeBatch {
   WorkerPtrs w[S2R_MAX_WORKERS];
   uint64_t* nnz_out;         // [W]
-  char* workspace;           // W chunks of ws_stride bytes: tile counts | tile prefix | slice ids
+  char* workspace;           // W chunks of ws_stride bytes: piece counts | tile prefix | slice parts
   uint64_t ws_stride;
   uint64_t prefix_off;       // byte offset of the tile prefix inside a chunk
   uint64_t hist_off;         // slice variant: byte offsets inside a chunk of the per-chunk bin histogram
@@ -93,8 +98,8 @@ struct EncodeBatch {
   uint32_t nworkers;         // W; a workgroup whose worker is not below it leaves at once
 };
 
-__device__ __forceinline__ uint32_t* ws_count(const EncodeBatch& B, uint32_t k) {
-  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride);
+__device__ __forceinline__ uint16_t* ws_piece_count(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint16_t*>(B.workspace + k * B.ws_stride);
 }
 __device__ __forceinline__ uint64_t* ws_prefix(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint64_t*>(B.workspace + k * B.ws_stride + B.prefix_off);
@@ -110,8 +115,7 @@ __device__ __forceinline__ uint2* ws_records(const EncodeBatch& B, uint32_t k) {
 }
 
 // ------------------------------------------------------------------ zero
-// Per worker: zeroes the tile counters and, when nvec/ntail are non-zero, the
-// sketch (nvec 16-byte units plus ntail trailing floats).
+// Per worker: zeroes the sketch (nvec 16-byte units plus ntail trailing floats).
 __global__ __launch_bounds__(kBlock) void zero_kernel(const EncodeBatch B, uint64_t nvec, uint32_t ntail) {
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
@@ -120,8 +124,6 @@ __global__ __launch_bounds__(kBlock) void zero_kernel(const EncodeBatch B, uint6
   uint4* p16 = reinterpret_cast<uint4*>(B.w[k].sketch);
   for (uint64_t i = tid; i < nvec; i += stride) p16[i] = make_uint4(0u, 0u, 0u, 0u);
   if (tid < ntail) B.w[k].sketch[nvec * 4 + tid] = 0.0f;
-  uint32_t* count = ws_count(B, k);
-  for (uint64_t i = tid; i < B.ntiles; i += stride) count[i] = 0u;
 }
 
 // ------------------------------------------------------------------ encode: dense scan
@@ -140,7 +142,9 @@ __device__ __forceinline__ void sketch_insert(float* sketch, uint32_t d, uint32_
 // k = 0..EPL-1: every load instruction is one coalesced 256-byte row and its
 // ballot is bitmap word k.  Consecutive workgroups read consecutive 8 KiB, so the
 // workgroups resident at any time sweep one compact window of memory.  The
-// workgroup's non-zero count is added to its tile's counter (zeroed beforehand).
+// workgroup's non-zero count (at most 2048) is stored as piece blockIdx.x of the
+// worker's 16-bit piece counts; the grid covers every piece of every tile, so
+// the pieces past the end of the gradient are written too (as zero).
 template <int EPL, bool INSERT>
 __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_wave_count[kWavesPerBlock];
@@ -177,7 +181,9 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
       if (INSERT && nz) sketch_insert(P.sketch, B.d, B.log2w, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
     }
   }
-  if (lane < (uint32_t)EPL && word0 + lane < B.nwords) P.bitmap[word0 + lane] = parked;
+  // streaming store: the words are not read again by this kernel, and keeping them out of the L2 leaves it
+  // to the gradient stream (measured: 8 % shorter scans at 4 GB per gradient)
+  if (lane < (uint32_t)EPL && word0 + lane < B.nwords) __builtin_nontemporal_store(parked, &P.bitmap[word0 + lane]);
 
   if (lane == 0) s_wave_count[wv] = count;
   __syncthreads();
@@ -185,66 +191,78 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
     uint32_t t = 0;
 #pragma unroll
     for (int q = 0; q < kWavesPerBlock; ++q) t += s_wave_count[q];
-    if (t != 0) atomicAdd(&ws_count(B, worker)[blockIdx.x / kScansPerTile], t);
+    ws_piece_count(B, worker)[blockIdx.x] = (uint16_t)t;
   }
 }
 
-// ------------------------------------------------------------------ per-tile popcounts (decode)
-// One wave per tile: lane l reads words l, l+64, ... of the tile.
+// ------------------------------------------------------------------ per-piece popcounts (decode)
+// One wave per tile: lane l reads the 8 consecutive words 8l .. 8l+7, so lanes
+// 4p .. 4p+3 hold piece p (32 words) of the tile; lane 4p stores its count.
 __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
-                                                              uint32_t ntiles, uint32_t* __restrict__ tile_count) {
+                                                              uint32_t ntiles, uint16_t* __restrict__ piece_count) {
+  constexpr int kPer = kTileWords / kWave;                   // 8
+  static_assert(kScanWords == 4 * kPer, "a piece is the words of four lanes");
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t tile = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  if (tile >= ntiles) return;
-  const uint64_t w0 = (uint64_t)tile * kTileWords;
+  if (tile >= ntiles) return;                                // uniform over the wave
+  const uint64_t w0 = (uint64_t)tile * kTileWords + lane * kPer;
   uint32_t c = 0;
 #pragma unroll
-  for (int q = 0; q < kTileWords / kWave; ++q) {
-    const uint64_t w = w0 + q * kWave + lane;
-    c += w < nwords ? (uint32_t)__popcll(bitmap[w]) : 0u;
-  }
-  c = wave_sum_u32(c);
-  if (lane == 0) tile_count[tile] = c;
+  for (int q = 0; q < kPer; ++q) c += w0 + q < nwords ? (uint32_t)__popcll(bitmap[w0 + q]) : 0u;
+  c += __shfl_xor(c, 1);
+  c += __shfl_xor(c, 2);
+  if ((lane & 3u) == 0) piece_count[(uint64_t)tile * kScansPerTile + lane / 4] = (uint16_t)c;
 }
 
 // ------------------------------------------------------------------ prefix of the tile counts
-// Single workgroup.  prefix[t] = sum of count[0..t), prefix[ntiles] = total, also
-// written to *total_out.  A round covers kPrefixPer rows of 1024 consecutive
-// counts; thread t owns column t of every row, so all loads and stores are
-// coalesced and the kPrefixPer loads of a thread are in flight together.  Each row
-// is scanned inside its waves, the 32 x 16 wave totals are scanned by wave 0, and
-// every element adds the offset of its (row, wave).  n <= 2^32 gives at most 2^17
-// tiles: four rounds.
+// Single workgroup.  A tile's count is the sum of its kScansPerTile 16-bit piece
+// counts (32 bytes, two 16-byte loads).  prefix[t] = sum of the counts of tiles
+// 0..t-1, prefix[ntiles] = total, also written to *total_out.  A round covers
+// kPrefixPer rows of 1024 consecutive tiles; thread t owns column t of every row,
+// and its 2 * kPrefixPer loads are in flight together.  Each row is scanned inside
+// its waves, the kPrefixPer x 16 wave totals are scanned by wave 0, and every
+// element adds the offset of its (row, wave).  n <= 2^32 gives at most 2^17 tiles:
+// sixteen rounds.
 // blockIdx.y selects one of several independent problems (the workers of an
-// encode batch): its counts are at ws + y*ws_stride, its prefix at prefix_off
-// bytes after them, its total at total_out[y].
+// encode batch): its piece counts are at ws + y*ws_stride, its prefix at
+// prefix_off bytes after them, its total at total_out[y].
+__device__ __forceinline__ uint32_t sum_u16x8(const uint4 x) {
+  const uint32_t lo = (x.x & 0xFFFFu) + (x.y & 0xFFFFu) + (x.z & 0xFFFFu) + (x.w & 0xFFFFu);
+  const uint32_t hi = (x.x >> 16) + (x.y >> 16) + (x.z >> 16) + (x.w >> 16);
+  return lo + hi;
+}
+
 __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const char* __restrict__ ws, uint64_t ws_stride,
                                                                    uint64_t prefix_off, uint32_t ntiles,
                                                                    uint64_t* __restrict__ total_out) {
-  const uint32_t* __restrict__ count = reinterpret_cast<const uint32_t*>(ws + blockIdx.y * ws_stride);
+  const uint4* __restrict__ pieces = reinterpret_cast<const uint4*>(ws + blockIdx.y * ws_stride);
   uint64_t* __restrict__ prefix =
       reinterpret_cast<uint64_t*>(const_cast<char*>(ws) + blockIdx.y * ws_stride + prefix_off);
   constexpr int kWaves = kPrefixBlock / kWave;               // 16
-  constexpr int kCells = kPrefixPer * kWaves;                // 512 (row, wave) totals per round
+  constexpr int kCells = kPrefixPer * kWaves;                // (row, wave) totals per round
+  constexpr int kPerLane = kCells / kWave;
+  static_assert(kCells % kWave == 0, "wave 0 scans the totals, kPerLane per lane");
   __shared__ uint32_t s_tot[kCells + 1];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
   uint64_t carry = 0;
   for (uint32_t base = 0; base < ntiles; base += kPrefixBlock * kPrefixPer) {
+    uint4 lo16[kPrefixPer], hi16[kPrefixPer];
     uint32_t c[kPrefixPer], incl[kPrefixPer];
 #pragma unroll
     for (int q = 0; q < kPrefixPer; ++q) {
       const uint32_t i = base + q * kPrefixBlock + threadIdx.x;
-      c[q] = i < ntiles ? count[i] : 0u;
+      lo16[q] = i < ntiles ? pieces[2 * (uint64_t)i] : make_uint4(0u, 0u, 0u, 0u);
+      hi16[q] = i < ntiles ? pieces[2 * (uint64_t)i + 1] : make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int q = 0; q < kPrefixPer; ++q) {
+      c[q] = sum_u16x8(lo16[q]) + sum_u16x8(hi16[q]);
       incl[q] = wave_inclusive_scan_u32(c[q], lane);
       if (lane == kWave - 1) s_tot[q * kWaves + wv] = incl[q];
     }
     __syncthreads();
-    if (wv == 0) {             // exclusive scan of the 512 totals, 8 per lane; a round holds < 2^31 non-zeros
-      constexpr int kPerLane = kCells / kWave;
+    if (wv == 0) {             // exclusive scan of the totals; a round holds < 2^31 non-zeros
       uint32_t t[kPerLane], sum = 0;
 #pragma unroll
       for (int r = 0; r < kPerLane; ++r) { t[r] = s_tot[lane * kPerLane + r]; sum += t[r]; }
@@ -270,49 +288,62 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const char* _
 }
 
 // ------------------------------------------------------------------ bitmap tile in LDS
-// read_tile_words issues the loads of the tile's words (two per thread);
+// A workgroup of THREADS threads (a multiple of 64 that divides kTileWords) takes
+// one tile.  read_tile_words issues the loads of the tile's words (thread t owns
+// the kTileWords / THREADS consecutive words starting at that multiple of t);
 // scan_tile_words leaves them in T.words and the exclusive prefix of their
 // popcounts in T.prefix (T.prefix[kTileWords] = tile total).  All threads of the
 // workgroup call both; the second ends with a barrier.  They are separate so
 // that a kernel can have its other loads in flight together with the words'.
 struct TileBits {
   uint64_t words[kTileWords];
-  uint32_t prefix[kTileWords + 1];
-  uint32_t wave_count[kWavesPerBlock];
+  uint16_t prefix[kTileWords + 2];     // a tile has at most 32768 = 0x8000 set bits
+  uint32_t wave_count[kBlock / kWave];
 };
 
-__device__ __forceinline__ void read_tile_words(uint64_t (&wd)[kWordsPerThread], const uint64_t* __restrict__ bitmap,
+template <int THREADS>
+__device__ __forceinline__ void read_tile_words(uint64_t (&wd)[kTileWords / THREADS], const uint64_t* __restrict__ bitmap,
                                                 uint64_t nwords, uint64_t word0) {
+  constexpr int kPer = kTileWords / THREADS;
+  const uint64_t w0 = word0 + (uint64_t)threadIdx.x * kPer;
+  if (w0 + kPer <= nwords) {
 #pragma unroll
-  for (int q = 0; q < kWordsPerThread; ++q) {        // thread t owns words 2t, 2t+1
-    const uint64_t wi = word0 + (uint64_t)threadIdx.x * kWordsPerThread + q;
-    wd[q] = wi < nwords ? bitmap[wi] : 0ull;
+    for (int q = 0; q < kPer; ++q) wd[q] = bitmap[w0 + q];
+  } else {
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) wd[q] = w0 + q < nwords ? bitmap[w0 + q] : 0ull;
   }
 }
 
-__device__ __forceinline__ void scan_tile_words(TileBits& T, const uint64_t (&wd)[kWordsPerThread]) {
+template <int THREADS>
+__device__ __forceinline__ void scan_tile_words(TileBits& T, const uint64_t (&wd)[kTileWords / THREADS]) {
+  constexpr int kPer = kTileWords / THREADS;
+  constexpr int kWaves = THREADS / kWave;
+  static_assert(THREADS % kWave == 0 && kTileWords % THREADS == 0 && THREADS <= kBlock, "unsupported workgroup size");
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
-  uint32_t pc[kWordsPerThread];
+  uint32_t pc[kPer];
   uint32_t cnt = 0;
 #pragma unroll
-  for (int q = 0; q < kWordsPerThread; ++q) {
+  for (int q = 0; q < kPer; ++q) {
     pc[q] = (uint32_t)__popcll(wd[q]);
     cnt += pc[q];
   }
   const uint32_t incl = wave_inclusive_scan_u32(cnt, lane);
-  if (lane == kWave - 1) T.wave_count[wv] = incl;
-  __syncthreads();
   uint32_t run = incl - cnt;
+  if (kWaves > 1) {
+    if (lane == kWave - 1) T.wave_count[wv] = incl;
+    __syncthreads();
 #pragma unroll
-  for (int q = 0; q < kWavesPerBlock; ++q) run += (uint32_t)q < wv ? T.wave_count[q] : 0u;
+    for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? T.wave_count[q] : 0u;
+  }
 #pragma unroll
-  for (int q = 0; q < kWordsPerThread; ++q) {
-    T.words[threadIdx.x * kWordsPerThread + q] = wd[q];
-    T.prefix[threadIdx.x * kWordsPerThread + q] = run;
+  for (int q = 0; q < kPer; ++q) {
+    T.words[threadIdx.x * kPer + q] = wd[q];
+    T.prefix[threadIdx.x * kPer + q] = (uint16_t)run;
     run += pc[q];
   }
-  if (threadIdx.x == kBlock - 1) T.prefix[kTileWords] = run;
+  if (threadIdx.x == THREADS - 1) T.prefix[kTileWords] = (uint16_t)run;
   __syncthreads();
 }
 
@@ -329,7 +360,9 @@ __device__ __forceinline__ uint32_t locate_set_bit(const TileBits& T, uint32_t t
 }
 
 // ------------------------------------------------------------------ encode: Sparse(g)
-__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B) {
+// One workgroup of THREADS threads per tile.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void encode_compact_kernel(const EncodeBatch B) {
   __shared__ TileBits T;
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
@@ -337,20 +370,20 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
   const uint64_t* prefix = ws_prefix(B, k);
   const uint32_t tile = blockIdx.x;
   const uint64_t word0 = (uint64_t)tile * kTileWords;
-  uint64_t wd[kWordsPerThread];
-  read_tile_words(wd, P.bitmap, B.nwords, word0);      // in flight together with the two prefix loads
+  uint64_t wd[kTileWords / THREADS];
+  read_tile_words<THREADS>(wd, P.bitmap, B.nwords, word0);      // in flight together with the two prefix loads
   const uint64_t base = prefix[tile];
   const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
   if (total == 0 || base >= B.cap) return;         // uniform over the workgroup
-  scan_tile_words(T, wd);
+  scan_tile_words<THREADS>(T, wd);
   // four output slots per thread and trip, so that the four value gathers are in flight together
   constexpr int kSlots = 4;
-  for (uint32_t t0 = threadIdx.x; t0 < total; t0 += kBlock * kSlots) {
+  for (uint32_t t0 = threadIdx.x; t0 < total; t0 += THREADS * kSlots) {
     uint32_t i[kSlots], v[kSlots];
     bool live[kSlots];
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
-      const uint32_t t = t0 + u * kBlock;
+      const uint32_t t = t0 + u * THREADS;
       live[u] = t < total && base + t < B.cap;
       i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
@@ -359,7 +392,7 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
       if (!live[u]) continue;
-      const uint64_t pos = base + t0 + u * kBlock;
+      const uint64_t pos = base + t0 + u * THREADS;
       P.nz_idx[pos] = i[u];
       P.nz_val[pos] = v[u];
     }
@@ -577,9 +610,9 @@ __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBat
     if (base + total <= B.cap) continue;                 // uniform over the workgroup
     const uint64_t word0 = (uint64_t)tile * kTileWords;
     uint64_t wd[kWordsPerThread];
-    read_tile_words(wd, P.bitmap, B.nwords, word0);
+    read_tile_words<kBlock>(wd, P.bitmap, B.nwords, word0);
     __syncthreads();                                     // T may still be read by the previous tile's loop
-    scan_tile_words(T, wd);
+    scan_tile_words<kBlock>(T, wd);
     const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
     for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
       const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
@@ -697,7 +730,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
   const uint32_t tile = blockIdx.x;
   const uint64_t word0 = (uint64_t)tile * kTileWords;
   uint64_t wd[kWordsPerThread];
-  read_tile_words(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
+  read_tile_words<kBlock>(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
   const uint64_t base = A.prefix[tile];
   const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
 
@@ -713,7 +746,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
     if (r < e1) A.dense_out[r] = 0.0f;
   }
   if (total == 0) return;                          // uniform over the workgroup
-  scan_tile_words(T, wd);
+  scan_tile_words<kBlock>(T, wd);
   for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
     const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
     const float g = query<D>(A, hp, i);
@@ -771,10 +804,12 @@ static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
 
 static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kTileWords); }
 
-// workspace of one worker: [tile counts u32[ntiles]] [tile prefix u64[ntiles + 1]], and for the slice
+// workspace of one worker: [piece counts u16[ntiles * 16]] [tile prefix u64[ntiles + 1]], and for the slice
 // strategy [bin histogram u32[nchunks][nbins]] [bin starts u32[nbins + 1]] [records 8 B x d*cap]; each part
 // 256-byte aligned.  The slice parts exist only when the caller's workspace is large enough for its cap.
-static inline size_t workspace_prefix_off(uint64_t n) { return align256((size_t)tiles_of(n) * sizeof(uint32_t)); }
+static inline size_t workspace_prefix_off(uint64_t n) {
+  return align256((size_t)tiles_of(n) * kScansPerTile * sizeof(uint16_t));
+}
 static inline size_t workspace_base(uint64_t n) {
   return workspace_prefix_off(n) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
 }
@@ -798,26 +833,28 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
   return L;
 }
 
-// How s2r_encode forms the sketch.  Cost models from measurements on MI355X:
-//  - scattered float32 atomics retire at about 21e9 per second over the whole chip
-//    whatever their scope; issued from the dense scan, about half of the scan's own
-//    time hides them (when the non-zeros are spread over many workgroups);
-//  - the slice strategy adds four kernels: about 30 us of launches,
-//    12 us per round of 256 slice workgroups (clearing and storing 128 KiB of LDS
-//    each), and the records at about 60e9 per second;
+// How s2r_encode forms the sketch.  Cost models fitted to measurements on MI355X
+// (W = 4..16, n = 2^20..1e9, d = 3..5, w = 2^14..2^22):
+//  - atomics: the sketch is zeroed first (about 4.5e12 bytes per second); scattered
+//    float32 atomics retire at about 21e9 per second over the whole chip whatever
+//    their scope, and when the dense scan issues them it hides at best 60 % of
+//    that time (less when the non-zeros are clustered in few workgroups);
+//  - slices: four more kernels, about 30 us of launches; 16 us per round of 256
+//    slice workgroups (each clears 128 KiB of LDS, waits for its records and
+//    stores the slice); histogram and scatter pass about 140e9 records per second.
 // `cap` is the caller's bound on the number of non-zeros.
 static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap,
                                size_t workspace_bytes) {
+  (void)n;
   if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice strategy reads Sparse(g)
   const SliceLayout L = slice_layout(n, d, w, cap);
   if (!L.possible || workspace_bytes < L.total) return S2R_INSERT_ATOMIC;
   if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
+  const double records = (double)cap * d;
   const double rounds = (double)ceil_div((uint64_t)W * L.nbins, 256);       // all workers' slices share the CUs
-  const double t_slice = 30e-6 + rounds * 12e-6 + (double)W * cap * d / 60e9;
-  const double t_stream = 4.0 * (double)n / 6.0e12;
-  double t_atomic = (double)cap * d / 21.0e9 - 0.5 * t_stream;
-  if (t_atomic < 0) t_atomic = 0;
-  return t_slice < W * t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
+  const double t_slice = 30e-6 + rounds * 16e-6 + W * records / 140e9;
+  const double t_atomic = W * (4.0 * d * w / 4.5e12 + 0.4 * records / 21e9);
+  return t_slice < t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
 }
 
 static inline void record(int slot, bool end, hipStream_t st) {
@@ -957,27 +994,30 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.log2w = log2w;
   E.slice_log2 = L.slice_log2;
 
-  // Tile counters, and the sketch when the scan inserts into it with atomics; then the scan.  Measured on
-  // config 5 (4 GB per worker, 84 MB sketches): a scan whose sketch was zeroed just before it takes 760 us,
-  // against 820 us when all 16 sketches were zeroed first and 800 us in groups of three, so gradients of
-  // 1 GiB and more, for which two extra launches per worker cost nothing, are zeroed and scanned worker by
-  // worker.  Smaller ones gain more from single launches over the whole batch.
+  // The scan, preceded by the zeroing of the sketch when the scan inserts into it with atomics.  Gradients
+  // of 1 GiB and more are scanned worker by worker, smaller ones with one launch over the whole batch.
+  // Measured on config 5 (4 GB per worker, 84 MB sketches): one launch per worker takes 632 us per worker,
+  // one launch over all workers 649 us; with atomics, a scan whose sketch was zeroed just before it takes
+  // 760 us against 820 us when all 16 sketches were zeroed first.  Below 1 GiB the launches saved count more.
   const uint64_t cells = (uint64_t)d * w;
-  const uint64_t nvec = strategy == S2R_INSERT_ATOMIC ? cells / 4 : 0;
-  const uint32_t ntail = strategy == S2R_INSERT_ATOMIC ? (uint32_t)(cells - nvec * 4) : 0u;
-  uint64_t zb = ceil_div(nvec > ntiles ? nvec : ntiles, kBlock);
+  const bool atomics = strategy == S2R_INSERT_ATOMIC;
+  const uint64_t nvec = cells / 4;
+  const uint32_t ntail = (uint32_t)(cells - nvec * 4);
+  uint64_t zb = ceil_div(nvec > 0 ? nvec : 1, kBlock);
   if (zb > 2048) zb = 2048;
-  const uint32_t group = (strategy == S2R_INSERT_ATOMIC && n * sizeof(float) >= (1ull << 30)) ? 1u : W;
-  const uint32_t scan_blocks = (uint32_t)ceil_div(E.nwords, kScanWords);
+  const uint32_t group = n * sizeof(float) >= (1ull << 30) ? 1u : W;
+  const uint32_t scan_blocks = ntiles * kScansPerTile;        // every piece of every tile gets its count
   uint32_t last_group = 0;
   for (uint32_t k0 = 0; k0 < W; k0 += group) {
     const uint32_t gy = W - k0 < group ? W - k0 : group;      // workers k0 .. k0 + gy - 1, all < W
     const bool last = k0 + gy == W;                           // the events bracket the last scan launch
     E.first_worker = k0;
-    hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, gy), dim3(kBlock), 0, st, E, nvec, ntail);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    if (atomics) {
+      hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, gy), dim3(kBlock), 0, st, E, nvec, ntail);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+    }
     if (last) record(S2R_KERNEL_ENCODE_SCAN, false, st);
-    if (strategy == S2R_INSERT_ATOMIC)
+    if (atomics)
       hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true>), dim3(scan_blocks, gy), dim3(kBlock), 0, st, E, hp);
     else
       hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false>), dim3(scan_blocks, gy), dim3(kBlock), 0, st, E, hp);
@@ -993,7 +1033,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
   if (lists && cap > 0) {
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(ntiles, W), dim3(kBlock), 0, st, E);
+    hipLaunchKernelGGL(encode_compact_kernel<kCompactThreads>, dim3(ntiles, W), dim3(kCompactThreads), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
 
@@ -1092,10 +1132,10 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   const uint32_t ntiles = tiles_of(n);
   const uint64_t nwords = ceil_div(n, 64);
 
-  uint32_t* tile_count = reinterpret_cast<uint32_t*>(workspace);
+  uint16_t* piece_count = reinterpret_cast<uint16_t*>(workspace);
   uint64_t* tile_prefix = reinterpret_cast<uint64_t*>((char*)workspace + workspace_prefix_off(n));
   hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
-                     bitmap, nwords, ntiles, tile_count);
+                     bitmap, nwords, ntiles, piece_count);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, (const char*)workspace, (uint64_t)0,
                      (uint64_t)workspace_prefix_off(n), ntiles, count_out);
