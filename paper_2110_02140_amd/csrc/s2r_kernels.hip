@@ -53,13 +53,20 @@ constexpr int kScansPerTile = kTileWords / kScanWords;       // 16
 constexpr int kCompactThreads = 256;              // workgroup of the list compaction (64 and 128 measured the same)
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
 constexpr int kPrefixPer = 8;                     // tiles per thread per round
-constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice workgroup
-constexpr int kSliceLog2Max = 15;                 // at most 2^15 cells = 128 KiB of LDS per slice (slices of
-                                                  // 2^12..2^14 cells with 256..1024 threads measured the same)
+#ifndef S2R_SLICE_BLOCK
+#define S2R_SLICE_BLOCK 1024
+#endif
+#ifndef S2R_SLICE_LOG2_PREF
+#define S2R_SLICE_LOG2_PREF 14
+#endif
+constexpr int kSliceBlock = S2R_SLICE_BLOCK;      // threads of a sketch-slice workgroup
+constexpr int kSliceLog2Max = 14;                 // at most 2^14 cells = 128 KiB of float64 accumulators in LDS
+constexpr int kSliceLog2Pref = S2R_SLICE_LOG2_PREF;   // slice size used unless it gives too many bins
 static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
 static_assert(kScanWords * 64 <= 0xFFFF, "a piece count must fit 16 bits");
 static_assert(kScansPerTile == 16, "tile_prefix_kernel reads a tile's piece counts as two 16-byte loads");
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));      // a 16-byte vector the nontemporal builtins accept
 
 static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -196,22 +203,47 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
 }
 
 // ------------------------------------------------------------------ per-piece popcounts (decode)
-// One wave per tile: lane l reads the 8 consecutive words 8l .. 8l+7, so lanes
-// 4p .. 4p+3 hold piece p (32 words) of the tile; lane 4p stores its count.
+// One wave per tile: lane l reads words l, l + 64, ... of the tile (coalesced), so
+// word q of a lane belongs to piece 2q (lanes 0..31) or 2q + 1 (lanes 32..63).
+// The eight popcounts travel as four pairs of 16-bit fields through a butterfly
+// over each half of the wave (a field holds at most 32 * 64); lane 0 then owns
+// the even pieces, fetches the odd ones from lane 32 and stores the tile's 16
+// counts as 32 contiguous bytes.
 __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
                                                               uint32_t ntiles, uint16_t* __restrict__ piece_count) {
   constexpr int kPer = kTileWords / kWave;                   // 8
-  static_assert(kScanWords == 4 * kPer, "a piece is the words of four lanes");
+  static_assert(kScanWords == kWave / 2 && kScansPerTile == 2 * kPer, "a piece is the words of half a wave");
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t tile = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
   if (tile >= ntiles) return;                                // uniform over the wave
-  const uint64_t w0 = (uint64_t)tile * kTileWords + lane * kPer;
-  uint32_t c = 0;
+  const uint64_t w0 = (uint64_t)tile * kTileWords;
+  uint32_t pk[kPer / 2];
 #pragma unroll
-  for (int q = 0; q < kPer; ++q) c += w0 + q < nwords ? (uint32_t)__popcll(bitmap[w0 + q]) : 0u;
-  c += __shfl_xor(c, 1);
-  c += __shfl_xor(c, 2);
-  if ((lane & 3u) == 0) piece_count[(uint64_t)tile * kScansPerTile + lane / 4] = (uint16_t)c;
+  for (int r = 0; r < kPer / 2; ++r) {
+    const uint64_t wa = w0 + (2 * r) * kWave + lane, wb = wa + kWave;
+    const uint32_t ca = wa < nwords ? (uint32_t)__popcll(bitmap[wa]) : 0u;
+    const uint32_t cb = wb < nwords ? (uint32_t)__popcll(bitmap[wb]) : 0u;
+    pk[r] = ca | (cb << 16);
+  }
+#pragma unroll
+  for (int step = 1; step < kWave / 2; step <<= 1) {
+#pragma unroll
+    for (int r = 0; r < kPer / 2; ++r) pk[r] += (uint32_t)__shfl_xor((int)pk[r], step);
+  }
+  uint32_t odd[kPer / 2];
+#pragma unroll
+  for (int r = 0; r < kPer / 2; ++r) odd[r] = (uint32_t)__shfl_xor((int)pk[r], kWave / 2);
+  if (lane == 0) {
+    uint32_t o[kPer];                                        // o[q] = piece 2q | piece 2q + 1 << 16
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      const uint32_t sh = 16u * (q & 1);
+      o[q] = ((pk[q / 2] >> sh) & 0xFFFFu) | (((odd[q / 2] >> sh) & 0xFFFFu) << 16);
+    }
+    uint4* dst = reinterpret_cast<uint4*>(piece_count + (uint64_t)tile * kScansPerTile);    // 32-byte aligned
+    dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+    dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+  }
 }
 
 // ------------------------------------------------------------------ prefix of the tile counts
@@ -401,7 +433,7 @@ __global__ __launch_bounds__(THREADS) void encode_compact_kernel(const EncodeBat
 
 // ------------------------------------------------------------------ encode: sketch by LDS slices
 // The insertions S[j, h_j(i)] += s_j(i) g(i) without global atomics.  Row j of the
-// sketch is cut into slices of 2^slice_log2 cells (128 KiB of LDS); bin (j, s)
+// sketch is cut into slices of 2^slice_log2 cells (float64 accumulators in LDS); bin (j, s)
 // collects the pairs (item, row j) whose bucket falls in slice s.  A counting sort
 // over the listed items brings each bin's records together:
 //   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins
@@ -409,14 +441,15 @@ __global__ __launch_bounds__(THREADS) void encode_compact_kernel(const EncodeBat
 //   bin_scatter_kernel  writes each record (cell in the slice | sign bit, value)
 //                       into its run (order inside a run is arbitrary)
 //   sketch_slice_kernel workgroup (j, s) clears its slice in LDS, adds its bin's
-//                       records with LDS float atomics and stores the slice
+//                       records with LDS float64 atomics and stores the slice as float32
 // Work is O(items x rows), whatever the number of slices, and every cell of the
 // sketch is written exactly once by plain coalesced stores.
 constexpr int kBinBlock = 1024;
-constexpr int kBinItems = 16;                          // list items per thread
-constexpr int kBinChunk = kBinBlock * kBinItems;       // 16384 items per workgroup
-constexpr int kMaxBins = 4096;                         // d * slices per row that the LDS histograms hold
-constexpr size_t kSliceLdsMax = sizeof(float) << kSliceLog2Max;
+constexpr int kBinItems = 8;                           // list items per thread
+constexpr int kBinChunk = kBinBlock * kBinItems;       // 8192 items per workgroup
+constexpr int kMaxBins = 8192;                         // d * slices per row that the LDS histograms hold
+constexpr size_t kSliceLdsMax = sizeof(double) << kSliceLog2Max;
+static_assert(kMaxBins <= (1 << 13) && kSliceLog2Max <= 14, "bin_scatter_kernel packs slice and cell into one word");
 
 __device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t k) {
   const uint64_t nnz = B.nnz_out[k];
@@ -459,7 +492,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B
 // (bin_start[nbins] = all records).  Thread t owns bins t, t + 1024, ...: for a
 // fixed chunk the threads read consecutive counters.
 __global__ __launch_bounds__(kBinBlock) void bin_scan_kernel(const EncodeBatch B) {
-  constexpr int kPerThread = kMaxBins / kBinBlock;       // 4
+  constexpr int kPerThread = kMaxBins / kBinBlock;       // 8
   constexpr int kWaves = kBinBlock / kWave;
   __shared__ uint32_t s_wave[kWaves];
   const uint32_t k = blockIdx.y;
@@ -509,79 +542,168 @@ __global__ __launch_bounds__(kBinBlock) void bin_scan_kernel(const EncodeBatch B
   if (threadIdx.x == 0) bin_start[B.nbins] = carry;
 }
 
+// One workgroup per chunk of kBinChunk list items, one pass per sketch row j.  The
+// chunk's records for row j are first sorted by slice inside LDS (a counting
+// sort: LDS counters give every record its rank in its slice, a scan of the
+// counters gives the start of every slice's run) and then copied out in sorted
+// order, so that consecutive lanes write consecutive records of the (chunk, bin)
+// run that the histogram pass reserved.  In LDS a record carries its slice number
+// in bits 16..28 of its first word (the cell takes bits 0..13, the sign bit 31).
+// Dynamic LDS: kBinChunk records, then two arrays of (slices per row) counters.
 __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
-  __shared__ uint32_t s_cursor[kMaxBins];                 // next free record of each bin's run of this chunk
+  extern __shared__ uint2 s_stage[];
+  constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;           // counters per thread in the scan, at most
+  __shared__ uint32_t s_wave[kWaves];
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
   const uint32_t chunk = blockIdx.x;
+  const uint64_t have = listed_items(B, k);
+  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
+  if (t0 >= have) return;                                 // uniform over the workgroup
+  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;
+  const uint32_t spr = 1u << spr_log2;                    // slices per row
+  uint32_t* s_loc = reinterpret_cast<uint32_t*>(s_stage + kBinChunk);
+  uint32_t* s_delta = s_loc + spr;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const WorkerPtrs P = B.w[k];
   const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
   const uint32_t* bin_start = ws_bin_start(B, k);
-  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_cursor[b] = bin_start[b] + hist[b];
-  __syncthreads();
-  const uint64_t have = listed_items(B, k);
-  const WorkerPtrs P = B.w[k];
   uint2* __restrict__ rec = ws_records(B, k);
-  const uint32_t spr_log2 = B.log2w - B.slice_log2;
   const uint32_t mask = (1u << B.slice_log2) - 1u;
+  const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan (<= kMaxPer)
+
   uint32_t i[kBinItems], v[kBinItems];
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
-    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-    i[u] = t < have ? P.nz_idx[t] : 0u;
-    v[u] = t < have ? P.nz_val[t] : 0u;
+    const uint32_t t = u * kBinBlock + threadIdx.x;
+    i[u] = t < count ? P.nz_idx[t0 + t] : 0u;
+    v[u] = t < count ? P.nz_val[t0 + t] : 0u;
   }
+  for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
+
+  for (uint32_t j = 0; j < B.d; ++j) {
+    // where the runs of this (chunk, row) start in the worker's records; needed after the scan
+    uint32_t gpos[kMaxPer];
 #pragma unroll
-  for (int u = 0; u < kBinItems; ++u) {
-    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-    if (t < have) {
-      for (uint32_t j = 0; j < B.d; ++j) {
+    for (int q = 0; q < kMaxPer; ++q) {
+      const uint32_t e = threadIdx.x * per + q;
+      gpos[q] = ((uint32_t)q < per && e < spr) ? bin_start[(j << spr_log2) + e] + hist[(j << spr_log2) + e] : 0u;
+    }
+    __syncthreads();                                      // s_loc is zero, s_stage is free
+    uint32_t key[kBinItems], rank[kBinItems];
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (u * kBinBlock + threadIdx.x < count) {
         const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
-        const uint32_t bin = (j << spr_log2) + (h >> B.slice_log2);
-        const uint32_t pos = __hip_atomic_fetch_add(&s_cursor[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        rec[pos] = make_uint2((h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]), v[u]);
+        const uint32_t sl = h >> B.slice_log2;
+        key[u] = (h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]) | (sl << 16);
+        rank[u] = __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
+    __syncthreads();
+    // exclusive scan of the counters; thread t owns counters t*per .. t*per + per - 1
+    uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
+      const uint32_t e = threadIdx.x * per + q;
+      c[q] = ((uint32_t)q < per && e < spr) ? s_loc[e] : 0u;
+      sum += c[q];
+    }
+    const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    uint32_t run = incl - sum;
+#pragma unroll
+    for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
+      const uint32_t e = threadIdx.x * per + q;
+      if ((uint32_t)q < per && e < spr) {
+        s_loc[e] = run;
+        s_delta[e] = gpos[q] - run;                       // sorted position p of slice e goes to record p + delta
+        run += c[q];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (u * kBinBlock + threadIdx.x < count)
+        s_stage[s_loc[(key[u] >> 16) & 0x1FFFu] + rank[u]] = make_uint2(key[u], v[u]);
+    }
+    __syncthreads();
+    for (uint32_t p = threadIdx.x; p < count; p += kBinBlock) {
+      const uint2 r = s_stage[p];
+      rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80003FFFu, r.y);
+    }
+    for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;      // for the next row; not read above
   }
 }
 
-// Workgroup = bin (j, s) of worker blockIdx.y.
+// Workgroup = bin (j, s) of worker blockIdx.y.  The slice is accumulated in
+// float64: the LDS float64 atomic add runs at full LDS rate on this chip (about
+// 1.7e12 per second over the chip at random addresses) while the float32 one
+// takes a slow path (0.2e12 per second, whatever the addresses); each cell is
+// rounded to float32 once, when the slice is stored.  The first records are
+// requested before the slice is cleared, and each later batch while the previous
+// one is added.
 __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B) {
-  extern __shared__ float s_slice[];
+  extern __shared__ double s_slice[];
   constexpr int kAhead = 4;                               // 8-byte record loads in flight per thread
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
   const uint32_t cells = 1u << B.slice_log2;
-  if (cells >= 4u * kSliceBlock) {                        // (the LDS array and every slice are 16-byte aligned)
-    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
-      reinterpret_cast<float4*>(s_slice)[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+  const uint32_t* bin_start = ws_bin_start(B, k);
+  const uint32_t first = bin_start[bin], last = bin_start[bin + 1];
+  const u32x2* __restrict__ rec = reinterpret_cast<const u32x2*>(ws_records(B, k));
+  const u32x2 none = {0u, 0u};
+  u32x2 x[kAhead];
+  uint64_t r0 = (uint64_t)first + threadIdx.x;            // 64 bits: positions near 2^32 must not wrap
+#pragma unroll
+  for (int u = 0; u < kAhead; ++u)
+    x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&rec[r0 + u * kSliceBlock]) : none;
+
+  if (cells >= 2u * kSliceBlock) {                        // (the LDS array is 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 2; c += kSliceBlock)
+      reinterpret_cast<double2*>(s_slice)[c] = make_double2(0.0, 0.0);
   } else {
-    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0f;
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0;
   }
   __syncthreads();
 
-  const uint32_t* bin_start = ws_bin_start(B, k);
-  const uint32_t first = bin_start[bin], last = bin_start[bin + 1];
-  const uint2* __restrict__ rec = ws_records(B, k);
-  for (uint32_t r0 = first + threadIdx.x; r0 < last; r0 += kSliceBlock * kAhead) {
-    uint2 x[kAhead];
+  while (r0 < last) {                                     // x holds the records r0 + u * kSliceBlock
+    const uint64_t r1 = r0 + kSliceBlock * kAhead;
+    u32x2 y[kAhead];
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u) x[u] = r0 + u * kSliceBlock < last ? rec[r0 + u * kSliceBlock] : make_uint2(0u, 0u);
+    for (int u = 0; u < kAhead; ++u)
+      y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&rec[r1 + u * kSliceBlock]) : none;
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
       if (r0 + u * kSliceBlock < last)
-        __hip_atomic_fetch_add(&s_slice[x[u].x & 0x7FFFFFFFu], __uint_as_float(x[u].y ^ (x[u].x & 0x80000000u)),
+        __hip_atomic_fetch_add(&s_slice[x[u].x & 0x7FFFFFFFu],
+                               (double)__uint_as_float(x[u].y ^ (x[u].x & 0x80000000u)),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) x[u] = y[u];
+    r0 = r1;
   }
   __syncthreads();
   // bin = j * slices-per-row + s, so the slice starts at cell bin * cells of the row-major sketch
   float* out = B.w[k].sketch + (uint64_t)bin * cells;
-  if (cells >= 4u * kSliceBlock) {
-    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
-      reinterpret_cast<float4*>(out)[c] = reinterpret_cast<const float4*>(s_slice)[c];
+  if (cells >= 4u * kSliceBlock) {                        // (every slice of 4 cells or more is 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock) {
+      const double2 lo = reinterpret_cast<const double2*>(s_slice)[2 * c];
+      const double2 hi = reinterpret_cast<const double2*>(s_slice)[2 * c + 1];
+      f32x4 o;
+      o.x = (float)lo.x; o.y = (float)lo.y; o.z = (float)hi.x; o.w = (float)hi.y;
+      __builtin_nontemporal_store(o, &reinterpret_cast<f32x4*>(out)[c]);
+    }
   } else {
-    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = s_slice[c];
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = (float)s_slice[c];
   }
 }
 
@@ -821,7 +943,9 @@ struct SliceLayout {
 static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   SliceLayout L;
   const uint32_t log2w = log2_of(w);
-  L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+  L.slice_log2 = log2w < (uint32_t)kSliceLog2Pref ? log2w : (uint32_t)kSliceLog2Pref;
+  while (((uint64_t)d << (log2w - L.slice_log2)) > (uint64_t)kMaxBins && L.slice_log2 < (uint32_t)kSliceLog2Max)
+    ++L.slice_log2;
   const uint64_t nbins = (uint64_t)d << (log2w - L.slice_log2);
   L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0;
   L.nbins = (uint32_t)(L.possible ? nbins : 0);
@@ -1038,11 +1162,14 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   }
 
   if (strategy == S2R_INSERT_SLICE) {
-    const size_t lds = sizeof(float) << E.slice_log2;
+    const size_t lds = sizeof(double) << E.slice_log2;
     static thread_local bool lds_raised = false;
     if (!lds_raised) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess)
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess ||
+          hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * kMaxBins)) != hipSuccess)
         return S2R_ERR_LAUNCH;
       lds_raised = true;
     }
@@ -1050,7 +1177,8 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_scan_kernel, dim3(1, W), dim3(kBinBlock), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, W), dim3(kBinBlock), 0, st, E, hp);
+    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (log2w - E.slice_log2));
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, W), dim3(kBinBlock), scatter_lds, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     record(S2R_KERNEL_ENCODE_SLICE, false, st);
     hipLaunchKernelGGL(sketch_slice_kernel, dim3(E.nbins, W), dim3(kSliceBlock), lds, st, E);
