@@ -18,7 +18,9 @@
 //                tile_prefix_kernel    tile counts from the piece counts, their
 //                                      exclusive prefix, total
 //                encode_compact_kernel Sparse(g): expands the bitmap (n/8 bytes)
-//                                      and gathers the values at the set bits
+//                                      and gathers the values at the set bits; tiles
+//                                      with more than kGroupSlots set bits get
+//                                      extra workgroups through a dense-tile list
 //                bin_hist_kernel,      (slice variant) Sparse(g) x rows is partitioned by
 //                bin_scan_kernel,      sketch slice (counting sort: histogram per chunk,
 //                bin_scatter_kernel    offsets, scatter of (cell, signed value) records)
@@ -50,7 +52,9 @@ constexpr int kWordsPerThread = kTileWords / kBlock;         // 2
 constexpr int kScanEPL = 8;                       // dense scan: bitmap words (loads in flight) per wave
 constexpr int kScanWords = kWavesPerBlock * kScanEPL;        // 32 words = 2048 elements per scan workgroup
 constexpr int kScansPerTile = kTileWords / kScanWords;       // 16
-constexpr int kCompactThreads = 256;              // workgroup of the list compaction (64 and 128 measured the same)
+constexpr int kGroupSlots = 2048;                 // list positions one expansion workgroup handles; a tile with more
+                                                  // set bits gets extra workgroups through the dense-tile list
+constexpr int kGroupsPerTile = kTileElems / kGroupSlots;     // 16
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
 constexpr int kPrefixPer = 8;                     // tiles per thread per round
 #ifndef S2R_SLICE_BLOCK
@@ -89,6 +93,7 @@ struct EncodeBatch {
   char* workspace;           // W chunks of ws_stride bytes: piece counts | tile prefix | slice parts
   uint64_t ws_stride;
   uint64_t prefix_off;       // byte offset of the tile prefix inside a chunk
+  uint64_t dense_off;        // byte offset of the dense-tile list (count, then entries 256 bytes later)
   uint64_t hist_off;         // slice variant: byte offsets inside a chunk of the per-chunk bin histogram
   uint64_t binstart_off;     //   [nchunks][nbins] u32, the bin starts [nbins + 1] u32,
   uint64_t rec_off;          //   and the binned records [d * cap] of 8 bytes
@@ -110,6 +115,9 @@ __device__ __forceinline__ uint16_t* ws_piece_count(const EncodeBatch& B, uint32
 }
 __device__ __forceinline__ uint64_t* ws_prefix(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint64_t*>(B.workspace + k * B.ws_stride + B.prefix_off);
+}
+__device__ __forceinline__ const uint32_t* ws_dense_list(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<const uint32_t*>(B.workspace + k * B.ws_stride + B.dense_off);
 }
 __device__ __forceinline__ uint32_t* ws_bin_hist(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.hist_off);
@@ -255,6 +263,11 @@ __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __
 // its waves, the kPrefixPer x 16 wave totals are scanned by wave 0, and every
 // element adds the offset of its (row, wave).  n <= 2^32 gives at most 2^17 tiles:
 // sixteen rounds.
+// Tiles with more than kGroupSlots set bits are also entered in the problem's
+// dense-tile list: one entry (tile | group << 20) for every further group of
+// kGroupSlots list positions, in arbitrary order, preceded by the entry count
+// (at dense_off: the count, 256 bytes later the entries).  The expansion kernels
+// give each entry a workgroup of its own.
 // blockIdx.y selects one of several independent problems (the workers of an
 // encode batch): its piece counts are at ws + y*ws_stride, its prefix at
 // prefix_off bytes after them, its total at total_out[y].
@@ -264,12 +277,16 @@ __device__ __forceinline__ uint32_t sum_u16x8(const uint4 x) {
   return lo + hi;
 }
 
-__global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const char* __restrict__ ws, uint64_t ws_stride,
-                                                                   uint64_t prefix_off, uint32_t ntiles,
-                                                                   uint64_t* __restrict__ total_out) {
+__global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(char* __restrict__ ws, uint64_t ws_stride,
+                                                                   uint64_t prefix_off, uint64_t dense_off,
+                                                                   uint32_t ntiles, uint64_t* __restrict__ total_out) {
   const uint4* __restrict__ pieces = reinterpret_cast<const uint4*>(ws + blockIdx.y * ws_stride);
-  uint64_t* __restrict__ prefix =
-      reinterpret_cast<uint64_t*>(const_cast<char*>(ws) + blockIdx.y * ws_stride + prefix_off);
+  uint64_t* __restrict__ prefix = reinterpret_cast<uint64_t*>(ws + blockIdx.y * ws_stride + prefix_off);
+  uint32_t* __restrict__ dense_count = reinterpret_cast<uint32_t*>(ws + blockIdx.y * ws_stride + dense_off);
+  uint32_t* __restrict__ dense_list = dense_count + 64;
+  __shared__ uint32_t s_dense;
+  if (threadIdx.x == 0) s_dense = 0u;
+  __syncthreads();
   constexpr int kWaves = kPrefixBlock / kWave;               // 16
   constexpr int kCells = kPrefixPer * kWaves;                // (row, wave) totals per round
   constexpr int kPerLane = kCells / kWave;
@@ -290,6 +307,12 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const char* _
 #pragma unroll
     for (int q = 0; q < kPrefixPer; ++q) {
       c[q] = sum_u16x8(lo16[q]) + sum_u16x8(hi16[q]);
+      if (c[q] > (uint32_t)kGroupSlots) {          // at most kGroupsPerTile - 1 further groups
+        const uint32_t more = (c[q] - 1u) / kGroupSlots;
+        const uint32_t at = __hip_atomic_fetch_add(&s_dense, more, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t tile = base + q * kPrefixBlock + threadIdx.x;
+        for (uint32_t g = 1; g <= more; ++g) dense_list[at + g - 1] = tile | (g << 20);
+      }
       incl[q] = wave_inclusive_scan_u32(c[q], lane);
       if (lane == kWave - 1) s_tot[q * kWaves + wv] = incl[q];
     }
@@ -313,9 +336,10 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(const char* _
     carry += s_tot[kCells];
     __syncthreads();               // s_tot is rewritten in the next round
   }
-  if (threadIdx.x == 0) {
+  if (threadIdx.x == 0) {                          // (after the last round's closing barrier)
     prefix[ntiles] = carry;
     total_out[blockIdx.y] = carry;
+    *dense_count = s_dense;
   }
 }
 
@@ -392,31 +416,28 @@ __device__ __forceinline__ uint32_t locate_set_bit(const TileBits& T, uint32_t t
 }
 
 // ------------------------------------------------------------------ encode: Sparse(g)
-// One workgroup of THREADS threads per tile.
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void encode_compact_kernel(const EncodeBatch B) {
-  __shared__ TileBits T;
-  const uint32_t k = blockIdx.y;
-  if (k >= B.nworkers) return;                           // uniform over the workgroup
-  const WorkerPtrs P = B.w[k];
-  const uint64_t* prefix = ws_prefix(B, k);
-  const uint32_t tile = blockIdx.x;
+// List positions [group * kGroupSlots, (group + 1) * kGroupSlots) of one tile, by
+// one workgroup of kBlock threads.  All threads call it with the same arguments.
+__device__ __forceinline__ void compact_group(const EncodeBatch& B, const WorkerPtrs& P, const uint64_t* prefix,
+                                              TileBits& T, uint32_t tile, uint32_t group) {
   const uint64_t word0 = (uint64_t)tile * kTileWords;
-  uint64_t wd[kTileWords / THREADS];
-  read_tile_words<THREADS>(wd, P.bitmap, B.nwords, word0);      // in flight together with the two prefix loads
+  uint64_t wd[kWordsPerThread];
+  read_tile_words<kBlock>(wd, P.bitmap, B.nwords, word0);      // in flight together with the two prefix loads
   const uint64_t base = prefix[tile];
   const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
-  if (total == 0 || base >= B.cap) return;         // uniform over the workgroup
-  scan_tile_words<THREADS>(T, wd);
+  const uint32_t first = group * kGroupSlots;
+  if (first >= total || base + first >= B.cap) return;          // uniform over the workgroup
+  const uint32_t last = total - first > (uint32_t)kGroupSlots ? first + kGroupSlots : total;
+  scan_tile_words<kBlock>(T, wd);
   // four output slots per thread and trip, so that the four value gathers are in flight together
   constexpr int kSlots = 4;
-  for (uint32_t t0 = threadIdx.x; t0 < total; t0 += THREADS * kSlots) {
+  for (uint32_t t0 = first + threadIdx.x; t0 < last; t0 += kBlock * kSlots) {
     uint32_t i[kSlots], v[kSlots];
     bool live[kSlots];
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
-      const uint32_t t = t0 + u * THREADS;
-      live[u] = t < total && base + t < B.cap;
+      const uint32_t t = t0 + u * kBlock;
+      live[u] = t < last && base + t < B.cap;
       i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
 #pragma unroll
@@ -424,10 +445,31 @@ __global__ __launch_bounds__(THREADS) void encode_compact_kernel(const EncodeBat
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
       if (!live[u]) continue;
-      const uint64_t pos = base + t0 + u * THREADS;
+      const uint64_t pos = base + t0 + u * kBlock;
       P.nz_idx[pos] = i[u];
       P.nz_val[pos] = v[u];
     }
+  }
+}
+
+// The first `helpers` workgroups of a worker take the further groups of the tiles
+// in the dense-tile list, one entry per trip (they start first: theirs is the
+// longest work); workgroup helpers + t takes the first kGroupSlots list positions
+// of tile t.
+__global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B, uint32_t helpers) {
+  __shared__ TileBits T;
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  if (blockIdx.x >= helpers) {
+    compact_group(B, B.w[k], ws_prefix(B, k), T, blockIdx.x - helpers, 0u);
+    return;
+  }
+  const uint32_t* dense = ws_dense_list(B, k);
+  const uint32_t entries = dense[0];
+  for (uint32_t e = blockIdx.x; e < entries; e += helpers) {
+    const uint32_t entry = dense[64 + e];
+    __syncthreads();                                     // T may still be read by the previous trip
+    compact_group(B, B.w[k], ws_prefix(B, k), T, entry & 0xFFFFFu, entry >> 20);
   }
 }
 
@@ -810,6 +852,7 @@ struct DecodeArgs {
   uint32_t d;
   uint32_t log2w;
   const uint64_t* prefix;    // [ntiles + 1]
+  const uint32_t* dense;     // dense-tile list: count, 64 words later the entries
   uint32_t* idx_out;         // may be null
   float* val_out;            // may be null
   uint64_t cap;
@@ -846,19 +889,21 @@ __device__ __forceinline__ float query(const DecodeArgs& A, const HashRows& hp, 
   return median_fixed<D>(est);
 }
 
+// List positions [group * kGroupSlots, (group + 1) * kGroupSlots) of one tile, by
+// one workgroup of kBlock threads; group 0 also clears the tile's part of the
+// dense output first (the kernel that handles the further groups runs afterwards).
 template <int D>
-__global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, const HashRows hp) {
-  __shared__ TileBits T;
-  const uint32_t tile = blockIdx.x;
+__device__ __forceinline__ void decode_group(const DecodeArgs& A, const HashRows& hp, TileBits& T, uint32_t tile,
+                                             uint32_t group) {
   const uint64_t word0 = (uint64_t)tile * kTileWords;
   uint64_t wd[kWordsPerThread];
   read_tile_words<kBlock>(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
   const uint64_t base = A.prefix[tile];
   const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
 
-  // dense output: this workgroup owns the tile's elements; clear them first, the
-  // estimates are written over the zeros after the barrier in scan_tile_words
-  if (A.dense_out != nullptr) {
+  // dense output: group 0 owns the tile's elements; it clears them, and the estimates are
+  // written over the zeros after the barrier in scan_tile_words
+  if (group == 0 && A.dense_out != nullptr) {
     const uint64_t e0 = word0 * 64;
     const uint64_t e1 = min(A.n, e0 + (uint64_t)kTileElems);
     float4* p4 = reinterpret_cast<float4*>(A.dense_out + e0);     // e0 is a multiple of 64 elements
@@ -867,17 +912,54 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
     const uint64_t r = e0 + n4 * 4 + threadIdx.x;
     if (r < e1) A.dense_out[r] = 0.0f;
   }
-  if (total == 0) return;                          // uniform over the workgroup
+  const uint32_t first = group * kGroupSlots;
+  if (first >= total) return;                      // uniform over the workgroup
+  const uint32_t last = total - first > (uint32_t)kGroupSlots ? first + kGroupSlots : total;
   scan_tile_words<kBlock>(T, wd);
-  for (uint32_t t = threadIdx.x; t < total; t += kBlock) {
-    const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
-    const float g = query<D>(A, hp, i);
-    const uint64_t pos = base + t;
-    if (A.idx_out != nullptr && pos < A.cap) {
-      A.idx_out[pos] = i;
-      A.val_out[pos] = g;
+  // two list positions per thread and trip: 2 D bucket reads in flight
+  constexpr int kSlots = 2;
+  for (uint32_t t0 = first + threadIdx.x; t0 < last; t0 += kBlock * kSlots) {
+    uint32_t i[kSlots];
+    float g[kSlots];
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      const uint32_t t = t0 + u * kBlock;
+      i[u] = t < last ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
-    if (A.dense_out != nullptr) A.dense_out[i] = g;
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) g[u] = t0 + u * kBlock < last ? query<D>(A, hp, i[u]) : 0.0f;
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      const uint32_t t = t0 + u * kBlock;
+      if (t >= last) continue;
+      const uint64_t pos = base + t;
+      if (A.idx_out != nullptr && pos < A.cap) {
+        A.idx_out[pos] = i[u];
+        A.val_out[pos] = g[u];
+      }
+      if (A.dense_out != nullptr) A.dense_out[i[u]] = g[u];
+    }
+  }
+}
+
+// Workgroups below `helpers` take the further groups of the tiles in the
+// dense-tile list (A.dense: the entry count, 64 words later the entries), one
+// entry per trip; workgroup helpers + t takes group 0 of tile t.  With a dense output the two kinds must
+// not share a launch (group 0 clears the tile's part of it): the host then
+// launches the tiles alone (helpers = 0) and afterwards the helpers alone
+// (tiles = 0).
+template <int D>
+__global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, const HashRows hp, uint32_t helpers) {
+  __shared__ TileBits T;
+  if (blockIdx.x >= helpers) {
+    decode_group<D>(A, hp, T, blockIdx.x - helpers, 0u);
+    return;
+  }
+  const uint32_t entries = A.dense[0];
+  for (uint32_t e = blockIdx.x; e < entries; e += helpers) {
+    const uint32_t entry = A.dense[64 + e];
+    __syncthreads();                                     // T may still be read by the previous trip
+    decode_group<D>(A, hp, T, entry & 0xFFFFFu, entry >> 20);
   }
 }
 
@@ -926,14 +1008,23 @@ static s2r_status check_sizes(uint64_t n, uint32_t d, uint32_t w) {
 
 static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div(n, 64), kTileWords); }
 
-// workspace of one worker: [piece counts u16[ntiles * 16]] [tile prefix u64[ntiles + 1]], and for the slice
+// workspace of one worker: [piece counts u16[ntiles * 16]] [tile prefix u64[ntiles + 1]]
+// [dense-tile list: count u32, at +256 bytes entries u32[ntiles * 16]], and for the slice
 // strategy [bin histogram u32[nchunks][nbins]] [bin starts u32[nbins + 1]] [records 8 B x d*cap]; each part
 // 256-byte aligned.  The slice parts exist only when the caller's workspace is large enough for its cap.
 static inline size_t workspace_prefix_off(uint64_t n) {
   return align256((size_t)tiles_of(n) * kScansPerTile * sizeof(uint16_t));
 }
-static inline size_t workspace_base(uint64_t n) {
+static inline size_t workspace_dense_off(uint64_t n) {
   return workspace_prefix_off(n) + align256(((size_t)tiles_of(n) + 1) * sizeof(uint64_t));
+}
+static inline size_t workspace_base(uint64_t n) {
+  return workspace_dense_off(n) + 256 + align256((size_t)tiles_of(n) * kGroupsPerTile * sizeof(uint32_t));
+}
+// workgroups of the kernels that take the dense-tile list (per problem); each loops over the entries
+static inline uint32_t dense_grid(uint32_t ntiles, uint32_t most) {
+  const uint64_t entries = (uint64_t)ntiles * (kGroupsPerTile - 1);
+  return (uint32_t)(entries < most ? (entries > 0 ? entries : 1) : most);
 }
 struct SliceLayout {
   bool possible;             // the bins fit the LDS histograms and record positions fit 32 bits
@@ -961,11 +1052,11 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
 // (W = 4..16, n = 2^20..1e9, d = 3..5, w = 2^14..2^22):
 //  - atomics: the sketch is zeroed first (about 4.5e12 bytes per second); scattered
 //    float32 atomics retire at about 21e9 per second over the whole chip whatever
-//    their scope, and when the dense scan issues them it hides at best 60 % of
-//    that time (less when the non-zeros are clustered in few workgroups);
-//  - slices: four more kernels, about 30 us of launches; 16 us per round of 256
-//    slice workgroups (each clears 128 KiB of LDS, waits for its records and
-//    stores the slice); histogram and scatter pass about 140e9 records per second.
+//    their scope, and when the dense scan issues them it hides about 40 % of that
+//    time (less when the non-zeros are clustered in few workgroups);
+//  - slices: five more kernels, about 20 us of launches; 4 us per round of 256
+//    slice workgroups (each clears and stores 128 KiB of LDS); histogram, scatter
+//    and slice kernels together pass about 180e9 records per second.
 // `cap` is the caller's bound on the number of non-zeros.
 static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap,
                                size_t workspace_bytes) {
@@ -976,8 +1067,8 @@ static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, b
   if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
   const double records = (double)cap * d;
   const double rounds = (double)ceil_div((uint64_t)W * L.nbins, 256);       // all workers' slices share the CUs
-  const double t_slice = 30e-6 + rounds * 16e-6 + W * records / 140e9;
-  const double t_atomic = W * (4.0 * d * w / 4.5e12 + 0.4 * records / 21e9);
+  const double t_slice = 20e-6 + rounds * 4e-6 + W * records / 180e9;
+  const double t_atomic = W * (4.0 * d * w / 4.5e12 + 0.6 * records / 21e9);
   return t_slice < t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
 }
 
@@ -989,8 +1080,13 @@ static inline void record(int slot, bool end, hipStream_t st) {
 static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
 template <int D>
-static void launch_decode(dim3 grid, hipStream_t st, const DecodeArgs& A, const HashRows& hp) {
-  hipLaunchKernelGGL(decode_kernel<D>, grid, dim3(kBlock), 0, st, A, hp);
+static void launch_decode(uint32_t ntiles, uint32_t helpers, hipStream_t st, const DecodeArgs& A, const HashRows& hp) {
+  if (A.dense_out == nullptr) {
+    hipLaunchKernelGGL(decode_kernel<D>, dim3(helpers + ntiles), dim3(kBlock), 0, st, A, hp, helpers);
+  } else {                                               // group 0 of every tile first: it clears the dense output
+    hipLaunchKernelGGL(decode_kernel<D>, dim3(ntiles), dim3(kBlock), 0, st, A, hp, 0u);
+    hipLaunchKernelGGL(decode_kernel<D>, dim3(helpers), dim3(kBlock), 0, st, A, hp, helpers);
+  }
 }
 
 }  // namespace s2r
@@ -1104,6 +1200,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.workspace = reinterpret_cast<char*>(workspace);
   E.ws_stride = ws_each;
   E.prefix_off = workspace_prefix_off(n);
+  E.dense_off = workspace_dense_off(n);
   const SliceLayout L = slice_layout(n, d, w, cap);
   E.hist_off = L.hist_off;
   E.binstart_off = L.binstart_off;
@@ -1153,11 +1250,12 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.first_worker = 0;
 
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1, W), dim3(kPrefixBlock), 0, st, E.workspace, E.ws_stride,
-                     E.prefix_off, ntiles, nnz_out);
+                     E.prefix_off, E.dense_off, ntiles, nnz_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
   if (lists && cap > 0) {
-    hipLaunchKernelGGL(encode_compact_kernel<kCompactThreads>, dim3(ntiles, W), dim3(kCompactThreads), 0, st, E);
+    const uint32_t helpers = dense_grid(ntiles, 512);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, W), dim3(kBlock), 0, st, E, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
 
@@ -1265,8 +1363,8 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
                      bitmap, nwords, ntiles, piece_count);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
-  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, (const char*)workspace, (uint64_t)0,
-                     (uint64_t)workspace_prefix_off(n), ntiles, count_out);
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, (char*)workspace, (uint64_t)0,
+                     (uint64_t)workspace_prefix_off(n), (uint64_t)workspace_dense_off(n), ntiles, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if ((idx_out == nullptr || cap == 0) && dense_out == nullptr) return S2R_OK;   // only the count was asked for
 
@@ -1278,30 +1376,31 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   A.d = d;
   A.log2w = log2_of(w);
   A.prefix = tile_prefix;
+  A.dense = reinterpret_cast<const uint32_t*>((char*)workspace + workspace_dense_off(n));
   A.idx_out = idx_out;
   A.val_out = val_out;
   A.cap = idx_out ? cap : 0;
   A.dense_out = dense_out;
 
   record(S2R_KERNEL_DECODE, false, st);
-  const dim3 grid(ntiles);
+  const uint32_t helpers = dense_grid(ntiles, 2048);
   switch (d) {
-    case 1: launch_decode<1>(grid, st, A, hp); break;
-    case 2: launch_decode<2>(grid, st, A, hp); break;
-    case 3: launch_decode<3>(grid, st, A, hp); break;
-    case 4: launch_decode<4>(grid, st, A, hp); break;
-    case 5: launch_decode<5>(grid, st, A, hp); break;
-    case 6: launch_decode<6>(grid, st, A, hp); break;
-    case 7: launch_decode<7>(grid, st, A, hp); break;
-    case 8: launch_decode<8>(grid, st, A, hp); break;
-    case 9: launch_decode<9>(grid, st, A, hp); break;
-    case 10: launch_decode<10>(grid, st, A, hp); break;
-    case 11: launch_decode<11>(grid, st, A, hp); break;
-    case 12: launch_decode<12>(grid, st, A, hp); break;
-    case 13: launch_decode<13>(grid, st, A, hp); break;
-    case 14: launch_decode<14>(grid, st, A, hp); break;
-    case 15: launch_decode<15>(grid, st, A, hp); break;
-    default: launch_decode<16>(grid, st, A, hp); break;
+    case 1: launch_decode<1>(ntiles, helpers, st, A, hp); break;
+    case 2: launch_decode<2>(ntiles, helpers, st, A, hp); break;
+    case 3: launch_decode<3>(ntiles, helpers, st, A, hp); break;
+    case 4: launch_decode<4>(ntiles, helpers, st, A, hp); break;
+    case 5: launch_decode<5>(ntiles, helpers, st, A, hp); break;
+    case 6: launch_decode<6>(ntiles, helpers, st, A, hp); break;
+    case 7: launch_decode<7>(ntiles, helpers, st, A, hp); break;
+    case 8: launch_decode<8>(ntiles, helpers, st, A, hp); break;
+    case 9: launch_decode<9>(ntiles, helpers, st, A, hp); break;
+    case 10: launch_decode<10>(ntiles, helpers, st, A, hp); break;
+    case 11: launch_decode<11>(ntiles, helpers, st, A, hp); break;
+    case 12: launch_decode<12>(ntiles, helpers, st, A, hp); break;
+    case 13: launch_decode<13>(ntiles, helpers, st, A, hp); break;
+    case 14: launch_decode<14>(ntiles, helpers, st, A, hp); break;
+    case 15: launch_decode<15>(ntiles, helpers, st, A, hp); break;
+    default: launch_decode<16>(ntiles, helpers, st, A, hp); break;
   }
   record(S2R_KERNEL_DECODE, true, st);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
