@@ -114,6 +114,29 @@ def test_ragged_lengths_dense_gradient(n, strategy):
     _run_and_check(_custom(n, idx, val, d=3, w=1 << 8), dense_out=True)
 
 
+@pytest.mark.parametrize("dense_out", [False, True], ids=["lists", "lists+dense"])
+def test_tiles_around_the_expansion_group_size(strategy, dense_out):
+    """Tiles (32768 elements) holding 0, 1, 2047, 2048, 2049, 4096, 4097 and 32768
+    non-zeros, the last tile ragged: every boundary of the 2048-position groups into
+    which the expansion kernels cut a dense tile, with and without the dense output
+    (which makes decode launch the tiles' first groups and the further ones apart)."""
+    tile = 32768
+    counts = [2049, 0, 32768, 1, 2048, 4097, 2047, 4096, 32768, 700]
+    n = tile * (len(counts) - 1) + 1000
+    rng = np.random.default_rng(77)
+    idx, val = [], []
+    for k in range(2):
+        parts = []
+        for t, c in enumerate(counts):
+            span = min(tile, n - t * tile)
+            pick = np.arange(span) if c >= span else np.sort(rng.choice(span, size=c, replace=False))
+            parts.append(t * tile + pick)
+        i = np.concatenate(parts).astype(np.uint32)
+        idx.append(i)
+        val.append((rng.normal(0, 1, len(i)) + 2.5).astype(np.float32))
+    _run_and_check(_custom(n, idx, val, d=3, w=1 << 10, W=2), dense_out=dense_out)
+
+
 def test_all_zero_gradient(strategy):
     wl = _custom(5000, [np.empty(0, dtype=np.uint32)] * 2, [np.empty(0, dtype=np.float32)] * 2, W=2)
     b, dec = _run_and_check(wl, dense_out=True)
@@ -166,6 +189,35 @@ def test_capacity_overflow_reports_true_count_and_keeps_prefix(strategy):
     assert (guard.cpu().numpy() == -1).all(), "nothing written past cap"
     enc = orc.encode_sparse(idx, val, n, 3, 1 << 10, 0)
     _check_sketch(b.sketch[0].cpu().numpy(), enc["S"], enc["M"], "sketch is complete despite the short list")
+
+
+def test_capacity_inside_a_dense_tile(strategy):
+    """A fully dense gradient of three tiles with list capacities that end inside
+    a later 2048-position group of the second tile: encode and decode write exactly
+    the first cap entries, report the true counts, and the sketch stays complete."""
+    rng = np.random.default_rng(5)
+    n, cap = 3 * 32768 - 100, 32768 + 5000
+    idx = np.arange(n, dtype=np.uint32)
+    val = (rng.normal(0, 1, n) + 3.0).astype(np.float32)
+    wl = _custom(n, [idx], [val], d=3, w=1 << 12)
+    b = pipeline.buffers_for(wl)
+    b.nz_idx[0] = torch.full((cap + 16,), -1, dtype=torch.int32, device="cuda")[:cap]
+    b.nz_val[0] = torch.zeros(cap, dtype=torch.float32, device="cuda")
+    b.out_idx = torch.full((cap + 16,), -1, dtype=torch.int32, device="cuda")[:cap]
+    b.out_val = torch.zeros(cap, dtype=torch.float32, device="cuda")
+    b.step()
+    torch.cuda.synchronize()
+    assert int(b.nnz.cpu()[0]) == n and int(b.out_count.cpu()[0]) == n
+    assert np.array_equal(b.nz_idx[0].cpu().numpy().view(np.uint32), idx[:cap])
+    assert np.array_equal(b.nz_val[0].cpu().numpy(), val[:cap])
+    assert (b.nz_idx[0]._base[cap:].cpu().numpy() == -1).all(), "encode wrote past cap"
+    assert np.array_equal(b.out_idx.cpu().numpy().view(np.uint32), idx[:cap])
+    assert (b.out_idx._base[cap:].cpu().numpy() == -1).all(), "decode wrote past cap"
+    enc = orc.encode_sparse(idx, val, n, 3, 1 << 12, 0)
+    _check_sketch(b.sketch[0].cpu().numpy(), enc["S"], enc["M"], "sketch is complete despite the short list")
+    dec = orc.decode(enc["S"], enc["bitmap"], n, 0)
+    tol = REL * orc.decode_tolerance_mass(enc["M"], dec["idx"][:cap], 0) + DENORM_SLACK
+    assert np.all(np.abs(b.out_val.cpu().numpy().astype(np.float64) - dec["val"][:cap]) <= tol)
 
 
 def test_null_lists_and_in_place_merge():
