@@ -25,14 +25,26 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the encode scan kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this file,
 # scaled by what the same counters read for a plain 1 GiB copy (profiles/hbm_traffic_<workload>.txt):
 # (workload, insert strategy, workers per launch) -> bytes.  Other combinations have not been counted.
-MEASURED_SCAN_TRAFFIC = {("cfg5_large_zipf", "atomic", 1): 4.299e9}
+MEASURED_SCAN_TRAFFIC = {("cfg5_large_zipf", "atomic", 1): 4.299e9, ("cfg5_large_zipf", "lds_slice", 1): 4.140e9}
+
+
+def algorithmic_bytes(wl, nnz, union: int) -> float:
+    """What the method itself must move in one step: per worker the dense read
+    (4n), the bitmap (n/8), the list (8 nnz) and the sketch written once (4dw);
+    the merge reads W sketches and bitmaps and writes one of each; the decode
+    reads the bitmap and the sketch and writes the union list (8 bytes each)."""
+    cells, words8 = 4.0 * wl.d * wl.w, wl.n / 8.0
+    encode = sum(4.0 * wl.n + words8 + 8.0 * float(c) + cells for c in nnz)
+    merge = wl.W * (cells + words8) + cells + words8
+    decode = words8 + cells + 8.0 * union
+    return encode + merge + decode
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="which BASELINE config to time (default: the largest single-GPU one)")
     ap.add_argument("--per-worker-calls", action="store_true",
@@ -56,34 +68,46 @@ def scan_kernel_bytes(n: int, nnz: float, d: int, inserts: bool) -> float:
 
 
 def cpu_baseline(wl, first_sample: int, budget_s: float = 12.0):
-    """The oracle, as it stands, on the first ns elements of each of up to 4
-    workers (dense scan + insert per worker, merge, decode).  ns doubles from
-    `first_sample` until the runs so far have used `budget_s` seconds (or ns is the
-    whole gradient); the last, largest run is the one reported."""
+    """The oracle, as it stands, on the first ns elements of Ws workers: per worker
+    the dense scan + insert (one dense buffer in host memory at a time; filling it
+    is not timed), then merge and decode.  The sample grows (ns doubles up to the
+    whole gradient, then Ws doubles up to W) until the runs so far have used
+    `budget_s` seconds; the last, largest run is the one reported."""
     import numpy as np
     from oracle import s2r_oracle as orc
     Ws = min(wl.W, 4)
     ns = min(wl.n, first_sample)
     spent = 0.0
     while True:
-        dense = []
+        dt = 0.0
+        sketches, bitmaps = [], []
         for k in range(Ws):
             cut = int(np.searchsorted(wl.idx[k], ns))
             g = np.zeros(ns, dtype=np.float32)
             g[wl.idx[k][:cut]] = wl.val[k][:cut]
-            dense.append(g)
+            t0 = time.perf_counter()
+            e = orc.encode(g, wl.d, wl.w, wl.seed)
+            dt += time.perf_counter() - t0
+            sketches.append(e["S"])
+            bitmaps.append(e["bitmap"])
+            del g, e
         t0 = time.perf_counter()
-        out = orc.reduce_workers(dense, wl.d, wl.w, wl.seed)
-        dt = time.perf_counter() - t0
+        S, C = orc.merge(sketches, bitmaps)
+        out = orc.decode(S, C, ns, wl.seed)
+        dt += time.perf_counter() - t0
         spent += dt
         union = len(out["idx"])
-        del dense, out
-        if spent >= budget_s or ns >= wl.n or spent + 2 * dt > 30.0:     # the next run takes about 2 dt
+        del sketches, bitmaps, S, C, out
+        grow_w = ns >= wl.n and Ws < wl.W
+        if spent >= budget_s or spent + 2 * dt > 30.0 or (ns >= wl.n and not grow_w):     # the next run takes about 2 dt
             break
-        ns = min(wl.n, ns * 2)
+        if grow_w:
+            Ws = min(wl.W, Ws * 2)
+        else:
+            ns = min(wl.n, ns * 2)
     gbs = Ws * ns * 4 / dt / 1e9
     return {"value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{Ws} workers x first {ns} elements of {wl.name} (dense scan+insert, merge, decode; "
+            "sample": f"{Ws} workers x first {ns} elements of {wl.name} (dense scan+insert per worker, merge, decode; "
                       f"{union} union indices), {dt:.1f} s on 1 thread"}
 
 
@@ -163,6 +187,19 @@ def main():
     atomic = binding.last_insert_strategy() == binding.S2R_INSERT_ATOMIC
     slice_ms = None if atomic else float(np.mean([a.elapsed_ms(c) for a, c in slice_pairs]))
 
+    # ---- the read rate this device delivers to a kernel that only reads (same access pattern as the scan)
+    sink = torch.zeros(1, dtype=torch.int64, device=b.device)
+    p0, p1 = binding.HipEvent(), binding.HipEvent()
+    probe_reps = min(4, wl.W)
+    for k in range(probe_reps):
+        binding.probe_read(b.grads[k], sink, stream)
+    p0.record(stream)
+    for k in range(probe_reps):
+        binding.probe_read(b.grads[k], sink, stream)
+    p1.record(stream)
+    torch.cuda.synchronize()
+    read_ceiling = probe_reps * wl.n * 4 / (p0.elapsed_ms(p1) * 1e-3) / 1e9
+
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=b.device)
         dst = torch.empty_like(src)
@@ -176,6 +213,7 @@ def main():
     assert [int(x) for x in nnz] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
     alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d, atomic)
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+    step_alg_bytes = algorithmic_bytes(wl, nnz, union)
 
     out = {
         "metric": "dense-gradient GB/s for encode+merge+decode on 1 MI355X",
@@ -194,6 +232,9 @@ def main():
                    "nnz_per_worker": int(nnz.mean()), "union_nnz": union,
                    "dense_bytes_per_step": wl.dense_bytes},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "algorithmic_bytes_per_step": int(step_alg_bytes),
+        "algorithmic_frac_of_hbm_peak": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "stream_read_GBs": round(read_ceiling, 1),
         "event_ms_per_step": round(ev_ms / args.steps, 4),
         "encode_calls": "s2r_encode_batch" if batched else "s2r_encode x W",
         "insert_strategy": "atomic" if atomic else "lds_slice",

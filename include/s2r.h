@@ -43,15 +43,18 @@
  *     w a power of two with 1 <= w <= 2^31 and d*w <= 2^32,
  *     1 <= W <= S2R_MAX_WORKERS.
  *   - Determinism: bitmaps, index lists and counts are bit-exact and identical
- *     from run to run.  Sketch cells are float32 sums formed by hardware
- *     atomics in arbitrary order, so they (and the decoded values that read
- *     them) are reproducible only up to float32 summation order; the hardware
- *     float32 atomic add may flush denormal operands and results to zero.
+ *     from run to run.  A worker's sketch cell is a sum formed by hardware
+ *     atomics in arbitrary order: float32 atomics in global memory (which may
+ *     flush denormal operands and results to zero), or float64 atomics in LDS
+ *     rounded to float32 once (see s2r_set_insert_strategy).  Cells, and the
+ *     decoded values that read them, are therefore reproducible only up to
+ *     the summation order.
  *   - Workspace: s2r_encode and s2r_decode need a device scratch buffer of at
- *     least s2r_workspace_bytes(n, d, w) bytes, 256-byte aligned (per-tile
- *     counts and their prefix sums).  Its contents on entry are irrelevant and
- *     on exit unspecified.  Two calls that overlap in time (different streams)
- *     must not share a workspace.
+ *     least s2r_workspace_bytes(n, d, w) bytes, 256-byte aligned (counts per
+ *     2048 elements, their prefix sums per 32768 elements, and the list of
+ *     the 32768-element tiles that hold more than 2048 non-zeros).  Its
+ *     contents on entry are irrelevant and on exit unspecified.  Two calls
+ *     that overlap in time (different streams) must not share a workspace.
  *   - No kernel of the library waits for another workgroup: every launch
  *     finishes whatever the order in which the hardware schedules workgroups.
  */
@@ -200,8 +203,9 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued
  *                      from the dense scan (the sketch is zeroed first)
  *   S2R_INSERT_SLICE   workgroups that each own a slice of one sketch row in
- *                      LDS and add the entries of Sparse(g), which a counting
- *                      sort has partitioned by slice; needs nz_idx / nz_val, a
+ *                      LDS (float64 accumulators, rounded to float32 once) and
+ *                      add the entries of Sparse(g), which a counting sort has
+ *                      partitioned by slice; needs nz_idx / nz_val, a
  *                      workspace of s2r_encode_workspace_bytes, d*w <= 2^27 and
  *                      d*cap < 2^32 (otherwise s2r_encode uses atomics whatever
  *                      is set here)
@@ -227,7 +231,7 @@ int32_t s2r_last_insert_strategy(void);
  *   slot S2R_KERNEL_ENCODE_SCAN : the dense scan kernel of s2r_encode / s2r_encode_batch
  *                                 (see s2r_scan_launch_workers)
  *   slot S2R_KERNEL_MERGE       : the kernel of s2r_merge
- *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel of s2r_decode
+ *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel(s) of s2r_decode
  *   slot S2R_KERNEL_ENCODE_SLICE: the LDS-slice sketch kernel of s2r_encode
  */
 #define S2R_KERNEL_ENCODE_SCAN  0
@@ -242,6 +246,19 @@ s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end);
  * bracketed (a batch may be scanned in one launch or worker by worker; in the
  * latter case the events bracket the last worker's launch).  Host only. */
 uint32_t s2r_scan_launch_workers(void);
+
+/*
+ * Measurement aid, no part of the method: one kernel that only reads the first
+ * bytes/16 16-byte words of src with streaming loads, in the access pattern of
+ * the dense scan of s2r_encode.  Timed by the caller, it gives the read rate the
+ * memory system delivers on this device, the ceiling for the scan.
+ *   src    dev, in : at least bytes bytes, 16-byte aligned; bytes >= 16
+ *   sink   dev, out: one uint64, 8-byte aligned; written only if the XOR of all
+ *                    words read equals an arbitrary constant (it keeps the loads
+ *                    alive), so normally left untouched
+ * Enqueues on stream and returns; S2R_ERR_NULL / _SIZE / _ALIGN / _LAUNCH as above.
+ */
+s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* stream);
 
 #ifdef __cplusplus
 }

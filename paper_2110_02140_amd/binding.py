@@ -56,6 +56,7 @@ SIGNATURES = {
     "s2r_set_insert_strategy": (c_int32, [c_int32]),
     "s2r_scan_launch_workers": (c_uint32, []),
     "s2r_last_insert_strategy": (c_int32, []),
+    "s2r_probe_read": (c_int32, [c_void_p, c_size_t, c_void_p, c_void_p]),
 }
 
 _lib = None
@@ -187,6 +188,14 @@ def last_insert_strategy() -> int:
 
 def scan_launch_workers() -> int:
     return load().s2r_scan_launch_workers()
+
+
+def probe_read(src, sink, stream=None, nbytes=None):
+    """s2r_probe_read over a device tensor (all of it unless nbytes is given); sink int64[1]."""
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    st = load().s2r_probe_read(_ptr(src), nbytes, _ptr(sink), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_probe_read")
 
 
 def set_kernel_events(slot: int, ev_begin, ev_end):

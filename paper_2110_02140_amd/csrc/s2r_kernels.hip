@@ -71,6 +71,7 @@ static_assert(kScanWords * 64 <= 0xFFFF, "a piece count must fit 16 bits");
 static_assert(kScansPerTile == 16, "tile_prefix_kernel reads a tile's piece counts as two 16-byte loads");
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));      // a 16-byte vector the nontemporal builtins accept
 
 static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -843,6 +844,29 @@ __global__ __launch_bounds__(kBlock) void merge_kernel(const MergeArgs A) {
   }
 }
 
+// ------------------------------------------------------------------ streaming-read probe
+// A plain read of nvec 16-byte words, shaped like the dense scan (each wave reads
+// kProbePer consecutive 1 KiB rows with streaming loads): what the memory system
+// delivers to a kernel that only reads.  The XOR of the words keeps the loads alive;
+// it is stored only if it equals a value the host chooses.
+constexpr int kProbePer = 8;
+__global__ __launch_bounds__(kBlock) void probe_read_kernel(const u32x4* __restrict__ src, uint64_t nvec,
+                                                            uint64_t* __restrict__ sink, uint32_t magic) {
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  const uint64_t v0 = wave * (kProbePer * kWave) + lane;
+  u32x4 x[kProbePer];
+#pragma unroll
+  for (int q = 0; q < kProbePer; ++q) {
+    const uint64_t v = v0 + (uint64_t)q * kWave;
+    x[q] = v < nvec ? __builtin_nontemporal_load(&src[v]) : u32x4{0u, 0u, 0u, 0u};
+  }
+  uint32_t acc = 0;
+#pragma unroll
+  for (int q = 0; q < kProbePer; ++q) acc ^= x[q].x ^ x[q].y ^ x[q].z ^ x[q].w;
+  if (acc == magic) *sink = acc;
+}
+
 // ------------------------------------------------------------------ decode
 struct DecodeArgs {
   const float* sketch;
@@ -1144,6 +1168,18 @@ s2r_status s2r_set_insert_strategy(int32_t strategy) {
 uint32_t s2r_scan_launch_workers(void) { return g_scan_launch_workers; }
 
 int32_t s2r_last_insert_strategy(void) { return g_last_strategy; }
+
+s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* stream) {
+  if (src == nullptr || sink == nullptr) return S2R_ERR_NULL;
+  if (bytes < 16 || bytes / 16 > (1ull << 40)) return S2R_ERR_SIZE;
+  if (((uintptr_t)src & 15u) || ((uintptr_t)sink & 7u)) return S2R_ERR_ALIGN;
+  const uint64_t nvec = bytes / 16;
+  const uint64_t blocks = ceil_div(nvec, (uint64_t)kBlock * kProbePer);
+  if (blocks > 0x7FFFFFFFull) return S2R_ERR_SIZE;
+  hipLaunchKernelGGL(probe_read_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0, (hipStream_t)stream,
+                     reinterpret_cast<const u32x4*>(src), nvec, sink, 0xA5C3F00Du);
+  return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+}
 
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
   if (slot < 0 || slot >= S2R_KERNEL_SLOTS) return S2R_ERR_SIZE;

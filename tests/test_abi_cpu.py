@@ -141,3 +141,12 @@ def test_set_kernel_events_argument_checks():
     assert b.load().s2r_set_kernel_events(7, None, None) == b.S2R_ERR_SIZE
     assert b.load().s2r_set_kernel_events(0, 0x10, None) == b.S2R_ERR_NULL
     assert b.load().s2r_set_kernel_events(0, None, None) == b.S2R_OK
+
+
+def test_probe_read_argument_checks():
+    lib = b.load()
+    assert lib.s2r_probe_read(None, 1024, 0x100, None) == b.S2R_ERR_NULL
+    assert lib.s2r_probe_read(0x1000, 1024, None, None) == b.S2R_ERR_NULL
+    assert lib.s2r_probe_read(0x1000, 8, 0x100, None) == b.S2R_ERR_SIZE
+    assert lib.s2r_probe_read(0x1004, 1024, 0x100, None) == b.S2R_ERR_ALIGN
+    assert lib.s2r_probe_read(0x1000, 1024, 0x104, None) == b.S2R_ERR_ALIGN
