@@ -49,6 +49,8 @@ def parse_args():
                     help="which BASELINE config to time (default: the largest single-GPU one)")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with W s2r_encode calls instead of one s2r_encode_batch call")
+    ap.add_argument("--insert-strategy", default="auto", choices=["auto", "atomic", "slice"],
+                    help="how s2r_encode forms the sketch (default: the library's own choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=0, help="override the oracle sample length")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -126,6 +128,8 @@ def main():
         print("bench.py: no GPU visible; the codec has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     binding.load()
+    binding.set_insert_strategy({"auto": binding.S2R_INSERT_AUTO, "atomic": binding.S2R_INSERT_ATOMIC,
+                                 "slice": binding.S2R_INSERT_SLICE}[args.insert_strategy])
 
     cfg = int(args.workload[3:])
     t_gen = time.perf_counter()
