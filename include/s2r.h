@@ -218,6 +218,39 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
 #define S2R_INSERT_SLICE  2
 s2r_status s2r_set_insert_strategy(int32_t strategy);
 
+/*
+ * How s2r_decode carries out the query loops of Algorithm 1 (the d bucket reads
+ * per union index); the result is the same either way, bit for bit.
+ *   S2R_DECODE_GATHER  every list position reads its d buckets from the sketch in
+ *                      device memory (one 128-byte line fetched per 4-byte cell)
+ *   S2R_DECODE_SLICE   the (position, row) queries are partitioned by sketch
+ *                      slice with a counting sort; workgroups that each hold a
+ *                      slice of one sketch row in LDS answer them; the answers
+ *                      return to list order through LDS and meet in the median.
+ *                      Needs idx_out / val_out, no dense_out, d <= 8,
+ *                      d*w <= 2^27, d*cap < 2^32 and a workspace of
+ *                      s2r_decode_workspace_bytes (otherwise s2r_decode gathers
+ *                      whatever is set here)
+ *   S2R_DECODE_AUTO    (default) chosen from d, w and cap, the capacity of the
+ *                      caller's lists
+ * State is per host thread.  Returns S2R_ERR_SIZE for any other value.
+ */
+#define S2R_DECODE_AUTO   0
+#define S2R_DECODE_GATHER 1
+#define S2R_DECODE_SLICE  2
+s2r_status s2r_set_decode_strategy(int32_t strategy);
+
+/* S2R_DECODE_GATHER or S2R_DECODE_SLICE: what the calling thread's last
+ * s2r_decode call used (S2R_DECODE_AUTO before any call, or when the call only
+ * counted).  Host only. */
+int32_t s2r_last_decode_strategy(void);
+
+/* Bytes of device scratch with which s2r_decode can also use S2R_DECODE_SLICE for
+ * lists of capacity cap (s2r_workspace_bytes plus 16*d bytes per list entry and
+ * two histograms).  With a smaller workspace (but at least s2r_workspace_bytes)
+ * it gathers.  Host only; returns 0 outside the limits or if cap > n. */
+size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
+
 /* S2R_INSERT_ATOMIC or S2R_INSERT_SLICE: what the calling thread's last
  * s2r_encode / s2r_encode_batch call used (S2R_INSERT_AUTO before any call).
  * Host only. */

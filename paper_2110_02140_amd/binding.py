@@ -31,6 +31,9 @@ S2R_KERNEL_ENCODE_SLICE = 3
 S2R_INSERT_AUTO = 0
 S2R_INSERT_ATOMIC = 1
 S2R_INSERT_SLICE = 2
+S2R_DECODE_AUTO = 0
+S2R_DECODE_GATHER = 1
+S2R_DECODE_SLICE = 2
 
 # every symbol include/s2r.h declares: name -> (restype, argtypes)
 SIGNATURES = {
@@ -57,6 +60,9 @@ SIGNATURES = {
     "s2r_scan_launch_workers": (c_uint32, []),
     "s2r_last_insert_strategy": (c_int32, []),
     "s2r_probe_read": (c_int32, [c_void_p, c_size_t, c_void_p, c_void_p]),
+    "s2r_set_decode_strategy": (c_int32, [c_int32]),
+    "s2r_last_decode_strategy": (c_int32, []),
+    "s2r_decode_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint64]),
 }
 
 _lib = None
@@ -180,6 +186,21 @@ def set_insert_strategy(strategy: int):
     st = load().s2r_set_insert_strategy(strategy)
     if st != S2R_OK:
         raise S2RError(st, "s2r_set_insert_strategy")
+
+
+def set_decode_strategy(strategy: int):
+    """S2R_DECODE_AUTO / _GATHER / _SLICE for the calling thread's s2r_decode calls."""
+    st = load().s2r_set_decode_strategy(strategy)
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_set_decode_strategy")
+
+
+def last_decode_strategy() -> int:
+    return load().s2r_last_decode_strategy()
+
+
+def decode_workspace_bytes(n: int, d: int, w: int, cap: int) -> int:
+    return load().s2r_decode_workspace_bytes(n, d, w, cap)
 
 
 def last_insert_strategy() -> int:

@@ -22,8 +22,9 @@
 //                                      with more than kGroupSlots set bits get
 //                                      extra workgroups through a dense-tile list
 //                bin_hist_kernel,      (slice variant) Sparse(g) x rows is partitioned by
-//                bin_scan_kernel,      sketch slice (counting sort: histogram per chunk,
-//                bin_scatter_kernel    offsets, scatter of (cell, signed value) records)
+//                bin_colscan_kernel,   sketch slice (counting sort: histogram per chunk,
+//                bin_start_kernel,     offsets, scatter of (cell, signed value) records
+//                bin_scatter_kernel    sorted by slice inside LDS first)
 //                sketch_slice_kernel   (slice variant) every workgroup owns a slice of
 //                                      one sketch row in LDS, adds the records of its
 //                                      bin and stores the slice: no global atomics, no
@@ -33,8 +34,12 @@
 //   s2r_merge  : merge_kernel          S = sum_k S_k (ascending k), C = OR_k C_k
 //   s2r_decode : bitmap_count_kernel   per-piece popcounts of the aggregated bitmap
 //                tile_prefix_kernel
-//                decode_kernel         expands the bitmap; per index the d signed
-//                                      bucket reads and their median
+//                decode_kernel         (gather variant) expands the bitmap; per index
+//                                      the d signed bucket reads and their median
+//                encode_compact_kernel, bin_*_kernel, decode_slice_kernel,
+//                decode_median_kernel  (slice variant) the union list, its queries
+//                                      partitioned by sketch slice, answered from
+//                                      LDS, brought back to list order, medians
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -98,6 +103,9 @@ struct EncodeBatch {
   uint64_t hist_off;         // slice variant: byte offsets inside a chunk of the per-chunk bin histogram
   uint64_t binstart_off;     //   [nchunks][nbins] u32, the bin starts [nbins + 1] u32,
   uint64_t rec_off;          //   and the binned records [d * cap] of 8 bytes
+  uint64_t rowpre_off;       // decode by slices: per chunk, the exclusive prefix of its histogram over the
+                             //   bins, [nchunks][nbins] u32; 0 when not wanted
+  uint32_t payload_slot;     // non-zero: a record carries its item's list position instead of nz_val
   uint64_t n;
   uint64_t nwords;
   uint64_t cap;
@@ -441,14 +449,15 @@ __device__ __forceinline__ void compact_group(const EncodeBatch& B, const Worker
       live[u] = t < last && base + t < B.cap;
       i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
+    const bool values = P.grad != nullptr;               // s2r_decode expands the aggregated bitmap without values
 #pragma unroll
-    for (int u = 0; u < kSlots; ++u) v[u] = live[u] ? P.grad[i[u]] : 0u;
+    for (int u = 0; u < kSlots; ++u) v[u] = live[u] && values ? P.grad[i[u]] : 0u;
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
       if (!live[u]) continue;
       const uint64_t pos = base + t0 + u * kBlock;
       P.nz_idx[pos] = i[u];
-      P.nz_val[pos] = v[u];
+      if (values) P.nz_val[pos] = v[u];
     }
   }
 }
@@ -480,7 +489,7 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
 // collects the pairs (item, row j) whose bucket falls in slice s.  A counting sort
 // over the listed items brings each bin's records together:
 //   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins
-//   bin_scan_kernel     offsets of every (chunk, bin) run and of every bin
+//   bin_colscan_kernel, bin_start_kernel   offsets of every (chunk, bin) run and of every bin
 //   bin_scatter_kernel  writes each record (cell in the slice | sign bit, value)
 //                       into its run (order inside a run is arbitrary)
 //   sketch_slice_kernel workgroup (j, s) clears its slice in LDS, adds its bin's
@@ -528,61 +537,127 @@ __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B
   __syncthreads();
   uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
+  if (B.rowpre_off == 0) return;                         // uniform over the workgroup
+  // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
+  constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
+  uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
+    sum += c[q];
+  }
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  __syncthreads();
+  uint32_t run = incl - sum;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
+  uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    if ((uint32_t)q < per && e < B.nbins) {
+      rowpre[e] = run;
+      run += c[q];
+    }
+  }
 }
 
-// One workgroup per worker.  In place: hist[c][b] becomes the number of records of
-// bin b in chunks before c; bin_start[b] the number of records in bins before b
-// (bin_start[nbins] = all records).  Thread t owns bins t, t + 1024, ...: for a
-// fixed chunk the threads read consecutive counters.
-__global__ __launch_bounds__(kBinBlock) void bin_scan_kernel(const EncodeBatch B) {
-  constexpr int kPerThread = kMaxBins / kBinBlock;       // 8
+// Offsets of the counting sort, two kernels.
+// bin_colscan_kernel: workgroup = 64 adjacent bins of one worker (lane = bin, so a
+// chunk's counters are read as one 256-byte row); its 16 waves split the chunks
+// into 16 consecutive ranges.  In place, hist[c][b] becomes the number of records
+// of bin b in chunks before c: every wave sums its range, the waves' sums are
+// exchanged through LDS, then every wave walks its range again with its running
+// offset.  The bin's total goes to bin_start[b].
+// bin_start_kernel: one workgroup per worker turns the totals in bin_start[0..nbins)
+// into the number of records in bins before b (bin_start[nbins] = all records).
+__global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatch B) {
+  constexpr int kWaves = kBinBlock / kWave;              // 16
+  constexpr uint32_t kAhead = 8;                         // counters in flight per thread
+  __shared__ uint32_t s_part[kWaves][kWave];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t b = blockIdx.x * kWave + lane;
+  const bool live = b < B.nbins;
+  uint32_t* hist = ws_bin_hist(B, k);
+  const uint32_t per = (B.nchunks + kWaves - 1) / kWaves;
+  const uint32_t c_begin = wv * per < B.nchunks ? wv * per : B.nchunks;
+  const uint32_t c_end = c_begin + per < B.nchunks ? c_begin + per : B.nchunks;
+  uint32_t sum = 0;
+  for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
+    uint32_t v[kAhead];
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) v[q] = (live && c0 + q < c_end) ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) sum += v[q];
+  }
+  s_part[wv][lane] = sum;
+  __syncthreads();
+  uint32_t run = 0, total = 0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) {
+    const uint32_t x = s_part[q][lane];
+    if ((uint32_t)q < wv) run += x;
+    total += x;
+  }
+  for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
+    uint32_t v[kAhead];
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) v[q] = (live && c0 + q < c_end) ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) {
+      if (live && c0 + q < c_end) hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
+      run += v[q];
+    }
+  }
+  if (wv == 0 && live) ws_bin_start(B, k)[b] = total;
+}
+
+__global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch B) {
   constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;           // 8
   __shared__ uint32_t s_wave[kWaves];
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
-  uint32_t* hist = ws_bin_hist(B, k);
   uint32_t* bin_start = ws_bin_start(B, k);
-  uint32_t total[kPerThread];
+  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;   // thread t owns bins t*per .. t*per + per - 1
+  uint32_t c[kMaxPer], sum = 0;
 #pragma unroll
-  for (int r = 0; r < kPerThread; ++r) {
-    const uint32_t b = r * kBinBlock + threadIdx.x;
-    uint32_t run = 0;
-    if (b < B.nbins) {
-      constexpr uint32_t kAhead = 8;                      // counters in flight per thread
-      for (uint32_t c0 = 0; c0 < B.nchunks; c0 += kAhead) {
-        uint32_t v[kAhead];
-#pragma unroll
-        for (uint32_t q = 0; q < kAhead; ++q) v[q] = c0 + q < B.nchunks ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
-#pragma unroll
-        for (uint32_t q = 0; q < kAhead; ++q) {
-          if (c0 + q < B.nchunks) hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
-          run += v[q];
-        }
-      }
-    }
-    total[r] = run;
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    c[q] = ((uint32_t)q < per && e < B.nbins) ? bin_start[e] : 0u;
+    sum += c[q];
   }
-  uint32_t carry = 0;                                     // records in the bins of earlier rounds
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  __syncthreads();
+  uint32_t run = incl - sum, all = 0;
 #pragma unroll
-  for (int r = 0; r < kPerThread; ++r) {                  // bins r*1024 .. r*1024+1023 in thread order
-    const uint32_t incl = wave_inclusive_scan_u32(total[r], lane);
-    if (lane == kWave - 1) s_wave[wv] = incl;
-    __syncthreads();
-    uint32_t wave_off = 0, round_total = 0;
-#pragma unroll
-    for (int q = 0; q < kWaves; ++q) {
-      const uint32_t x = s_wave[q];
-      if ((uint32_t)q < wv) wave_off += x;
-      round_total += x;
-    }
-    const uint32_t b = r * kBinBlock + threadIdx.x;
-    if (b < B.nbins) bin_start[b] = carry + wave_off + incl - total[r];
-    carry += round_total;
-    __syncthreads();
+  for (int q = 0; q < kWaves; ++q) {
+    const uint32_t x = s_wave[q];
+    if ((uint32_t)q < wv) run += x;
+    all += x;
   }
-  if (threadIdx.x == 0) bin_start[B.nbins] = carry;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    if ((uint32_t)q < per && e < B.nbins) {
+      bin_start[e] = run;
+      run += c[q];
+    }
+  }
+  if (threadIdx.x == 0) bin_start[B.nbins] = all;
 }
 
 // One workgroup per chunk of kBinChunk list items, one pass per sketch row j.  The
@@ -623,7 +698,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
   for (int u = 0; u < kBinItems; ++u) {
     const uint32_t t = u * kBinBlock + threadIdx.x;
     i[u] = t < count ? P.nz_idx[t0 + t] : 0u;
-    v[u] = t < count ? P.nz_val[t0 + t] : 0u;
+    v[u] = t >= count ? 0u : B.payload_slot != 0 ? (uint32_t)(t0 + t) : P.nz_val[t0 + t];
   }
   for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
 
@@ -987,11 +1062,135 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
   }
 }
 
+// ------------------------------------------------------------------ decode by sketch slices
+// The bucket reads of decode_kernel each fetch a 128-byte line for 4 useful
+// bytes.  When the union list is long, s2r_decode instead partitions the
+// (list position, row) queries by sketch slice with the kernels of the encode's
+// slice strategy (records carry the list position instead of a value) and
+//   decode_slice_kernel   workgroup (j, s) loads slice s of row j into LDS with
+//                         coalesced loads, answers its bin's queries from LDS
+//                         and writes (estimate, position in chunk) into the
+//                         region of the query's chunk of kBinChunk list
+//                         positions: row j's answers of chunk c start at
+//                         (c * kBinChunk * d) + j * (items in c), and inside
+//                         them bin (j, s) starts where the prefix of the
+//                         chunk's histogram over the bins says
+//   decode_median_kernel  workgroup = chunk: row by row, the answers go through
+//                         LDS into the registers of the thread that owns the
+//                         list position; then the medians, stored coalesced
+struct DecodeSliceArgs {
+  const float* sketch;
+  const u32x2* rec;          // queries sorted by bin: (cell in slice | sign bit, list position)
+  uint2* answers;            // [nchunks][d][kBinChunk]-shaped regions, see above
+  const uint32_t* bin_start; // [nbins + 1]
+  const uint32_t* colpre;    // [nchunks][nbins]: queries of the bin in earlier chunks
+  const uint32_t* rowpre;    // [nchunks][nbins]: queries of the chunk in earlier bins
+  const uint64_t* count;     // the union count (device)
+  uint64_t cap;
+  float* val_out;
+  uint32_t nbins;
+  uint32_t slice_log2;
+  uint32_t d;
+};
+
+constexpr int kBinChunkLog2 = 13;
+static_assert((1 << kBinChunkLog2) == kBinChunk, "list positions are split into chunk and offset by shifts");
+
+__global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeSliceArgs A) {
+  extern __shared__ float s_cells[];
+  constexpr int kAhead = 4;
+  const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
+  const uint32_t first = A.bin_start[bin], last = A.bin_start[bin + 1];
+  if (first == last) return;                              // uniform over the workgroup
+  const uint32_t cells = 1u << A.slice_log2;
+  const float* src = A.sketch + (uint64_t)bin * cells;    // row-major sketch: slice s of row j starts at bin * cells
+  if (cells >= 4u * kSliceBlock) {                        // (the sketch and every slice of 4 cells or more are 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
+      reinterpret_cast<float4*>(s_cells)[c] = reinterpret_cast<const float4*>(src)[c];
+  } else {
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_cells[c] = src[c];
+  }
+  __syncthreads();
+  const u32x2 none = {0u, 0u};
+  for (uint64_t r0 = (uint64_t)first + threadIdx.x; r0 < last; r0 += kSliceBlock * kAhead) {
+    u32x2 x[kAhead];
+    uint32_t colp[kAhead], rowp[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u)
+      x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r0 + u * kSliceBlock]) : none;
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const uint64_t at = (uint64_t)(x[u].y >> kBinChunkLog2) * A.nbins + bin;
+      const bool live = r0 + u * kSliceBlock < last;
+      colp[u] = live ? A.colpre[at] : 0u;
+      rowp[u] = live ? A.rowpre[at] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const uint64_t r = r0 + u * kSliceBlock;
+      if (r >= last) continue;
+      const uint32_t est = __float_as_uint(s_cells[x[u].x & 0x7FFFFFFFu]) ^ (x[u].x & 0x80000000u);
+      const uint64_t chunk = x[u].y >> kBinChunkLog2;
+      const uint64_t at = chunk * kBinChunk * A.d + rowp[u] + (uint32_t)(r - first - colp[u]);
+      A.answers[at] = make_uint2(est, x[u].y & (kBinChunk - 1));
+    }
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSliceArgs A) {
+  __shared__ float s_est[kBinChunk];
+  const uint32_t chunk = blockIdx.x;
+  const uint64_t total = *A.count;
+  const uint64_t have = total < A.cap ? total : A.cap;
+  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
+  if (t0 >= have) return;                                 // uniform over the workgroup
+  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+  float est[kBinItems][D];
+  uint2 cur[kBinItems], nxt[kBinItems];                   // row j's answers, and row j + 1's on their way
+  const uint2* rows = A.answers + t0 * D;
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint32_t t = u * kBinBlock + threadIdx.x;
+    cur[u] = t < count ? rows[t] : make_uint2(0u, 0u);
+  }
+#pragma unroll
+  for (int j = 0; j < D; ++j) {
+    if (j + 1 < D) {
+#pragma unroll
+      for (int u = 0; u < kBinItems; ++u) {
+        const uint32_t t = u * kBinBlock + threadIdx.x;
+        nxt[u] = t < count ? rows[(uint64_t)(j + 1) * count + t] : make_uint2(0u, 0u);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (u * kBinBlock + threadIdx.x < count) s_est[cur[u].y] = __uint_as_float(cur[u].x);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      const uint32_t t = u * kBinBlock + threadIdx.x;
+      est[u][j] = t < count ? s_est[t] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) cur[u] = nxt[u];
+  }
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint32_t t = u * kBinBlock + threadIdx.x;
+    if (t < count) A.val_out[t0 + t] = median_fixed<D>(est[u]);
+  }
+}
+
 // ------------------------------------------------------------------ host side
 struct EventPair { hipEvent_t begin, end; };
 static thread_local EventPair g_events[S2R_KERNEL_SLOTS] = {};
 static thread_local int32_t g_strategy = S2R_INSERT_AUTO;
 static thread_local int32_t g_last_strategy = S2R_INSERT_AUTO;   // what the last encode call used
+static thread_local int32_t g_decode_strategy = S2R_DECODE_AUTO;
+static thread_local int32_t g_last_decode_strategy = S2R_DECODE_AUTO;   // what the last decode call used
 static thread_local uint32_t g_scan_launch_workers = 0;     // workers covered by the scan launch the events bracket
 
 static inline uint64_t splitmix_next(uint64_t& state) {
@@ -1096,6 +1295,69 @@ static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, b
   return t_slice < t_atomic ? S2R_INSERT_SLICE : S2R_INSERT_ATOMIC;
 }
 
+// Workspace of s2r_decode when it partitions its queries by sketch slice: the base parts, then
+// [bin histogram u32[nchunks][nbins]] [its per-chunk prefix over the bins, same shape] [bin starts u32[nbins + 1]]
+// [queries sorted by bin, 8 B x d*cap] [answers grouped by chunk, 8 B x d * nchunks * kBinChunk].
+constexpr int kDecodeSliceMaxRows = 8;                   // decode_median_kernel keeps 8 x d estimates per thread
+struct DecodeLayout {
+  bool possible;
+  uint32_t slice_log2, nbins, nchunks;
+  size_t hist_off, rowpre_off, binstart_off, rec_off, answers_off, total;
+};
+static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
+  DecodeLayout L;
+  const uint32_t log2w = log2_of(w);
+  L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+  const uint64_t nbins = (uint64_t)d << (log2w - L.slice_log2);
+  L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0 &&
+               d <= (uint32_t)kDecodeSliceMaxRows;
+  L.nbins = (uint32_t)(L.possible ? nbins : 0);
+  L.nchunks = (uint32_t)(L.possible ? ceil_div(cap, kBinChunk) : 0);
+  const size_t matrix = align256((size_t)L.nchunks * L.nbins * sizeof(uint32_t));
+  L.hist_off = workspace_base(n);
+  L.rowpre_off = L.hist_off + matrix;
+  L.binstart_off = L.rowpre_off + matrix;
+  L.rec_off = L.binstart_off + align256(((size_t)L.nbins + 1) * sizeof(uint32_t));
+  L.answers_off = L.rec_off + align256((size_t)(L.possible ? d * cap : 0) * 8);
+  L.total = L.answers_off + align256((size_t)L.nchunks * kBinChunk * d * 8);
+  return L;
+}
+
+// How s2r_decode reads the buckets.  Measured on MI355X: gathers from a sketch far larger than the L2
+// (4 MB per XCD) run at about 56e9 per second (each fetches a 128-byte line), from one of a few L2 sizes at
+// about 70e9, from one that fits at about 200e9; the slice route costs about 80 us of launches and latency
+// and passes about 110e9 queries per second.
+// `cap` (the capacity of the caller's lists) stands in for the number of union indices, which only the
+// device knows.
+static int32_t choose_decode(uint64_t n, uint32_t d, uint32_t w, bool have_lists, bool dense_out, uint64_t cap,
+                             size_t workspace_bytes) {
+  if (!have_lists || dense_out || cap == 0) return S2R_DECODE_GATHER;
+  const DecodeLayout L = decode_layout(n, d, w, cap);
+  if (!L.possible || workspace_bytes < L.total) return S2R_DECODE_GATHER;
+  if (g_decode_strategy != S2R_DECODE_AUTO) return g_decode_strategy;
+  const double queries = (double)cap * d;
+  const double sketch_bytes = 4.0 * d * w;
+  const double t_gather = queries / (sketch_bytes > 16e6 ? 56e9 : sketch_bytes > 4e6 ? 70e9 : 200e9);
+  const double t_slice = 80e-6 + queries / 110e9;
+  return t_slice < t_gather ? S2R_DECODE_SLICE : S2R_DECODE_GATHER;
+}
+
+// The slice kernels use more dynamic LDS than the default limit allows; raised once per host thread.
+static bool raise_lds_limits() {
+  static thread_local bool raised = false;
+  if (raised) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)(kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * kMaxBins)) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(decode_slice_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kSliceLog2Max)) != hipSuccess)
+    return false;
+  raised = true;
+  return true;
+}
+
 static inline void record(int slot, bool end, hipStream_t st) {
   hipEvent_t ev = end ? g_events[slot].end : g_events[slot].begin;
   if (ev != nullptr) (void)hipEventRecord(ev, st);
@@ -1165,6 +1427,20 @@ s2r_status s2r_set_insert_strategy(int32_t strategy) {
   return S2R_OK;
 }
 
+s2r_status s2r_set_decode_strategy(int32_t strategy) {
+  if (strategy != S2R_DECODE_AUTO && strategy != S2R_DECODE_GATHER && strategy != S2R_DECODE_SLICE) return S2R_ERR_SIZE;
+  g_decode_strategy = strategy;
+  return S2R_OK;
+}
+
+int32_t s2r_last_decode_strategy(void) { return g_last_decode_strategy; }
+
+size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
+  if (check_sizes(n, d, w) != S2R_OK || cap > n) return 0;
+  const DecodeLayout L = decode_layout(n, d, w, cap);
+  return L.possible ? L.total : workspace_base(n);
+}
+
 uint32_t s2r_scan_launch_workers(void) { return g_scan_launch_workers; }
 
 int32_t s2r_last_insert_strategy(void) { return g_last_strategy; }
@@ -1232,6 +1508,8 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   g_last_strategy = strategy;
 
   E.nworkers = W;
+  E.rowpre_off = 0;
+  E.payload_slot = 0;
   E.nnz_out = nnz_out;
   E.workspace = reinterpret_cast<char*>(workspace);
   E.ws_stride = ws_each;
@@ -1297,19 +1575,12 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
 
   if (strategy == S2R_INSERT_SLICE) {
     const size_t lds = sizeof(double) << E.slice_log2;
-    static thread_local bool lds_raised = false;
-    if (!lds_raised) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess ||
-          hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)(kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * kMaxBins)) != hipSuccess)
-        return S2R_ERR_LAUNCH;
-      lds_raised = true;
-    }
+    if (!raise_lds_limits()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_hist_kernel, dim3(E.nchunks, W), dim3(kBinBlock), 0, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_scan_kernel, dim3(1, W), dim3(kBinBlock), 0, st, E);
+    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(E.nbins, kWave), W), dim3(kBinBlock), 0, st, E);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_start_kernel, dim3(1, W), dim3(kBinBlock), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (log2w - E.slice_log2));
     hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, W), dim3(kBinBlock), scatter_lds, st, E, hp);
@@ -1403,6 +1674,86 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
                      (uint64_t)workspace_prefix_off(n), (uint64_t)workspace_dense_off(n), ntiles, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if ((idx_out == nullptr || cap == 0) && dense_out == nullptr) return S2R_OK;   // only the count was asked for
+
+  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr, idx_out ? cap : 0,
+                                         workspace_bytes);
+  g_last_decode_strategy = strategy;
+  if (strategy == S2R_DECODE_SLICE) {
+    if (cap > n) cap = n;
+    const DecodeLayout L = decode_layout(n, d, w, cap);
+    if (!raise_lds_limits()) return S2R_ERR_LAUNCH;
+    // the kernels of the encode's slice strategy, on one "worker" whose list is the union list
+    static thread_local EncodeBatch X;                     // (2.6 KB: not on the stack of every call)
+    X.w[0].grad = nullptr;                                 // expansion without values
+    X.w[0].sketch = nullptr;
+    X.w[0].bitmap = const_cast<uint64_t*>(bitmap);        // only read
+    X.w[0].nz_idx = idx_out;
+    X.w[0].nz_val = nullptr;
+    X.nnz_out = count_out;
+    X.workspace = reinterpret_cast<char*>(workspace);
+    X.ws_stride = 0;
+    X.prefix_off = workspace_prefix_off(n);
+    X.dense_off = workspace_dense_off(n);
+    X.hist_off = L.hist_off;
+    X.binstart_off = L.binstart_off;
+    X.rec_off = L.rec_off;
+    X.rowpre_off = L.rowpre_off;
+    X.payload_slot = 1;
+    X.n = n;
+    X.nwords = nwords;
+    X.cap = cap;
+    X.ntiles = ntiles;
+    X.d = d;
+    X.log2w = log2_of(w);
+    X.slice_log2 = L.slice_log2;
+    X.nbins = L.nbins;
+    X.nchunks = L.nchunks;
+    X.first_worker = 0;
+    X.nworkers = 1;
+    char* ws = reinterpret_cast<char*>(workspace);
+    DecodeSliceArgs Q;
+    Q.sketch = sketch;
+    Q.rec = reinterpret_cast<const u32x2*>(ws + L.rec_off);
+    Q.answers = reinterpret_cast<uint2*>(ws + L.answers_off);
+    Q.bin_start = reinterpret_cast<const uint32_t*>(ws + L.binstart_off);
+    Q.colpre = reinterpret_cast<const uint32_t*>(ws + L.hist_off);
+    Q.rowpre = reinterpret_cast<const uint32_t*>(ws + L.rowpre_off);
+    Q.count = count_out;
+    Q.cap = cap;
+    Q.val_out = val_out;
+    Q.nbins = L.nbins;
+    Q.slice_log2 = L.slice_log2;
+    Q.d = d;
+
+    record(S2R_KERNEL_DECODE, false, st);
+    const uint32_t helpers = dense_grid(ntiles, 2048);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, X, helpers);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_hist_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), 0, st, X, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(L.nbins, kWave), 1), dim3(kBinBlock), 0, st, X);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_start_kernel, dim3(1, 1), dim3(kBinBlock), 0, st, X);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (X.log2w - X.slice_log2));
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), scatter_lds, st, X, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(decode_slice_kernel, dim3(L.nbins), dim3(kSliceBlock), sizeof(float) << L.slice_log2, st, Q);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    const dim3 mgrid(L.nchunks), mblock(kBinBlock);
+    switch (d) {
+      case 1: hipLaunchKernelGGL(decode_median_kernel<1>, mgrid, mblock, 0, st, Q); break;
+      case 2: hipLaunchKernelGGL(decode_median_kernel<2>, mgrid, mblock, 0, st, Q); break;
+      case 3: hipLaunchKernelGGL(decode_median_kernel<3>, mgrid, mblock, 0, st, Q); break;
+      case 4: hipLaunchKernelGGL(decode_median_kernel<4>, mgrid, mblock, 0, st, Q); break;
+      case 5: hipLaunchKernelGGL(decode_median_kernel<5>, mgrid, mblock, 0, st, Q); break;
+      case 6: hipLaunchKernelGGL(decode_median_kernel<6>, mgrid, mblock, 0, st, Q); break;
+      case 7: hipLaunchKernelGGL(decode_median_kernel<7>, mgrid, mblock, 0, st, Q); break;
+      default: hipLaunchKernelGGL(decode_median_kernel<8>, mgrid, mblock, 0, st, Q); break;
+    }
+    record(S2R_KERNEL_DECODE, true, st);
+    return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+  }
 
   DecodeArgs A;
   A.sketch = sketch;

@@ -50,9 +50,11 @@ class Buffers:
         self.out_count = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dense_out = torch.empty(n, dtype=torch.float32, device=dev) if dense_out else None
         ws = binding.encode_workspace_bytes(n, d, w, min(max(nz_cap, 1), n))
-        if ws == 0:
+        ws_decode = binding.decode_workspace_bytes(n, d, w, min(max(union_cap, 1), n))
+        if ws == 0 or ws_decode == 0:
             raise ValueError("sizes outside the library's limits")
-        self.workspace = torch.empty(ws * W, dtype=torch.uint8, device=dev)     # W shares for encode_batch
+        # W shares for encode_batch; the same buffer serves s2r_decode afterwards
+        self.workspace = torch.empty(max(ws * W, ws_decode), dtype=torch.uint8, device=dev)
         assert self.workspace.data_ptr() % 256 == 0
 
     # ------------------------------------------------------------ the path

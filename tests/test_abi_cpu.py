@@ -150,3 +150,15 @@ def test_probe_read_argument_checks():
     assert lib.s2r_probe_read(0x1000, 8, 0x100, None) == b.S2R_ERR_SIZE
     assert lib.s2r_probe_read(0x1004, 1024, 0x100, None) == b.S2R_ERR_ALIGN
     assert lib.s2r_probe_read(0x1000, 1024, 0x104, None) == b.S2R_ERR_ALIGN
+
+
+def test_decode_strategy_and_workspace_argument_checks():
+    lib = b.load()
+    assert lib.s2r_set_decode_strategy(5) == b.S2R_ERR_SIZE
+    for st in (b.S2R_DECODE_SLICE, b.S2R_DECODE_GATHER, b.S2R_DECODE_AUTO):
+        assert lib.s2r_set_decode_strategy(st) == b.S2R_OK
+    base = b.workspace_bytes(1 << 20, 3, 1 << 14)
+    assert b.decode_workspace_bytes(1 << 20, 3, 1 << 14, 50000) >= base + 16 * 3 * 50000
+    assert b.decode_workspace_bytes(1 << 20, 9, 1 << 14, 50000) == base        # more than 8 rows: gather only
+    assert b.decode_workspace_bytes(1 << 20, 3, 1 << 14, (1 << 20) + 1) == 0    # cap > n
+    assert b.decode_workspace_bytes(0, 3, 1 << 14, 0) == 0

@@ -29,6 +29,17 @@ def strategy(request):
     yield request.param
     binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
 
+DECODES = {"gather": binding.S2R_DECODE_GATHER, "slice": binding.S2R_DECODE_SLICE}
+
+
+@pytest.fixture(params=["gather", "slice"])
+def decode_strategy(request):
+    """Run the test once per way of reading the buckets in s2r_decode."""
+    binding.set_decode_strategy(DECODES[request.param])
+    yield request.param
+    binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
 REL = 1e-5
 DENORM_SLACK = 64 * float(np.finfo(np.float32).tiny)
 
@@ -135,6 +146,97 @@ def test_tiles_around_the_expansion_group_size(strategy, dense_out):
         idx.append(i)
         val.append((rng.normal(0, 1, len(i)) + 2.5).astype(np.float32))
     _run_and_check(_custom(n, idx, val, d=3, w=1 << 10, W=2), dense_out=dense_out)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_small_recipes_both_decodes(cfg, decode_strategy):
+    """Without a dense output the decode may take either route; with one (the
+    tests above) it gathers."""
+    b, _ = _run_and_check(workloads.make_small(cfg))
+    assert binding.last_decode_strategy() == DECODES[decode_strategy]
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_full_size_recipes_both_decodes(cfg, decode_strategy):
+    _run_and_check(workloads.make(cfg))
+    assert binding.last_decode_strategy() == DECODES[decode_strategy]
+
+
+@pytest.mark.parametrize("n", [1, 65, 8191, 8192, 8193, 3 * 8192 + 5, 100003])
+def test_decode_by_slices_dense_gradient_chunk_boundaries(n):
+    """Every element set: list chunks (8192 positions) full, ragged and single."""
+    binding.set_decode_strategy(binding.S2R_DECODE_SLICE)
+    try:
+        rng = np.random.default_rng(n)
+        wl = _custom(n, [np.arange(n)] * 2, [rng.normal(0, 1, n).astype(np.float32) + 3.0 for _ in range(2)],
+                     d=5, w=1 << 9, W=2)
+        _run_and_check(wl)
+        assert binding.last_decode_strategy() == binding.S2R_DECODE_SLICE
+    finally:
+        binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
+@pytest.mark.parametrize("d,w", [(1, 1), (2, 4), (4, 1 << 14), (6, 1 << 15), (7, 1 << 3), (8, 1 << 16), (9, 1 << 6)])
+def test_decode_by_slices_rows_and_widths(d, w):
+    """Even and odd d up to the route's limit of 8 rows (d = 9 must gather), widths
+    below, at and above one LDS slice."""
+    binding.set_decode_strategy(binding.S2R_DECODE_SLICE)
+    try:
+        rng = np.random.default_rng(100 * d + 7)
+        n = 70001
+        idx = [np.sort(rng.choice(n, 9000, replace=False)) for _ in range(3)]
+        val = [rng.normal(0, 1, 9000).astype(np.float32) for _ in range(3)]
+        _run_and_check(_custom(n, idx, val, d=d, w=w, W=3))
+        want = binding.S2R_DECODE_SLICE if d <= 8 else binding.S2R_DECODE_GATHER
+        assert binding.last_decode_strategy() == want
+    finally:
+        binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
+def test_decode_by_slices_respects_capacity():
+    """Union of 30000 indices, lists of 20000: the first 20000 entries, the true
+    count, nothing beyond the lists."""
+    binding.set_decode_strategy(binding.S2R_DECODE_SLICE)
+    try:
+        rng = np.random.default_rng(3)
+        n, cap = 200000, 20000
+        idx = np.sort(rng.choice(n, 30000, replace=False)).astype(np.uint32)
+        val = rng.normal(0, 1, 30000).astype(np.float32)
+        wl = _custom(n, [idx], [val], d=3, w=1 << 12)
+        b = pipeline.buffers_for(wl)
+        b.out_idx = torch.full((cap + 16,), -1, dtype=torch.int32, device="cuda")[:cap]
+        b.out_val = torch.full((cap + 16,), -7.0, dtype=torch.float32, device="cuda")[:cap]
+        b.step()
+        torch.cuda.synchronize()
+        assert binding.last_decode_strategy() == binding.S2R_DECODE_SLICE
+        assert int(b.out_count.cpu()[0]) == 30000
+        assert np.array_equal(b.out_idx.cpu().numpy().view(np.uint32), idx[:cap])
+        assert (b.out_idx._base[cap:].cpu().numpy() == -1).all() and (b.out_val._base[cap:].cpu().numpy() == -7.0).all()
+        enc = orc.encode_sparse(idx, val, n, 3, 1 << 12, 0)
+        dec = orc.decode(enc["S"], enc["bitmap"], n, 0)
+        tol = REL * orc.decode_tolerance_mass(enc["M"], dec["idx"][:cap], 0) + DENORM_SLACK
+        assert np.all(np.abs(b.out_val.cpu().numpy().astype(np.float64) - dec["val"][:cap]) <= tol)
+    finally:
+        binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
+def test_both_decodes_return_identical_values():
+    """The two routes read the same cells and take the same median: bit-identical."""
+    wl = workloads.make_small(4)
+    b = pipeline.buffers_for(wl)
+    b.encode_all()
+    b.merge()
+    got = {}
+    for name, st in DECODES.items():
+        binding.set_decode_strategy(st)
+        b.out_val.fill_(0)
+        b.decode()
+        torch.cuda.synchronize()
+        cnt = int(b.out_count.cpu()[0])
+        got[name] = (b.out_idx[:cnt].cpu().numpy().copy(), b.out_val[:cnt].cpu().numpy().copy())
+    binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+    assert np.array_equal(got["gather"][0], got["slice"][0])
+    assert np.array_equal(got["gather"][1].view(np.uint32), got["slice"][1].view(np.uint32))
 
 
 def test_all_zero_gradient(strategy):
