@@ -501,7 +501,9 @@ constexpr int kBinItems = 8;                           // list items per thread
 constexpr int kBinChunk = kBinBlock * kBinItems;       // 8192 items per workgroup
 constexpr int kMaxBins = 8192;                         // d * slices per row that the LDS histograms hold
 constexpr size_t kSliceLdsMax = sizeof(double) << kSliceLog2Max;
-static_assert(kMaxBins <= (1 << 13) && kSliceLog2Max <= 14, "bin_scatter_kernel packs slice and cell into one word");
+constexpr int kDecodeSliceLog2Max = 15;               // decode holds float32 cells: 2^15 of them are 128 KiB of LDS
+static_assert(kMaxBins <= (1 << 13) && kSliceLog2Max <= 15 && kDecodeSliceLog2Max <= 15,
+              "bin_scatter_kernel packs slice (bits 16..28) and cell (bits 0..14) into one word");
 
 __device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t k) {
   const uint64_t nnz = B.nnz_out[k];
@@ -666,7 +668,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch 
 // counters gives the start of every slice's run) and then copied out in sorted
 // order, so that consecutive lanes write consecutive records of the (chunk, bin)
 // run that the histogram pass reserved.  In LDS a record carries its slice number
-// in bits 16..28 of its first word (the cell takes bits 0..13, the sign bit 31).
+// in bits 16..28 of its first word (the cell takes bits 0..14, the sign bit 31).
 // Dynamic LDS: kBinChunk records, then two arrays of (slices per row) counters.
 __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
   extern __shared__ uint2 s_stage[];
@@ -754,7 +756,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
     __syncthreads();
     for (uint32_t p = threadIdx.x; p < count; p += kBinBlock) {
       const uint2 r = s_stage[p];
-      rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80003FFFu, r.y);
+      rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80007FFFu, r.y);
     }
     for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;      // for the next row; not read above
   }
@@ -1102,6 +1104,12 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
   const uint32_t first = A.bin_start[bin], last = A.bin_start[bin + 1];
   if (first == last) return;                              // uniform over the workgroup
+  const u32x2 none = {0u, 0u};
+  u32x2 x[kAhead];                                        // the first queries are requested together with the slice
+  uint64_t r0 = (uint64_t)first + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < kAhead; ++u)
+    x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r0 + u * kSliceBlock]) : none;
   const uint32_t cells = 1u << A.slice_log2;
   const float* src = A.sketch + (uint64_t)bin * cells;    // row-major sketch: slice s of row j starts at bin * cells
   if (cells >= 4u * kSliceBlock) {                        // (the sketch and every slice of 4 cells or more are 16-byte aligned)
@@ -1111,13 +1119,13 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
     for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_cells[c] = src[c];
   }
   __syncthreads();
-  const u32x2 none = {0u, 0u};
-  for (uint64_t r0 = (uint64_t)first + threadIdx.x; r0 < last; r0 += kSliceBlock * kAhead) {
-    u32x2 x[kAhead];
+  while (r0 < last) {                                     // x holds the queries r0 + u * kSliceBlock
+    const uint64_t r1 = r0 + kSliceBlock * kAhead;
+    u32x2 y[kAhead];
     uint32_t colp[kAhead], rowp[kAhead];
 #pragma unroll
     for (int u = 0; u < kAhead; ++u)
-      x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r0 + u * kSliceBlock]) : none;
+      y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r1 + u * kSliceBlock]) : none;
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
       const uint64_t at = (uint64_t)(x[u].y >> kBinChunkLog2) * A.nbins + bin;
@@ -1134,6 +1142,9 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
       const uint64_t at = chunk * kBinChunk * A.d + rowp[u] + (uint32_t)(r - first - colp[u]);
       A.answers[at] = make_uint2(est, x[u].y & (kBinChunk - 1));
     }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) x[u] = y[u];
+    r0 = r1;
   }
 }
 
@@ -1307,7 +1318,7 @@ struct DecodeLayout {
 static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   DecodeLayout L;
   const uint32_t log2w = log2_of(w);
-  L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
+  L.slice_log2 = log2w < (uint32_t)kDecodeSliceLog2Max ? log2w : (uint32_t)kDecodeSliceLog2Max;
   const uint64_t nbins = (uint64_t)d << (log2w - L.slice_log2);
   L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0 &&
                d <= (uint32_t)kDecodeSliceMaxRows;
@@ -1352,7 +1363,7 @@ static bool raise_lds_limits() {
                           hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)(kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * kMaxBins)) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(decode_slice_kernel),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kSliceLog2Max)) != hipSuccess)
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kDecodeSliceLog2Max)) != hipSuccess)
     return false;
   raised = true;
   return true;
