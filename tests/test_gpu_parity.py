@@ -453,3 +453,24 @@ def test_large_gradients_are_scanned_worker_by_worker():
         assert binding.scan_launch_workers() == 1
     finally:
         binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+
+
+def test_estimation_quality_matches_oracle_and_improves_with_sketch_size():
+    """The relative error of the decoded sum (quality.py) equals the oracle's on the
+    same inputs, falls as the sketch grows, and is smaller with 3 rows than with 1
+    at equal width (median of independent estimates, Section 3.1)."""
+    from paper_2110_02140_amd import quality
+    errs = {}
+    for d in (1, 3):
+        for L in (10, 13, 16):
+            wl = workloads.cfg1(W=3, n=1 << 18, density=0.01, d=d, w=1 << L)
+            r = quality.relative_error(wl)
+            ref = orc.reduce_workers([wl.dense(k) for k in range(wl.W)], d, 1 << L, wl.seed)
+            union, total = quality.true_sum(wl)
+            assert np.array_equal(ref["idx"], union)
+            ref_err = np.linalg.norm(ref["val"] - total) / np.linalg.norm(total)
+            assert abs(r["rel_error"] - ref_err) <= 1e-4 * max(ref_err, 1e-3), (d, L, r["rel_error"], ref_err)
+            errs[(d, L)] = r["rel_error"]
+    for d in (1, 3):
+        assert errs[(d, 10)] > errs[(d, 13)] > errs[(d, 16)]
+    assert errs[(3, 13)] < errs[(1, 13)] and errs[(3, 16)] < errs[(1, 16)]
