@@ -44,6 +44,15 @@ design notes of the repository):
   * the decoder returns the estimate of the SUM over workers (Algorithm 1 has no
     division by W).
 
+Block-granular variant (the *_blocks functions at the end): Section 3.1 sizes the
+bitmap by "the number of word vectors or gradient blocks", one bit saying whether
+the block contains a non-zero gradient; Algorithm 1's bitmap line is written per
+block.  There the bitmap has one bit per block of B consecutive elements (the last
+block may be shorter), the sketch still receives the non-zero elements only (the
+zeros "have no effect on the bucket value"), and decompression queries every
+element of every block whose aggregated bit is set.  B = 1 is the element-granular
+codec above.
+
 Parity pins: see tests/test_oracle_*.py.  No function in this file is unpinned,
 but the hash family itself is a reading (the paper names none); it is pinned to a
 big-integer re-statement and to the published SplitMix64 reference outputs.
@@ -261,5 +270,58 @@ def reduce_workers(grads: list[np.ndarray], d: int, w: int, seed: int, dense: bo
     S, C = merge([e["S"] for e in enc], [e["bitmap"] for e in enc])
     M = np.sum([e["M"] for e in enc], axis=0)
     out = decode(S, C, grads[0].shape[0], seed, dense=dense)
+    out.update({"S": S, "M": M, "bitmap": C, "workers": enc})
+    return out
+
+
+# --------------------------------------------------------------------------
+# block-granular variant (Section 3.1: bitmap over word vectors / gradient
+# blocks; Algorithm 1: "C[x] <- 1 if x-th block is non-zero")
+# --------------------------------------------------------------------------
+
+def block_mask(g: np.ndarray, B: int) -> np.ndarray:
+    """bool[ceil(n / B)]: block x is set iff one of its elements g[xB .. xB+B) is non-zero."""
+    nz = nonzero_mask(np.ascontiguousarray(g, dtype=np.float32))
+    nb = (nz.shape[0] + B - 1) // B
+    padded = np.zeros(nb * B, dtype=bool)
+    padded[: nz.shape[0]] = nz
+    return padded.reshape(nb, B).any(axis=1)
+
+
+def block_elements(blocks: np.ndarray, B: int, n: int) -> np.ndarray:
+    """Ascending element indices (int64) of the listed blocks, those below n only."""
+    e = (np.asarray(blocks, dtype=np.int64)[:, None] * B + np.arange(B, dtype=np.int64)[None, :]).reshape(-1)
+    return e[e < n]
+
+
+def encode_blocks(g: np.ndarray, B: int, d: int, w: int, seed: int) -> dict:
+    """One worker's compress step with a bitmap over blocks of B elements.  The
+    sketch is the one encode() builds: only non-zero elements are inserted."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    bm = block_mask(g, B)
+    idx, val = sparse_of(g)
+    S, M = insert(idx, val, d, w, seed)
+    return {"bitmap": pack_bitmap(bm), "blocks": np.flatnonzero(bm).astype(np.uint32), "S": S, "M": M}
+
+
+def decode_blocks(S: np.ndarray, bitmap: np.ndarray, n: int, B: int, seed: int) -> dict:
+    """Decompress with a block bitmap: the set blocks (ascending), and for each the
+    median-of-rows estimate of every one of its B elements.  `val` is
+    [len(blocks), B]; positions of the last block that lie beyond n hold 0."""
+    nb = (n + B - 1) // B
+    blocks = bitmap_indices(bitmap, nb)
+    e = (blocks.astype(np.int64)[:, None] * B + np.arange(B, dtype=np.int64)[None, :]).reshape(-1)
+    inside = e < n
+    val = np.zeros(e.shape[0], dtype=np.float64)
+    val[inside] = median_rows(estimates(S, e[inside].astype(np.uint32), seed))
+    return {"blocks": blocks, "val": val.reshape(len(blocks), B)}
+
+
+def reduce_workers_blocks(grads: list[np.ndarray], B: int, d: int, w: int, seed: int) -> dict:
+    """Whole of Algorithm 1 with the block bitmap for W dense-stored worker gradients."""
+    enc = [encode_blocks(g, B, d, w, seed) for g in grads]
+    S, C = merge([e["S"] for e in enc], [e["bitmap"] for e in enc])
+    M = np.sum([e["M"] for e in enc], axis=0)
+    out = decode_blocks(S, C, grads[0].shape[0], B, seed)
     out.update({"S": S, "M": M, "bitmap": C, "workers": enc})
     return out

@@ -102,3 +102,38 @@ def decompress(C, S, seed):
                 est.append(s(i, c, e) * S[j][h(i, a, b, w)])
             out[i] = median(est)
     return out
+
+
+# ---- block-granular variant: the bitmap has one flag per block of B elements
+def block_flags(g, B):
+    """flags[x] = 1 iff some element of block x (g[xB .. xB+B), cut at len(g)) is non-zero."""
+    n = len(g)
+    out = []
+    x = 0
+    while x * B < n:
+        out.append(1 if any(is_nonzero(g[i]) for i in range(x * B, min(n, x * B + B))) else 0)
+        x += 1
+    return out
+
+
+def decompress_blocks(Cb, S, n, B, seed):
+    """{block: [B estimates]} for every set block; positions at or beyond n hold 0.0."""
+    d, w = len(S), len(S[0])
+    P = params(seed, d)
+    out = {}
+    for x, f in enumerate(Cb):
+        if not f:
+            continue
+        vals = []
+        for o in range(B):
+            i = x * B + o
+            if i >= n:
+                vals.append(0.0)
+                continue
+            est = []
+            for j in range(d):
+                a, b, c, e = P[j]
+                est.append(s(i, c, e) * S[j][h(i, a, b, w)])
+            vals.append(median(est))
+        out[x] = vals
+    return out

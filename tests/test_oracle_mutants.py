@@ -31,6 +31,8 @@ def _some_pin_fails():
         (pins.test_merged_bitmap_popcount_is_union_size, ()),
         (pins.test_single_element_gradient, ()),
         (pins.test_hash_params_order_and_oddness, ()),
+        (pins.test_block_algorithm_matches_pure_python, (7, 4, 32, 2)),
+        (pins.test_block_sketch_equals_element_sketch_and_values_agree_on_the_union, ()),
     ]
     return any(_fails(fn, *a) for fn, a in checks)
 
@@ -127,11 +129,43 @@ def _mut_insert_assign_not_accumulate(monkeypatch):
     monkeypatch.setattr(orc, "insert", bad)
 
 
+def _mut_block_needs_all_elements(monkeypatch):
+    real = orc.block_mask
+    def bad(g, B):
+        nz = orc.nonzero_mask(np.ascontiguousarray(g, dtype=np.float32))
+        nb = (nz.shape[0] + B - 1) // B
+        padded = np.ones(nb * B, dtype=bool)
+        padded[: nz.shape[0]] = nz
+        return padded.reshape(nb, B).all(axis=1)
+    monkeypatch.setattr(orc, "block_mask", bad)
+
+
+def _mut_block_boundary_shifted(monkeypatch):
+    def bad(g, B):
+        nz = orc.nonzero_mask(np.ascontiguousarray(g, dtype=np.float32))
+        nz = np.concatenate([[False], nz[:-1]])                     # element i counted in the block of i + 1
+        nb = (nz.shape[0] + B - 1) // B
+        padded = np.zeros(nb * B, dtype=bool)
+        padded[: nz.shape[0]] = nz
+        return padded.reshape(nb, B).any(axis=1)
+    monkeypatch.setattr(orc, "block_mask", bad)
+
+
+def _mut_block_decode_skips_zero_elements(monkeypatch):
+    real = orc.decode_blocks
+    def bad(S, bitmap, n, B, seed):
+        out = real(S, bitmap, n, B, seed)
+        out["val"] = np.where(np.abs(out["val"]) < 1e-3, 0.0, out["val"])      # as if only "large" entries were queried
+        return out
+    monkeypatch.setattr(orc, "decode_blocks", bad)
+
+
 @pytest.mark.parametrize("mutant", [
     _mut_sign_dropped_in_query, _mut_msb_first_bitmap, _mut_median_off_by_one,
     _mut_low_bits_bucket, _mut_sign_uses_bucket_multiplier, _mut_merge_xor,
     _mut_merge_drops_last_worker, _mut_negative_zero_counts,
     _mut_insert_assign_not_accumulate,
+    _mut_block_needs_all_elements, _mut_block_boundary_shifted, _mut_block_decode_skips_zero_elements,
 ], ids=lambda f: f.__name__)
 def test_planted_mistake_is_caught(monkeypatch, mutant):
     mutant(monkeypatch)

@@ -325,3 +325,82 @@ def test_mass_table_bounds_sketch():
     assert np.all(res["M"] >= np.abs(res["S"]) - 1e-18)
     m = orc.decode_tolerance_mass(res["M"], res["idx"], wl.seed)
     assert np.all(m >= np.abs(res["val"]) - 1e-18)
+
+
+# ---------------------------------------------------------------- block-granular variant
+@pytest.mark.parametrize("B,d,w,seed", [(1, 3, 16, 0), (4, 3, 16, 1), (7, 4, 32, 2), (64, 5, 8, 3), (250, 2, 4, 4)])
+def test_block_algorithm_matches_pure_python(B, d, w, seed):
+    """Bitmap per block, sketch from the non-zero elements, every element of a set
+    block queried: against Python loops over lists, with a ragged last block."""
+    rng = np.random.default_rng(300 + seed)
+    n, W = 203, 3
+    gs = _tiny_grads(rng, W, n, 0.05, specials=True)
+    res = orc.reduce_workers_blocks(gs, B, d, w, seed)
+    flags = [bf.block_flags([float(x) for x in g], B) for g in gs]
+    Ss = [bf.compress([float(x) for x in g], d, w, seed)[1] for g in gs]
+    for k in range(W):
+        assert [int(x) for x in res["workers"][k]["bitmap"]] == bf.words_of(flags[k])
+        assert res["workers"][k]["blocks"].tolist() == [x for x, f in enumerate(flags[k]) if f]
+        assert np.allclose(res["workers"][k]["S"], np.array(Ss[k]), rtol=0, atol=1e-18)
+    Cb, S = bf.aggregate(flags, Ss)
+    assert [int(x) for x in res["bitmap"]] == bf.words_of(Cb)
+    want = bf.decompress_blocks(Cb, S, n, B, seed)
+    assert res["blocks"].tolist() == sorted(want)
+    assert res["val"].shape == (len(want), B)
+    for row, x in zip(res["val"], res["blocks"].tolist()):
+        assert row.tolist() == pytest.approx(want[x], rel=0, abs=1e-17)
+
+
+def test_block_size_one_is_the_element_codec():
+    rng = np.random.default_rng(11)
+    gs = _tiny_grads(rng, 2, 500, 0.1, specials=True)
+    a = orc.reduce_workers(gs, 3, 64, 5)
+    b = orc.reduce_workers_blocks(gs, 1, 3, 64, 5)
+    assert np.array_equal(a["bitmap"], b["bitmap"]) and np.array_equal(a["S"], b["S"])
+    assert np.array_equal(a["idx"], b["blocks"]) and np.array_equal(a["val"], b["val"][:, 0])
+
+
+def test_block_sketch_equals_element_sketch_and_values_agree_on_the_union():
+    """The zeros inside a set block are inert (Section 3.1), so the sketch does not
+    depend on B, and at the union's elements the block decoder returns what the
+    element decoder returns."""
+    rng = np.random.default_rng(12)
+    n, B = 1000, 16
+    gs = _tiny_grads(rng, 3, n, 0.03)
+    a = orc.reduce_workers(gs, 5, 128, 2)
+    b = orc.reduce_workers_blocks(gs, B, 5, 128, 2)
+    assert np.array_equal(a["S"], b["S"])
+    flat = b["val"].reshape(-1)
+    pos = {int(x): p for p, x in enumerate(b["blocks"])}
+    for i, v in zip(a["idx"].tolist(), a["val"].tolist()):
+        assert i // B in pos
+        assert flat[pos[i // B] * B + i % B] == v
+    union_blocks = set()
+    for g in gs:
+        union_blocks |= {int(i) // B for i in np.flatnonzero(g)}
+    assert set(pos) == union_blocks                        # popcount of the merged bitmap = blocks in the union
+
+
+def test_block_exact_recovery_when_collision_free():
+    """With a width at which every element of the set blocks has a bucket of its own
+    in every row, the block decoder returns the true sum, zeros included."""
+    n, B, W, d = 4096, 32, 2, 3
+    rng = np.random.default_rng(13)
+    gs = []
+    for k in range(W):
+        g = np.zeros(n, dtype=np.float32)
+        for x in rng.choice(n // B, 3, replace=False):
+            sel = rng.choice(B, 5, replace=False)
+            g[x * B + sel] = rng.normal(0, 1, 5).astype(np.float32)
+        gs.append(g)
+    total = np.sum([g.astype(np.float64) for g in gs], axis=0)
+    for seed in range(200):
+        res = orc.reduce_workers_blocks(gs, B, d, 1 << 16, seed)
+        elems = orc.block_elements(res["blocks"], B, n)
+        ok = True
+        for j, (a, b, _c, _e) in enumerate(orc.hash_params(seed, d)):
+            ok &= len(set(orc.bucket_hash(elems.astype(np.uint32), a, b, 1 << 16).tolist())) == len(elems)
+        if ok:
+            assert np.array_equal(res["val"].reshape(-1), total[elems])
+            return
+    raise AssertionError("no collision-free seed found: widen the sketch")
