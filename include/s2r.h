@@ -198,6 +198,82 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
                       void* stream);
 
 /*
+ * Block-granular codec: the bitmap as Section 3.1 sizes it, one bit per word
+ * vector or gradient block that tells whether the block holds a non-zero
+ * gradient (the bitmap line of Algorithm 1 is written per block).  Block x is
+ * the elements x*block .. x*block + block - 1 (the last block may be shorter);
+ * the bitmap has nb = ceil(n / block) bits in the layout described at the top of
+ * this file.  The sketch is the one s2r_encode builds: only non-zero elements
+ * are inserted (Section 3.1: zeros do not change a bucket), so it does not
+ * depend on block, and block = 1 is the element codec.  Aggregation is s2r_merge with n = nb.
+ * Decompression queries every element of every block whose aggregated bit is
+ * set.  Limits: as above, and 1 <= block <= 2^31.
+ *
+ * s2r_blocks_workspace_bytes: the least scratch for s2r_encode_blocks* and
+ * s2r_decode_blocks; the other two: what lets them also use S2R_INSERT_SLICE /
+ * S2R_DECODE_SLICE for lists of blk_cap blocks (needs d * blk_cap * block < 2^32).
+ * Host only; 0 outside the limits or if blk_cap > nb.
+ */
+size_t s2r_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w);
+size_t s2r_encode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t blk_cap);
+size_t s2r_decode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t blk_cap);
+
+/*
+ * Compress with a block bitmap (Algorithm 1: the bitmap line as printed, and the
+ * two insertion loops).  Arguments as s2r_encode / s2r_encode_batch except:
+ *   block          elements per bitmap bit
+ *   block_bitmap   dev, out: ceil(nb/64) uint64, OVERWRITTEN; 8-byte aligned
+ *   blk_idx        dev, out: the non-zero blocks in ascending order, capacity
+ *                  blk_cap entries; may be NULL (then blk_cap is ignored and the
+ *                  insertions are atomics).  Entries at positions >= blk_cap are
+ *                  not written.
+ *   nblk_out       dev, out: uint64 (one per worker), the true number of non-zero
+ *                  blocks.  Required.
+ * The sketch is complete whatever blk_cap is.  The batch form takes host arrays of
+ * W device pointers, blk_idx NULL or an array of W non-NULL pointers, and splits
+ * the workspace evenly between the workers.
+ */
+s2r_status s2r_encode_blocks(const float* grad, uint64_t n, uint32_t block,
+                             uint32_t d, uint32_t w, uint64_t seed,
+                             float* sketch, uint64_t* block_bitmap,
+                             uint32_t* blk_idx, uint64_t blk_cap,
+                             uint64_t* nblk_out,
+                             void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+s2r_status s2r_encode_blocks_batch(const float* const* grads /* host array */, uint32_t W,
+                                   uint64_t n, uint32_t block,
+                                   uint32_t d, uint32_t w, uint64_t seed,
+                                   float* const* sketches /* host array */,
+                                   uint64_t* const* block_bitmaps /* host array */,
+                                   uint32_t* const* blk_idx /* host array or NULL */, uint64_t blk_cap,
+                                   uint64_t* nblk_out /* dev, W entries */,
+                                   void* workspace, size_t workspace_bytes,
+                                   void* stream);
+
+/*
+ * Decompress with a block bitmap (Algorithm 1: the recovery line and the query
+ * loops over every element of the recovered blocks).
+ *   sketch, block_bitmap   dev, in : the aggregated sketch and block bitmap
+ *   blk_idx_out  dev, out: the set blocks in ascending order, blk_cap entries
+ *   val_out      dev, out: blk_cap * block float32; entry p*block + o is the
+ *                median-of-rows estimate of element blk_idx_out[p]*block + o, or
+ *                +0.0 where that element is not below n.  Both NULL (count only)
+ *                or both non-NULL; nothing is written for list positions
+ *                >= blk_cap.
+ *   nblk_out     dev, out: one uint64, the true number of set blocks.  Required.
+ * Routes and their conditions as for s2r_decode (s2r_set_decode_strategy), with
+ * cap = blk_cap * block; there is no dense output.
+ */
+s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap,
+                             uint64_t n, uint32_t block,
+                             uint32_t d, uint32_t w, uint64_t seed,
+                             uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,
+                             uint64_t* nblk_out,
+                             void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * How s2r_encode carries out the insertion loops of Algorithm 1
  * (S[j, h_j(i)] += s_j(i) g(i)); the result is the same sketch either way.
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued

@@ -45,11 +45,11 @@ design notes of the repository):
     division by W).
 
 Block-granular variant (the *_blocks functions at the end): Section 3.1 sizes the
-bitmap by "the number of word vectors or gradient blocks", one bit saying whether
-the block contains a non-zero gradient; Algorithm 1's bitmap line is written per
+bitmap by the number of word vectors or gradient blocks, one bit telling whether
+the block holds a non-zero gradient, and Algorithm 1's bitmap line is written per
 block.  There the bitmap has one bit per block of B consecutive elements (the last
-block may be shorter), the sketch still receives the non-zero elements only (the
-zeros "have no effect on the bucket value"), and decompression queries every
+block may be shorter), the sketch still receives the non-zero elements only
+(Section 3.1: zeros do not change a bucket), and decompression queries every
 element of every block whose aggregated bit is set.  B = 1 is the element-granular
 codec above.
 
@@ -67,8 +67,8 @@ _MASK64 = (1 << 64) - 1
 
 
 # --------------------------------------------------------------------------
-# hash family (Section 3.1: "randomly mapped to a bucket by a hash function h",
-# "vector of random sign"; Algorithm 1 initialisation: {s_ij}, {h_ij})
+# hash family (Section 3.1: a hash function h picks the bucket of a non-zero, a
+# random sign vector s weights it; Algorithm 1 initialisation: {s_ij}, {h_ij})
 # --------------------------------------------------------------------------
 
 def splitmix64_stream(seed: int, count: int) -> list[int]:
@@ -276,7 +276,7 @@ def reduce_workers(grads: list[np.ndarray], d: int, w: int, seed: int, dense: bo
 
 # --------------------------------------------------------------------------
 # block-granular variant (Section 3.1: bitmap over word vectors / gradient
-# blocks; Algorithm 1: "C[x] <- 1 if x-th block is non-zero")
+# blocks; Algorithm 1: the bitmap line, which sets the bit of a non-zero block)
 # --------------------------------------------------------------------------
 
 def block_mask(g: np.ndarray, B: int) -> np.ndarray:

@@ -63,6 +63,16 @@ SIGNATURES = {
     "s2r_set_decode_strategy": (c_int32, [c_int32]),
     "s2r_last_decode_strategy": (c_int32, []),
     "s2r_decode_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint64]),
+    "s2r_blocks_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint32]),
+    "s2r_encode_blocks_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint32, c_uint64]),
+    "s2r_decode_blocks_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint32, c_uint64]),
+    "s2r_encode_blocks": (c_int32, [c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
+                                    c_void_p, c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "s2r_encode_blocks_batch": (c_int32, [ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32, c_uint32, c_uint32,
+                                          c_uint64, ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
+                                          ctypes.POINTER(c_void_p), c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "s2r_decode_blocks": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
+                                    c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
 
 _lib = None
@@ -179,6 +189,50 @@ def decode(sketch, bitmap, n, d, w, seed, idx_out, val_out, count_out, dense_out
                            workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_decode")
+
+
+def blocks_workspace_bytes(n: int, block: int, d: int, w: int) -> int:
+    return load().s2r_blocks_workspace_bytes(n, block, d, w)
+
+
+def encode_blocks_workspace_bytes(n: int, block: int, d: int, w: int, blk_cap: int) -> int:
+    return load().s2r_encode_blocks_workspace_bytes(n, block, d, w, blk_cap)
+
+
+def decode_blocks_workspace_bytes(n: int, block: int, d: int, w: int, blk_cap: int) -> int:
+    return load().s2r_decode_blocks_workspace_bytes(n, block, d, w, blk_cap)
+
+
+def encode_blocks(grad, block, d, w, seed, sketch, block_bitmap, blk_idx, nblk_out, workspace, stream=None, n=None):
+    """s2r_encode_blocks on torch device tensors; blk_idx int32[blk_cap] or None."""
+    n = grad.numel() if n is None else n
+    cap = 0 if blk_idx is None else blk_idx.numel()
+    st = load().s2r_encode_blocks(_ptr(grad), n, block, d, w, seed, _ptr(sketch), _ptr(block_bitmap), _ptr(blk_idx), cap,
+                                  _ptr(nblk_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_encode_blocks")
+
+
+def encode_blocks_batch(grads, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, nblk_out, workspace, stream=None):
+    """s2r_encode_blocks_batch: lists of W device tensors; blk_idx a list or None; nblk_out int64[W]."""
+    cap = 0 if blk_idx is None else min(t.numel() for t in blk_idx)
+    st = load().s2r_encode_blocks_batch(_ptr_array(grads), len(grads), n, block, d, w, seed, _ptr_array(sketches),
+                                        _ptr_array(block_bitmaps), None if blk_idx is None else _ptr_array(blk_idx),
+                                        cap, _ptr(nblk_out), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_encode_blocks_batch")
+
+
+def decode_blocks(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, nblk_out, workspace, stream=None):
+    """s2r_decode_blocks; blk_idx_out int32[blk_cap] and val_out float32[blk_cap * block], or both None."""
+    cap = 0 if blk_idx_out is None else blk_idx_out.numel()
+    st = load().s2r_decode_blocks(_ptr(sketch), _ptr(block_bitmap), n, block, d, w, seed, _ptr(blk_idx_out),
+                                  _ptr(val_out), cap, _ptr(nblk_out), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_decode_blocks")
 
 
 def set_insert_strategy(strategy: int):

@@ -106,6 +106,8 @@ struct EncodeBatch {
   uint64_t rowpre_off;       // decode by slices: per chunk, the exclusive prefix of its histogram over the
                              //   bins, [nchunks][nbins] u32; 0 when not wanted
   uint32_t payload_slot;     // non-zero: a record carries its item's list position instead of nz_val
+  uint32_t block;            // block-granular codec: elements per bitmap bit; nz_idx then lists blocks, and
+                             //   bitmap / nwords / ntiles / cap describe the block bitmap.  0: one bit per element
   uint64_t n;
   uint64_t nwords;
   uint64_t cap;
@@ -139,8 +141,10 @@ __device__ __forceinline__ uint2* ws_records(const EncodeBatch& B, uint32_t k) {
 }
 
 // ------------------------------------------------------------------ zero
-// Per worker: zeroes the sketch (nvec 16-byte units plus ntail trailing floats).
-__global__ __launch_bounds__(kBlock) void zero_kernel(const EncodeBatch B, uint64_t nvec, uint32_t ntail) {
+// Per worker: zeroes the sketch (nvec 16-byte units plus ntail trailing floats)
+// and, with bitmap_words, the (block) bitmap that the scan then sets bit by bit.
+__global__ __launch_bounds__(kBlock) void zero_kernel(const EncodeBatch B, uint64_t nvec, uint32_t ntail,
+                                                      uint64_t bitmap_words) {
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   const uint64_t tid = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -148,6 +152,7 @@ __global__ __launch_bounds__(kBlock) void zero_kernel(const EncodeBatch B, uint6
   uint4* p16 = reinterpret_cast<uint4*>(B.w[k].sketch);
   for (uint64_t i = tid; i < nvec; i += stride) p16[i] = make_uint4(0u, 0u, 0u, 0u);
   if (tid < ntail) B.w[k].sketch[nvec * 4 + tid] = 0.0f;
+  for (uint64_t i = tid; i < bitmap_words; i += stride) B.w[k].bitmap[i] = 0ull;
 }
 
 // ------------------------------------------------------------------ encode: dense scan
@@ -169,7 +174,11 @@ __device__ __forceinline__ void sketch_insert(float* sketch, uint32_t d, uint32_
 // workgroup's non-zero count (at most 2048) is stored as piece blockIdx.x of the
 // worker's 16-bit piece counts; the grid covers every piece of every tile, so
 // the pieces past the end of the gradient are written too (as zero).
-template <int EPL, bool INSERT>
+// BLOCKS: the block-granular codec.  No element bitmap and no counts are written;
+// instead every non-zero element sets the bit of its block B.block in the worker's
+// (zeroed) block bitmap with an atomic OR, once per run of non-zero lanes of a
+// word that fall in the same block.
+template <int EPL, bool INSERT, bool BLOCKS>
 __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_wave_count[kWavesPerBlock];
 
@@ -199,12 +208,22 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
   for (int k = 0; k < EPL; ++k) {
     const bool nz = (v[k] << 1) != 0u;                   // anything but +0.0 / -0.0
     const uint64_t b = __ballot(nz);
-    if (lane == (uint32_t)k) parked = b;
+    if (!BLOCKS && lane == (uint32_t)k) parked = b;
     if (b != 0) {                                        // uniform: most words are empty
       count += (uint32_t)__popcll(b);
-      if (INSERT && nz) sketch_insert(P.sketch, B.d, B.log2w, hp, (uint32_t)(e0 + k * kWave + lane), v[k]);
+      const uint32_t i = (uint32_t)(e0 + k * kWave + lane);       // < 2^32 wherever nz holds
+      if (INSERT && nz) sketch_insert(P.sketch, B.d, B.log2w, hp, i, v[k]);
+      if (BLOCKS) {
+        const uint32_t x = i / B.block;
+        const uint64_t below = b & ((1ull << lane) - 1ull);       // non-zero lanes before this one
+        const uint32_t prev = below != 0 ? 63u - (uint32_t)__clzll((long long)below) : lane;
+        const uint32_t xp = (uint32_t)__shfl((int)x, (int)prev, kWave);
+        if (nz && (below == 0 || xp != x))
+          atomicOr(reinterpret_cast<unsigned long long*>(&P.bitmap[x >> 6]), 1ull << (x & 63u));
+      }
     }
   }
+  if (BLOCKS) return;
   // streaming store: the words are not read again by this kernel, and keeping them out of the L2 leaves it
   // to the gradient stream (measured: 8 % shorter scans at 4 GB per gradient)
   if (lane < (uint32_t)EPL && word0 + lane < B.nwords) __builtin_nontemporal_store(parked, &P.bitmap[word0 + lane]);
@@ -226,8 +245,8 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
 // over each half of the wave (a field holds at most 32 * 64); lane 0 then owns
 // the even pieces, fetches the odd ones from lane 32 and stores the tile's 16
 // counts as 32 contiguous bytes.
-__global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
-                                                              uint32_t ntiles, uint16_t* __restrict__ piece_count) {
+__device__ __forceinline__ void count_tile_pieces(const uint64_t* __restrict__ bitmap, uint64_t nwords, uint32_t ntiles,
+                                                  uint16_t* __restrict__ piece_count) {
   constexpr int kPer = kTileWords / kWave;                   // 8
   static_assert(kScanWords == kWave / 2 && kScansPerTile == 2 * kPer, "a piece is the words of half a wave");
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -261,6 +280,18 @@ __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __
     dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
     dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
   }
+}
+
+__global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __restrict__ bitmap, uint64_t nwords,
+                                                              uint32_t ntiles, uint16_t* __restrict__ piece_count) {
+  count_tile_pieces(bitmap, nwords, ntiles, piece_count);
+}
+
+// The same for the (block) bitmaps of the workers of an encode batch.
+__global__ __launch_bounds__(kBlock) void bitmap_count_batch_kernel(const EncodeBatch B) {
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  count_tile_pieces(B.w[k].bitmap, B.nwords, B.ntiles, ws_piece_count(B, k));
 }
 
 // ------------------------------------------------------------------ prefix of the tile counts
@@ -449,7 +480,7 @@ __device__ __forceinline__ void compact_group(const EncodeBatch& B, const Worker
       live[u] = t < last && base + t < B.cap;
       i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
-    const bool values = P.grad != nullptr;               // s2r_decode expands the aggregated bitmap without values
+    const bool values = P.nz_val != nullptr;             // expansions of aggregated or block bitmaps carry no values
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) v[u] = live[u] && values ? P.grad[i[u]] : 0u;
 #pragma unroll
@@ -505,9 +536,38 @@ constexpr int kDecodeSliceLog2Max = 15;               // decode holds float32 ce
 static_assert(kMaxBins <= (1 << 13) && kSliceLog2Max <= 15 && kDecodeSliceLog2Max <= 15,
               "bin_scatter_kernel packs slice (bits 16..28) and cell (bits 0..14) into one word");
 
+// The items of the counting sort: the entries of the worker's list, or, in the
+// block-granular codec, the elements of the listed blocks (block by block).
 __device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t k) {
   const uint64_t nnz = B.nnz_out[k];
-  return nnz < B.cap ? nnz : B.cap;
+  const uint64_t listed = nnz < B.cap ? nnz : B.cap;
+  return B.block != 0 ? listed * B.block : listed;
+}
+
+// Item t (t < listed_items): its element index i and its payload v (the value's
+// bits, or the item's position t when B.payload_slot is set).  Returns whether
+// the item takes part: with blocks, elements beyond n never do, and elements
+// whose value is zero only when the payload is the position (a query), not when
+// it is the value (an insertion: zeros are inert).  An item that does not take
+// part in a query run is still given d answers (of element 0), which the median
+// kernel discards, so that every chunk holds the same number of answers per row.
+__device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs& P, uint64_t t, uint32_t& i, uint32_t& v) {
+  if (B.block == 0) {
+    i = P.nz_idx[t];
+    v = B.payload_slot != 0 ? (uint32_t)t : P.nz_val[t];
+    return true;
+  }
+  const uint64_t q = t / B.block;
+  const uint64_t e = (uint64_t)P.nz_idx[q] * B.block + (t - q * B.block);
+  const bool inside = e < B.n;
+  if (B.payload_slot != 0) {
+    i = inside ? (uint32_t)e : 0u;
+    v = (uint32_t)t;
+    return true;
+  }
+  i = (uint32_t)e;
+  v = inside ? P.grad[e] : 0u;
+  return inside && (v << 1) != 0u;
 }
 
 __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
@@ -518,18 +578,18 @@ __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
   __syncthreads();
   const uint64_t have = listed_items(B, k);
-  const uint32_t* __restrict__ idx = B.w[k].nz_idx;
+  const WorkerPtrs P = B.w[k];
   const uint32_t spr_log2 = B.log2w - B.slice_log2;
-  uint32_t i[kBinItems];
+  uint32_t i[kBinItems], v[kBinItems];
+  bool ok[kBinItems];
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
     const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-    i[u] = t < have ? idx[t] : 0u;
+    ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
   }
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
-    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-    if (t < have) {
+    if (ok[u]) {
       for (uint32_t j = 0; j < B.d; ++j) {
         const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
         __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -696,11 +756,11 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
   const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan (<= kMaxPer)
 
   uint32_t i[kBinItems], v[kBinItems];
+  bool ok[kBinItems];                                     // the item exists and takes part (see load_item)
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
     const uint32_t t = u * kBinBlock + threadIdx.x;
-    i[u] = t < count ? P.nz_idx[t0 + t] : 0u;
-    v[u] = t >= count ? 0u : B.payload_slot != 0 ? (uint32_t)(t0 + t) : P.nz_val[t0 + t];
+    ok[u] = t < count && load_item(B, P, t0 + t, i[u], v[u]);
   }
   for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
 
@@ -716,7 +776,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
     uint32_t key[kBinItems], rank[kBinItems];
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
-      if (u * kBinBlock + threadIdx.x < count) {
+      if (ok[u]) {
         const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
         const uint32_t sl = h >> B.slice_log2;
         key[u] = (h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]) | (sl << 16);
@@ -735,9 +795,13 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
     const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
     if (lane == kWave - 1) s_wave[wv] = incl;
     __syncthreads();
-    uint32_t run = incl - sum;
+    uint32_t run = incl - sum, records = 0;               // records: the chunk's items that take part
 #pragma unroll
-    for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
+    for (int q = 0; q < kWaves; ++q) {
+      const uint32_t x = s_wave[q];
+      if ((uint32_t)q < wv) run += x;
+      records += x;
+    }
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) {
       const uint32_t e = threadIdx.x * per + q;
@@ -750,11 +814,10 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
-      if (u * kBinBlock + threadIdx.x < count)
-        s_stage[s_loc[(key[u] >> 16) & 0x1FFFu] + rank[u]] = make_uint2(key[u], v[u]);
+      if (ok[u]) s_stage[s_loc[(key[u] >> 16) & 0x1FFFu] + rank[u]] = make_uint2(key[u], v[u]);
     }
     __syncthreads();
-    for (uint32_t p = threadIdx.x; p < count; p += kBinBlock) {
+    for (uint32_t p = threadIdx.x; p < records; p += kBinBlock) {
       const uint2 r = s_stage[p];
       rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80007FFFu, r.y);
     }
@@ -858,7 +921,16 @@ __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBat
     const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
     for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
       const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
-      sketch_insert(P.sketch, B.d, B.log2w, hp, i, P.grad[i]);
+      if (B.block == 0) {
+        sketch_insert(P.sketch, B.d, B.log2w, hp, i, P.grad[i]);
+      } else {                                           // an unlisted block: its non-zero elements
+        for (uint32_t o = 0; o < B.block; ++o) {
+          const uint64_t e = (uint64_t)i * B.block + o;
+          if (e >= B.n) break;
+          const uint32_t v = P.grad[e];
+          if ((v << 1) != 0u) sketch_insert(P.sketch, B.d, B.log2w, hp, (uint32_t)e, v);
+        }
+      }
     }
   }
 }
@@ -1064,6 +1136,37 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, cons
   }
 }
 
+// Block-granular decode by gathers: list position t is element t mod block of
+// the (t / block)-th listed block; every position gets its d bucket reads and
+// their median (0 for positions of the last block beyond the gradient).  One
+// thread per position and trip, kBlock * 4 positions per workgroup.
+template <int D>
+__global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const DecodeArgs A, const HashRows hp, uint32_t block,
+                                                               const uint32_t* __restrict__ blk_list,
+                                                               const uint64_t* __restrict__ count) {
+  constexpr int kPer = 4;
+  const uint64_t total = *count;
+  const uint64_t have = (total < A.cap ? total : A.cap) * block;
+  const uint64_t t0 = (uint64_t)blockIdx.x * (kBlock * kPer) + threadIdx.x;
+  if ((uint64_t)blockIdx.x * (kBlock * kPer) >= have) return;
+  float g[kPer];
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const uint64_t t = t0 + (uint64_t)u * kBlock;
+    g[u] = 0.0f;
+    if (t < have) {
+      const uint64_t q = t / block;
+      const uint64_t e = (uint64_t)blk_list[q] * block + (t - q * block);
+      if (e < A.n) g[u] = query<D>(A, hp, (uint32_t)e);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const uint64_t t = t0 + (uint64_t)u * kBlock;
+    if (t < have) A.val_out[t] = g[u];
+  }
+}
+
 // ------------------------------------------------------------------ decode by sketch slices
 // The bucket reads of decode_kernel each fetch a 128-byte line for 4 useful
 // bytes.  When the union list is long, s2r_decode instead partitions the
@@ -1093,6 +1196,9 @@ struct DecodeSliceArgs {
   uint32_t nbins;
   uint32_t slice_log2;
   uint32_t d;
+  uint32_t block;            // block-granular codec: list positions are elements of listed blocks
+  uint64_t n;                //   (positions whose element is not below n get 0)
+  const uint32_t* blk_list;
 };
 
 constexpr int kBinChunkLog2 = 13;
@@ -1153,7 +1259,8 @@ __global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSl
   __shared__ float s_est[kBinChunk];
   const uint32_t chunk = blockIdx.x;
   const uint64_t total = *A.count;
-  const uint64_t have = total < A.cap ? total : A.cap;
+  const uint64_t listed = total < A.cap ? total : A.cap;
+  const uint64_t have = A.block != 0 ? listed * A.block : listed;
   const uint64_t t0 = (uint64_t)chunk * kBinChunk;
   if (t0 >= have) return;                                 // uniform over the workgroup
   const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
@@ -1191,7 +1298,13 @@ __global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSl
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
     const uint32_t t = u * kBinBlock + threadIdx.x;
-    if (t < count) A.val_out[t0 + t] = median_fixed<D>(est[u]);
+    if (t >= count) continue;
+    float g = median_fixed<D>(est[u]);
+    if (A.block != 0) {                                   // the tail of the last block lies beyond the gradient
+      const uint64_t q = (t0 + t) / A.block;
+      if ((uint64_t)A.blk_list[q] * A.block + (t0 + t - q * A.block) >= A.n) g = 0.0f;
+    }
+    A.val_out[t0 + t] = g;
   }
 }
 
@@ -1479,8 +1592,11 @@ s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
 // The encode of W workers (W = 1 for s2r_encode): every kernel is launched once
 // with the worker in blockIdx.y.  workspace_bytes is the size of the whole
 // workspace, split evenly between the workers.
-static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t n, uint32_t d, uint32_t w,
-                                 uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
+// block = 0: the element codec (bitmaps of n bits, lists of non-zero elements with their values).
+// block >= 1: the block-granular codec (bitmaps of ceil(n / block) bits, lists of non-zero blocks, nz_val
+// unused, cap counted in blocks).
+static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
+                                 uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
                                  uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
                                  void* workspace, size_t workspace_bytes, hipStream_t st) {
   if (grads == nullptr || sketches == nullptr || bitmaps == nullptr || nnz_out == nullptr) return S2R_ERR_NULL;
@@ -1488,15 +1604,16 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
   const bool lists = nz_idx != nullptr && nz_idx[0] != nullptr;
-  if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
+  if (block == 0 && (nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
   if (((uintptr_t)nnz_out & 7u) != 0) return S2R_ERR_ALIGN;
+  const uint64_t nbits = block != 0 ? ceil_div(n, block) : n;      // bits of a worker's bitmap
 
   EncodeBatch E;
   for (uint32_t k = 0; k < W; ++k) {
     if (grads[k] == nullptr || sketches[k] == nullptr || bitmaps[k] == nullptr) return S2R_ERR_NULL;
     uint32_t* ik = nz_idx ? nz_idx[k] : nullptr;
     float* vk = nz_val ? nz_val[k] : nullptr;
-    if ((ik == nullptr) != (vk == nullptr) || (ik != nullptr) != lists) return S2R_ERR_NULL;
+    if ((block == 0 && (ik == nullptr) != (vk == nullptr)) || (ik != nullptr) != lists) return S2R_ERR_NULL;
     if (((uintptr_t)grads[k] & 3u) || ((uintptr_t)sketches[k] & 15u) || ((uintptr_t)bitmaps[k] & 7u) ||
         ((uintptr_t)ik & 3u) || ((uintptr_t)vk & 3u)) return S2R_ERR_ALIGN;
     E.w[k].grad = reinterpret_cast<const uint32_t*>(grads[k]);
@@ -1506,16 +1623,17 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
     E.w[k].nz_val = reinterpret_cast<uint32_t*>(vk);
   }
   if (!lists) cap = 0;
-  if (cap > n) cap = n;                                       // there cannot be more non-zeros than elements
+  if (cap > nbits) cap = nbits;                               // there cannot be more list entries than bits
+  const uint64_t cap_items = block != 0 ? cap * block : cap;  // elements the lists stand for, at most
   const size_t ws_each = (workspace_bytes / W) & ~(size_t)255;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_base(n))
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_base(nbits))
     return S2R_ERR_WORKSPACE;
 
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-  const uint32_t ntiles = tiles_of(n);
+  const uint32_t ntiles = tiles_of(nbits);
   const uint32_t log2w = log2_of(w);
-  const int32_t strategy = choose_strategy(W, n, d, w, lists, cap, ws_each);
+  const int32_t strategy = choose_strategy(W, nbits, d, w, lists, cap_items, ws_each);
   g_last_strategy = strategy;
 
   E.nworkers = W;
@@ -1524,16 +1642,17 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.nnz_out = nnz_out;
   E.workspace = reinterpret_cast<char*>(workspace);
   E.ws_stride = ws_each;
-  E.prefix_off = workspace_prefix_off(n);
-  E.dense_off = workspace_dense_off(n);
-  const SliceLayout L = slice_layout(n, d, w, cap);
+  E.block = block;
+  E.prefix_off = workspace_prefix_off(nbits);
+  E.dense_off = workspace_dense_off(nbits);
+  const SliceLayout L = slice_layout(nbits, d, w, cap_items);
   E.hist_off = L.hist_off;
   E.binstart_off = L.binstart_off;
   E.rec_off = L.rec_off;
   E.nbins = L.nbins;
   E.nchunks = L.nchunks;
   E.n = n;
-  E.nwords = ceil_div(n, 64);
+  E.nwords = ceil_div(nbits, 64);
   E.cap = cap;
   E.ntiles = ntiles;
   E.d = d;
@@ -1552,21 +1671,28 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   uint64_t zb = ceil_div(nvec > 0 ? nvec : 1, kBlock);
   if (zb > 2048) zb = 2048;
   const uint32_t group = n * sizeof(float) >= (1ull << 30) ? 1u : W;
-  const uint32_t scan_blocks = ntiles * kScansPerTile;        // every piece of every tile gets its count
+  // element codec: every piece of every tile gets its count; block codec: the pieces that hold elements
+  const uint32_t scan_blocks = block != 0 ? (uint32_t)ceil_div(ceil_div(n, 64), kScanWords) : ntiles * kScansPerTile;
   uint32_t last_group = 0;
   for (uint32_t k0 = 0; k0 < W; k0 += group) {
     const uint32_t gy = W - k0 < group ? W - k0 : group;      // workers k0 .. k0 + gy - 1, all < W
     const bool last = k0 + gy == W;                           // the events bracket the last scan launch
     E.first_worker = k0;
-    if (atomics) {
-      hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, gy), dim3(kBlock), 0, st, E, nvec, ntail);
+    if (atomics || block != 0) {                              // the block bitmap is set bit by bit: zero it first
+      hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, gy), dim3(kBlock), 0, st, E, atomics ? nvec : (uint64_t)0,
+                         atomics ? ntail : 0u, block != 0 ? E.nwords : (uint64_t)0);
       if (!launch_ok()) return S2R_ERR_LAUNCH;
     }
     if (last) record(S2R_KERNEL_ENCODE_SCAN, false, st);
-    if (atomics)
-      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true>), dim3(scan_blocks, gy), dim3(kBlock), 0, st, E, hp);
+    const dim3 sgrid(scan_blocks, gy), sblock(kBlock);
+    if (block != 0 && atomics)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true, true>), sgrid, sblock, 0, st, E, hp);
+    else if (block != 0)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false, true>), sgrid, sblock, 0, st, E, hp);
+    else if (atomics)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true, false>), sgrid, sblock, 0, st, E, hp);
     else
-      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false>), dim3(scan_blocks, gy), dim3(kBlock), 0, st, E, hp);
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false, false>), sgrid, sblock, 0, st, E, hp);
     if (last) record(S2R_KERNEL_ENCODE_SCAN, true, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     last_group = gy;
@@ -1574,6 +1700,11 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   g_scan_launch_workers = last_group;
   E.first_worker = 0;
 
+  if (block != 0) {                                          // the counts of the block bitmap's pieces
+    hipLaunchKernelGGL(bitmap_count_batch_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock), W), dim3(kBlock), 0,
+                       st, E);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1, W), dim3(kPrefixBlock), 0, st, E.workspace, E.ws_stride,
                      E.prefix_off, E.dense_off, ntiles, nnz_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
@@ -1611,7 +1742,7 @@ s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uin
                       float* sketch, uint64_t* bitmap, uint32_t* nz_idx, float* nz_val, uint64_t cap,
                       uint64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream) {
   if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
-  return encode_workers(&grad, 1, n, d, w, seed, &sketch, &bitmap, nz_idx ? &nz_idx : nullptr,
+  return encode_workers(&grad, 1, n, 0u, d, w, seed, &sketch, &bitmap, nz_idx ? &nz_idx : nullptr,
                         nz_val ? &nz_val : nullptr, cap, nnz_out, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
@@ -1619,7 +1750,7 @@ s2r_status s2r_encode_batch(const float* const* grads, uint32_t W, uint64_t n, u
                             uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
                             uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
                             void* workspace, size_t workspace_bytes, void* stream) {
-  return encode_workers(grads, W, n, d, w, seed, sketches, bitmaps, nz_idx, nz_val, cap, nnz_out, workspace,
+  return encode_workers(grads, W, n, 0u, d, w, seed, sketches, bitmaps, nz_idx, nz_val, cap, nnz_out, workspace,
                         workspace_bytes, (hipStream_t)stream);
 }
 
@@ -1658,13 +1789,19 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
-s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
-                      uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out,
-                      float* dense_out, void* workspace, size_t workspace_bytes, void* stream) {
+// block = 0: the element codec.  block >= 1: the block-granular codec: the bitmap has ceil(n / block) bits,
+// idx_out lists the set blocks (cap of them at most), val_out holds block values per listed block, and there
+// is no dense output.
+static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t block, uint32_t d,
+                              uint32_t w, uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap,
+                              uint64_t* count_out, float* dense_out, void* workspace, size_t workspace_bytes,
+                              void* stream) {
   if (sketch == nullptr || bitmap == nullptr || count_out == nullptr) return S2R_ERR_NULL;
   if ((idx_out == nullptr) != (val_out == nullptr)) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
+  const uint64_t elements = n;
+  if (block != 0) n = ceil_div(n, block);                  // from here on n counts the bits of the bitmap
   if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < workspace_base(n))
     return S2R_ERR_WORKSPACE;
   if (((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) || ((uintptr_t)idx_out & 3u) ||
@@ -1686,12 +1823,13 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if ((idx_out == nullptr || cap == 0) && dense_out == nullptr) return S2R_OK;   // only the count was asked for
 
-  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr, idx_out ? cap : 0,
+  if (cap > n) cap = n;
+  const uint64_t cap_items = block != 0 ? cap * block : cap;    // list positions that get a value, at most
+  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr, idx_out ? cap_items : 0,
                                          workspace_bytes);
   g_last_decode_strategy = strategy;
   if (strategy == S2R_DECODE_SLICE) {
-    if (cap > n) cap = n;
-    const DecodeLayout L = decode_layout(n, d, w, cap);
+    const DecodeLayout L = decode_layout(n, d, w, cap_items);
     if (!raise_lds_limits()) return S2R_ERR_LAUNCH;
     // the kernels of the encode's slice strategy, on one "worker" whose list is the union list
     static thread_local EncodeBatch X;                     // (2.6 KB: not on the stack of every call)
@@ -1710,7 +1848,8 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
     X.rec_off = L.rec_off;
     X.rowpre_off = L.rowpre_off;
     X.payload_slot = 1;
-    X.n = n;
+    X.block = block;
+    X.n = elements;
     X.nwords = nwords;
     X.cap = cap;
     X.ntiles = ntiles;
@@ -1735,6 +1874,9 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
     Q.nbins = L.nbins;
     Q.slice_log2 = L.slice_log2;
     Q.d = d;
+    Q.block = block;
+    Q.n = elements;
+    Q.blk_list = idx_out;
 
     record(S2R_KERNEL_DECODE, false, st);
     const uint32_t helpers = dense_grid(ntiles, 2048);
@@ -1769,7 +1911,7 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   DecodeArgs A;
   A.sketch = sketch;
   A.bitmap = bitmap;
-  A.n = n;
+  A.n = block != 0 ? elements : n;
   A.nwords = nwords;
   A.d = d;
   A.log2w = log2_of(w);
@@ -1779,6 +1921,56 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   A.val_out = val_out;
   A.cap = idx_out ? cap : 0;
   A.dense_out = dense_out;
+
+  if (block != 0) {                                        // the block list, then one thread per element of a listed block
+    static thread_local EncodeBatch X;
+    X.w[0].grad = nullptr;
+    X.w[0].sketch = nullptr;
+    X.w[0].bitmap = const_cast<uint64_t*>(bitmap);        // only read
+    X.w[0].nz_idx = idx_out;
+    X.w[0].nz_val = nullptr;
+    X.nnz_out = count_out;
+    X.workspace = reinterpret_cast<char*>(workspace);
+    X.ws_stride = 0;
+    X.prefix_off = workspace_prefix_off(n);
+    X.dense_off = workspace_dense_off(n);
+    X.rowpre_off = 0;
+    X.payload_slot = 0;
+    X.block = block;
+    X.n = elements;
+    X.nwords = nwords;
+    X.cap = cap;
+    X.ntiles = ntiles;
+    X.d = d;
+    X.log2w = A.log2w;
+    X.first_worker = 0;
+    X.nworkers = 1;
+    record(S2R_KERNEL_DECODE, false, st);
+    const uint32_t helpers = dense_grid(ntiles, 2048);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, X, helpers);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    const dim3 bgrid((uint32_t)ceil_div(cap_items, (uint64_t)kBlock * 4)), bblock(kBlock);
+    switch (d) {
+      case 1: hipLaunchKernelGGL(decode_blocks_kernel<1>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 2: hipLaunchKernelGGL(decode_blocks_kernel<2>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 3: hipLaunchKernelGGL(decode_blocks_kernel<3>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 4: hipLaunchKernelGGL(decode_blocks_kernel<4>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 5: hipLaunchKernelGGL(decode_blocks_kernel<5>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 6: hipLaunchKernelGGL(decode_blocks_kernel<6>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 7: hipLaunchKernelGGL(decode_blocks_kernel<7>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 8: hipLaunchKernelGGL(decode_blocks_kernel<8>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 9: hipLaunchKernelGGL(decode_blocks_kernel<9>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 10: hipLaunchKernelGGL(decode_blocks_kernel<10>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 11: hipLaunchKernelGGL(decode_blocks_kernel<11>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 12: hipLaunchKernelGGL(decode_blocks_kernel<12>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 13: hipLaunchKernelGGL(decode_blocks_kernel<13>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 14: hipLaunchKernelGGL(decode_blocks_kernel<14>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      case 15: hipLaunchKernelGGL(decode_blocks_kernel<15>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+      default: hipLaunchKernelGGL(decode_blocks_kernel<16>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
+    }
+    record(S2R_KERNEL_DECODE, true, st);
+    return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+  }
 
   record(S2R_KERNEL_DECODE, false, st);
   const uint32_t helpers = dense_grid(ntiles, 2048);
@@ -1802,6 +1994,61 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
   }
   record(S2R_KERNEL_DECODE, true, st);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+}
+
+
+s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
+                      uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out,
+                      float* dense_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, dense_out, workspace,
+                     workspace_bytes, stream);
+}
+
+// ---- block-granular codec
+static inline bool block_ok(uint64_t n, uint32_t block) { return block >= 1 && n >= 1 && (uint64_t)block <= (1ull << 31); }
+
+size_t s2r_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w) {
+  if (check_sizes(n, d, w) != S2R_OK || !block_ok(n, block)) return 0;
+  return workspace_base(ceil_div(n, block));
+}
+
+size_t s2r_encode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t blk_cap) {
+  if (check_sizes(n, d, w) != S2R_OK || !block_ok(n, block) || blk_cap > ceil_div(n, block)) return 0;
+  const uint64_t nb = ceil_div(n, block);
+  const SliceLayout L = slice_layout(nb, d, w, blk_cap * block);
+  return L.possible ? L.total : workspace_base(nb);
+}
+
+size_t s2r_decode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t blk_cap) {
+  if (check_sizes(n, d, w) != S2R_OK || !block_ok(n, block) || blk_cap > ceil_div(n, block)) return 0;
+  const uint64_t nb = ceil_div(n, block);
+  const DecodeLayout L = decode_layout(nb, d, w, blk_cap * block);
+  return L.possible ? L.total : workspace_base(nb);
+}
+
+s2r_status s2r_encode_blocks_batch(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
+                                   uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* block_bitmaps,
+                                   uint32_t* const* blk_idx, uint64_t blk_cap, uint64_t* nblk_out, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  return encode_workers(grads, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, nullptr, blk_cap, nblk_out,
+                        workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+s2r_status s2r_encode_blocks(const float* grad, uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t seed,
+                             float* sketch, uint64_t* block_bitmap, uint32_t* blk_idx, uint64_t blk_cap,
+                             uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  return encode_workers(&grad, 1, n, block, d, w, seed, &sketch, &block_bitmap, blk_idx ? &blk_idx : nullptr, nullptr,
+                        blk_cap, nblk_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block, uint32_t d,
+                             uint32_t w, uint64_t seed, uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,
+                             uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  return decode_impl(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, blk_cap, nblk_out, nullptr,
+                     workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

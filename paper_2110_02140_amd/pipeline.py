@@ -97,6 +97,68 @@ def buffers_for(wl, device="cuda:0", dense_out: bool = False, slack: int = 0) ->
     return b
 
 
+class BlockBuffers:
+    """Device memory of the block-granular codec for a (W, n, block, d, w) problem."""
+
+    def __init__(self, W: int, n: int, block: int, d: int, w: int, seed: int, blk_cap: int, union_cap: int,
+                 device="cuda:0"):
+        self.W, self.n, self.block, self.d, self.w, self.seed = W, n, block, d, w, seed
+        self.device = torch.device(device)
+        dev = self.device
+        self.nb = (n + block - 1) // block
+        nw = words_of(self.nb)
+        blk_cap, union_cap = min(max(blk_cap, 1), self.nb), min(max(union_cap, 1), self.nb)
+        self.grads: list[torch.Tensor] = []
+        self.sketch = [torch.empty(d * w, dtype=torch.float32, device=dev) for _ in range(W)]
+        self.bitmap = [torch.empty(nw, dtype=torch.int64, device=dev) for _ in range(W)]
+        self.blk_idx = [torch.empty(blk_cap, dtype=torch.int32, device=dev) for _ in range(W)]
+        self.nblk = torch.zeros(W, dtype=torch.int64, device=dev)
+        self.sketch_sum = torch.empty(d * w, dtype=torch.float32, device=dev)
+        self.bitmap_or = torch.empty(nw, dtype=torch.int64, device=dev)
+        self.out_blk = torch.empty(union_cap, dtype=torch.int32, device=dev)
+        self.out_val = torch.empty(union_cap * block, dtype=torch.float32, device=dev)
+        self.out_count = torch.zeros(1, dtype=torch.int64, device=dev)
+        ws = binding.encode_blocks_workspace_bytes(n, block, d, w, blk_cap)
+        ws_decode = binding.decode_blocks_workspace_bytes(n, block, d, w, union_cap)
+        if ws == 0 or ws_decode == 0:
+            raise ValueError("sizes outside the library's limits")
+        self.workspace = torch.empty(max(ws * W, ws_decode), dtype=torch.uint8, device=dev)
+
+    def encode(self, k: int, stream=None):
+        binding.encode_blocks(self.grads[k], self.block, self.d, self.w, self.seed, self.sketch[k], self.bitmap[k],
+                              self.blk_idx[k], self.nblk[k:k + 1], self.workspace, stream, n=self.n)
+
+    def encode_all(self, stream=None):
+        binding.encode_blocks_batch(self.grads, self.n, self.block, self.d, self.w, self.seed, self.sketch,
+                                    self.bitmap, self.blk_idx, self.nblk, self.workspace, stream)
+
+    def merge(self, stream=None):
+        binding.merge(self.sketch, self.bitmap, self.nb, self.d, self.w, self.seed,
+                      self.sketch_sum, self.bitmap_or, stream)
+
+    def decode(self, stream=None):
+        binding.decode_blocks(self.sketch_sum, self.bitmap_or, self.n, self.block, self.d, self.w, self.seed,
+                              self.out_blk, self.out_val, self.out_count, self.workspace, stream)
+
+    def step(self, stream=None, batched: bool = True):
+        if batched:
+            self.encode_all(stream)
+        else:
+            for k in range(self.W):
+                self.encode(k, stream)
+        self.merge(stream)
+        self.decode(stream)
+
+
+def block_buffers_for(wl, block: int, device="cuda:0", slack: int = 0) -> BlockBuffers:
+    """BlockBuffers sized for a workloads.Workload cut into blocks of `block` elements."""
+    per_worker = [len(np.unique(i // np.uint32(block))) for i in wl.idx]
+    b = BlockBuffers(wl.W, wl.n, block, wl.d, wl.w, wl.seed, max(per_worker) + slack, sum(per_worker) + slack, device)
+    for k in range(wl.W):
+        b.grads.append(upload_dense(wl.idx[k], wl.val[k], wl.n, b.device))
+    return b
+
+
 def u64(t: torch.Tensor) -> np.ndarray:
     """Device int64 words -> host uint64 array."""
     return t.cpu().numpy().view(np.uint64)

@@ -474,3 +474,106 @@ def test_estimation_quality_matches_oracle_and_improves_with_sketch_size():
     for d in (1, 3):
         assert errs[(d, 10)] > errs[(d, 13)] > errs[(d, 16)]
     assert errs[(3, 13)] < errs[(1, 13)] and errs[(3, 16)] < errs[(1, 16)]
+
+
+# ---------------------------------------------------------------- block-granular codec
+def _oracle_blocks(wl, B):
+    """The block oracle from the workload's sparse form (dense buffers only for small n)."""
+    gs = [wl.dense(k) for k in range(wl.W)]
+    return orc.reduce_workers_blocks(gs, B, wl.d, wl.w, wl.seed)
+
+
+def _run_blocks_and_check(wl, B, batched=True):
+    print(f"[case] blocks {wl.name} W={wl.W} n={wl.n} B={B} d={wl.d} w={wl.w} batched={batched}", flush=True)
+    ref = _oracle_blocks(wl, B)
+    b = pipeline.block_buffers_for(wl, B)
+    b.step(batched=batched)
+    torch.cuda.synchronize()
+    nblk = b.nblk.cpu().numpy()
+    for k in range(wl.W):
+        e = ref["workers"][k]
+        assert nblk[k] == len(e["blocks"]), f"worker {k} block count"
+        assert np.array_equal(pipeline.u64(b.bitmap[k]), e["bitmap"]), f"worker {k} block bitmap"
+        assert np.array_equal(b.blk_idx[k][: nblk[k]].cpu().numpy().view(np.uint32), e["blocks"]), f"worker {k} block list"
+        _check_sketch(b.sketch[k].cpu().numpy(), e["S"], e["M"], f"worker {k} sketch")
+    assert np.array_equal(pipeline.u64(b.bitmap_or), ref["bitmap"]), "merged block bitmap"
+    _check_sketch(b.sketch_sum.cpu().numpy(), ref["S"], ref["M"], "merged sketch")
+    cnt = int(b.out_count.cpu()[0])
+    assert cnt == len(ref["blocks"]), "set blocks"
+    assert np.array_equal(b.out_blk[:cnt].cpu().numpy().view(np.uint32), ref["blocks"])
+    got = b.out_val[: cnt * B].cpu().numpy().astype(np.float64)
+    want = ref["val"].reshape(-1)
+    elems = (ref["blocks"].astype(np.int64)[:, None] * B + np.arange(B)[None, :]).reshape(-1)
+    inside = elems < wl.n
+    tol = np.zeros(len(elems))
+    tol[inside] = REL * orc.decode_tolerance_mass(ref["M"], elems[inside].astype(np.uint32), wl.seed) + DENORM_SLACK
+    assert np.all(np.abs(got - want) <= tol), f"block values: worst {np.abs(got - want).max():.3e}"
+    assert not got[~inside].any(), "positions beyond the gradient must hold 0"
+    return b, ref
+
+
+@pytest.mark.parametrize("batched", [True, False], ids=["batch", "per_worker"])
+@pytest.mark.parametrize("cfg,B", [(1, 1), (1, 37), (2, 25), (3, 64), (3, 256), (4, 96), (5, 1000)])
+def test_small_recipes_block_codec(cfg, B, strategy, decode_strategy, batched):
+    _run_blocks_and_check(workloads.make_small(cfg), B, batched=batched)
+
+
+@pytest.mark.parametrize("cfg,B", [(2, 650), (3, 256)])
+def test_full_size_recipes_block_codec(cfg, B):
+    """Configs 2 and 3 with their natural blocks (embedding rows of 650, blocks of 256),
+    in the library's own choice of strategies."""
+    _run_blocks_and_check(workloads.make(cfg), B)
+
+
+@pytest.mark.parametrize("n,B", [(1, 1), (63, 64), (64, 64), (65, 64), (1000, 7), (70000, 650), (200001, 4096), (5000, 9000)])
+def test_block_codec_dense_gradient_ragged(n, B, strategy, decode_strategy):
+    """Every element set, lengths that are not multiples of the block, one block larger than n."""
+    rng = np.random.default_rng(n + B)
+    wl = _custom(n, [np.arange(n)] * 2, [rng.normal(0, 1, n).astype(np.float32) + 3.0 for _ in range(2)],
+                 d=3, w=1 << 9, W=2)
+    _run_blocks_and_check(wl, B)
+
+
+def test_block_codec_zero_and_special_values(strategy):
+    """All-zero gradients give empty bitmaps; -0.0 does not set a block, denormals do."""
+    n, B = 5000, 50
+    wl = _custom(n, [np.empty(0, dtype=np.uint32)] * 2, [np.empty(0, dtype=np.float32)] * 2, W=2)
+    b, _ = _run_blocks_and_check(wl, B)
+    assert int(b.out_count.cpu()[0]) == 0
+    g = np.zeros(n, dtype=np.float32)
+    g[120] = -0.0
+    g[777] = np.float32(1e-42)          # denormal
+    g[2049] = 1.5
+    b = pipeline.block_buffers_for(_custom(n, [np.array([777, 2049])], [g[[777, 2049]]]), B)
+    b.grads[0][120] = -0.0
+    b.encode(0)
+    torch.cuda.synchronize()
+    assert b.blk_idx[0][: int(b.nblk.cpu()[0])].cpu().numpy().tolist() == [777 // B, 2049 // B]
+
+
+def test_block_codec_capacity(strategy, decode_strategy):
+    """More set blocks than the lists hold: true counts, the first blk_cap entries,
+    nothing beyond them, and a complete sketch."""
+    rng = np.random.default_rng(9)
+    n, B, cap = 64000, 32, 100
+    blocks = np.sort(rng.choice(n // B, 300, replace=False))
+    idx = (blocks[:, None] * B + np.arange(B)[None, :]).reshape(-1).astype(np.uint32)
+    val = (rng.normal(0, 1, len(idx)) + 2.0).astype(np.float32)
+    wl = _custom(n, [idx], [val], d=3, w=1 << 11)
+    ref = _oracle_blocks(wl, B)
+    b = pipeline.block_buffers_for(wl, B)
+    b.blk_idx[0] = torch.full((cap + 8,), -1, dtype=torch.int32, device="cuda")[:cap]
+    b.out_blk = torch.full((cap + 8,), -1, dtype=torch.int32, device="cuda")[:cap]
+    b.out_val = torch.full((cap * B + 8,), -7.0, dtype=torch.float32, device="cuda")[: cap * B]
+    b.step()
+    torch.cuda.synchronize()
+    assert int(b.nblk.cpu()[0]) == 300 and int(b.out_count.cpu()[0]) == 300
+    assert np.array_equal(b.blk_idx[0].cpu().numpy().view(np.uint32), blocks[:cap])
+    assert (b.blk_idx[0]._base[cap:].cpu().numpy() == -1).all()
+    assert np.array_equal(b.out_blk.cpu().numpy().view(np.uint32), blocks[:cap])
+    assert (b.out_blk._base[cap:].cpu().numpy() == -1).all() and (b.out_val._base[cap * B:].cpu().numpy() == -7.0).all()
+    _check_sketch(b.sketch[0].cpu().numpy(), ref["S"], ref["M"], "sketch is complete despite the short list")
+    want = ref["val"][:cap].reshape(-1)
+    elems = (blocks[:cap, None] * B + np.arange(B)[None, :]).reshape(-1)
+    tol = REL * orc.decode_tolerance_mass(ref["M"], elems.astype(np.uint32), 0) + DENORM_SLACK
+    assert np.all(np.abs(b.out_val.cpu().numpy().astype(np.float64) - want) <= tol)
