@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="which BASELINE config to time (default: the largest single-GPU one)")
+    ap.add_argument("--block", type=int, default=0,
+                    help="use the block-granular codec with blocks of this many elements (0: one bitmap bit per "
+                         "element); the natural sizes are 650 for cfg2 and 256 for cfg3")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with W s2r_encode calls instead of one s2r_encode_batch call")
     ap.add_argument("--insert-strategy", default="auto", choices=["auto", "atomic", "slice"],
@@ -57,6 +60,17 @@ def parse_args():
                     help="also run one plain device copy of this many MiB (a kernel of known traffic, for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
+
+
+def algorithmic_bytes_blocks(wl, block: int, nnz, nblk, union_blocks: int) -> float:
+    """The same count for the block-granular codec: bitmaps of n / block bits, lists
+    of 4 bytes per non-zero block, decode writing block values per set block."""
+    nb = (wl.n + block - 1) // block
+    cells, words8 = 4.0 * wl.d * wl.w, nb / 8.0
+    encode = sum(4.0 * wl.n + words8 + 4.0 * float(c) + cells for c in nblk)
+    merge = wl.W * (cells + words8) + cells + words8
+    decode = words8 + cells + (4.0 + 4.0 * block) * union_blocks
+    return encode + merge + decode
 
 
 def scan_kernel_bytes(n: int, nnz: float, d: int, inserts: bool) -> float:
@@ -135,7 +149,7 @@ def main():
     t_gen = time.perf_counter()
     wl = workloads.make(cfg)
     t_gen = time.perf_counter() - t_gen
-    b = pipeline.buffers_for(wl)
+    b = pipeline.block_buffers_for(wl, args.block) if args.block > 0 else pipeline.buffers_for(wl)
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
 
@@ -212,12 +226,20 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    nnz = b.nnz.cpu().numpy().astype(np.float64)
     union = int(b.out_count.cpu()[0])
-    assert [int(x) for x in nnz] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
-    alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d, atomic)
+    nnz = np.array([len(i) for i in wl.idx], dtype=np.float64)
+    if args.block > 0:
+        nblk = b.nblk.cpu().numpy()
+        assert [int(x) for x in nblk] == [len(np.unique(i // np.uint32(args.block))) for i in wl.idx], \
+            "encode's block counts differ from the generator's"
+        per_worker = 4.0 * wl.n + ((wl.n + args.block - 1) // args.block) / 8.0 + (8.0 * wl.d * nnz.mean() if atomic else 0.0)
+        alg_bytes = workers_per_launch * per_worker
+        step_alg_bytes = algorithmic_bytes_blocks(wl, args.block, nnz, nblk, union)
+    else:
+        assert [int(x) for x in b.nnz.cpu().numpy()] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
+        alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d, atomic)
+        step_alg_bytes = algorithmic_bytes(wl, nnz, union)
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
-    step_alg_bytes = algorithmic_bytes(wl, nnz, union)
 
     out = {
         "metric": "dense-gradient GB/s for encode+merge+decode on 1 MI355X",
@@ -233,22 +255,25 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "W": wl.W, "n": wl.n, "d": wl.d, "w": wl.w, "seed": wl.seed,
-                   "nnz_per_worker": int(nnz.mean()), "union_nnz": union,
+                   "block": args.block, "nnz_per_worker": int(nnz.mean()),
+                   "union_blocks" if args.block > 0 else "union_nnz": union,
                    "dense_bytes_per_step": wl.dense_bytes},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "algorithmic_bytes_per_step": int(step_alg_bytes),
         "algorithmic_frac_of_hbm_peak": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "stream_read_GBs": round(read_ceiling, 1),
         "event_ms_per_step": round(ev_ms / args.steps, 4),
-        "encode_calls": "s2r_encode_batch" if batched else "s2r_encode x W",
+        "encode_calls": ("s2r_encode_blocks_batch" if batched else "s2r_encode_blocks x W") if args.block > 0
+                        else ("s2r_encode_batch" if batched else "s2r_encode x W"),
+        "decode_route": "slice" if binding.last_decode_strategy() == binding.S2R_DECODE_SLICE else "gather",
         "insert_strategy": "atomic" if atomic else "lds_slice",
         "kernel_ms": {"encode_scan_per_launch": round(scan_ms, 4), "workers_per_scan_launch": workers_per_launch,
                       "encode_slice_per_launch": None if slice_ms is None else round(slice_ms, 4),
                       "merge": round(merge_ms, 4), "decode": round(decode_ms, 4)},
         "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_SCAN_TRAFFIC.get((wl.name, "atomic" if atomic else "lds_slice",
-                                                           workers_per_launch)),
+                     "traffic": None if args.block > 0 else
+                                MEASURED_SCAN_TRAFFIC.get((wl.name, "atomic" if atomic else "lds_slice", workers_per_launch)),
                      "algorithmic_bytes_per_launch": int(alg_bytes)},
         "setup_s": {"generate": round(t_gen, 1)},
     }

@@ -174,6 +174,14 @@ __device__ __forceinline__ void sketch_insert(float* sketch, uint32_t d, uint32_
 // workgroup's non-zero count (at most 2048) is stored as piece blockIdx.x of the
 // worker's 16-bit piece counts; the grid covers every piece of every tile, so
 // the pieces past the end of the gradient are written too (as zero).
+// Sets bit x of a block bitmap.  Atomics on one address retire one at a time, and many waves meet in the
+// 64 blocks of a word, so the bit is only written when it is not yet seen set.
+__device__ __forceinline__ void set_block_bit(uint64_t* bitmap, uint32_t x) {
+  unsigned long long* word = reinterpret_cast<unsigned long long*>(&bitmap[x >> 6]);
+  const unsigned long long bit = 1ull << (x & 63u);
+  if ((__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit) == 0) atomicOr(word, bit);
+}
+
 // BLOCKS: the block-granular codec.  No element bitmap and no counts are written;
 // instead every non-zero element sets the bit of its block B.block in the worker's
 // (zeroed) block bitmap with an atomic OR, once per run of non-zero lanes of a
@@ -181,12 +189,17 @@ __device__ __forceinline__ void sketch_insert(float* sketch, uint32_t d, uint32_
 template <int EPL, bool INSERT, bool BLOCKS>
 __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_wave_count[kWavesPerBlock];
+  __shared__ unsigned long long s_block_bits[2];         // BLOCKS: the workgroup's bits of two bitmap words
 
   const uint32_t worker = B.first_worker + blockIdx.y;
   if (worker >= B.nworkers) return;                      // uniform over the workgroup
   const WorkerPtrs P = B.w[worker];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
+  if (BLOCKS && B.block >= (uint32_t)kWave) {            // uniform over the workgroup
+    if (threadIdx.x < 2) s_block_bits[threadIdx.x] = 0ull;
+    __syncthreads();
+  }
   const uint64_t word0 = (uint64_t)blockIdx.x * kScanWords + (uint64_t)wv * EPL;   // this wave's first word
   const uint64_t e0 = word0 * 64;
 
@@ -204,6 +217,7 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
 
   uint32_t count = 0;          // non-zeros seen by this wave (uniform)
   uint64_t parked = 0;         // lane k keeps word k until the store below
+  uint64_t bal[EPL] = {};      // BLOCKS: the ballots (uniform)
 #pragma unroll
   for (int k = 0; k < EPL; ++k) {
     const bool nz = (v[k] << 1) != 0u;                   // anything but +0.0 / -0.0
@@ -214,16 +228,58 @@ __global__ __launch_bounds__(kBlock) void encode_scan_kernel(const EncodeBatch B
       const uint32_t i = (uint32_t)(e0 + k * kWave + lane);       // < 2^32 wherever nz holds
       if (INSERT && nz) sketch_insert(P.sketch, B.d, B.log2w, hp, i, v[k]);
       if (BLOCKS) {
-        const uint32_t x = i / B.block;
-        const uint64_t below = b & ((1ull << lane) - 1ull);       // non-zero lanes before this one
-        const uint32_t prev = below != 0 ? 63u - (uint32_t)__clzll((long long)below) : lane;
-        const uint32_t xp = (uint32_t)__shfl((int)x, (int)prev, kWave);
-        if (nz && (below == 0 || xp != x))
-          atomicOr(reinterpret_cast<unsigned long long*>(&P.bitmap[x >> 6]), 1ull << (x & 63u));
+        bal[k] = b;
+        if (B.block < (uint32_t)kWave) {
+          // small blocks: one atomic per run of non-zero lanes of this word that share a block
+          const uint32_t x = i / B.block;
+          const uint64_t below = b & ((1ull << lane) - 1ull);     // non-zero lanes before this one
+          const uint32_t prev = below != 0 ? 63u - (uint32_t)__clzll((long long)below) : lane;
+          const uint32_t xp = (uint32_t)__shfl((int)x, (int)prev, kWave);
+          if (nz && (below == 0 || xp != x)) set_block_bit(P.bitmap, x);
+        }
       }
     }
   }
-  if (BLOCKS) return;
+  if (BLOCKS) {
+    // blocks of 64 elements and more: the wave's EPL * 64 elements meet at most EPL + 1 blocks; lane j takes
+    // the j-th of them and tests the ballots (which every lane holds) against the block's range of bits.
+    // The workgroup's 2048 elements meet at most 33 blocks, whose bits lie in two adjacent bitmap words:
+    // they are collected in LDS and go out as at most two atomics per workgroup.
+    if (B.block >= (uint32_t)kWave) {
+      const uint64_t g0 = (uint64_t)blockIdx.x * kScanWords * 64;   // the workgroup's first element
+      const uint64_t wbase = (g0 / B.block) >> 6;                   // bitmap word of its first block (uniform)
+      if (count != 0) {
+        const uint64_t c1 = e0 + (uint64_t)EPL * kWave;             // the wave's elements are [e0, c1)
+        const uint64_t x = (uint32_t)e0 / B.block + lane;           // (a wave that saw a non-zero starts below 2^32)
+        const uint64_t lo = x * B.block, hi = lo + B.block;         // the block's elements are [lo, hi)
+        if (lo < c1 && hi > e0) {
+          const uint32_t r0 = lo > e0 ? (uint32_t)(lo - e0) : 0u;
+          const uint32_t r1 = hi < c1 ? (uint32_t)(hi - e0) : (uint32_t)(EPL * kWave);
+          bool any = false;
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) {
+            const uint32_t a = r0 > (uint32_t)(k * kWave) ? r0 - k * kWave : 0u;          // bits [a, z) of word k
+            const uint32_t z = r1 < (uint32_t)((k + 1) * kWave) ? (r1 > (uint32_t)(k * kWave) ? r1 - k * kWave : 0u) : (uint32_t)kWave;
+            if (a < z) {
+              const uint64_t upto = z == (uint32_t)kWave ? ~0ull : (1ull << z) - 1ull;
+              any |= (bal[k] & upto & ~((1ull << a) - 1ull)) != 0;
+            }
+          }
+          if (any)
+            __hip_atomic_fetch_or(&s_block_bits[(x >> 6) - wbase], 1ull << (x & 63u), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
+      __syncthreads();
+      if (threadIdx.x < 2 && wbase + threadIdx.x < B.nwords) {
+        const unsigned long long bits = s_block_bits[threadIdx.x];
+        unsigned long long* word = reinterpret_cast<unsigned long long*>(&P.bitmap[wbase + threadIdx.x]);
+        if (bits != 0 && (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bits) != bits)
+          atomicOr(word, bits);
+      }
+    }
+    return;
+  }
   // streaming store: the words are not read again by this kernel, and keeping them out of the L2 leaves it
   // to the gradient stream (measured: 8 % shorter scans at 4 GB per gradient)
   if (lane < (uint32_t)EPL && word0 + lane < B.nwords) __builtin_nontemporal_store(parked, &P.bitmap[word0 + lane]);
@@ -557,8 +613,8 @@ __device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs
     v = B.payload_slot != 0 ? (uint32_t)t : P.nz_val[t];
     return true;
   }
-  const uint64_t q = t / B.block;
-  const uint64_t e = (uint64_t)P.nz_idx[q] * B.block + (t - q * B.block);
+  const uint32_t q = (uint32_t)t / B.block;                // (the sort's items are fewer than 2^32)
+  const uint64_t e = (uint64_t)P.nz_idx[q] * B.block + ((uint32_t)t - q * B.block);
   const bool inside = e < B.n;
   if (B.payload_slot != 0) {
     i = inside ? (uint32_t)e : 0u;
