@@ -53,6 +53,16 @@ block may be shorter), the sketch still receives the non-zero elements only
 element of every block whose aggregated bit is set.  B = 1 is the element-granular
 codec above.
 
+Block-wise Top-K with error feedback (topk_blocks at the end), the sparsifier the
+paper puts in front of the codec for dense layers (Section 2.2: the l2 norm of
+every block, the K largest blocks are kept; Theorem 2 and its proof: what is not
+sent stays in an error sequence that is added to the next gradient).  Readings:
+the score of a block is the sum of the squares of its float32 elements
+accumulated in float64 and rounded once to float32 (same order as the norm);
+equal scores are ordered by block index, lower first; the residual is the part of
+(gradient + old residual) that is not kept: the sketch's own estimation error is
+not fed back (a worker cannot see it: the decoder returns the sum over workers).
+
 Parity pins: see tests/test_oracle_*.py.  No function in this file is unpinned,
 but the hash family itself is a reading (the paper names none); it is pinned to a
 big-integer re-statement and to the published SplitMix64 reference outputs.
@@ -325,3 +335,36 @@ def reduce_workers_blocks(grads: list[np.ndarray], B: int, d: int, w: int, seed:
     out = decode_blocks(S, C, grads[0].shape[0], B, seed)
     out.update({"S": S, "M": M, "bitmap": C, "workers": enc})
     return out
+
+
+# --------------------------------------------------------------------------
+# block-wise Top-K sparsifier with error feedback (Section 2.2; Theorem 2)
+# --------------------------------------------------------------------------
+
+def block_scores(acc: np.ndarray, B: int) -> np.ndarray:
+    """float32[ceil(n / B)]: per block, the sum of squares of its elements (float64
+    accumulation of exact products, one rounding to float32)."""
+    acc = np.ascontiguousarray(acc, dtype=np.float32)
+    nb = (acc.shape[0] + B - 1) // B
+    padded = np.zeros(nb * B, dtype=np.float64)
+    padded[: acc.shape[0]] = acc.astype(np.float64)
+    return np.sum(padded.reshape(nb, B) ** 2, axis=1).astype(np.float32)
+
+
+def topk_blocks(g: np.ndarray, e, B: int, K: int) -> dict:
+    """acc = g + e (float32); keep the K blocks of largest score (ties: lower block
+    first).  Returns the kept blocks (ascending), the sparse gradient (acc in the
+    kept blocks, +0.0 elsewhere), the new residual (acc elsewhere, +0.0 in the kept
+    blocks) and the scores."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    acc = g if e is None else (g + np.ascontiguousarray(e, dtype=np.float32)).astype(np.float32)
+    score = block_scores(acc, B)
+    nb = score.shape[0]
+    order = sorted(range(nb), key=lambda x: (-float(score[x]), x))
+    kept = np.array(sorted(order[:K]), dtype=np.uint32)
+    mask = np.zeros(nb, dtype=bool)
+    mask[kept] = True
+    elem = np.repeat(mask, B)[: acc.shape[0]]
+    sparse = np.where(elem, acc, np.float32(0.0)).astype(np.float32)
+    resid = np.where(elem, np.float32(0.0), acc).astype(np.float32)
+    return {"blocks": kept, "sparse": sparse, "residual": resid, "score": score, "acc": acc}

@@ -33,6 +33,10 @@ def _some_pin_fails():
         (pins.test_hash_params_order_and_oddness, ()),
         (pins.test_block_algorithm_matches_pure_python, (7, 4, 32, 2)),
         (pins.test_block_sketch_equals_element_sketch_and_values_agree_on_the_union, ()),
+        (pins.test_topk_blocks_matches_pure_python, (4, 3)),
+        (pins.test_topk_blocks_matches_pure_python, (16, 13)),
+        (pins.test_topk_ties_go_to_the_lower_block_and_extremes, ()),
+        (pins.test_topk_is_a_delta_approximate_compressor_and_loses_nothing, ()),
     ]
     return any(_fails(fn, *a) for fn, a in checks)
 
@@ -160,12 +164,33 @@ def _mut_block_decode_skips_zero_elements(monkeypatch):
     monkeypatch.setattr(orc, "decode_blocks", bad)
 
 
+def _mut_topk_scores_by_abs_sum(monkeypatch):
+    def bad(acc, B):
+        acc = np.ascontiguousarray(acc, dtype=np.float32)
+        nb = (acc.shape[0] + B - 1) // B
+        padded = np.zeros(nb * B, dtype=np.float64)
+        padded[: acc.shape[0]] = np.abs(acc.astype(np.float64))                  # l1 instead of l2
+        return np.sum(padded.reshape(nb, B), axis=1).astype(np.float32)
+    monkeypatch.setattr(orc, "block_scores", bad)
+
+
+def _mut_topk_keeps_smallest(monkeypatch):
+    real = orc.block_scores
+    monkeypatch.setattr(orc, "block_scores", lambda acc, B: (-real(acc, B)).astype(np.float32))
+
+
+def _mut_topk_residual_forgets_old_error(monkeypatch):
+    real = orc.topk_blocks
+    monkeypatch.setattr(orc, "topk_blocks", lambda g, e, B, K: real(g, None, B, K))
+
+
 @pytest.mark.parametrize("mutant", [
     _mut_sign_dropped_in_query, _mut_msb_first_bitmap, _mut_median_off_by_one,
     _mut_low_bits_bucket, _mut_sign_uses_bucket_multiplier, _mut_merge_xor,
     _mut_merge_drops_last_worker, _mut_negative_zero_counts,
     _mut_insert_assign_not_accumulate,
     _mut_block_needs_all_elements, _mut_block_boundary_shifted, _mut_block_decode_skips_zero_elements,
+    _mut_topk_scores_by_abs_sum, _mut_topk_keeps_smallest, _mut_topk_residual_forgets_old_error,
 ], ids=lambda f: f.__name__)
 def test_planted_mistake_is_caught(monkeypatch, mutant):
     mutant(monkeypatch)

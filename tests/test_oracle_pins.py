@@ -404,3 +404,70 @@ def test_block_exact_recovery_when_collision_free():
             assert np.array_equal(res["val"].reshape(-1), total[elems])
             return
     raise AssertionError("no collision-free seed found: widen the sketch")
+
+
+# ---------------------------------------------------------------- block Top-K with error feedback
+def _topk_pure_python(g, e, B, K):
+    """Lists and Python floats only; exact sums of squares with math.fsum."""
+    import math
+    n = len(g)
+    acc = [float(np.float32(np.float32(a) + np.float32(b))) for a, b in zip(g, e)]
+    nb = (n + B - 1) // B
+    score = [float(np.float32(math.fsum(v * v for v in acc[x * B: x * B + B]))) for x in range(nb)]
+    ranked = sorted(range(nb), key=lambda x: (-score[x], x))
+    kept = set(ranked[:K])
+    sparse = [acc[i] if i // B in kept else 0.0 for i in range(n)]
+    resid = [0.0 if i // B in kept else acc[i] for i in range(n)]
+    return sorted(kept), sparse, resid
+
+
+@pytest.mark.parametrize("B,K", [(1, 5), (4, 3), (7, 0), (16, 13), (50, 2), (300, 1)])
+def test_topk_blocks_matches_pure_python(B, K):
+    rng = np.random.default_rng(B * 31 + K)
+    n = 203
+    g = rng.normal(0, 1, n).astype(np.float32)
+    e = (rng.normal(0, 0.3, n) * (rng.random(n) < 0.5)).astype(np.float32)
+    K = min(K, (n + B - 1) // B)
+    out = orc.topk_blocks(g, e, B, K)
+    kept, sparse, resid = _topk_pure_python(g.tolist(), e.tolist(), B, K)
+    assert out["blocks"].tolist() == kept
+    assert out["sparse"].tolist() == sparse and out["residual"].tolist() == resid
+
+
+def test_topk_ties_go_to_the_lower_block_and_extremes():
+    g = np.tile(np.array([1.0, -2.0, 0.5, 0.0], dtype=np.float32), 10)          # ten identical blocks of 4
+    out = orc.topk_blocks(g, None, 4, 3)
+    assert out["blocks"].tolist() == [0, 1, 2]
+    g[4 * 7] = 3.0                                                               # block 7 now leads
+    assert orc.topk_blocks(g, None, 4, 3)["blocks"].tolist() == [0, 1, 7]
+    full = orc.topk_blocks(g, None, 4, 10)
+    assert np.array_equal(full["sparse"], g) and not full["residual"].any()
+    none = orc.topk_blocks(g, None, 4, 0)
+    assert not none["sparse"].any() and np.array_equal(none["residual"], g)
+
+
+def test_topk_is_a_delta_approximate_compressor_and_loses_nothing():
+    """Theorem 2 (proof): what the K of b blocks leave behind has squared norm
+    |acc|^2 - |sparse|^2 <= (1 - K/b) |acc|^2; and sparse + residual is acc exactly,
+    so over iterations nothing of the gradients is dropped."""
+    rng = np.random.default_rng(21)
+    n, B = 4096, 32
+    b = n // B
+    e = np.zeros(n, dtype=np.float32)
+    sent = np.zeros(n, dtype=np.float64)
+    total = np.zeros(n, dtype=np.float64)
+    for step in range(5):
+        g = (rng.normal(0, 1, n) * rng.gamma(0.3, 1.0, n)).astype(np.float32)
+        K = [1, 8, 32, 64, 128][step]
+        out = orc.topk_blocks(g, e, B, K)
+        acc = out["acc"].astype(np.float64)
+        left = np.sum(out["residual"].astype(np.float64) ** 2)
+        assert left == pytest.approx(np.sum(acc ** 2) - np.sum(out["sparse"].astype(np.float64) ** 2), rel=1e-12)
+        assert left <= (1 - K / b) * np.sum(acc ** 2) * (1 + 1e-12)
+        assert np.array_equal(out["sparse"] + out["residual"], out["acc"])      # disjoint supports: exact
+        kept_min = out["score"][out["blocks"]].min()
+        assert (np.delete(out["score"], out["blocks"]) <= kept_min).all()
+        sent += out["sparse"]
+        total += g
+        e = out["residual"]
+    assert np.allclose(sent + e, total, rtol=0, atol=1e-4)                       # only float32 roundings of g + e apart
