@@ -274,6 +274,52 @@ s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap,
                              void* stream);
 
 /*
+ * Block-wise Top-K sparsifier with error feedback, the step the paper puts in
+ * front of the codec for dense layers (Section 2.2: the gradient is cut into
+ * blocks, the l2 norm of every block is computed and the K largest blocks are
+ * the ones communicated; Theorem 2 and its proof: the part that is not sent is
+ * kept as an error sequence and added to the next gradient).
+ *
+ *   acc[i]   = grad[i] + residual[i]                    (float32; grad[i] alone without a residual)
+ *   score[x] = sum of acc[i]^2 over block x, accumulated in float64 and rounded
+ *              once to float32 (the same order as the l2 norm)
+ *   kept     = the K blocks that come first when ordered by (score descending,
+ *              block index ascending); all blocks if K >= ceil(n / block)
+ *   sparse_out[i] = acc[i] in kept blocks, +0.0 elsewhere
+ *   residual[i]   = +0.0 in kept blocks, acc[i] elsewhere         (updated in place)
+ *
+ *   grad         dev, in    : n float32; 16-byte aligned
+ *   residual     dev, in/out: n float32, 16-byte aligned, or NULL (plain Top-K:
+ *                             what is not kept is dropped)
+ *   sparse_out   dev, out   : n float32, 16-byte aligned; may be grad itself
+ *   kept_bitmap  dev, out   : ceil(ceil(n/block)/64) uint64 in the bitmap layout
+ *                             of this file, bit x set iff block x is kept; or NULL
+ *   workspace    dev scratch, 256-byte aligned, W * s2r_topk_workspace_bytes
+ * The float64 sums are formed in an order of the library's choosing: two blocks
+ * whose sums of squares differ by less than a float64 rounding may swap places
+ * against another summation order; everything else is bit-exact.  Inputs are
+ * expected to be finite.  Limits: 1 <= n <= 2^32, 1 <= block <= 2^31 (blocks of
+ * more than a few thousand elements are served by one wave each).  The batch
+ * form takes host arrays of W device pointers (residuals and kept_bitmaps may be
+ * NULL as a whole).  Enqueues on stream and returns; errors as for s2r_encode.
+ */
+size_t s2r_topk_workspace_bytes(uint64_t n, uint32_t block);
+
+s2r_status s2r_topk_blocks(const float* grad, float* residual, uint64_t n,
+                           uint32_t block, uint64_t K,
+                           float* sparse_out, uint64_t* kept_bitmap,
+                           void* workspace, size_t workspace_bytes,
+                           void* stream);
+
+s2r_status s2r_topk_blocks_batch(const float* const* grads /* host array */,
+                                 float* const* residuals /* host array or NULL */, uint32_t W,
+                                 uint64_t n, uint32_t block, uint64_t K,
+                                 float* const* sparse_out /* host array */,
+                                 uint64_t* const* kept_bitmaps /* host array or NULL */,
+                                 void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/*
  * How s2r_encode carries out the insertion loops of Algorithm 1
  * (S[j, h_j(i)] += s_j(i) g(i)); the result is the same sketch either way.
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued

@@ -71,6 +71,12 @@ SIGNATURES = {
     "s2r_encode_blocks_batch": (c_int32, [ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32, c_uint32, c_uint32,
                                           c_uint64, ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
                                           ctypes.POINTER(c_void_p), c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "s2r_topk_workspace_bytes": (c_size_t, [c_uint64, c_uint32]),
+    "s2r_topk_blocks": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint64, c_void_p, c_void_p,
+                                  c_void_p, c_size_t, c_void_p]),
+    "s2r_topk_blocks_batch": (c_int32, [ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32,
+                                        c_uint64, ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
+                                        c_void_p, c_size_t, c_void_p]),
     "s2r_decode_blocks": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
                                     c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
@@ -233,6 +239,29 @@ def decode_blocks(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_o
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_decode_blocks")
+
+
+def topk_workspace_bytes(n: int, block: int) -> int:
+    return load().s2r_topk_workspace_bytes(n, block)
+
+
+def topk_blocks_batch(grads, residuals, n, block, K, sparse_out, kept_bitmaps, workspace, stream=None):
+    """s2r_topk_blocks_batch: lists of W device tensors; residuals / kept_bitmaps lists or None."""
+    st = load().s2r_topk_blocks_batch(_ptr_array(grads), None if residuals is None else _ptr_array(residuals),
+                                      len(grads), n, block, K, _ptr_array(sparse_out),
+                                      None if kept_bitmaps is None else _ptr_array(kept_bitmaps), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_topk_blocks_batch")
+
+
+def topk_blocks(grad, residual, block, K, sparse_out, kept_bitmap, workspace, stream=None, n=None):
+    """s2r_topk_blocks on torch device tensors (residual / kept_bitmap may be None)."""
+    n = grad.numel() if n is None else n
+    st = load().s2r_topk_blocks(_ptr(grad), _ptr(residual), n, block, K, _ptr(sparse_out), _ptr(kept_bitmap),
+                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_topk_blocks")
 
 
 def set_insert_strategy(strategy: int):

@@ -9,7 +9,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "s2r_kernels.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "s2r_kernels.hip"), os.path.join(HERE, "csrc", "s2r_topk.hip")]
 LIB_PATH = os.path.join(HERE, "libs2r.so")
 
 HIPCC_FLAGS = [

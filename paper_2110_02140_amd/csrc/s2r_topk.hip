@@ -1,0 +1,352 @@
+// gfx950 kernels and C ABI of the block-wise Top-K sparsifier with error
+// feedback that the paper puts in front of the codec for dense layers
+// (Section 2.2: the l2 norm of every block, the K largest blocks are kept;
+// Theorem 2: what is not sent stays in an error sequence added to the next
+// gradient).  See include/s2r.h for the contract.
+//
+//   topk_score_kernel   acc = g + e per element; per block the sum of squares
+//                       (float64 accumulation, one rounding to float32) packed
+//                       with the block index into a 64-bit key, larger key =
+//                       kept first (higher score, then lower block)
+//   topk_hist_kernel,   radix select of the K-th largest key: six digits of 11
+//   topk_pick_kernel    or 10 bits from the top; per digit a histogram of the
+//                       keys that share the digits found so far, then one
+//                       workgroup picks the digit.  Keys are distinct, so the
+//                       result is the exact threshold
+//   topk_apply_kernel   second pass over g and e: kept blocks go to the sparse
+//                       gradient, the rest to the new residual
+//   topk_bitmap_kernel  optional bitmap of the kept blocks
+// No kernel waits for another workgroup.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/s2r.h"
+#include "s2r_device.h"
+
+namespace s2r_topk {
+using s2r::kWave;
+using s2r::wave_inclusive_scan_u32;
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kHistBlock = 1024;
+constexpr int kHistPer = 8;                       // keys per thread of a histogram workgroup
+constexpr int kBins = 2048;                       // 11-bit digits (the last two digits have 10 bits)
+constexpr int kPasses = 6;
+__constant__ const uint32_t kShift[kPasses] = {53, 42, 31, 20, 10, 0};
+__constant__ const uint32_t kWidth[kPasses] = {11, 11, 11, 11, 10, 10};
+constexpr int kApplyPer = 4;                      // elements per thread of the apply kernel (one 16-byte access)
+
+static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct TopkState {          // per worker, in the workspace
+  uint64_t prefix;          // the digits of the K-th largest key found so far; after the last pass, the key itself
+  uint64_t remaining;       // how many keys still to take among those that share the prefix
+};
+
+struct TopkWorker {
+  const float* grad;
+  float* residual;           // may be null: no error feedback
+  float* sparse;
+  uint64_t* kept_bitmap;     // may be null
+};
+
+struct TopkBatch {
+  TopkWorker w[S2R_MAX_WORKERS];
+  char* workspace;           // W chunks of ws_stride bytes: keys u64[nb] | histogram u32[kBins] | TopkState
+  uint64_t ws_stride;
+  uint64_t hist_off, state_off;
+  uint64_t n;
+  uint64_t nb;
+  uint64_t K;
+  uint32_t block;
+  uint32_t nworkers;
+};
+
+__device__ __forceinline__ uint64_t* ws_keys(const TopkBatch& B, uint32_t k) {
+  return reinterpret_cast<uint64_t*>(B.workspace + k * B.ws_stride);
+}
+__device__ __forceinline__ uint32_t* ws_hist(const TopkBatch& B, uint32_t k) {
+  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.hist_off);
+}
+__device__ __forceinline__ TopkState* ws_state(const TopkBatch& B, uint32_t k) {
+  return reinterpret_cast<TopkState*>(B.workspace + k * B.ws_stride + B.state_off);
+}
+
+__device__ __forceinline__ uint64_t make_key(double sum_sq, uint64_t x) {
+  const uint32_t bits = __float_as_uint((float)sum_sq) & 0x7FFFFFFFu;      // a sum of squares has no sign
+  return ((uint64_t)bits << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)x);
+}
+
+// One wave per block (blocks of 32 elements and more) or one thread per block.
+// Workgroup 0 of every worker also resets the histogram and the selection state.
+__global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const TopkWorker P = B.w[k];
+  uint64_t* keys = ws_keys(B, k);
+  if (blockIdx.x == 0) {
+    uint32_t* hist = ws_hist(B, k);
+    for (uint32_t b = threadIdx.x; b < kBins; b += kBlock) hist[b] = 0u;
+    if (threadIdx.x == 0) {
+      TopkState* st = ws_state(B, k);
+      st->prefix = 0ull;
+      st->remaining = B.K;
+    }
+  }
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  if (B.block >= 32u) {
+    const uint64_t x = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (x >= B.nb) return;                                 // uniform over the wave
+    const uint64_t i0 = x * B.block;
+    double sum = 0.0;
+    for (uint32_t o = lane; o < B.block; o += 4 * kWave) {  // four loads of g (and of e) in flight
+      float a[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint64_t i = i0 + o + (uint64_t)u * kWave;
+        const bool in = o + u * kWave < B.block && i < B.n;
+        a[u] = in ? P.grad[i] : 0.0f;
+        if (in && P.residual != nullptr) a[u] += P.residual[i];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sum += (double)a[u] * (double)a[u];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+    if (lane == 0) keys[x] = make_key(sum, x);
+  } else {
+    const uint64_t x = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (x >= B.nb) return;
+    double sum = 0.0;
+    for (uint32_t o = 0; o < B.block; ++o) {
+      const uint64_t i = x * B.block + o;
+      if (i >= B.n) break;
+      float a = P.grad[i];
+      if (P.residual != nullptr) a += P.residual[i];
+      sum += (double)a * (double)a;
+    }
+    keys[x] = make_key(sum, x);
+  }
+}
+
+// Histogram of digit `pass` over the keys that share the digits found so far.
+__global__ __launch_bounds__(kHistBlock) void topk_hist_kernel(const TopkBatch B, uint32_t pass) {
+  __shared__ uint32_t s_hist[kBins];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  for (uint32_t b = threadIdx.x; b < kBins; b += kHistBlock) s_hist[b] = 0u;
+  __syncthreads();
+  const uint64_t* __restrict__ keys = ws_keys(B, k);
+  const uint64_t prefix = ws_state(B, k)->prefix;
+  const uint32_t shift = kShift[pass], above = shift + kWidth[pass];
+  const uint32_t mask = (1u << kWidth[pass]) - 1u;
+  uint64_t key[kHistPer];
+#pragma unroll
+  for (int u = 0; u < kHistPer; ++u) {
+    const uint64_t x = ((uint64_t)blockIdx.x * kHistPer + u) * kHistBlock + threadIdx.x;
+    key[u] = x < B.nb ? keys[x] : ~0ull;                   // ~0 is no key (bit 63 of a key is clear)
+  }
+#pragma unroll
+  for (int u = 0; u < kHistPer; ++u) {
+    const bool same = above >= 64u || (key[u] >> above) == (prefix >> above);
+    if (key[u] != ~0ull && same)
+      __hip_atomic_fetch_add(&s_hist[(uint32_t)(key[u] >> shift) & mask], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  __syncthreads();
+  uint32_t* hist = ws_hist(B, k);
+  for (uint32_t b = threadIdx.x; b < kBins; b += kHistBlock)
+    if (s_hist[b] != 0u) atomicAdd(&hist[b], s_hist[b]);
+}
+
+// One workgroup per worker: the digit d with (keys above d) < remaining <= (keys
+// above d) + (keys in d); the histogram is cleared for the next pass.
+__global__ __launch_bounds__(kHistBlock) void topk_pick_kernel(const TopkBatch B, uint32_t pass) {
+  constexpr int kWaves = kHistBlock / kWave;
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+  uint32_t* hist = ws_hist(B, k);
+  TopkState* st = ws_state(B, k);
+  const uint64_t remaining = st->remaining;
+  const uint32_t c0 = hist[2 * threadIdx.x], c1 = hist[2 * threadIdx.x + 1];   // bins 2t, 2t + 1
+  const uint32_t sum = c0 + c1;
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  __syncthreads();
+  uint32_t before = incl - sum, total = 0;                 // keys in bins below 2t; all keys counted
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) {
+    const uint32_t x = s_wave[q];
+    if ((uint32_t)q < wv) before += x;
+    total += x;
+  }
+  hist[2 * threadIdx.x] = 0u;
+  hist[2 * threadIdx.x + 1] = 0u;
+  if (remaining == 0 || remaining > total) return;         // nothing to find (the host does not launch such a case)
+  const uint64_t above1 = total - before - sum;            // keys in bins above 2t + 1
+  const uint64_t above0 = above1 + c1;                     // keys in bins above 2t
+  if (above1 < remaining && remaining <= above1 + c1) {
+    st->prefix |= (uint64_t)(2 * threadIdx.x + 1) << kShift[pass];
+    st->remaining = remaining - above1;
+  } else if (above0 < remaining && remaining <= above0 + c0) {
+    st->prefix |= (uint64_t)(2 * threadIdx.x) << kShift[pass];
+    st->remaining = remaining - above0;
+  }
+}
+
+// Four consecutive elements per thread.  `all` / `none` bypass the threshold
+// (K >= number of blocks, K = 0).
+__global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, uint32_t all, uint32_t none) {
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const TopkWorker P = B.w[k];
+  const uint64_t* __restrict__ keys = ws_keys(B, k);
+  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
+  const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * kApplyPer;
+  if (i0 >= B.n) return;
+  float a[kApplyPer];
+  const bool whole = i0 + kApplyPer <= B.n;
+  if (whole) {
+    const float4 g4 = *reinterpret_cast<const float4*>(P.grad + i0);
+    a[0] = g4.x; a[1] = g4.y; a[2] = g4.z; a[3] = g4.w;
+    if (P.residual != nullptr) {
+      const float4 e4 = *reinterpret_cast<const float4*>(P.residual + i0);
+      a[0] += e4.x; a[1] += e4.y; a[2] += e4.z; a[3] += e4.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) {
+      a[j] = 0.0f;
+      if (i0 + j < B.n) {
+        a[j] = P.grad[i0 + j];
+        if (P.residual != nullptr) a[j] += P.residual[i0 + j];
+      }
+    }
+  }
+  uint64_t x = i0 / B.block;
+  uint32_t r = (uint32_t)(i0 - x * B.block);
+  float s[kApplyPer], e[kApplyPer];
+#pragma unroll
+  for (int j = 0; j < kApplyPer; ++j) {
+    const bool kept = x < B.nb && keys[x] >= T;
+    s[j] = kept ? a[j] : 0.0f;
+    e[j] = kept ? 0.0f : a[j];
+    if (++r == B.block) { r = 0; ++x; }
+  }
+  if (whole) {
+    *reinterpret_cast<float4*>(P.sparse + i0) = make_float4(s[0], s[1], s[2], s[3]);
+    if (P.residual != nullptr) *reinterpret_cast<float4*>(P.residual + i0) = make_float4(e[0], e[1], e[2], e[3]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) {
+      if (i0 + j < B.n) {
+        P.sparse[i0 + j] = s[j];
+        if (P.residual != nullptr) P.residual[i0 + j] = e[j];
+      }
+    }
+  }
+}
+
+// One thread per word of the kept-block bitmap.
+__global__ __launch_bounds__(kBlock) void topk_bitmap_kernel(const TopkBatch B, uint32_t all, uint32_t none) {
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers || B.w[k].kept_bitmap == nullptr) return;
+  const uint64_t* __restrict__ keys = ws_keys(B, k);
+  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
+  const uint64_t wd = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (wd >= ceil_div(B.nb, 64)) return;
+  uint64_t bits = 0;
+  for (uint32_t b = 0; b < 64; ++b) {
+    const uint64_t x = wd * 64 + b;
+    if (x < B.nb && keys[x] >= T) bits |= 1ull << b;
+  }
+  B.w[k].kept_bitmap[wd] = bits;
+}
+
+static inline size_t keys_bytes(uint64_t nb) { return align256((size_t)nb * sizeof(uint64_t)); }
+static inline size_t workspace_each(uint64_t nb) { return keys_bytes(nb) + align256(kBins * sizeof(uint32_t)) + 256; }
+static inline bool sizes_ok(uint64_t n, uint32_t block) {
+  return n >= 1 && n <= (1ull << 32) && block >= 1 && (uint64_t)block <= (1ull << 31);
+}
+static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+}  // namespace s2r_topk
+
+using namespace s2r_topk;
+
+extern "C" {
+
+size_t s2r_topk_workspace_bytes(uint64_t n, uint32_t block) {
+  if (!sizes_ok(n, block)) return 0;
+  return workspace_each(ceil_div(n, block));
+}
+
+s2r_status s2r_topk_blocks_batch(const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
+                                 uint32_t block, uint64_t K, float* const* sparse_out, uint64_t* const* kept_bitmaps,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (grads == nullptr || sparse_out == nullptr) return S2R_ERR_NULL;
+  if (W == 0 || W > S2R_MAX_WORKERS || !sizes_ok(n, block)) return S2R_ERR_SIZE;
+  const uint64_t nb = ceil_div(n, block);
+  if (K > nb) K = nb;
+  static thread_local TopkBatch B;
+  for (uint32_t k = 0; k < W; ++k) {
+    float* ek = residuals ? residuals[k] : nullptr;
+    uint64_t* bk = kept_bitmaps ? kept_bitmaps[k] : nullptr;
+    if (grads[k] == nullptr || sparse_out[k] == nullptr || (residuals && ek == nullptr) || (kept_bitmaps && bk == nullptr))
+      return S2R_ERR_NULL;
+    if (((uintptr_t)grads[k] & 15u) || ((uintptr_t)sparse_out[k] & 15u) || ((uintptr_t)ek & 15u) || ((uintptr_t)bk & 7u))
+      return S2R_ERR_ALIGN;
+    B.w[k].grad = grads[k];
+    B.w[k].residual = ek;
+    B.w[k].sparse = sparse_out[k];
+    B.w[k].kept_bitmap = bk;
+  }
+  const size_t ws_each = (workspace_bytes / W) & ~(size_t)255;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_each(nb)) return S2R_ERR_WORKSPACE;
+  B.workspace = reinterpret_cast<char*>(workspace);
+  B.ws_stride = ws_each;
+  B.hist_off = keys_bytes(nb);
+  B.state_off = B.hist_off + align256(kBins * sizeof(uint32_t));
+  B.n = n;
+  B.nb = nb;
+  B.K = K;
+  B.block = block;
+  B.nworkers = W;
+  hipStream_t st = (hipStream_t)stream;
+
+  const uint32_t all = K == nb ? 1u : 0u, none = K == 0 ? 1u : 0u;
+  const uint64_t score_blocks = block >= 32u ? ceil_div(nb, kWavesPerBlock) : ceil_div(nb, kBlock);
+  hipLaunchKernelGGL(topk_score_kernel, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+  if (!all && !none) {
+    const uint32_t hist_blocks = (uint32_t)ceil_div(nb, (uint64_t)kHistBlock * kHistPer);
+    for (uint32_t pass = 0; pass < (uint32_t)kPasses; ++pass) {
+      hipLaunchKernelGGL(topk_hist_kernel, dim3(hist_blocks, W), dim3(kHistBlock), 0, st, B, pass);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+      hipLaunchKernelGGL(topk_pick_kernel, dim3(1, W), dim3(kHistBlock), 0, st, B, pass);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+    }
+  }
+  hipLaunchKernelGGL(topk_apply_kernel, dim3((uint32_t)ceil_div(n, (uint64_t)kBlock * kApplyPer), W), dim3(kBlock), 0, st,
+                     B, all, none);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+  if (kept_bitmaps != nullptr) {
+    hipLaunchKernelGGL(topk_bitmap_kernel, dim3((uint32_t)ceil_div(ceil_div(nb, 64), kBlock), W), dim3(kBlock), 0, st, B,
+                       all, none);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+  return S2R_OK;
+}
+
+s2r_status s2r_topk_blocks(const float* grad, float* residual, uint64_t n, uint32_t block, uint64_t K,
+                           float* sparse_out, uint64_t* kept_bitmap, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  return s2r_topk_blocks_batch(&grad, residual ? &residual : nullptr, 1, n, block, K, &sparse_out,
+                               kept_bitmap ? &kept_bitmap : nullptr, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

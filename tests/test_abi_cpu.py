@@ -179,3 +179,13 @@ def test_block_codec_argument_checks():
     assert lib.s2r_decode_blocks(0x1000, 0x2000, n, 0, d, w, 0, None, None, 0, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_SIZE
     assert lib.s2r_decode_blocks(0x1000, 0x2000, n, 256, d, w, 0, 0x3000, None, 10, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_NULL
     assert lib.s2r_decode_blocks(0x1000, 0x2000, n, 256, d, w + 1, 0, None, None, 0, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_WIDTH
+
+
+def test_topk_argument_checks():
+    lib = b.load()
+    assert b.topk_workspace_bytes(1 << 20, 0) == 0 and b.topk_workspace_bytes(0, 256) == 0
+    assert b.topk_workspace_bytes(1 << 20, 256) >= 8 * 4096 + 4 * 2048
+    assert lib.s2r_topk_blocks(None, None, 1000, 10, 5, 0x2000, None, 0x4000, 1 << 20, None) == b.S2R_ERR_NULL
+    assert lib.s2r_topk_blocks(0x1000, None, 1000, 0, 5, 0x2000, None, 0x4000, 1 << 20, None) == b.S2R_ERR_SIZE
+    assert lib.s2r_topk_blocks(0x1004, None, 1000, 10, 5, 0x2000, None, 0x4000, 1 << 20, None) == b.S2R_ERR_ALIGN
+    assert lib.s2r_topk_blocks(0x1000, None, 1000, 10, 5, 0x2000, None, 0x4000, 64, None) == b.S2R_ERR_WORKSPACE

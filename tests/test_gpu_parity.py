@@ -577,3 +577,91 @@ def test_block_codec_capacity(strategy, decode_strategy):
     elems = (blocks[:cap, None] * B + np.arange(B)[None, :]).reshape(-1)
     tol = REL * orc.decode_tolerance_mass(ref["M"], elems.astype(np.uint32), 0) + DENORM_SLACK
     assert np.all(np.abs(b.out_val.cpu().numpy().astype(np.float64) - want) <= tol)
+
+
+# ---------------------------------------------------------------- block Top-K with error feedback
+def _topk_check(gs, es, B, K, in_place=False):
+    """Runs s2r_topk_blocks_batch and checks it against oracle.topk_blocks.  The kept set must
+    be the oracle's unless two scores around the threshold are within one float32 rounding of
+    each other (the float64 sums may be formed in another order); sparse and residual must be
+    bit-exact for the set the library kept."""
+    W, n = len(gs), len(gs[0])
+    nb = (n + B - 1) // B
+    dev = "cuda"
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = None if es is None else [torch.from_numpy(e).to(dev) for e in es]
+    sparse = grads if in_place else [torch.full((n,), 7.0, dtype=torch.float32, device=dev) for _ in range(W)]
+    kept = [torch.full(((nb + 63) // 64,), -1, dtype=torch.int64, device=dev) for _ in range(W)]
+    ws = torch.empty(binding.topk_workspace_bytes(n, B) * W, dtype=torch.uint8, device=dev)
+    binding.topk_blocks_batch(grads, resid, n, B, K, sparse, kept, ws)
+    torch.cuda.synchronize()
+    for k in range(W):
+        ref = orc.topk_blocks(gs[k], None if es is None else es[k], B, K)
+        mask = orc.unpack_bitmap(pipeline.u64(kept[k]), nb)
+        assert int(mask.sum()) == min(K, nb), f"worker {k}: kept {int(mask.sum())} blocks"
+        got = np.flatnonzero(mask)
+        if not np.array_equal(got, ref["blocks"]):
+            sc = ref["score"].astype(np.float64)
+            lo, hi = sc[mask].min(), sc[~mask].max()
+            assert hi <= lo * (1 + 2.0 ** -22), f"worker {k}: a kept block scores {lo}, a dropped one {hi}"
+        elem = np.repeat(mask, B)[:n]
+        acc = ref["acc"]
+        want_s = np.where(elem, acc, np.float32(0.0)).astype(np.float32)
+        want_e = np.where(elem, np.float32(0.0), acc).astype(np.float32)
+        assert np.array_equal(sparse[k].cpu().numpy().view(np.uint32), want_s.view(np.uint32)), f"worker {k} sparse"
+        if es is not None:
+            assert np.array_equal(resid[k].cpu().numpy().view(np.uint32), want_e.view(np.uint32)), f"worker {k} residual"
+
+
+@pytest.mark.parametrize("n,B,K", [(1, 1, 1), (1000, 1, 37), (1000, 7, 20), (4096, 32, 5), (70001, 256, 50),
+                                   (70001, 650, 3), (200000, 31, 1000), (200000, 33, 1000), (50000, 60000, 1),
+                                   (300000, 4096, 10), (65536, 64, 0), (65536, 64, 1024), (65536, 64, 5000)])
+def test_topk_blocks_match_oracle(n, B, K):
+    rng = np.random.default_rng(n + 31 * B + K)
+    gs = [(rng.normal(0, 1, n) * rng.gamma(0.5, 1.0, n)).astype(np.float32) for _ in range(3)]
+    es = [(rng.normal(0, 0.2, n) * (rng.random(n) < 0.3)).astype(np.float32) for _ in range(3)]
+    _topk_check(gs, es, B, K)
+
+
+def test_topk_without_residual_in_place_and_ties():
+    rng = np.random.default_rng(5)
+    n, B = 40000, 100
+    g = rng.normal(0, 1, n).astype(np.float32)
+    _topk_check([g.copy(), g.copy()], None, B, 40, in_place=True)
+    tied = np.tile(rng.normal(0, 1, B).astype(np.float32), n // B)      # every block identical: the lowest indices win
+    _topk_check([tied], [np.zeros(n, dtype=np.float32)], B, 17)
+    sparse = np.zeros(n, dtype=np.float32)
+    sparse[:5 * B] = 1.0                                                # five non-zero blocks, K larger: zero blocks by index
+    _topk_check([sparse], [np.zeros(n, dtype=np.float32)], B, 9)
+
+
+def test_topk_error_feedback_over_steps_feeds_the_codec():
+    """Three steps of gradient -> Top-K (+ residual) -> block codec on two workers: at
+    every step the decoded blocks are the union of the kept blocks, and what the workers
+    have sent plus their residuals is what they were given."""
+    rng = np.random.default_rng(8)
+    n, B, K, W, d, w = 32768, 64, 20, 2, 3, 1 << 14
+    nb = n // B
+    dev = "cuda"
+    resid = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(W)]
+    sent = [np.zeros(n) for _ in range(W)]
+    given = [np.zeros(n) for _ in range(W)]
+    ws = torch.empty(binding.topk_workspace_bytes(n, B) * W, dtype=torch.uint8, device=dev)
+    wl = _custom(n, [np.empty(0, dtype=np.uint32)] * W, [np.empty(0, dtype=np.float32)] * W, d=d, w=w, W=W)
+    bb = pipeline.BlockBuffers(W, n, B, d, w, 0, K, W * K)
+    for step in range(3):
+        gs = [rng.normal(0, 1, n).astype(np.float32) for _ in range(W)]
+        grads = [torch.from_numpy(g).to(dev) for g in gs]
+        kept = [torch.zeros((nb + 63) // 64, dtype=torch.int64, device=dev) for _ in range(W)]
+        binding.topk_blocks_batch(grads, resid, n, B, K, grads, kept, ws)          # sparse gradient in place
+        bb.grads = grads
+        bb.step()
+        torch.cuda.synchronize()
+        union = np.zeros(nb, dtype=bool)
+        for k in range(W):
+            union |= orc.unpack_bitmap(pipeline.u64(kept[k]), nb)
+            sent[k] += grads[k].cpu().numpy()
+            given[k] += gs[k]
+            assert np.allclose(sent[k] + resid[k].cpu().numpy(), given[k], rtol=0, atol=1e-4)
+        cnt = int(bb.out_count.cpu()[0])
+        assert np.array_equal(bb.out_blk[:cnt].cpu().numpy(), np.flatnonzero(union))
