@@ -50,6 +50,10 @@ def parse_args():
     ap.add_argument("--block", type=int, default=0,
                     help="use the block-granular codec with blocks of this many elements (0: one bitmap bit per "
                          "element); the natural sizes are 650 for cfg2 and 256 for cfg3")
+    ap.add_argument("--topk-frac", type=float, default=0.0,
+                    help="with --block: start every step from DENSE random gradients of the workload's W and n and "
+                         "put the block-wise Top-K sparsifier with error feedback (this fraction of the blocks kept) "
+                         "in front of the block codec")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with W s2r_encode calls instead of one s2r_encode_batch call")
     ap.add_argument("--insert-strategy", default="auto", choices=["auto", "atomic", "slice"],
@@ -149,19 +153,44 @@ def main():
     t_gen = time.perf_counter()
     wl = workloads.make(cfg)
     t_gen = time.perf_counter() - t_gen
-    b = pipeline.block_buffers_for(wl, args.block) if args.block > 0 else pipeline.buffers_for(wl)
-    torch.cuda.synchronize()
-    stream = torch.cuda.current_stream()
-
+    topk = args.topk_frac > 0
+    if topk and args.block <= 0:
+        print("bench.py: --topk-frac needs --block", file=sys.stderr)
+        sys.exit(2)
     batched = not args.per_worker_calls
+    stream = torch.cuda.current_stream()
+    if topk:
+        # dense N(0, 0.01) gradients, one per worker, resident; the sparsifier writes the sparse gradients the
+        # block codec then reads, and keeps its residuals from step to step
+        nb = (wl.n + args.block - 1) // args.block
+        K = max(1, int(round(args.topk_frac * nb)))
+        b = pipeline.BlockBuffers(wl.W, wl.n, args.block, wl.d, wl.w, wl.seed, K, wl.W * K)
+        gen = torch.Generator(device=b.device).manual_seed(1000 * cfg + 998)
+        dense = [torch.empty(wl.n, dtype=torch.float32, device=b.device).normal_(0, 0.01, generator=gen)
+                 for _ in range(wl.W)]
+        resid = [torch.zeros(wl.n, dtype=torch.float32, device=b.device) for _ in range(wl.W)]
+        b.grads = [torch.empty(wl.n, dtype=torch.float32, device=b.device) for _ in range(wl.W)]
+        ws_topk = torch.empty(binding.topk_workspace_bytes(wl.n, args.block) * wl.W, dtype=torch.uint8, device=b.device)
+        tk_pairs = []
+
+        def step():
+            binding.topk_blocks_batch(dense, resid, wl.n, args.block, K, b.grads, None, ws_topk, stream)
+            b.step(stream, batched)
+    else:
+        b = pipeline.block_buffers_for(wl, args.block) if args.block > 0 else pipeline.buffers_for(wl)
+
+        def step():
+            b.step(stream, batched)
+    torch.cuda.synchronize()
+
     for _ in range(args.warmup):
-        b.step(stream, batched)
+        step()
     torch.cuda.synchronize()
     ev0, ev1 = binding.HipEvent(), binding.HipEvent()
     t0 = time.perf_counter()
     ev0.record(stream)
     for _ in range(args.steps):
-        b.step(stream, batched)
+        step()
     ev1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -191,6 +220,12 @@ def main():
             slice_pairs.append((s0, s1))
 
     for r in range(reps):
+        if topk:
+            t_a, t_b = binding.HipEvent(), binding.HipEvent()
+            t_a.record(stream)
+            binding.topk_blocks_batch(dense, resid, wl.n, args.block, K, b.grads, None, ws_topk, stream)
+            t_b.record(stream)
+            tk_pairs.append((t_a, t_b))
         if batched:
             bracket("scan", lambda: b.encode_all(stream))
         else:
@@ -228,13 +263,20 @@ def main():
 
     union = int(b.out_count.cpu()[0])
     nnz = np.array([len(i) for i in wl.idx], dtype=np.float64)
+    topk_ms = float(np.mean([a.elapsed_ms(c) for a, c in tk_pairs])) if topk else None
     if args.block > 0:
         nblk = b.nblk.cpu().numpy()
-        assert [int(x) for x in nblk] == [len(np.unique(i // np.uint32(args.block))) for i in wl.idx], \
-            "encode's block counts differ from the generator's"
+        if topk:
+            assert all(int(x) == K for x in nblk), "every worker must send exactly K blocks"
+            nnz = np.full(wl.W, float(K * args.block))
+        else:
+            assert [int(x) for x in nblk] == [len(np.unique(i // np.uint32(args.block))) for i in wl.idx], \
+                "encode's block counts differ from the generator's"
         per_worker = 4.0 * wl.n + ((wl.n + args.block - 1) // args.block) / 8.0 + (8.0 * wl.d * nnz.mean() if atomic else 0.0)
         alg_bytes = workers_per_launch * per_worker
         step_alg_bytes = algorithmic_bytes_blocks(wl, args.block, nnz, nblk, union)
+        if topk:        # g and e read for the scores, read again and both written by the apply pass
+            step_alg_bytes += wl.W * 24.0 * wl.n
     else:
         assert [int(x) for x in b.nnz.cpu().numpy()] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
         alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d, atomic)
@@ -255,7 +297,9 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "W": wl.W, "n": wl.n, "d": wl.d, "w": wl.w, "seed": wl.seed,
-                   "block": args.block, "nnz_per_worker": int(nnz.mean()),
+                   "block": args.block, "topk_blocks_kept": K if topk else None,
+                   "input": "dense N(0, 0.01) gradients + residuals" if topk else "dense-stored sparse gradients",
+                   "nnz_per_worker": int(nnz.mean()),
                    "union_blocks" if args.block > 0 else "union_nnz": union,
                    "dense_bytes_per_step": wl.dense_bytes},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
@@ -269,7 +313,8 @@ def main():
         "insert_strategy": "atomic" if atomic else "lds_slice",
         "kernel_ms": {"encode_scan_per_launch": round(scan_ms, 4), "workers_per_scan_launch": workers_per_launch,
                       "encode_slice_per_launch": None if slice_ms is None else round(slice_ms, 4),
-                      "merge": round(merge_ms, 4), "decode": round(decode_ms, 4)},
+                      "merge": round(merge_ms, 4), "decode": round(decode_ms, 4),
+                      "topk_sparsifier": None if topk_ms is None else round(topk_ms, 4)},
         "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None if args.block > 0 else

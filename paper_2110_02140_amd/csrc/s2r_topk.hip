@@ -36,6 +36,8 @@ constexpr int kBins = 2048;                       // 11-bit digits (the last two
 constexpr int kPasses = 6;
 __constant__ const uint32_t kShift[kPasses] = {53, 42, 31, 20, 10, 0};
 __constant__ const uint32_t kWidth[kPasses] = {11, 11, 11, 11, 10, 10};
+constexpr int kScorePer = 4;                      // blocks per wave of the score kernel
+constexpr int kScoreLoads = 4;                    // rows of 64 elements per block and trip
 constexpr int kApplyPer = 4;                      // elements per thread of the apply kernel (one 16-byte access)
 
 static inline __host__ __device__ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -98,25 +100,37 @@ __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
   }
   const uint32_t lane = threadIdx.x & (kWave - 1);
   if (B.block >= 32u) {
-    const uint64_t x = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    if (x >= B.nb) return;                                 // uniform over the wave
-    const uint64_t i0 = x * B.block;
-    double sum = 0.0;
-    for (uint32_t o = lane; o < B.block; o += 4 * kWave) {  // four loads of g (and of e) in flight
-      float a[4];
+    // a wave takes kScorePer consecutive blocks and walks them together, kScoreLoads rows of 64 elements of
+    // each per trip: 2 * kScorePer * kScoreLoads streaming loads in flight per lane
+    const uint64_t x0 = ((uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave) * kScorePer;
+    if (x0 >= B.nb) return;                                // uniform over the wave
+    double sum[kScorePer];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint64_t i = i0 + o + (uint64_t)u * kWave;
-        const bool in = o + u * kWave < B.block && i < B.n;
-        a[u] = in ? P.grad[i] : 0.0f;
-        if (in && P.residual != nullptr) a[u] += P.residual[i];
+    for (int q = 0; q < kScorePer; ++q) sum[q] = 0.0;
+    for (uint32_t o = lane; o < B.block; o += kScoreLoads * kWave) {
+      float a[kScorePer][kScoreLoads];
+#pragma unroll
+      for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+        for (int u = 0; u < kScoreLoads; ++u) {
+          const uint64_t i = (x0 + q) * B.block + o + (uint64_t)u * kWave;
+          const bool in = x0 + q < B.nb && o + u * kWave < B.block && i < B.n;
+          a[q][u] = in ? __builtin_nontemporal_load(&P.grad[i]) : 0.0f;
+          if (in && P.residual != nullptr) a[q][u] += __builtin_nontemporal_load(&P.residual[i]);
+        }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) sum += (double)a[u] * (double)a[u];
+      for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+        for (int u = 0; u < kScoreLoads; ++u) sum[q] += (double)a[q][u] * (double)a[q][u];
+      }
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
-    if (lane == 0) keys[x] = make_key(sum, x);
+    for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) sum[q] += __shfl_xor(sum[q], off, kWave);
+      if (lane == 0 && x0 + q < B.nb) keys[x0 + q] = make_key(sum[q], x0 + q);
+    }
   } else {
     const uint64_t x = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (x >= B.nb) return;
@@ -319,7 +333,7 @@ s2r_status s2r_topk_blocks_batch(const float* const* grads, float* const* residu
   hipStream_t st = (hipStream_t)stream;
 
   const uint32_t all = K == nb ? 1u : 0u, none = K == 0 ? 1u : 0u;
-  const uint64_t score_blocks = block >= 32u ? ceil_div(nb, kWavesPerBlock) : ceil_div(nb, kBlock);
+  const uint64_t score_blocks = block >= 32u ? ceil_div(nb, (uint64_t)kWavesPerBlock * kScorePer) : ceil_div(nb, kBlock);
   hipLaunchKernelGGL(topk_score_kernel, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if (!all && !none) {
