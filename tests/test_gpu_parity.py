@@ -665,3 +665,77 @@ def test_topk_error_feedback_over_steps_feeds_the_codec():
             assert np.allclose(sent[k] + resid[k].cpu().numpy(), given[k], rtol=0, atol=1e-4)
         cnt = int(bb.out_count.cpu()[0])
         assert np.array_equal(bb.out_blk[:cnt].cpu().numpy(), np.flatnonzero(union))
+
+
+# ---------------------------------------------------------------- sizes at the limits, random shapes
+def test_maximum_length_gradient():
+    """n = 2^32 (the limit: indices are uint32), non-zeros at both ends, across the 2^31
+    boundary and scattered: counts, index lists and decoded values against the oracle's
+    building blocks (the oracle's dense bitmap unpacking is skipped: 2^32 flags)."""
+    n, d, w, seed = 1 << 32, 3, 1 << 16, 7
+    rng = np.random.default_rng(42)
+    special = np.array([0, 1, 63, 64, (1 << 31) - 1, 1 << 31, (1 << 31) + 1, n - 65, n - 64, n - 2, n - 1], dtype=np.int64)
+    idx = np.unique(np.concatenate([special, rng.integers(0, n, 20000), (3 << 30) + np.arange(5000)])).astype(np.uint32)
+    val = (rng.normal(0, 1, len(idx)) + 3.0).astype(np.float32)
+    print(f"[case] maximum length n={n} nnz={len(idx)}", flush=True)
+    g = torch.zeros(n, dtype=torch.float32, device="cuda")
+    g[torch.from_numpy(idx.astype(np.int64)).cuda()] = torch.from_numpy(val).cuda()
+    b = pipeline.Buffers(1, n, d, w, seed, len(idx) + 7, len(idx) + 7)
+    b.grads = [g]
+    for strategy in ("atomic", "slice"):
+        for route in ("gather", "slice"):
+            binding.set_insert_strategy(STRATEGIES[strategy])
+            binding.set_decode_strategy(DECODES[route])
+            try:
+                b.nz_idx[0].fill_(-1)
+                b.out_idx.fill_(-1)
+                b.step()
+                torch.cuda.synchronize()
+            finally:
+                binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+                binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+            assert int(b.nnz.cpu()[0]) == len(idx) and int(b.out_count.cpu()[0]) == len(idx)
+            assert np.array_equal(b.nz_idx[0][: len(idx)].cpu().numpy().view(np.uint32), idx)
+            assert np.array_equal(b.nz_val[0][: len(idx)].cpu().numpy(), val)
+            assert np.array_equal(b.out_idx[: len(idx)].cpu().numpy().view(np.uint32), idx)
+            words = pipeline.u64(b.bitmap[0])
+            assert int(np.unpackbits(words.view(np.uint8)).sum()) == len(idx)
+            bit = (words[(idx >> np.uint32(6)).astype(np.int64)] >> (idx & np.uint32(63)).astype(np.uint64)) & np.uint64(1)
+            assert bit.all(), "a listed index has no bit"
+            S, M = orc.insert(idx, val, d, w, seed)
+            _check_sketch(b.sketch[0].cpu().numpy(), S, M, f"sketch ({strategy})")
+            want = orc.median_rows(orc.estimates(S, idx, seed))
+            tol = REL * orc.decode_tolerance_mass(M, idx, seed) + DENORM_SLACK
+            got = b.out_val[: len(idx)].cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(got - want) <= tol), f"decoded values ({strategy}, {route})"
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes(case):
+    """Seeded random problems: length, rows, width, workers, density, clustering, both
+    insertion strategies and both decode routes, element and block codec."""
+    rng = np.random.default_rng(9000 + case)
+    n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 70000), rng.integers(70000, 400000)]))
+    d = int(rng.integers(1, 9))
+    w = 1 << int(rng.integers(0, 18))
+    W = int(rng.integers(1, 6))
+    density = float(rng.choice([0.0005, 0.01, 0.2, 1.0]))
+    run = int(rng.choice([1, 1, 17, 256]))
+    idx, val = [], []
+    for k in range(W):
+        starts = np.flatnonzero(rng.random((n + run - 1) // run) < density) * run
+        i = (starts[:, None] + np.arange(run)[None, :]).reshape(-1)
+        i = np.unique(i[i < n]).astype(np.uint32)
+        idx.append(i)
+        val.append((rng.normal(0, 1, len(i)) + np.where(rng.random(len(i)) < 0.5, 2.0, -2.0)).astype(np.float32))
+    wl = _custom(n, idx, val, d=d, w=w, W=W, seed=int(rng.integers(0, 1 << 40)))
+    binding.set_insert_strategy(STRATEGIES[["atomic", "slice"][case % 2]])
+    binding.set_decode_strategy(DECODES[["gather", "slice"][(case // 2) % 2]])
+    try:
+        if case % 3 == 2:
+            _run_blocks_and_check(wl, int(rng.choice([1, 3, 64, 100, 1000])), batched=bool(case % 4 < 2))
+        else:
+            _run_and_check(wl, dense_out=(case % 3 == 0), batched=bool(case % 4 < 2))
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+        binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
