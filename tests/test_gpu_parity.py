@@ -739,3 +739,30 @@ def test_random_shapes(case):
     finally:
         binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
         binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
+def test_very_sparse_gradient_with_dense_pockets(strategy):
+    """Forty tiles with a handful of non-zeros per 2048-element piece, one piece of exactly
+    8, one of 9 and one full piece, a ragged last tile, and a list capacity that ends inside
+    a sparse tile."""
+    rng = np.random.default_rng(123)
+    n = 32768 * 40 + 1234
+    parts = [np.sort(rng.choice(n, 2500, replace=False))]
+    parts.append(32768 * 3 + 2048 * 5 + np.arange(8) * 7)              # a piece with exactly 8
+    parts.append(32768 * 7 + 2048 * 2 + np.arange(9) * 5)              # a piece with 9: its tile expands the bitmap
+    parts.append(32768 * 11 + 2048 * 9 + np.arange(2048))              # a full piece
+    idx = np.unique(np.concatenate(parts)).astype(np.uint32)
+    val = (rng.normal(0, 1, len(idx)) + 2.0).astype(np.float32)
+    assert len(idx) + 5 < n // 256
+    wl = _custom(n, [idx, idx[::3]], [val, val[::3]], d=3, w=1 << 12, W=2)
+    _run_and_check(wl)
+    b = pipeline.buffers_for(wl)
+    cap = 1000
+    b.nz_idx[0] = torch.full((cap + 16,), -1, dtype=torch.int32, device="cuda")[:cap]
+    b.nz_val[0] = torch.zeros(cap, dtype=torch.float32, device="cuda")
+    b.encode(0)
+    torch.cuda.synchronize()
+    assert int(b.nnz.cpu()[0]) == len(idx)
+    assert np.array_equal(b.nz_idx[0].cpu().numpy().view(np.uint32), idx[:cap])
+    assert np.array_equal(b.nz_val[0].cpu().numpy(), val[:cap])
+    assert (b.nz_idx[0]._base[cap:].cpu().numpy() == -1).all()
