@@ -62,15 +62,9 @@ constexpr int kGroupSlots = 2048;                 // list positions one expansio
 constexpr int kGroupsPerTile = kTileElems / kGroupSlots;     // 16
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
 constexpr int kPrefixPer = 8;                     // tiles per thread per round
-#ifndef S2R_SLICE_BLOCK
-#define S2R_SLICE_BLOCK 1024
-#endif
-#ifndef S2R_SLICE_LOG2_PREF
-#define S2R_SLICE_LOG2_PREF 14
-#endif
-constexpr int kSliceBlock = S2R_SLICE_BLOCK;      // threads of a sketch-slice workgroup
-constexpr int kSliceLog2Max = 14;                 // at most 2^14 cells = 128 KiB of float64 accumulators in LDS
-constexpr int kSliceLog2Pref = S2R_SLICE_LOG2_PREF;   // slice size used unless it gives too many bins
+constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice workgroup
+constexpr int kSliceLog2Max = 14;                 // 2^14 cells = 128 KiB of float64 accumulators in LDS (smaller slices
+                                                  // with smaller workgroups measured slower in total: more bins)
 static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
 static_assert(kScanWords * 64 <= 0xFFFF, "a piece count must fit 16 bits");
 static_assert(kScansPerTile == 16, "tile_prefix_kernel reads a tile's piece counts as two 16-byte loads");
@@ -1437,9 +1431,7 @@ struct SliceLayout {
 static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   SliceLayout L;
   const uint32_t log2w = log2_of(w);
-  L.slice_log2 = log2w < (uint32_t)kSliceLog2Pref ? log2w : (uint32_t)kSliceLog2Pref;
-  while (((uint64_t)d << (log2w - L.slice_log2)) > (uint64_t)kMaxBins && L.slice_log2 < (uint32_t)kSliceLog2Max)
-    ++L.slice_log2;
+  L.slice_log2 = log2w < (uint32_t)kSliceLog2Max ? log2w : (uint32_t)kSliceLog2Max;
   const uint64_t nbins = (uint64_t)d << (log2w - L.slice_log2);
   L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0;
   L.nbins = (uint32_t)(L.possible ? nbins : 0);
