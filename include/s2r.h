@@ -10,6 +10,9 @@
  *                workers' buffers: S = sum_k S_k, C = OR_k C_k
  *   s2r_decode   the decompress step: indices from the aggregated bitmap and,
  *                at each, the median over rows of s_j(i) * S[j, h_j(i)]
+ * and, around it, the paper's block-granular bitmap (s2r_encode_blocks,
+ * s2r_decode_blocks) and its block-wise Top-K sparsifier with error feedback
+ * (s2r_topk_blocks).
  *
  * Notation.  n = gradient length (the paper's d in Section 3.1), d = sketch rows
  * (the paper's r), w = sketch columns (the paper's c, m in Section 3.1), W =
@@ -29,7 +32,8 @@
  *     (i mod 64), least significant first, of word floor(i/64); the unused high
  *     bits of the last word are written as 0.  (The paper does not fix a
  *     layout; Section 3.1 only says one flag per block.  A block is one
- *     element here.)
+ *     element in s2r_encode / s2r_decode and `block` elements in the *_blocks
+ *     calls.)
  *   - "Non-zero" is decided on the float32 bit pattern: everything except +0.0
  *     and -0.0, i.e. (bits & 0x7fffffff) != 0.
  *   - Sketch layout: d rows of w float32 cells, row-major, S[j*w + b].

@@ -1553,7 +1553,7 @@ using namespace s2r;
 
 extern "C" {
 
-int32_t s2r_version(void) { return 200; }
+int32_t s2r_version(void) { return 300; }
 
 const char* s2r_status_string(s2r_status status) {
   switch (status) {
