@@ -54,6 +54,9 @@ def parse_args():
                     help="with --block: start every step from DENSE random gradients of the workload's W and n and "
                          "put the block-wise Top-K sparsifier with error feedback (this fraction of the blocks kept) "
                          "in front of the block codec")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph (torch.cuda.CUDAGraph) and time its replays: the same "
+                         "kernels without the per-launch host work, which matters for the small configs")
     ap.add_argument("--per-worker-calls", action="store_true",
                     help="encode with W s2r_encode calls instead of one s2r_encode_batch call")
     ap.add_argument("--insert-strategy", default="auto", choices=["auto", "atomic", "slice"],
@@ -183,14 +186,26 @@ def main():
             b.step(stream, batched)
     torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1) if args.graph else args.warmup):
         step()
     torch.cuda.synchronize()
+    timed_step = step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        eager_stream = stream
+        with torch.cuda.graph(graph):
+            stream = torch.cuda.current_stream()            # the capture stream
+            step()
+        stream = eager_stream
+        timed_step = graph.replay
+        for _ in range(2):
+            timed_step()
+        torch.cuda.synchronize()
     ev0, ev1 = binding.HipEvent(), binding.HipEvent()
     t0 = time.perf_counter()
     ev0.record(stream)
     for _ in range(args.steps):
-        step()
+        timed_step()
     ev1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -307,6 +322,7 @@ def main():
         "algorithmic_frac_of_hbm_peak": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "stream_read_GBs": round(read_ceiling, 1),
         "event_ms_per_step": round(ev_ms / args.steps, 4),
+        "launch": "hip graph replay" if args.graph else "eager",
         "encode_calls": ("s2r_encode_blocks_batch" if batched else "s2r_encode_blocks x W") if args.block > 0
                         else ("s2r_encode_batch" if batched else "s2r_encode x W"),
         "decode_route": "slice" if binding.last_decode_strategy() == binding.S2R_DECODE_SLICE else "gather",

@@ -766,3 +766,43 @@ def test_very_sparse_gradient_with_dense_pockets(strategy):
     assert np.array_equal(b.nz_idx[0].cpu().numpy().view(np.uint32), idx[:cap])
     assert np.array_equal(b.nz_val[0].cpu().numpy(), val[:cap])
     assert (b.nz_idx[0]._base[cap:].cpu().numpy() == -1).all()
+
+
+def test_step_replays_from_a_captured_graph():
+    """The library only enqueues kernels (no allocation, no memset, no host wait), so a
+    caller can capture encode + merge + decode into a HIP graph.  The graph is replayed
+    three times over gradients that change between the replays, with eager work and
+    synchronisations in between; every replay must equal the eager result on the same
+    gradients (bit-exact for bitmaps and lists; the slice routes make the values
+    reproducible too)."""
+    wl = workloads.make_small(3)
+    b = pipeline.buffers_for(wl)
+    binding.set_insert_strategy(binding.S2R_INSERT_SLICE)
+    try:
+        b.step()                                           # warm-up: raises the LDS limits outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            b.step(torch.cuda.current_stream())
+        rng = np.random.default_rng(3)
+        for replay in range(3):
+            for k in range(wl.W):                          # new gradients: scale, and move a few non-zeros
+                b.grads[k].mul_(1.5 + replay)
+                pos = torch.from_numpy(rng.integers(0, wl.n, 50)).cuda()
+                b.grads[k][pos] = float(replay + 1)
+            torch.cuda.synchronize()
+            b.step()                                       # eager reference on the same gradients
+            torch.cuda.synchronize()
+            want = (pipeline.u64(b.bitmap_or).copy(), int(b.out_count.cpu()[0]), b.out_idx.cpu().numpy().copy(),
+                    b.out_val.cpu().numpy().copy(), b.sketch_sum.cpu().numpy().copy())
+            b.out_val.zero_(); b.out_idx.zero_(); b.sketch_sum.zero_(); b.bitmap_or.zero_(); b.out_count.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            cnt = int(b.out_count.cpu()[0])
+            assert cnt == want[1] and np.array_equal(pipeline.u64(b.bitmap_or), want[0]), f"replay {replay}"
+            assert np.array_equal(b.out_idx.cpu().numpy()[:cnt], want[2][:cnt])
+            assert np.allclose(b.sketch_sum.cpu().numpy(), want[4], rtol=1e-5, atol=1e-30)
+            assert np.allclose(b.out_val.cpu().numpy()[:cnt], want[3][:cnt], rtol=1e-4, atol=1e-6)
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
