@@ -1514,10 +1514,13 @@ static int32_t choose_decode(uint64_t n, uint32_t d, uint32_t w, bool have_lists
   return t_slice < t_gather ? S2R_DECODE_SLICE : S2R_DECODE_GATHER;
 }
 
-// The slice kernels use more dynamic LDS than the default limit allows; raised once per host thread.
+// The slice kernels use more dynamic LDS than the default limit allows; raised once per host thread and device.
 static bool raise_lds_limits() {
-  static thread_local bool raised = false;
-  if (raised) return true;
+  constexpr int kMaxDevices = 64;
+  static thread_local bool raised[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) return false;
+  if (dev < kMaxDevices && raised[dev]) return true;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter_kernel),
@@ -1526,7 +1529,7 @@ static bool raise_lds_limits() {
       hipFuncSetAttribute(reinterpret_cast<const void*>(decode_slice_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kDecodeSliceLog2Max)) != hipSuccess)
     return false;
-  raised = true;
+  if (dev < kMaxDevices) raised[dev] = true;
   return true;
 }
 
