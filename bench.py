@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the encode scan kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this file,
 # scaled by what the same counters read for a plain 1 GiB copy (profiles/hbm_traffic_<workload>.txt):
 # (workload, insert strategy, workers per launch) -> bytes.  Other combinations have not been counted.
-MEASURED_SCAN_TRAFFIC = {("cfg5_large_zipf", "atomic", 1): 4.299e9, ("cfg5_large_zipf", "lds_slice", 1): 4.140e9}
+MEASURED_SCAN_TRAFFIC = {("cfg5_large_zipf", "atomic", 1): 4.299e9, ("cfg5_large_zipf", "lds_slice", 1): 4.138e9}
 
 
 def algorithmic_bytes(wl, nnz, union: int) -> float:
