@@ -263,6 +263,18 @@ def decode(S: np.ndarray, bitmap: np.ndarray, n: int, seed: int, dense: bool = F
     return out
 
 
+def decode_update(S: np.ndarray, bitmap: np.ndarray, n: int, seed: int, params: np.ndarray, scale: float) -> np.ndarray:
+    """Decompress straight into a parameter update (Section 1: the aggregated
+    gradient is what updates the model; Algorithm 1 returns the sum, so the caller's
+    scale carries the learning rate and the 1/W): params[i] + scale * g_hat(i) at
+    the indices of the aggregated bitmap, params[i] elsewhere.  float64, one
+    rounding to float32."""
+    out = decode(S, bitmap, n, seed)
+    new = np.ascontiguousarray(params, dtype=np.float32).astype(np.float64)
+    new[out["idx"]] += float(np.float32(scale)) * out["val"]
+    return new.astype(np.float32)
+
+
 def decode_tolerance_mass(M: np.ndarray, idx: np.ndarray, seed: int) -> np.ndarray:
     """max_j M[j, h_j(i)] per index: the scale against which a decoded value's
     float32 error is judged (the median moves by at most the largest per-row

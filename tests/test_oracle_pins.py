@@ -471,3 +471,36 @@ def test_topk_is_a_delta_approximate_compressor_and_loses_nothing():
         total += g
         e = out["residual"]
     assert np.allclose(sent + e, total, rtol=0, atol=1e-4)                       # only float32 roundings of g + e apart
+
+
+# ---------------------------------------------------------------- decode into a parameter update
+def test_decode_update_is_params_plus_scaled_dense_decode():
+    rng = np.random.default_rng(31)
+    n = 3000
+    gs = _tiny_grads(rng, 3, n, 0.05)
+    res = orc.reduce_workers(gs, 3, 256, 4, dense=True)
+    params = rng.normal(0, 1, n).astype(np.float32)
+    for scale in (0.0, 1.0, -0.1 / 3):
+        got = orc.decode_update(res["S"], res["bitmap"], n, 4, params, scale)
+        want = (params.astype(np.float64) + float(np.float32(scale)) * res["dense"]).astype(np.float32)
+        assert np.array_equal(got, want)
+    untouched = np.ones(n, dtype=bool)
+    untouched[res["idx"]] = False
+    assert np.array_equal(orc.decode_update(res["S"], res["bitmap"], n, 4, params, 7.0)[untouched], params[untouched])
+
+
+def test_decode_update_is_an_sgd_step_when_recovery_is_exact():
+    """One worker, a width without collisions: the update equals params - lr * g."""
+    n, d, w = 500, 3, 1 << 16
+    rng = np.random.default_rng(32)
+    g = np.zeros(n, dtype=np.float32)
+    sel = rng.choice(n, 12, replace=False)
+    g[sel] = rng.normal(0, 1, 12).astype(np.float32)
+    params = rng.normal(0, 1, n).astype(np.float32)
+    for seed in range(100):
+        e = orc.encode(g, d, w, seed)
+        if all(len(set(orc.bucket_hash(e["idx"], a, b, w).tolist())) == len(e["idx"]) for a, b, _c, _e in orc.hash_params(seed, d)):
+            got = orc.decode_update(e["S"], e["bitmap"], n, seed, params, -0.25)
+            assert np.array_equal(got, (params.astype(np.float64) - 0.25 * g.astype(np.float64)).astype(np.float32))
+            return
+    raise AssertionError("no collision-free seed")
