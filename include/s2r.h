@@ -324,6 +324,25 @@ s2r_status s2r_topk_blocks_batch(const float* const* grads /* host array */,
                                  void* stream);
 
 /*
+ * s2r_decode that applies the aggregated gradient instead of (or besides)
+ * returning it: params[i] <- params[i] + scale * g_hat(i) (one fused
+ * multiply-add) at every index i of the aggregated bitmap, also at those beyond
+ * the lists' capacity; other entries of params are not touched.  Section 1: the
+ * aggregated gradient is what updates the model; Algorithm 1 returns the sum
+ * over workers, so scale carries the learning rate, its sign and the 1/W.
+ *   params   dev, in/out: n float32, 4-byte aligned.  Required.
+ *   idx_out, val_out, cap, count_out, workspace: as s2r_decode (the lists may be
+ *   NULL).  The bucket reads are gathers (S2R_DECODE_GATHER).
+ */
+s2r_status s2r_decode_update(const float* sketch, const uint64_t* bitmap,
+                             uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                             float* params, float scale,
+                             uint32_t* idx_out, float* val_out, uint64_t cap,
+                             uint64_t* count_out,
+                             void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * How s2r_encode carries out the insertion loops of Algorithm 1
  * (S[j, h_j(i)] += s_j(i) g(i)); the result is the same sketch either way.
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued

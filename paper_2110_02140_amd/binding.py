@@ -55,6 +55,8 @@ SIGNATURES = {
     "s2r_decode": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
                              c_void_p, c_void_p, c_uint64, c_void_p, c_void_p,
                              c_void_p, c_size_t, c_void_p]),
+    "s2r_decode_update": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64, c_void_p, ctypes.c_float,
+                                    c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "s2r_set_kernel_events": (c_int32, [c_int32, c_void_p, c_void_p]),
     "s2r_set_insert_strategy": (c_int32, [c_int32]),
     "s2r_scan_launch_workers": (c_uint32, []),
@@ -262,6 +264,16 @@ def topk_blocks(grad, residual, block, K, sparse_out, kept_bitmap, workspace, st
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_topk_blocks")
+
+
+def decode_update(sketch, bitmap, n, d, w, seed, params, scale, idx_out, val_out, count_out, workspace, stream=None):
+    """s2r_decode_update: params float32[n] updated in place; idx_out / val_out may both be None."""
+    cap = 0 if idx_out is None else idx_out.numel()
+    st = load().s2r_decode_update(_ptr(sketch), _ptr(bitmap), n, d, w, seed, _ptr(params), float(scale), _ptr(idx_out),
+                                  _ptr(val_out), cap, _ptr(count_out), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_decode_update")
 
 
 def set_insert_strategy(strategy: int):

@@ -1080,6 +1080,8 @@ struct DecodeArgs {
   float* val_out;            // may be null
   uint64_t cap;
   float* dense_out;          // may be null
+  float* params;             // may be null; else params[i] += scale * estimate at every union index
+  float scale;
 };
 
 // Median of D values by a fully unrolled exchange network: every output is one
@@ -1161,6 +1163,7 @@ __device__ __forceinline__ void decode_group(const DecodeArgs& A, const HashRows
         A.val_out[pos] = g[u];
       }
       if (A.dense_out != nullptr) A.dense_out[i[u]] = g[u];
+      if (A.params != nullptr) A.params[i[u]] = fmaf(A.scale, g[u], A.params[i[u]]);   // union indices are distinct
     }
   }
 }
@@ -1846,7 +1849,7 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
 static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t block, uint32_t d,
                               uint32_t w, uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap,
                               uint64_t* count_out, float* dense_out, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+                              void* stream, float* params = nullptr, float scale = 0.0f) {
   if (sketch == nullptr || bitmap == nullptr || count_out == nullptr) return S2R_ERR_NULL;
   if ((idx_out == nullptr) != (val_out == nullptr)) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
@@ -1872,11 +1875,12 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, (char*)workspace, (uint64_t)0,
                      (uint64_t)workspace_prefix_off(n), (uint64_t)workspace_dense_off(n), ntiles, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
-  if ((idx_out == nullptr || cap == 0) && dense_out == nullptr) return S2R_OK;   // only the count was asked for
+  if ((idx_out == nullptr || cap == 0) && dense_out == nullptr && params == nullptr) return S2R_OK;   // only the count was asked for
 
   if (cap > n) cap = n;
   const uint64_t cap_items = block != 0 ? cap * block : cap;    // list positions that get a value, at most
-  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr, idx_out ? cap_items : 0,
+  // (an update of parameters, like a dense output, must reach the union indices beyond the lists' capacity too)
+  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr || params != nullptr, idx_out ? cap_items : 0,
                                          workspace_bytes);
   g_last_decode_strategy = strategy;
   if (strategy == S2R_DECODE_SLICE) {
@@ -1972,6 +1976,8 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
   A.val_out = val_out;
   A.cap = idx_out ? cap : 0;
   A.dense_out = dense_out;
+  A.params = params;
+  A.scale = scale;
 
   if (block != 0) {                                        // the block list, then one thread per element of a listed block
     static thread_local EncodeBatch X;
@@ -2053,6 +2059,15 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
                       float* dense_out, void* workspace, size_t workspace_bytes, void* stream) {
   return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, dense_out, workspace,
                      workspace_bytes, stream);
+}
+
+s2r_status s2r_decode_update(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
+                             uint64_t seed, float* params, float scale, uint32_t* idx_out, float* val_out, uint64_t cap,
+                             uint64_t* count_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (params == nullptr) return S2R_ERR_NULL;
+  if (((uintptr_t)params & 3u) != 0) return S2R_ERR_ALIGN;
+  return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, nullptr, workspace,
+                     workspace_bytes, stream, params, scale);
 }
 
 // ---- block-granular codec

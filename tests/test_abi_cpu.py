@@ -189,3 +189,11 @@ def test_topk_argument_checks():
     assert lib.s2r_topk_blocks(0x1000, None, 1000, 0, 5, 0x2000, None, 0x4000, 1 << 20, None) == b.S2R_ERR_SIZE
     assert lib.s2r_topk_blocks(0x1004, None, 1000, 10, 5, 0x2000, None, 0x4000, 1 << 20, None) == b.S2R_ERR_ALIGN
     assert lib.s2r_topk_blocks(0x1000, None, 1000, 10, 5, 0x2000, None, 0x4000, 64, None) == b.S2R_ERR_WORKSPACE
+
+
+def test_decode_update_argument_checks():
+    lib = b.load()
+    args = (0x1000, 0x2000, 1 << 20, 3, 1 << 14, 0)
+    assert lib.s2r_decode_update(*args, None, 1.0, None, None, 0, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_NULL
+    assert lib.s2r_decode_update(*args, 0x3002, 1.0, None, None, 0, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_ALIGN
+    assert lib.s2r_decode_update(*args, 0x3000, 1.0, None, None, 0, 0x4000, None, 1 << 20, None) == b.S2R_ERR_WORKSPACE

@@ -806,3 +806,36 @@ def test_step_replays_from_a_captured_graph():
             assert np.allclose(b.out_val.cpu().numpy()[:cnt], want[3][:cnt], rtol=1e-4, atol=1e-6)
     finally:
         binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+
+
+@pytest.mark.parametrize("lists", [True, False], ids=["with_lists", "update_only"])
+def test_decode_update_matches_oracle(lists):
+    """params += scale * decoded sum, against the oracle, with lists shorter than the
+    union (the update must still reach every union index) and without lists."""
+    wl = workloads.make_small(4)
+    enc, S, C, M, dec = _oracle_for(wl)
+    b = pipeline.buffers_for(wl)
+    b.encode_all()
+    b.merge()
+    rng = np.random.default_rng(17)
+    params0 = rng.normal(0, 1, wl.n).astype(np.float32)
+    params = torch.from_numpy(params0.copy()).cuda()
+    scale = -0.05 / wl.W
+    cap = len(dec["idx"]) // 3
+    idx_out = torch.full((cap,), -1, dtype=torch.int32, device="cuda") if lists else None
+    val_out = torch.zeros(cap, dtype=torch.float32, device="cuda") if lists else None
+    binding.decode_update(b.sketch_sum, b.bitmap_or, wl.n, wl.d, wl.w, wl.seed, params, scale, idx_out, val_out,
+                          b.out_count, b.workspace)
+    torch.cuda.synchronize()
+    assert int(b.out_count.cpu()[0]) == len(dec["idx"])
+    want = orc.decode_update(S, C, wl.n, wl.seed, params0, scale).astype(np.float64)
+    got = params.cpu().numpy().astype(np.float64)
+    tol = np.zeros(wl.n)
+    tol[dec["idx"]] = abs(scale) * (REL * orc.decode_tolerance_mass(M, dec["idx"], wl.seed) + DENORM_SLACK)
+    tol += np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+    untouched = np.ones(wl.n, dtype=bool)
+    untouched[dec["idx"]] = False
+    assert np.array_equal(params.cpu().numpy()[untouched], params0[untouched]), "entries outside the union changed"
+    assert np.all(np.abs(got - want) <= tol), f"worst {np.abs(got - want).max():.3e}"
+    if lists:
+        assert np.array_equal(idx_out.cpu().numpy().view(np.uint32), dec["idx"][:cap])
