@@ -504,3 +504,44 @@ def test_decode_update_is_an_sgd_step_when_recovery_is_exact():
             assert np.array_equal(got, (params.astype(np.float64) - 0.25 * g.astype(np.float64)).astype(np.float32))
             return
     raise AssertionError("no collision-free seed")
+
+
+# ---------------------------------------------------------------- random tiny problems against the pure-Python loops
+def _hyp():
+    import hypothesis
+    from hypothesis import strategies as st
+    return hypothesis, st
+
+
+def test_random_tiny_problems_match_pure_python():
+    """Hypothesis draws (n, d, log2 w, W, B, seed, values); the numpy oracle must agree with
+    the list-and-loop implementation on bitmaps, sketches and decoded values, for the element
+    codec and the block codec alike."""
+    hypothesis, st = _hyp()
+
+    @hypothesis.settings(max_examples=60, deadline=None, derandomize=True)
+    @hypothesis.given(n=st.integers(1, 150), d=st.integers(1, 6), L=st.integers(0, 6), W=st.integers(1, 3),
+                      B=st.integers(1, 40), seed=st.integers(0, 2**64 - 1), data=st.data())
+    def check(n, d, L, W, B, seed, data):
+        w = 1 << L
+        vals = st.sampled_from([0.0, 0.0, 0.0, -0.0, 1.0, -2.5, 0.125, 3.0e-40, 1.0e20])
+        gs = [np.array(data.draw(st.lists(vals, min_size=n, max_size=n)), dtype=np.float32) for _ in range(W)]
+        res = orc.reduce_workers(gs, d, w, seed)
+        flags, Ss = zip(*[bf.compress([float(x) for x in g], d, w, seed) for g in gs])
+        C, S = bf.aggregate(flags, Ss)
+        assert [int(x) for x in res["bitmap"]] == bf.words_of(C)
+        assert np.allclose(res["S"], np.array(S), rtol=1e-15, atol=0)
+        want = bf.decompress(C, S, seed)
+        assert res["idx"].tolist() == sorted(want)
+        for i, v in zip(res["idx"].tolist(), res["val"].tolist()):
+            assert v == pytest.approx(want[i], rel=1e-15, abs=0)
+        blk = orc.reduce_workers_blocks(gs, B, d, w, seed)
+        bflags = [bf.block_flags([float(x) for x in g], B) for g in gs]
+        Cb, _ = bf.aggregate(bflags, Ss)
+        assert [int(x) for x in blk["bitmap"]] == bf.words_of(Cb)
+        wantb = bf.decompress_blocks(Cb, S, n, B, seed)
+        assert blk["blocks"].tolist() == sorted(wantb)
+        for row, x in zip(blk["val"], blk["blocks"].tolist()):
+            assert row.tolist() == pytest.approx(wantb[x], rel=1e-15, abs=0)
+
+    check()
