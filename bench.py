@@ -299,7 +299,7 @@ def main():
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
 
     out = {
-        "metric": "dense-gradient GB/s for encode+merge+decode on 1 MI355X",
+        "metric": "dense-gradient GB/s for encode+merge+decode on 1 MI355X; % of HBM peak",
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
