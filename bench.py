@@ -45,8 +45,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
-                    help="which BASELINE config to time (default: the largest single-GPU one)")
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg1_lds"],
+                    help="which BASELINE config to time (default: the largest single-GPU one); cfg1_lds is "
+                         "config 1 with w = 2^13, the only size whose whole sketch fits one compute unit's LDS")
     ap.add_argument("--block", type=int, default=0,
                     help="use the block-granular codec with blocks of this many elements (0: one bitmap bit per "
                          "element); the natural sizes are 650 for cfg2 and 256 for cfg3")
@@ -152,9 +153,9 @@ def main():
     binding.set_insert_strategy({"auto": binding.S2R_INSERT_AUTO, "atomic": binding.S2R_INSERT_ATOMIC,
                                  "slice": binding.S2R_INSERT_SLICE}[args.insert_strategy])
 
-    cfg = int(args.workload[3:])
+    cfg = int(args.workload[3])
     t_gen = time.perf_counter()
-    wl = workloads.make(cfg)
+    wl = workloads.make_cfg1_lds() if args.workload == "cfg1_lds" else workloads.make(cfg)
     t_gen = time.perf_counter() - t_gen
     topk = args.topk_frac > 0
     if topk and args.block <= 0:

@@ -204,6 +204,15 @@ def make(cfg: int) -> Workload:
     return _FULL[cfg]()
 
 
+def make_cfg1_lds() -> Workload:
+    """Recipe 1 with a sketch of 3 x 2^13 cells (96 KB): the one size at which a
+    whole sketch fits the LDS of a compute unit.  None of the five recipes does;
+    this one exercises the codec where the sketch is two LDS slices."""
+    wl = cfg1(w=1 << 13)
+    wl.name = "cfg1_uniform_1pct_w8192"
+    return wl
+
+
 def make_small(cfg: int) -> Workload:
     """A reduced copy of recipe cfg with the same structure (ragged length, rows
     straddling bitmap words, shared and private blocks, Zipf overlap) at a size a

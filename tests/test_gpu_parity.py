@@ -103,6 +103,12 @@ def test_recipe1_full_size(strategy):
     _run_and_check(workloads.make(1), dense_out=True)
 
 
+def test_recipe1_with_lds_sized_sketch(strategy, decode_strategy):
+    """Recipe 1 with a 96 KB sketch (w = 2^13): the size at which the sketch is
+    two LDS slices; heavy collisions (41 000 union items in 8192 columns)."""
+    _run_and_check(workloads.make_cfg1_lds(), dense_out=False)
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 4])
 def test_full_size_recipes_match_oracle(cfg, strategy):
     _run_and_check(workloads.make(cfg), batched=(cfg != 3))
