@@ -380,3 +380,21 @@ def topk_blocks(g: np.ndarray, e, B: int, K: int) -> dict:
     sparse = np.where(elem, acc, np.float32(0.0)).astype(np.float32)
     resid = np.where(elem, np.float32(0.0), acc).astype(np.float32)
     return {"blocks": kept, "sparse": sparse, "residual": resid, "score": score, "acc": acc}
+
+
+def topk_encode_blocks(g: np.ndarray, e, B: int, K: int, d: int, w: int, seed: int) -> dict:
+    """Sparsify, then compress, as one step (Section 2.2 feeding Algorithm 1's
+    compress lines): the K blocks that topk_blocks keeps are the blocks that are
+    communicated, so the bitmap marks exactly the kept blocks (a kept block whose
+    elements are all zero is still marked: the sparsifier chose it, the codec does
+    not look again) and the sketch receives the non-zero elements of acc = g + e
+    in those blocks.  Returns the bitmap, the kept blocks, the sketch with its
+    absolute-mass companion, and the new residual."""
+    tk = topk_blocks(g, e, B, K)
+    nb = tk["score"].shape[0]
+    flags = np.zeros(nb, dtype=bool)
+    flags[tk["blocks"]] = True
+    idx, val = sparse_of(tk["sparse"])
+    S, M = insert(idx, val, d, w, seed)
+    return {"bitmap": pack_bitmap(flags), "blocks": tk["blocks"], "S": S, "M": M, "residual": tk["residual"],
+            "sparse": tk["sparse"]}

@@ -162,3 +162,44 @@ def block_buffers_for(wl, block: int, device="cuda:0", slack: int = 0) -> BlockB
 def u64(t: torch.Tensor) -> np.ndarray:
     """Device int64 words -> host uint64 array."""
     return t.cpu().numpy().view(np.uint64)
+
+
+class SparsifiedStep:
+    """One data-parallel parameter update of W simulated workers, start to end in
+    the library's kernels (Algorithm 1 with the block-wise Top-K sparsifier and
+    the error-feedback residual of Section 2.2 / Appendix A.2 in front of it):
+
+        dense gradients g_k  ->  s2r_topk_blocks_batch   acc_k = g_k + e_k, keep K blocks, e_k <- rest
+                             ->  s2r_encode_batch        bitmap C_k, sketch S_k of the kept elements
+                             ->  s2r_merge               S = sum_k S_k, C = OR_k C_k  (stands in for AllReduce)
+                             ->  s2r_decode_update       params[i] += scale * median_j(...) at every bit of C
+
+    The caller owns the gradients and the parameters (float32[n] device tensors);
+    this object owns the residuals and every intermediate buffer.
+    """
+
+    def __init__(self, W: int, n: int, block: int, K: int, d: int, w: int, seed: int = 0, device="cuda:0"):
+        nb = (n + block - 1) // block
+        if not 0 < K <= nb:
+            raise ValueError("K must be in 1..number of blocks")
+        self.block, self.K = block, K
+        cap = min(n, K * block)
+        self.codec = Buffers(W, n, d, w, seed, cap, 1, device)
+        dev = self.codec.device
+        self.residual = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(W)]
+        self.codec.grads = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(W)]    # sparsified gradients
+        self.topk_ws = torch.empty(binding.topk_workspace_bytes(n, block) * W, dtype=torch.uint8, device=dev)
+
+    @property
+    def sparse(self):
+        return self.codec.grads
+
+    def step(self, grads, params, scale: float, stream=None):
+        """params += scale * (estimate of the sum over workers of their sparsified
+        gradients); scale is typically -learning_rate / W."""
+        c = self.codec
+        binding.topk_blocks_batch(grads, self.residual, c.n, self.block, self.K, c.grads, None, self.topk_ws, stream)
+        c.encode_all(stream)
+        c.merge(stream)
+        binding.decode_update(c.sketch_sum, c.bitmap_or, c.n, c.d, c.w, c.seed, params, scale, None, None,
+                              c.out_count, c.workspace, stream)

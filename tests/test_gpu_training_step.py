@@ -1,0 +1,121 @@
+"""The whole chain in use: dense gradients -> block-wise Top-K with error feedback
+(Section 2.2, Appendix A.2) -> encode -> merge -> decode fused with the parameter
+update (Algorithm 1), on a synthetic least-squares problem split over W simulated
+workers.
+
+Two checks.  (1) Parity, step by step: before every step the device state
+(gradients, residuals, parameters) is downloaded and the oracle's own chain is run
+from it on the CPU; residuals must agree bit for bit and the parameters within the
+decode tolerance.  (2) The behaviour the method exists for: with a sketch wide
+enough for the union, sparsified training with residuals reaches a loss close to
+that of dense gradient descent with the same step size, and a far narrower sketch
+(heavy collisions) still descends (the estimation errors act like
+gradient noise).
+
+The gradients themselves come from torch matmuls: they are the model's side of
+the loop, an input to the path under test.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import s2r_oracle as orc
+from paper_2110_02140_amd import binding, pipeline
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-5
+DENORM_SLACK = 64 * float(np.finfo(np.float32).tiny)
+
+
+class LeastSquares:
+    """Worker k holds (A_k, b_k); loss = mean_k |A_k x - b_k|^2 / (2 m)."""
+
+    def __init__(self, W, n, m, seed):
+        gen = torch.Generator().manual_seed(seed)
+        self.W, self.n, self.m = W, n, m
+        x_true = torch.randn(n, generator=gen)
+        # column scales spread over two decades: some blocks of the gradient matter far more than others
+        scale = torch.logspace(-1, 1, n)[torch.randperm(n, generator=gen)]
+        self.A = [(torch.randn(m, n, generator=gen) * scale / np.sqrt(n)).cuda() for _ in range(W)]
+        self.b = [(a @ x_true.cuda()) for a in self.A]
+
+    def grads(self, x):
+        return [(a.t() @ (a @ x - b) / self.m).contiguous() for a, b in zip(self.A, self.b)]
+
+    def loss(self, x):
+        return float(sum(((a @ x - b) ** 2).sum() for a, b in zip(self.A, self.b)) / (2 * self.m * self.W))
+
+
+def _oracle_step(gs, es, params, B, K, d, w, seed, scale):
+    tk = [orc.topk_blocks(g, e, B, K) for g, e in zip(gs, es)]
+    enc = [orc.encode(t["sparse"], d, w, seed) for t in tk]
+    S, C = orc.merge([e["S"] for e in enc], [e["bitmap"] for e in enc])
+    M = np.sum([e["M"] for e in enc], axis=0)
+    union = orc.bitmap_indices(C, params.shape[0])
+    new = orc.decode_update(S, C, params.shape[0], seed, params, scale)
+    return tk, union, M, new
+
+
+def test_training_steps_match_the_oracle_chain():
+    W, n, m, B, K, d, w, seed = 3, 32768 + 40, 48, 64, 24, 3, 1 << 12, 5      # ragged last block; w below the union: collisions
+    prob = LeastSquares(W, n, m, seed=3)
+    st = pipeline.SparsifiedStep(W, n, B, K, d, w, seed)
+    x = torch.zeros(n, dtype=torch.float32, device="cuda")
+    scale = -0.5 / W
+    for it in range(4):
+        print(f"[case] training step {it}", flush=True)
+        grads = prob.grads(x)
+        gs = [g.cpu().numpy() for g in grads]
+        es = [e.cpu().numpy().copy() for e in st.residual]
+        x0 = x.cpu().numpy().copy()
+        st.step(grads, x, scale)
+        torch.cuda.synchronize()
+        tk, union, M, want = _oracle_step(gs, es, x0, B, K, d, w, seed, scale)
+        for k in range(W):
+            assert np.array_equal(st.residual[k].cpu().numpy().view(np.uint32), tk[k]["residual"].view(np.uint32)), \
+                f"step {it}: residual of worker {k}"
+            assert np.array_equal(st.sparse[k].cpu().numpy().view(np.uint32), tk[k]["sparse"].view(np.uint32)), \
+                f"step {it}: sparsified gradient of worker {k}"
+        assert int(st.codec.out_count.cpu()[0]) == len(union)
+        got = x.cpu().numpy()
+        tol = np.zeros(n)
+        tol[union] = abs(scale) * (REL * orc.decode_tolerance_mass(M, union, seed) + DENORM_SLACK)
+        tol += np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+        untouched = np.ones(n, dtype=bool)
+        untouched[union] = False
+        assert np.array_equal(got[untouched], x0[untouched]), f"step {it}: parameters outside the union changed"
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        assert np.all(err <= tol), f"step {it}: worst parameter error {err.max():.3e}"
+        if it == 0:
+            assert not any(e.any() for e in es) and all(r.any() for r in st.residual), "residuals start at zero and fill up"
+
+
+def _train(prob, steps, lr, sparsifier=None):
+    x = torch.zeros(prob.n, dtype=torch.float32, device="cuda")
+    for _ in range(steps):
+        grads = prob.grads(x)
+        if sparsifier is None:
+            x -= lr / prob.W * sum(grads)
+        else:
+            sparsifier.step(grads, x, -lr / prob.W)
+    torch.cuda.synchronize()
+    return prob.loss(x)
+
+
+def test_sparsified_training_with_residuals_descends_like_dense_training():
+    W, n, m, B = 4, 1 << 16, 64, 256
+    nb = n // B
+    K = nb // 8                                   # each worker sends 1/8 of its blocks
+    prob = LeastSquares(W, n, m, seed=11)
+    lr, steps = 0.5, 150
+    start = prob.loss(torch.zeros(n, device="cuda"))
+    dense = _train(prob, steps, lr)
+    wide = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 17))     # lambda = w / union >= 4 per row
+    narrow = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 13))   # lambda <= 1: many collisions
+    print(f"[loss] start {start:.4e} dense {dense:.4e} sparsified(wide sketch) {wide:.4e} (narrow) {narrow:.4e}", flush=True)
+    assert dense < 0.05 * start
+    assert wide < 0.15 * start, "Top-K with residuals and a roomy sketch must follow dense training"
+    assert wide < 6 * dense
+    assert narrow < 0.5 * start, "a sketch far below the union still descends"

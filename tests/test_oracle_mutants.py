@@ -37,6 +37,9 @@ def _some_pin_fails():
         (pins.test_topk_blocks_matches_pure_python, (16, 13)),
         (pins.test_topk_ties_go_to_the_lower_block_and_extremes, ()),
         (pins.test_topk_is_a_delta_approximate_compressor_and_loses_nothing, ()),
+        (pins.test_topk_encode_blocks_matches_pure_python, (4, 3)),
+        (pins.test_topk_encode_blocks_is_topk_then_encode_blocks_unless_a_kept_block_is_zero, ()),
+        (pins.test_topk_encode_blocks_round_trip_without_collisions_returns_acc_in_the_kept_blocks, ()),
     ]
     return any(_fails(fn, *a) for fn, a in checks)
 
@@ -184,6 +187,37 @@ def _mut_topk_residual_forgets_old_error(monkeypatch):
     monkeypatch.setattr(orc, "topk_blocks", lambda g, e, B, K: real(g, None, B, K))
 
 
+def _mut_fused_step_marks_only_nonzero_blocks(monkeypatch):
+    real = orc.topk_encode_blocks
+    def bad(g, e, B, K, d, w, seed):
+        out = real(g, e, B, K, d, w, seed)
+        out["bitmap"] = orc.pack_bitmap(orc.block_mask(out["sparse"], B))        # looks at the values again
+        return out
+    monkeypatch.setattr(orc, "topk_encode_blocks", bad)
+
+
+def _mut_fused_step_sketches_the_gradient_without_the_residual(monkeypatch):
+    real = orc.topk_encode_blocks
+    def bad(g, e, B, K, d, w, seed):
+        out = real(g, e, B, K, d, w, seed)
+        elems = orc.block_elements(out["blocks"], B, len(g))
+        only_g = np.zeros(len(g), dtype=np.float32)
+        only_g[elems] = np.asarray(g, dtype=np.float32)[elems]
+        idx, val = orc.sparse_of(only_g)
+        out["S"], out["M"] = orc.insert(idx, val, d, w, seed)
+        return out
+    monkeypatch.setattr(orc, "topk_encode_blocks", bad)
+
+
+def _mut_fused_step_keeps_the_residual_of_sent_blocks(monkeypatch):
+    real = orc.topk_encode_blocks
+    def bad(g, e, B, K, d, w, seed):
+        out = real(g, e, B, K, d, w, seed)
+        out["residual"] = (out["residual"] + out["sparse"]).astype(np.float32)   # sent blocks not cleared
+        return out
+    monkeypatch.setattr(orc, "topk_encode_blocks", bad)
+
+
 @pytest.mark.parametrize("mutant", [
     _mut_sign_dropped_in_query, _mut_msb_first_bitmap, _mut_median_off_by_one,
     _mut_low_bits_bucket, _mut_sign_uses_bucket_multiplier, _mut_merge_xor,
@@ -191,6 +225,8 @@ def _mut_topk_residual_forgets_old_error(monkeypatch):
     _mut_insert_assign_not_accumulate,
     _mut_block_needs_all_elements, _mut_block_boundary_shifted, _mut_block_decode_skips_zero_elements,
     _mut_topk_scores_by_abs_sum, _mut_topk_keeps_smallest, _mut_topk_residual_forgets_old_error,
+    _mut_fused_step_marks_only_nonzero_blocks, _mut_fused_step_sketches_the_gradient_without_the_residual,
+    _mut_fused_step_keeps_the_residual_of_sent_blocks,
 ], ids=lambda f: f.__name__)
 def test_planted_mistake_is_caught(monkeypatch, mutant):
     mutant(monkeypatch)

@@ -545,3 +545,74 @@ def test_random_tiny_problems_match_pure_python():
             assert row.tolist() == pytest.approx(wantb[x], rel=1e-15, abs=0)
 
     check()
+
+
+# ---------------------------------------------------------------- Top-K and compress as one step
+def _topk_encode_pure_python(g, e, B, K, d, w, seed):
+    """Brute force from the definitions: kept blocks by the pure-Python Top-K, flags
+    of exactly those, and the mapping S[j][h_j(i)] += s_j(i) acc[i] over their elements."""
+    from tests import bruteforce as bf
+    kept, sparse, resid = _topk_pure_python(g, e, B, K)
+    nb = (len(g) + B - 1) // B
+    flags = [1 if x in set(kept) else 0 for x in range(nb)]
+    _C, S = bf.compress(sparse, d, w, seed)
+    return flags, kept, S, resid
+
+
+@pytest.mark.parametrize("B,K", [(4, 3), (16, 5), (50, 2), (7, 40)])
+def test_topk_encode_blocks_matches_pure_python(B, K):
+    from tests import bruteforce as bf
+    rng = np.random.default_rng(B * 17 + K)
+    n, d, w, seed = 203, 3, 32, 9
+    g = rng.normal(0, 1, n).astype(np.float32)
+    e = (rng.normal(0, 0.3, n) * (rng.random(n) < 0.5)).astype(np.float32)
+    K = min(K, (n + B - 1) // B)
+    out = orc.topk_encode_blocks(g, e, B, K, d, w, seed)
+    flags, kept, S, resid = _topk_encode_pure_python(g.tolist(), e.tolist(), B, K, d, w, seed)
+    assert out["blocks"].tolist() == kept
+    assert out["bitmap"].tolist() == bf.words_of(flags)
+    assert np.allclose(out["S"], np.array(S), rtol=0, atol=1e-12)
+    assert out["residual"].tolist() == resid
+
+
+def test_topk_encode_blocks_is_topk_then_encode_blocks_unless_a_kept_block_is_zero():
+    rng = np.random.default_rng(77)
+    n, B, d, w, seed = 1000, 8, 3, 64, 2
+    g = rng.normal(0, 1, n).astype(np.float32)
+    e = rng.normal(0, 0.1, n).astype(np.float32)
+    one = orc.topk_encode_blocks(g, e, B, 20, d, w, seed)
+    tk = orc.topk_blocks(g, e, B, 20)
+    two = orc.encode_blocks(tk["sparse"], B, d, w, seed)
+    assert np.array_equal(one["bitmap"], two["bitmap"]) and np.array_equal(one["S"], two["S"])
+    assert np.array_equal(one["blocks"], two["blocks"]) and np.array_equal(one["residual"], tk["residual"])
+    # only 3 blocks hold anything, K = 6: the three zero blocks of lowest index are kept and marked too
+    g = np.zeros(n, dtype=np.float32)
+    g[[8 * 10, 8 * 50 + 3, 8 * 90 + 7]] = [1.0, -2.0, 0.5]
+    one = orc.topk_encode_blocks(g, None, B, 6, d, w, seed)
+    two = orc.encode_blocks(g, B, d, w, seed)
+    assert one["blocks"].tolist() == [0, 1, 2, 10, 50, 90] and two["blocks"].tolist() == [10, 50, 90]
+    assert int(sum(bin(int(x)).count("1") for x in one["bitmap"])) == 6
+    assert np.array_equal(one["S"], two["S"]), "zero elements are inert in the sketch"
+    dec = orc.decode_blocks(one["S"], one["bitmap"], n, B, seed)
+    assert dec["blocks"].tolist() == [0, 1, 2, 10, 50, 90]
+
+
+def test_topk_encode_blocks_round_trip_without_collisions_returns_acc_in_the_kept_blocks():
+    rng = np.random.default_rng(3)
+    n, B, K, d = 640, 16, 5, 3
+    g = rng.normal(0, 1, n).astype(np.float32)
+    e = rng.normal(0, 0.2, n).astype(np.float32)
+    for seed in range(200):
+        out = orc.topk_encode_blocks(g, e, B, K, d, 1 << 16, seed)
+        elems = orc.block_elements(out["blocks"], B, n).astype(np.uint32)
+        if all(len(set(orc.bucket_hash(elems, a, b, 1 << 16).tolist())) == len(elems)
+               for a, b, _c, _e in orc.hash_params(seed, d)):
+            dec = orc.decode_blocks(out["S"], out["bitmap"], n, B, seed)
+            acc = (g + e).astype(np.float32)
+            assert np.array_equal(dec["val"].reshape(-1), acc[elems].astype(np.float64))
+            assert not out["residual"][elems].any()
+            rest = np.ones(n, dtype=bool)
+            rest[elems] = False
+            assert np.array_equal(out["residual"][rest], acc[rest])
+            return
+    raise AssertionError("no collision-free seed found: widen the sketch")
