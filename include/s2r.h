@@ -12,7 +12,7 @@
  *                at each, the median over rows of s_j(i) * S[j, h_j(i)]
  * and, around it, the paper's block-granular bitmap (s2r_encode_blocks,
  * s2r_decode_blocks) and its block-wise Top-K sparsifier with error feedback
- * (s2r_topk_blocks).
+ * (s2r_topk_blocks; s2r_topk_encode_blocks_batch fuses it with the compress step).
  *
  * Notation.  n = gradient length (the paper's d in Section 3.1), d = sketch rows
  * (the paper's r), w = sketch columns (the paper's c, m in Section 3.1), W =
@@ -322,6 +322,46 @@ s2r_status s2r_topk_blocks_batch(const float* const* grads /* host array */,
                                  uint64_t* const* kept_bitmaps /* host array or NULL */,
                                  void* workspace, size_t workspace_bytes,
                                  void* stream);
+
+/*
+ * The sparsifier and the compress step as one call, for W workers: what
+ * s2r_topk_blocks_batch followed by s2r_encode_blocks_batch computes, without
+ * the sparse gradient in between (Section 2.2 feeding the compress lines of
+ * Algorithm 1; Section 3.1: the bitmap has one bit per gradient block).
+ *
+ *   acc, score, kept  as for s2r_topk_blocks
+ *   block_bitmaps[k]  bit x set iff block x of worker k is kept -- the blocks the
+ *                     sparsifier chose ARE the communicated blocks; a kept block
+ *                     whose elements are all zero is still marked (it differs
+ *                     from s2r_encode_blocks of the sparse gradient only there)
+ *   blk_idx[k]        the kept blocks, ascending, at most blk_cap; nblk_out[k] =
+ *                     min(K, ceil(n / block))
+ *   sketches[k]       the count-sketch of the non-zero elements of acc in the kept
+ *                     blocks, complete whatever blk_cap is
+ *   residuals[k]      updated in place: +0.0 in kept blocks, acc elsewhere
+ *
+ * residuals may be NULL as a whole (plain Top-K: acc = grad, nothing is written
+ * besides the outputs).  Otherwise residuals[k] must not overlap grads[k]; while
+ * the call's kernels run it holds acc everywhere.  Every element is read once
+ * (grad and residual) and the residual written once: 12 bytes per element
+ * against 28 for the two calls.  Pointers, alignment, limits and the float64
+ * summation order as for s2r_topk_blocks and s2r_encode_blocks_batch; workspace:
+ * W * s2r_topk_encode_blocks_workspace_bytes(n, block, d, w, blk_cap), 256-byte
+ * aligned.  Enqueues on stream and returns; errors as for s2r_encode.
+ */
+size_t s2r_topk_encode_blocks_workspace_bytes(uint64_t n, uint32_t block,
+                                              uint32_t d, uint32_t w, uint64_t blk_cap);
+
+s2r_status s2r_topk_encode_blocks_batch(const float* const* grads /* host array */,
+                                        float* const* residuals /* host array or NULL */, uint32_t W,
+                                        uint64_t n, uint32_t block, uint64_t K,
+                                        uint32_t d, uint32_t w, uint64_t seed,
+                                        float* const* sketches /* host array */,
+                                        uint64_t* const* block_bitmaps /* host array */,
+                                        uint32_t* const* blk_idx /* host array or NULL */, uint64_t blk_cap,
+                                        uint64_t* nblk_out /* dev, W entries */,
+                                        void* workspace, size_t workspace_bytes,
+                                        void* stream);
 
 /*
  * s2r_decode that applies the aggregated gradient instead of (or besides)

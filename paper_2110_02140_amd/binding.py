@@ -79,6 +79,12 @@ SIGNATURES = {
     "s2r_topk_blocks_batch": (c_int32, [ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32,
                                         c_uint64, ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
                                         c_void_p, c_size_t, c_void_p]),
+    "s2r_topk_encode_blocks_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint32, c_uint64]),
+    "s2r_topk_encode_blocks_batch": (c_int32, [ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p), c_uint32, c_uint64,
+                                               c_uint32, c_uint64, c_uint32, c_uint32, c_uint64,
+                                               ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
+                                               ctypes.POINTER(c_void_p), c_uint64, c_void_p, c_void_p, c_size_t,
+                                               c_void_p]),
     "s2r_decode_blocks": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
                                     c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
@@ -255,6 +261,23 @@ def topk_blocks_batch(grads, residuals, n, block, K, sparse_out, kept_bitmaps, w
                                       workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_topk_blocks_batch")
+
+
+def topk_encode_blocks_workspace_bytes(n: int, block: int, d: int, w: int, blk_cap: int) -> int:
+    return load().s2r_topk_encode_blocks_workspace_bytes(n, block, d, w, blk_cap)
+
+
+def topk_encode_blocks_batch(grads, residuals, n, block, K, d, w, seed, sketches, block_bitmaps, blk_idx, nblk_out,
+                             workspace, stream=None):
+    """s2r_topk_encode_blocks_batch: lists of W device tensors; residuals / blk_idx lists or None."""
+    cap = 0 if blk_idx is None else min(t.numel() for t in blk_idx)
+    st = load().s2r_topk_encode_blocks_batch(_ptr_array(grads), None if residuals is None else _ptr_array(residuals),
+                                             len(grads), n, block, K, d, w, seed, _ptr_array(sketches),
+                                             _ptr_array(block_bitmaps), None if blk_idx is None else _ptr_array(blk_idx),
+                                             cap, _ptr(nblk_out), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_topk_encode_blocks_batch")
 
 
 def topk_blocks(grad, residual, block, K, sparse_out, kept_bitmap, workspace, stream=None, n=None):

@@ -1,0 +1,25 @@
+// Calls between the library's translation units; not part of the C ABI.
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/s2r.h"
+
+namespace s2r {
+
+// The block-granular compress step (Algorithm 1) of W workers whose block bitmaps
+// are already filled in on the device: bit x of block_bitmaps[k] set for every block
+// that is communicated, bits at and beyond ceil(n / block) clear.  Lists the set
+// blocks in blk_idx (ascending, at most cap; may be NULL), counts them in nblk_out
+// and forms the sketches from the non-zero elements of values[k] inside the set
+// blocks; values[k] is not read anywhere else.  Arguments, workspace size
+// (s2r_encode_blocks_workspace_bytes per worker) and errors as for
+// s2r_encode_blocks_batch.
+__attribute__((visibility("hidden")))
+s2r_status encode_marked_blocks(const float* const* values, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
+                                uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* block_bitmaps,
+                                uint32_t* const* blk_idx, uint64_t cap, uint64_t* nblk_out, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+}  // namespace s2r

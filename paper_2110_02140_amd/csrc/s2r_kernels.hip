@@ -46,6 +46,7 @@
 
 #include "../../include/s2r.h"
 #include "s2r_device.h"
+#include "s2r_internal.h"
 
 namespace s2r {
 
@@ -1652,9 +1653,10 @@ s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
 static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
                                  uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
                                  uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
-                                 void* workspace, size_t workspace_bytes, hipStream_t st) {
+                                 void* workspace, size_t workspace_bytes, hipStream_t st, bool marked = false) {
+  // marked: the (block) bitmaps are given; there is no scan, and grads[k] is read inside the set blocks only
   if (grads == nullptr || sketches == nullptr || bitmaps == nullptr || nnz_out == nullptr) return S2R_ERR_NULL;
-  if (W == 0 || W > S2R_MAX_WORKERS) return S2R_ERR_SIZE;
+  if (W == 0 || W > S2R_MAX_WORKERS || (marked && block == 0)) return S2R_ERR_SIZE;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
   const bool lists = nz_idx != nullptr && nz_idx[0] != nullptr;
@@ -1728,7 +1730,12 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   // element codec: every piece of every tile gets its count; block codec: the pieces that hold elements
   const uint32_t scan_blocks = block != 0 ? (uint32_t)ceil_div(ceil_div(n, 64), kScanWords) : ntiles * kScansPerTile;
   uint32_t last_group = 0;
-  for (uint32_t k0 = 0; k0 < W; k0 += group) {
+  if (marked && atomics) {                                    // the sketches only: the bitmaps are the caller's
+    E.first_worker = 0;
+    hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, W), dim3(kBlock), 0, st, E, nvec, ntail, (uint64_t)0);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+  for (uint32_t k0 = 0; k0 < W && !marked; k0 += group) {
     const uint32_t gy = W - k0 < group ? W - k0 : group;      // workers k0 .. k0 + gy - 1, all < W
     const bool last = k0 + gy == W;                           // the events bracket the last scan launch
     E.first_worker = k0;
@@ -1787,6 +1794,12 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
     if (!launch_ok()) return S2R_ERR_LAUNCH;
 
     hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), W), dim3(kBlock), 0, st, E, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  } else if (marked) {
+    // no scan has inserted anything: every set block goes the way of the blocks beyond the lists
+    EncodeBatch A = E;
+    A.cap = 0;
+    hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), W), dim3(kBlock), 0, st, A, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
   return S2R_OK;
@@ -2108,6 +2121,19 @@ s2r_status s2r_encode_blocks(const float* grad, uint64_t n, uint32_t block, uint
   return encode_workers(&grad, 1, n, block, d, w, seed, &sketch, &block_bitmap, blk_idx ? &blk_idx : nullptr, nullptr,
                         blk_cap, nblk_out, workspace, workspace_bytes, (hipStream_t)stream);
 }
+
+}  // extern "C"
+
+s2r_status s2r::encode_marked_blocks(const float* const* values, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
+                                     uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* block_bitmaps,
+                                     uint32_t* const* blk_idx, uint64_t cap, uint64_t* nblk_out, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  return encode_workers(values, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, nullptr, cap, nblk_out,
+                        workspace, workspace_bytes, (hipStream_t)stream, true);
+}
+
+extern "C" {
 
 s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block, uint32_t d,
                              uint32_t w, uint64_t seed, uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,

@@ -23,6 +23,7 @@
 
 #include "../../include/s2r.h"
 #include "s2r_device.h"
+#include "s2r_internal.h"
 
 namespace s2r_topk {
 using s2r::kWave;
@@ -84,6 +85,9 @@ __device__ __forceinline__ uint64_t make_key(double sum_sq, uint64_t x) {
 
 // One wave per block (blocks of 32 elements and more) or one thread per block.
 // Workgroup 0 of every worker also resets the histogram and the selection state.
+// STORE: acc = g + e is also written back over e (the caller wants the residual
+// updated in place and reads acc from there afterwards); needs a residual.
+template <bool STORE>
 __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
@@ -119,6 +123,17 @@ __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
           if (in && P.residual != nullptr) a[q][u] += __builtin_nontemporal_load(&P.residual[i]);
         }
       }
+      if (STORE) {
+#pragma unroll
+        for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+          for (int u = 0; u < kScoreLoads; ++u) {
+            const uint64_t i = (x0 + q) * B.block + o + (uint64_t)u * kWave;
+            const bool in = x0 + q < B.nb && o + u * kWave < B.block && i < B.n;
+            if (in) P.residual[i] = a[q][u];
+          }
+        }
+      }
 #pragma unroll
       for (int q = 0; q < kScorePer; ++q) {
 #pragma unroll
@@ -140,6 +155,7 @@ __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
       if (i >= B.n) break;
       float a = P.grad[i];
       if (P.residual != nullptr) a += P.residual[i];
+      if (STORE) P.residual[i] = a;
       sum += (double)a * (double)a;
     }
     keys[x] = make_key(sum, x);
@@ -281,12 +297,97 @@ __global__ __launch_bounds__(kBlock) void topk_bitmap_kernel(const TopkBatch B, 
   B.w[k].kept_bitmap[wd] = bits;
 }
 
+// One wave per block: the residual of a kept block becomes +0.0 (the block has
+// been sent).  Blocks of fewer than 32 elements: one thread per block.
+__global__ __launch_bounds__(kBlock) void topk_clear_kept_kernel(const TopkBatch B, uint32_t all, uint32_t none) {
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers || B.w[k].residual == nullptr) return;
+  float* __restrict__ e = B.w[k].residual;
+  const uint64_t* __restrict__ keys = ws_keys(B, k);
+  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
+  if (B.block >= 32u) {
+    const uint64_t x = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (x >= B.nb || keys[x] < T) return;                  // uniform over the wave
+    const uint64_t i0 = x * B.block;
+    for (uint32_t o = threadIdx.x & (kWave - 1); o < B.block && i0 + o < B.n; o += kWave) e[i0 + o] = 0.0f;
+  } else {
+    const uint64_t x = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (x >= B.nb || keys[x] < T) return;
+    for (uint32_t o = 0; o < B.block && x * B.block + o < B.n; ++o) e[x * B.block + o] = 0.0f;
+  }
+}
+
 static inline size_t keys_bytes(uint64_t nb) { return align256((size_t)nb * sizeof(uint64_t)); }
 static inline size_t workspace_each(uint64_t nb) { return keys_bytes(nb) + align256(kBins * sizeof(uint32_t)) + 256; }
 static inline bool sizes_ok(uint64_t n, uint32_t block) {
   return n >= 1 && n <= (1ull << 32) && block >= 1 && (uint64_t)block <= (1ull << 31);
 }
 static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+// Fills B for W workers and checks the arguments that every entry point shares.
+static s2r_status fill_batch(TopkBatch& B, const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
+                             uint32_t block, uint64_t K, float* const* sparse_out, uint64_t* const* kept_bitmaps,
+                             void* workspace, size_t workspace_bytes) {
+  if (grads == nullptr) return S2R_ERR_NULL;
+  if (W == 0 || W > S2R_MAX_WORKERS || !sizes_ok(n, block)) return S2R_ERR_SIZE;
+  const uint64_t nb = ceil_div(n, block);
+  for (uint32_t k = 0; k < W; ++k) {
+    float* ek = residuals ? residuals[k] : nullptr;
+    float* sk = sparse_out ? sparse_out[k] : nullptr;
+    uint64_t* bk = kept_bitmaps ? kept_bitmaps[k] : nullptr;
+    if (grads[k] == nullptr || (sparse_out && sk == nullptr) || (residuals && ek == nullptr) ||
+        (kept_bitmaps && bk == nullptr))
+      return S2R_ERR_NULL;
+    if (((uintptr_t)grads[k] & 15u) || ((uintptr_t)sk & 15u) || ((uintptr_t)ek & 15u) || ((uintptr_t)bk & 7u))
+      return S2R_ERR_ALIGN;
+    B.w[k].grad = grads[k];
+    B.w[k].residual = ek;
+    B.w[k].sparse = sk;
+    B.w[k].kept_bitmap = bk;
+  }
+  const size_t ws_each = (workspace_bytes / W) & ~(size_t)255;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_each(nb)) return S2R_ERR_WORKSPACE;
+  B.workspace = reinterpret_cast<char*>(workspace);
+  B.ws_stride = ws_each;
+  B.hist_off = keys_bytes(nb);
+  B.state_off = B.hist_off + align256(kBins * sizeof(uint32_t));
+  B.n = n;
+  B.nb = nb;
+  B.K = K > nb ? nb : K;
+  B.block = block;
+  B.nworkers = W;
+  return S2R_OK;
+}
+
+// Scores (with acc written over the residuals if store_acc) and the radix select
+// of the K-th largest key; afterwards block x is kept iff keys[x] >= state.prefix.
+static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream_t st) {
+  const uint32_t W = B.nworkers;
+  const uint64_t score_blocks =
+      B.block >= 32u ? ceil_div(B.nb, (uint64_t)kWavesPerBlock * kScorePer) : ceil_div(B.nb, kBlock);
+  if (store_acc)
+    hipLaunchKernelGGL(topk_score_kernel<true>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
+  else
+    hipLaunchKernelGGL(topk_score_kernel<false>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+  if (B.K != B.nb && B.K != 0) {
+    const uint32_t hist_blocks = (uint32_t)ceil_div(B.nb, (uint64_t)kHistBlock * kHistPer);
+    for (uint32_t pass = 0; pass < (uint32_t)kPasses; ++pass) {
+      hipLaunchKernelGGL(topk_hist_kernel, dim3(hist_blocks, W), dim3(kHistBlock), 0, st, B, pass);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+      hipLaunchKernelGGL(topk_pick_kernel, dim3(1, W), dim3(kHistBlock), 0, st, B, pass);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+    }
+  }
+  return S2R_OK;
+}
+
+static s2r_status launch_bitmaps(const TopkBatch& B, hipStream_t st) {
+  const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
+  hipLaunchKernelGGL(topk_bitmap_kernel, dim3((uint32_t)ceil_div(ceil_div(B.nb, 64), kBlock), B.nworkers), dim3(kBlock), 0,
+                     st, B, all, none);
+  return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+}
 
 }  // namespace s2r_topk
 
@@ -302,58 +403,17 @@ size_t s2r_topk_workspace_bytes(uint64_t n, uint32_t block) {
 s2r_status s2r_topk_blocks_batch(const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
                                  uint32_t block, uint64_t K, float* const* sparse_out, uint64_t* const* kept_bitmaps,
                                  void* workspace, size_t workspace_bytes, void* stream) {
-  if (grads == nullptr || sparse_out == nullptr) return S2R_ERR_NULL;
-  if (W == 0 || W > S2R_MAX_WORKERS || !sizes_ok(n, block)) return S2R_ERR_SIZE;
-  const uint64_t nb = ceil_div(n, block);
-  if (K > nb) K = nb;
+  if (sparse_out == nullptr) return S2R_ERR_NULL;
   static thread_local TopkBatch B;
-  for (uint32_t k = 0; k < W; ++k) {
-    float* ek = residuals ? residuals[k] : nullptr;
-    uint64_t* bk = kept_bitmaps ? kept_bitmaps[k] : nullptr;
-    if (grads[k] == nullptr || sparse_out[k] == nullptr || (residuals && ek == nullptr) || (kept_bitmaps && bk == nullptr))
-      return S2R_ERR_NULL;
-    if (((uintptr_t)grads[k] & 15u) || ((uintptr_t)sparse_out[k] & 15u) || ((uintptr_t)ek & 15u) || ((uintptr_t)bk & 7u))
-      return S2R_ERR_ALIGN;
-    B.w[k].grad = grads[k];
-    B.w[k].residual = ek;
-    B.w[k].sparse = sparse_out[k];
-    B.w[k].kept_bitmap = bk;
-  }
-  const size_t ws_each = (workspace_bytes / W) & ~(size_t)255;
-  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_each(nb)) return S2R_ERR_WORKSPACE;
-  B.workspace = reinterpret_cast<char*>(workspace);
-  B.ws_stride = ws_each;
-  B.hist_off = keys_bytes(nb);
-  B.state_off = B.hist_off + align256(kBins * sizeof(uint32_t));
-  B.n = n;
-  B.nb = nb;
-  B.K = K;
-  B.block = block;
-  B.nworkers = W;
+  s2r_status rc = fill_batch(B, grads, residuals, W, n, block, K, sparse_out, kept_bitmaps, workspace, workspace_bytes);
+  if (rc != S2R_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
-
-  const uint32_t all = K == nb ? 1u : 0u, none = K == 0 ? 1u : 0u;
-  const uint64_t score_blocks = block >= 32u ? ceil_div(nb, (uint64_t)kWavesPerBlock * kScorePer) : ceil_div(nb, kBlock);
-  hipLaunchKernelGGL(topk_score_kernel, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
-  if (!launch_ok()) return S2R_ERR_LAUNCH;
-  if (!all && !none) {
-    const uint32_t hist_blocks = (uint32_t)ceil_div(nb, (uint64_t)kHistBlock * kHistPer);
-    for (uint32_t pass = 0; pass < (uint32_t)kPasses; ++pass) {
-      hipLaunchKernelGGL(topk_hist_kernel, dim3(hist_blocks, W), dim3(kHistBlock), 0, st, B, pass);
-      if (!launch_ok()) return S2R_ERR_LAUNCH;
-      hipLaunchKernelGGL(topk_pick_kernel, dim3(1, W), dim3(kHistBlock), 0, st, B, pass);
-      if (!launch_ok()) return S2R_ERR_LAUNCH;
-    }
-  }
+  if ((rc = launch_selection(B, false, st)) != S2R_OK) return rc;
+  const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
   hipLaunchKernelGGL(topk_apply_kernel, dim3((uint32_t)ceil_div(n, (uint64_t)kBlock * kApplyPer), W), dim3(kBlock), 0, st,
                      B, all, none);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
-  if (kept_bitmaps != nullptr) {
-    hipLaunchKernelGGL(topk_bitmap_kernel, dim3((uint32_t)ceil_div(ceil_div(nb, 64), kBlock), W), dim3(kBlock), 0, st, B,
-                       all, none);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-  }
-  return S2R_OK;
+  return kept_bitmaps != nullptr ? launch_bitmaps(B, st) : S2R_OK;
 }
 
 s2r_status s2r_topk_blocks(const float* grad, float* residual, uint64_t n, uint32_t block, uint64_t K,
@@ -361,6 +421,57 @@ s2r_status s2r_topk_blocks(const float* grad, float* residual, uint64_t n, uint3
                            void* stream) {
   return s2r_topk_blocks_batch(&grad, residual ? &residual : nullptr, 1, n, block, K, &sparse_out,
                                kept_bitmap ? &kept_bitmap : nullptr, workspace, workspace_bytes, stream);
+}
+
+size_t s2r_topk_encode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t blk_cap) {
+  const size_t select = s2r_topk_workspace_bytes(n, block);
+  const size_t codec = s2r_encode_blocks_workspace_bytes(n, block, d, w, blk_cap);
+  return select == 0 || codec == 0 ? 0 : select + codec;          // both are multiples of 256
+}
+
+s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
+                                        uint32_t block, uint64_t K, uint32_t d, uint32_t w, uint64_t seed,
+                                        float* const* sketches, uint64_t* const* block_bitmaps,
+                                        uint32_t* const* blk_idx, uint64_t blk_cap, uint64_t* nblk_out,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (block_bitmaps == nullptr || sketches == nullptr || nblk_out == nullptr) return S2R_ERR_NULL;
+  if (W == 0 || W > S2R_MAX_WORKERS || !sizes_ok(n, block)) return S2R_ERR_SIZE;
+  // everything the compress step would refuse is refused here, before the residuals are touched
+  if (((uintptr_t)nblk_out & 7u) != 0) return S2R_ERR_ALIGN;
+  for (uint32_t k = 0; k < W; ++k) {
+    if (sketches[k] == nullptr || (blk_idx != nullptr && blk_idx[k] == nullptr)) return S2R_ERR_NULL;
+    if (((uintptr_t)sketches[k] & 15u) || (blk_idx != nullptr && ((uintptr_t)blk_idx[k] & 3u))) return S2R_ERR_ALIGN;
+  }
+  const size_t select_each = s2r_topk_workspace_bytes(n, block);
+  const size_t codec_each = s2r_encode_blocks_workspace_bytes(n, block, d, w, blk_cap);
+  if (select_each == 0 || codec_each == 0) return S2R_ERR_SIZE;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 ||
+      workspace_bytes / W < select_each + codec_each)
+    return S2R_ERR_WORKSPACE;
+  // the workspace: W selection shares, then W codec shares
+  char* select_ws = reinterpret_cast<char*>(workspace);
+  char* codec_ws = select_ws + (size_t)W * select_each;
+  const size_t codec_bytes = workspace_bytes - (size_t)W * select_each;
+  static thread_local TopkBatch B;
+  s2r_status rc = fill_batch(B, grads, residuals, W, n, block, K, nullptr, block_bitmaps, select_ws,
+                             (size_t)W * select_each);
+  if (rc != S2R_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  // acc = g + e replaces e during the scores' pass; the kept blocks are read from there and cleared at the end
+  if ((rc = launch_selection(B, residuals != nullptr, st)) != S2R_OK) return rc;
+  if ((rc = launch_bitmaps(B, st)) != S2R_OK) return rc;
+  const float* values[S2R_MAX_WORKERS];
+  for (uint32_t k = 0; k < W; ++k) values[k] = residuals != nullptr ? residuals[k] : grads[k];
+  rc = s2r::encode_marked_blocks(values, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, blk_cap, nblk_out,
+                                 codec_ws, codec_bytes, stream);
+  if (rc != S2R_OK) return rc;
+  if (residuals != nullptr) {
+    const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
+    const uint64_t blocks = block >= 32u ? ceil_div(B.nb, kWavesPerBlock) : ceil_div(B.nb, kBlock);
+    hipLaunchKernelGGL(topk_clear_kept_kernel, dim3((uint32_t)blocks, W), dim3(kBlock), 0, st, B, all, none);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+  return S2R_OK;
 }
 
 }  // extern "C"

@@ -191,6 +191,25 @@ def test_topk_argument_checks():
     assert lib.s2r_topk_blocks(0x1000, None, 1000, 10, 5, 0x2000, None, 0x4000, 64, None) == b.S2R_ERR_WORKSPACE
 
 
+def test_topk_encode_blocks_argument_checks():
+    import ctypes
+    lib = b.load()
+    n, B, d, w, cap = 1 << 20, 256, 3, 1 << 14, 40
+    each = b.topk_encode_blocks_workspace_bytes(n, B, d, w, cap)
+    assert each == b.topk_workspace_bytes(n, B) + b.encode_blocks_workspace_bytes(n, B, d, w, cap) and each % 256 == 0
+    assert b.topk_encode_blocks_workspace_bytes(n, 0, d, w, cap) == 0
+    assert b.topk_encode_blocks_workspace_bytes(n, B, d, 1000, cap) == 0
+    one = lambda v: (ctypes.c_void_p * 1)(v)
+    call = lambda grads, bitmaps, ws, ws_bytes, block=B, sketches=one(0x3000): lib.s2r_topk_encode_blocks_batch(
+        grads, None, 1, n, block, 40, d, w, 0, sketches, bitmaps, None, 0, 0x6000, ws, ws_bytes, None)
+    assert call(one(0x1000), None, 0x10000, 1 << 30) == b.S2R_ERR_NULL
+    assert call(None, one(0x5000), 0x10000, 1 << 30) == b.S2R_ERR_NULL
+    assert call(one(0x1000), one(0x5000), 0x10000, 1 << 30, block=0) == b.S2R_ERR_SIZE
+    assert call(one(0x1004), one(0x5000), 0x10000, 1 << 30) == b.S2R_ERR_ALIGN
+    assert call(one(0x1000), one(0x5000), 0x10000, 4096) == b.S2R_ERR_WORKSPACE
+    assert call(one(0x1000), one(0x5000), None, 1 << 30) == b.S2R_ERR_WORKSPACE
+
+
 def test_decode_update_argument_checks():
     lib = b.load()
     args = (0x1000, 0x2000, 1 << 20, 3, 1 << 14, 0)

@@ -673,6 +673,109 @@ def test_topk_error_feedback_over_steps_feeds_the_codec():
         assert np.array_equal(bb.out_blk[:cnt].cpu().numpy(), np.flatnonzero(union))
 
 
+def _fused_topk_check(gs, es, B, K, d, w, seed=0, cap=None, lists=True):
+    """Runs s2r_topk_encode_blocks_batch and checks bitmap, block list, sketch and residual
+    against the oracle's pieces for the set of blocks the library kept (which must be the
+    oracle's set up to scores within one float32 rounding, as for s2r_topk_blocks)."""
+    W, n = len(gs), len(gs[0])
+    nb = (n + B - 1) // B
+    cap = min(K, nb) if cap is None else cap
+    dev = "cuda"
+    print(f"[case] fused top-k W={W} n={n} B={B} K={K} d={d} w={w} cap={cap} lists={lists} residual={es is not None}", flush=True)
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = None if es is None else [torch.from_numpy(e).to(dev) for e in es]
+    sketch = [torch.full((d * w,), 3.0, dtype=torch.float32, device=dev) for _ in range(W)]
+    bitmap = [torch.full(((nb + 63) // 64,), -1, dtype=torch.int64, device=dev) for _ in range(W)]
+    blk = [torch.full((max(cap, 1),), -1, dtype=torch.int32, device=dev) for _ in range(W)] if lists else None
+    nblk = torch.zeros(W, dtype=torch.int64, device=dev)
+    ws = torch.empty(binding.topk_encode_blocks_workspace_bytes(n, B, d, w, max(cap, 1) if lists else 0) * W, dtype=torch.uint8,
+                     device=dev)
+    binding.topk_encode_blocks_batch(grads, resid, n, B, K, d, w, seed, sketch, bitmap, blk, nblk, ws)
+    torch.cuda.synchronize()
+    for k in range(W):
+        ref = orc.topk_encode_blocks(gs[k], None if es is None else es[k], B, K, d, w, seed)
+        tk = orc.topk_blocks(gs[k], None if es is None else es[k], B, K)
+        mask = orc.unpack_bitmap(pipeline.u64(bitmap[k]), nb)
+        assert int(mask.sum()) == min(K, nb) == int(nblk[k].cpu()), f"worker {k}: kept {int(mask.sum())} blocks"
+        got = np.flatnonzero(mask)
+        acc = tk["acc"]
+        if np.array_equal(got, ref["blocks"]):
+            S, M, want_e = ref["S"], ref["M"], ref["residual"]
+            assert np.array_equal(pipeline.u64(bitmap[k]), ref["bitmap"])
+        else:
+            sc = tk["score"].astype(np.float64)
+            lo, hi = sc[mask].min(), sc[~mask].max()
+            assert hi <= lo * (1 + 2.0 ** -22), f"worker {k}: a kept block scores {lo}, a dropped one {hi}"
+            elem = np.repeat(mask, B)[:n]
+            S, M = orc.insert(*orc.sparse_of(np.where(elem, acc, np.float32(0.0)).astype(np.float32)), d, w, seed)
+            want_e = np.where(elem, np.float32(0.0), acc).astype(np.float32)
+        if lists:
+            m = min(cap, len(got))
+            assert np.array_equal(blk[k][:m].cpu().numpy().view(np.uint32), got[:m].astype(np.uint32)), f"worker {k} list"
+            assert (blk[k][m:].cpu().numpy() == -1).all(), "entries beyond the count are not written"
+        _check_sketch(sketch[k].cpu().numpy(), S, M, f"worker {k} sketch")
+        if es is not None:
+            assert np.array_equal(resid[k].cpu().numpy().view(np.uint32), want_e.view(np.uint32)), f"worker {k} residual"
+        assert np.array_equal(grads[k].cpu().numpy().view(np.uint32), gs[k].view(np.uint32)), "the gradient is an input"
+
+
+@pytest.mark.parametrize("n,B,K,d,w", [(1, 1, 1, 1, 1), (1000, 1, 37, 3, 256), (1000, 7, 20, 3, 64), (4096, 32, 5, 5, 1 << 10),
+                                       (70001, 256, 50, 3, 1 << 14), (70001, 650, 3, 4, 1 << 12),
+                                       (200000, 31, 1000, 3, 1 << 15), (200000, 33, 1000, 5, 1 << 16),
+                                       (50000, 60000, 1, 3, 1 << 13), (300000, 4096, 10, 3, 1 << 17),
+                                       (65536, 64, 0, 3, 1 << 12), (65536, 64, 1024, 2, 1 << 18), (65536, 64, 5000, 3, 1 << 14)])
+def test_fused_topk_encode_blocks_match_oracle(n, B, K, d, w, strategy):
+    rng = np.random.default_rng(n + 31 * B + K)
+    gs = [(rng.normal(0, 1, n) * rng.gamma(0.5, 1.0, n)).astype(np.float32) for _ in range(3)]
+    es = [(rng.normal(0, 0.2, n) * (rng.random(n) < 0.3)).astype(np.float32) for _ in range(3)]
+    _fused_topk_check(gs, es, B, K, d, w, seed=n % 7)
+
+
+def test_fused_topk_short_lists_no_lists_no_residual_and_zero_blocks(strategy):
+    rng = np.random.default_rng(15)
+    n, B = 90000 + 13, 128
+    gs = [rng.normal(0, 1, n).astype(np.float32) for _ in range(2)]
+    es = [rng.normal(0, 0.3, n).astype(np.float32) for _ in range(2)]
+    _fused_topk_check(gs, es, B, 300, 3, 1 << 14, cap=100)                 # 200 kept blocks beyond the lists
+    _fused_topk_check(gs, es, B, 300, 3, 1 << 14, lists=False)             # no lists: every block by atomics
+    _fused_topk_check(gs, None, B, 300, 5, 1 << 13)                        # plain Top-K: nothing but the outputs written
+    sparse = np.zeros(n, dtype=np.float32)
+    sparse[B * 40: B * 43] = rng.normal(0, 1, 3 * B).astype(np.float32)
+    sparse[B * 41 + 5] = 0.0                                               # a zero inside a kept block is not inserted
+    _fused_topk_check([sparse], [np.zeros(n, dtype=np.float32)], B, 9, 3, 1 << 12)   # six all-zero blocks kept and marked
+
+
+def test_fused_topk_equals_the_two_calls():
+    """Same inputs through s2r_topk_blocks_batch + s2r_encode_blocks_batch and through the
+    fused call: bitmaps, lists and residuals identical, sketches equal up to summation order."""
+    rng = np.random.default_rng(23)
+    W, n, B, K, d, w = 4, 1 << 20, 256, 200, 3, 1 << 16
+    nb = n // B
+    dev = "cuda"
+    gs = [torch.from_numpy(rng.normal(0, 1, n).astype(np.float32)).to(dev) for _ in range(W)]
+    e1 = [torch.from_numpy(rng.normal(0, 0.5, n).astype(np.float32)).to(dev) for _ in range(W)]
+    e2 = [e.clone() for e in e1]
+    mk = lambda: dict(sketch=[torch.empty(d * w, dtype=torch.float32, device=dev) for _ in range(W)],
+                      bitmap=[torch.zeros(nb // 64, dtype=torch.int64, device=dev) for _ in range(W)],
+                      blk=[torch.full((K,), -1, dtype=torch.int32, device=dev) for _ in range(W)],
+                      nblk=torch.zeros(W, dtype=torch.int64, device=dev))
+    a, f = mk(), mk()
+    sparse = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(W)]
+    ws1 = torch.empty(binding.topk_workspace_bytes(n, B) * W, dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(binding.encode_blocks_workspace_bytes(n, B, d, w, K) * W, dtype=torch.uint8, device=dev)
+    binding.topk_blocks_batch(gs, e1, n, B, K, sparse, None, ws1)
+    binding.encode_blocks_batch(sparse, n, B, d, w, 0, a["sketch"], a["bitmap"], a["blk"], a["nblk"], ws2)
+    ws3 = torch.empty(binding.topk_encode_blocks_workspace_bytes(n, B, d, w, K) * W, dtype=torch.uint8, device=dev)
+    binding.topk_encode_blocks_batch(gs, e2, n, B, K, d, w, 0, f["sketch"], f["bitmap"], f["blk"], f["nblk"], ws3)
+    torch.cuda.synchronize()
+    assert torch.equal(a["nblk"], f["nblk"])
+    for k in range(W):
+        assert torch.equal(a["bitmap"][k], f["bitmap"][k]) and torch.equal(a["blk"][k], f["blk"][k])
+        assert torch.equal(e1[k].view(torch.int32), e2[k].view(torch.int32)), "residuals"
+        sa, sf = a["sketch"][k].double(), f["sketch"][k].double()
+        assert float((sa - sf).abs().max()) <= 2e-5 * float(sa.abs().max())
+
+
 # ---------------------------------------------------------------- sizes at the limits, random shapes
 def test_maximum_length_gradient():
     """n = 2^32 (the limit: indices are uint32), non-zeros at both ends, across the 2^31
