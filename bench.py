@@ -4,7 +4,8 @@ s2r_decode over one batch of synthetic worker gradients resident in HBM.
 
 Prints ONE JSON line.  `value` is dense-gradient GB/s = W*n*4 bytes per step /
 time per step.  `roofline` is for the dominant kernel (the dense scan of
-s2r_encode), timed with HIP events on the launch stream.  `cpu_baseline` is the
+s2r_encode; with --fused-topk the sparsifier's pass over gradient and residual),
+timed with HIP events on the launch stream.  `cpu_baseline` is the
 CPU oracle timed on a bounded sample of the same workload.
 """
 
@@ -55,6 +56,9 @@ def parse_args():
                     help="with --block: start every step from DENSE random gradients of the workload's W and n and "
                          "put the block-wise Top-K sparsifier with error feedback (this fraction of the blocks kept) "
                          "in front of the block codec")
+    ap.add_argument("--fused-topk", action="store_true",
+                    help="with --topk-frac: sparsifier and compress step through the one call "
+                         "s2r_topk_encode_blocks_batch (no sparse gradient in between) instead of two")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph (torch.cuda.CUDAGraph) and time its replays: the same "
                          "kernels without the per-launch host work, which matters for the small configs")
@@ -177,9 +181,15 @@ def main():
         ws_topk = torch.empty(binding.topk_workspace_bytes(wl.n, args.block) * wl.W, dtype=torch.uint8, device=b.device)
         tk_pairs = []
 
-        def step():
-            binding.topk_blocks_batch(dense, resid, wl.n, args.block, K, b.grads, None, ws_topk, stream)
-            b.step(stream, batched)
+        if args.fused_topk:
+            def step():
+                b.topk_encode_all(dense, resid, K, stream)
+                b.merge(stream)
+                b.decode(stream)
+        else:
+            def step():
+                binding.topk_blocks_batch(dense, resid, wl.n, args.block, K, b.grads, None, ws_topk, stream)
+                b.step(stream, batched)
     else:
         b = pipeline.block_buffers_for(wl, args.block) if args.block > 0 else pipeline.buffers_for(wl)
 
@@ -236,6 +246,21 @@ def main():
             slice_pairs.append((s0, s1))
 
     for r in range(reps):
+        if topk and args.fused_topk:        # one call; its dominant kernel is the scores' pass over g and e
+            t_a, t_b, c0, c1, s0, s1 = (binding.HipEvent() for _ in range(6))
+            binding.set_kernel_events(binding.S2R_KERNEL_TOPK_SCORES, c0.handle, c1.handle)
+            binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SLICE, s0.handle, s1.handle)
+            t_a.record(stream)
+            b.topk_encode_all(dense, resid, K, stream)
+            t_b.record(stream)
+            binding.set_kernel_events(binding.S2R_KERNEL_TOPK_SCORES, None, None)
+            binding.set_kernel_events(binding.S2R_KERNEL_ENCODE_SLICE, None, None)
+            tk_pairs.append((t_a, t_b))
+            timed["scan"].append((c0, c1))
+            slice_pairs.append((s0, s1))
+            bracket("merge", lambda: b.merge(stream))
+            bracket("decode", lambda: b.decode(stream))
+            continue
         if topk:
             t_a, t_b = binding.HipEvent(), binding.HipEvent()
             t_a.record(stream)
@@ -252,7 +277,8 @@ def main():
     torch.cuda.synchronize()
     scan_ms, merge_ms, decode_ms = (float(np.mean([a.elapsed_ms(c) for a, c in timed[k]]))
                                     for k in ("scan", "merge", "decode"))
-    workers_per_launch = binding.scan_launch_workers()
+    fused = topk and args.fused_topk
+    workers_per_launch = wl.W if fused else binding.scan_launch_workers()
     atomic = binding.last_insert_strategy() == binding.S2R_INSERT_ATOMIC
     slice_ms = None if atomic else float(np.mean([a.elapsed_ms(c) for a, c in slice_pairs]))
 
@@ -291,7 +317,10 @@ def main():
         per_worker = 4.0 * wl.n + ((wl.n + args.block - 1) // args.block) / 8.0 + (8.0 * wl.d * nnz.mean() if atomic else 0.0)
         alg_bytes = workers_per_launch * per_worker
         step_alg_bytes = algorithmic_bytes_blocks(wl, args.block, nnz, nblk, union)
-        if topk:        # g and e read for the scores, read again and both written by the apply pass
+        if fused:       # g and e read once, e written once; no sparse gradient for a codec scan to read
+            alg_bytes = wl.W * 12.0 * wl.n
+            step_alg_bytes += wl.W * (12.0 - 4.0) * wl.n
+        elif topk:      # g and e read for the scores, read again and both written by the apply pass
             step_alg_bytes += wl.W * 24.0 * wl.n
     else:
         assert [int(x) for x in b.nnz.cpu().numpy()] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
@@ -324,15 +353,18 @@ def main():
         "stream_read_GBs": round(read_ceiling, 1),
         "event_ms_per_step": round(ev_ms / args.steps, 4),
         "launch": "hip graph replay" if args.graph else "eager",
-        "encode_calls": ("s2r_encode_blocks_batch" if batched else "s2r_encode_blocks x W") if args.block > 0
+        "encode_calls": "s2r_topk_encode_blocks_batch" if fused else
+                        ("s2r_encode_blocks_batch" if batched else "s2r_encode_blocks x W") if args.block > 0
                         else ("s2r_encode_batch" if batched else "s2r_encode x W"),
         "decode_route": "slice" if binding.last_decode_strategy() == binding.S2R_DECODE_SLICE else "gather",
         "insert_strategy": "atomic" if atomic else "lds_slice",
-        "kernel_ms": {"encode_scan_per_launch": round(scan_ms, 4), "workers_per_scan_launch": workers_per_launch,
+        "kernel_ms": {"topk_scores_per_launch" if fused else "encode_scan_per_launch": round(scan_ms, 4),
+                      "workers_per_scan_launch": workers_per_launch,
                       "encode_slice_per_launch": None if slice_ms is None else round(slice_ms, 4),
                       "merge": round(merge_ms, 4), "decode": round(decode_ms, 4),
-                      "topk_sparsifier": None if topk_ms is None else round(topk_ms, 4)},
-        "roofline": {"kernel": "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+                      "topk_and_compress_call" if fused else "topk_sparsifier":
+                          None if topk_ms is None else round(topk_ms, 4)},
+        "roofline": {"kernel": "topk_score_kernel" if fused else "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None if args.block > 0 else
                                 MEASURED_SCAN_TRAFFIC.get((wl.name, "atomic" if atomic else "lds_slice", workers_per_launch)),

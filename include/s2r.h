@@ -451,12 +451,15 @@ int32_t s2r_last_insert_strategy(void);
  *   slot S2R_KERNEL_MERGE       : the kernel of s2r_merge
  *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel(s) of s2r_decode
  *   slot S2R_KERNEL_ENCODE_SLICE: the LDS-slice sketch kernel of s2r_encode
+ *   slot S2R_KERNEL_TOPK_SCORES : the scores kernel (the pass over grad and residual)
+ *                                 of s2r_topk_blocks* and s2r_topk_encode_blocks_batch
  */
 #define S2R_KERNEL_ENCODE_SCAN  0
 #define S2R_KERNEL_MERGE        1
 #define S2R_KERNEL_DECODE       2
 #define S2R_KERNEL_ENCODE_SLICE 3
-#define S2R_KERNEL_SLOTS        4
+#define S2R_KERNEL_TOPK_SCORES  4
+#define S2R_KERNEL_SLOTS        5
 s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end);
 
 /* Number of workers covered by the dense-scan launch that the

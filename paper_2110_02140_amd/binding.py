@@ -28,6 +28,7 @@ S2R_KERNEL_ENCODE_SCAN = 0
 S2R_KERNEL_MERGE = 1
 S2R_KERNEL_DECODE = 2
 S2R_KERNEL_ENCODE_SLICE = 3
+S2R_KERNEL_TOPK_SCORES = 4
 S2R_INSERT_AUTO = 0
 S2R_INSERT_ATOMIC = 1
 S2R_INSERT_SLICE = 2

@@ -22,4 +22,9 @@ s2r_status encode_marked_blocks(const float* const* values, uint32_t W, uint64_t
                                 uint32_t* const* blk_idx, uint64_t cap, uint64_t* nblk_out, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
+// Records the calling thread's begin (end = false) or end event of a
+// s2r_set_kernel_events slot on the stream, if one is set.
+__attribute__((visibility("hidden")))
+void record_kernel_event(int slot, bool end, void* stream);
+
 }  // namespace s2r

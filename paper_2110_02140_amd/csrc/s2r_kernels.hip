@@ -2124,6 +2124,8 @@ s2r_status s2r_encode_blocks(const float* grad, uint64_t n, uint32_t block, uint
 
 }  // extern "C"
 
+void s2r::record_kernel_event(int slot, bool end, void* stream) { record(slot, end, (hipStream_t)stream); }
+
 s2r_status s2r::encode_marked_blocks(const float* const* values, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
                                      uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* block_bitmaps,
                                      uint32_t* const* blk_idx, uint64_t cap, uint64_t* nblk_out, void* workspace,

@@ -162,6 +162,94 @@ __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
   }
 }
 
+// The same for blocks of a multiple of 4 elements (32 and more): 16-byte accesses.
+// A wave takes kScorePer consecutive blocks; lane l owns the 4-element chunks
+// l, l + 64, ... of each, kVecTrips of them per block and trip.  The last block
+// of a gradient whose length is not a multiple of 4 ends in a chunk that is read
+// and written element by element.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kVecTrips = 2;
+
+template <bool STORE>
+__global__ __launch_bounds__(kBlock) void topk_score_vec_kernel(const TopkBatch B) {
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const TopkWorker P = B.w[k];
+  uint64_t* keys = ws_keys(B, k);
+  if (blockIdx.x == 0) {
+    uint32_t* hist = ws_hist(B, k);
+    for (uint32_t b = threadIdx.x; b < kBins; b += kBlock) hist[b] = 0u;
+    if (threadIdx.x == 0) {
+      TopkState* st = ws_state(B, k);
+      st->prefix = 0ull;
+      st->remaining = B.K;
+    }
+  }
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint64_t x0 = ((uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave) * kScorePer;
+  if (x0 >= B.nb) return;                                  // uniform over the wave
+  const uint32_t chunks = B.block / 4;
+  double sum[kScorePer];
+#pragma unroll
+  for (int q = 0; q < kScorePer; ++q) sum[q] = 0.0;
+  for (uint32_t c = lane; c < chunks; c += kVecTrips * kWave) {
+    f32x4 a[kScorePer][kVecTrips];
+#pragma unroll
+    for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+      for (int u = 0; u < kVecTrips; ++u) {
+        const uint32_t cc = c + (uint32_t)u * kWave;
+        const uint64_t i = (x0 + q) * B.block + 4ull * cc;
+        const bool in = x0 + q < B.nb && cc < chunks && i < B.n;
+        a[q][u] = (f32x4)(0.0f);
+        if (in && i + 4 <= B.n) {
+          a[q][u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(P.grad + i));
+          if (P.residual != nullptr) a[q][u] += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(P.residual + i));
+        } else if (in) {
+          for (int j = 0; j < 4; ++j) {
+            if (i + j < B.n) {
+              float v = P.grad[i + j];
+              if (P.residual != nullptr) v += P.residual[i + j];
+              a[q][u][j] = v;
+            }
+          }
+        }
+      }
+    }
+    if (STORE) {
+#pragma unroll
+      for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+        for (int u = 0; u < kVecTrips; ++u) {
+          const uint32_t cc = c + (uint32_t)u * kWave;
+          const uint64_t i = (x0 + q) * B.block + 4ull * cc;
+          const bool in = x0 + q < B.nb && cc < chunks && i < B.n;
+          if (in && i + 4 <= B.n) {
+            __builtin_nontemporal_store(a[q][u], reinterpret_cast<f32x4*>(P.residual + i));
+          } else if (in) {
+            for (int j = 0; j < 4; ++j)
+              if (i + j < B.n) P.residual[i + j] = a[q][u][j];
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+      for (int u = 0; u < kVecTrips; ++u) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sum[q] += (double)a[q][u][j] * (double)a[q][u][j];
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < kScorePer; ++q) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum[q] += __shfl_xor(sum[q], off, kWave);
+    if (lane == 0 && x0 + q < B.nb) keys[x0 + q] = make_key(sum[q], x0 + q);
+  }
+}
+
 // Histogram of digit `pass` over the keys that share the digits found so far.
 __global__ __launch_bounds__(kHistBlock) void topk_hist_kernel(const TopkBatch B, uint32_t pass) {
   __shared__ uint32_t s_hist[kBins];
@@ -365,10 +453,17 @@ static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream
   const uint32_t W = B.nworkers;
   const uint64_t score_blocks =
       B.block >= 32u ? ceil_div(B.nb, (uint64_t)kWavesPerBlock * kScorePer) : ceil_div(B.nb, kBlock);
-  if (store_acc)
+  const bool vec = B.block >= 32u && B.block % 4u == 0u;   // (gradients and residuals are 16-byte aligned)
+  s2r::record_kernel_event(S2R_KERNEL_TOPK_SCORES, false, st);
+  if (vec && store_acc)
+    hipLaunchKernelGGL(topk_score_vec_kernel<true>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
+  else if (vec)
+    hipLaunchKernelGGL(topk_score_vec_kernel<false>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
+  else if (store_acc)
     hipLaunchKernelGGL(topk_score_kernel<true>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
   else
     hipLaunchKernelGGL(topk_score_kernel<false>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
+  s2r::record_kernel_event(S2R_KERNEL_TOPK_SCORES, true, st);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if (B.K != B.nb && B.K != 0) {
     const uint32_t hist_blocks = (uint32_t)ceil_div(B.nb, (uint64_t)kHistBlock * kHistPer);

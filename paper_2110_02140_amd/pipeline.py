@@ -132,6 +132,16 @@ class BlockBuffers:
         binding.encode_blocks_batch(self.grads, self.n, self.block, self.d, self.w, self.seed, self.sketch,
                                     self.bitmap, self.blk_idx, self.nblk, self.workspace, stream)
 
+    def topk_encode_all(self, dense, residuals, K: int, stream=None):
+        """Sparsifier and compress step in one call (s2r_topk_encode_blocks_batch) from the
+        dense gradients and the residuals; self.grads is not used."""
+        need = binding.topk_encode_blocks_workspace_bytes(self.n, self.block, self.d, self.w,
+                                                          self.blk_idx[0].numel()) * self.W
+        if getattr(self, "fused_ws", None) is None or self.fused_ws.numel() < need:
+            self.fused_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        binding.topk_encode_blocks_batch(dense, residuals, self.n, self.block, K, self.d, self.w, self.seed,
+                                         self.sketch, self.bitmap, self.blk_idx, self.nblk, self.fused_ws, stream)
+
     def merge(self, stream=None):
         binding.merge(self.sketch, self.bitmap, self.nb, self.d, self.w, self.seed,
                       self.sketch_sum, self.bitmap_or, stream)
