@@ -369,39 +369,50 @@ __global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, u
   }
 }
 
-// One thread per word of the kept-block bitmap.
+// One wave per word of the kept-block bitmap: lane l tests block 64 * word + l,
+// and the ballot is the word.
+__device__ __forceinline__ uint64_t kept_word(const TopkBatch& B, uint32_t k, uint64_t wd, uint32_t all, uint32_t none) {
+  const uint64_t* __restrict__ keys = ws_keys(B, k);
+  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
+  const uint64_t x = wd * 64 + (threadIdx.x & (kWave - 1));
+  return __ballot(x < B.nb && keys[x] >= T);
+}
+
 __global__ __launch_bounds__(kBlock) void topk_bitmap_kernel(const TopkBatch B, uint32_t all, uint32_t none) {
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers || B.w[k].kept_bitmap == nullptr) return;
-  const uint64_t* __restrict__ keys = ws_keys(B, k);
-  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
-  const uint64_t wd = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (wd >= ceil_div(B.nb, 64)) return;
-  uint64_t bits = 0;
-  for (uint32_t b = 0; b < 64; ++b) {
-    const uint64_t x = wd * 64 + b;
-    if (x < B.nb && keys[x] >= T) bits |= 1ull << b;
-  }
-  B.w[k].kept_bitmap[wd] = bits;
+  const uint64_t wd = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (wd >= ceil_div(B.nb, 64)) return;                    // uniform over the wave
+  const uint64_t bits = kept_word(B, k, wd, all, none);
+  if ((threadIdx.x & (kWave - 1)) == 0) B.w[k].kept_bitmap[wd] = bits;
 }
 
-// One wave per block: the residual of a kept block becomes +0.0 (the block has
-// been sent).  Blocks of fewer than 32 elements: one thread per block.
+// The residual of every kept block becomes +0.0 (the block has been sent).  A
+// wave finds the kept blocks among its 64 and clears them one after the other.
 __global__ __launch_bounds__(kBlock) void topk_clear_kept_kernel(const TopkBatch B, uint32_t all, uint32_t none) {
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers || B.w[k].residual == nullptr) return;
   float* __restrict__ e = B.w[k].residual;
-  const uint64_t* __restrict__ keys = ws_keys(B, k);
-  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
-  if (B.block >= 32u) {
-    const uint64_t x = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    if (x >= B.nb || keys[x] < T) return;                  // uniform over the wave
-    const uint64_t i0 = x * B.block;
-    for (uint32_t o = threadIdx.x & (kWave - 1); o < B.block && i0 + o < B.n; o += kWave) e[i0 + o] = 0.0f;
-  } else {
-    const uint64_t x = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (x >= B.nb || keys[x] < T) return;
-    for (uint32_t o = 0; o < B.block && x * B.block + o < B.n; ++o) e[x * B.block + o] = 0.0f;
+  const uint64_t wd = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (wd >= ceil_div(B.nb, 64)) return;                    // uniform over the wave
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  uint64_t bits = kept_word(B, k, wd, all, none);          // the same in every lane
+  while (bits != 0) {
+    const uint64_t x = wd * 64 + (uint32_t)__builtin_ctzll(bits);
+    bits &= bits - 1;
+    const uint64_t i0 = x * B.block;                       // < n: block x exists
+    const uint64_t len = B.n - i0 < (uint64_t)B.block ? B.n - i0 : (uint64_t)B.block;
+    if (B.block % 4u == 0u) {                              // 16-byte aligned block starts
+      for (uint64_t c = lane; 4 * c < len; c += kWave) {
+        if (4 * c + 4 <= len) {
+          *reinterpret_cast<f32x4*>(e + i0 + 4 * c) = (f32x4)(0.0f);
+        } else {
+          for (uint64_t o = 4 * c; o < len; ++o) e[i0 + o] = 0.0f;
+        }
+      }
+    } else {
+      for (uint64_t o = lane; o < len; o += kWave) e[i0 + o] = 0.0f;
+    }
   }
 }
 
@@ -479,8 +490,8 @@ static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream
 
 static s2r_status launch_bitmaps(const TopkBatch& B, hipStream_t st) {
   const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
-  hipLaunchKernelGGL(topk_bitmap_kernel, dim3((uint32_t)ceil_div(ceil_div(B.nb, 64), kBlock), B.nworkers), dim3(kBlock), 0,
-                     st, B, all, none);
+  hipLaunchKernelGGL(topk_bitmap_kernel, dim3((uint32_t)ceil_div(ceil_div(B.nb, 64), kWavesPerBlock), B.nworkers),
+                     dim3(kBlock), 0, st, B, all, none);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
@@ -562,7 +573,7 @@ s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const*
   if (rc != S2R_OK) return rc;
   if (residuals != nullptr) {
     const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
-    const uint64_t blocks = block >= 32u ? ceil_div(B.nb, kWavesPerBlock) : ceil_div(B.nb, kBlock);
+    const uint64_t blocks = ceil_div(ceil_div(B.nb, 64), kWavesPerBlock);
     hipLaunchKernelGGL(topk_clear_kept_kernel, dim3((uint32_t)blocks, W), dim3(kBlock), 0, st, B, all, none);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
