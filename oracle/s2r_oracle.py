@@ -339,6 +339,19 @@ def decode_blocks(S: np.ndarray, bitmap: np.ndarray, n: int, B: int, seed: int) 
     return {"blocks": blocks, "val": val.reshape(len(blocks), B)}
 
 
+def decode_blocks_update(S: np.ndarray, bitmap: np.ndarray, n: int, B: int, seed: int, params: np.ndarray,
+                         scale: float) -> np.ndarray:
+    """decode_update with a block bitmap: params[i] + scale * g_hat(i) at every
+    element i < n of every set block, params[i] elsewhere.  float64, one rounding
+    to float32."""
+    out = decode_blocks(S, bitmap, n, B, seed)
+    elems = block_elements(out["blocks"], B, n)
+    inside = (out["blocks"].astype(np.int64)[:, None] * B + np.arange(B, dtype=np.int64)[None, :]).reshape(-1) < n
+    new = np.ascontiguousarray(params, dtype=np.float32).astype(np.float64)
+    new[elems] += float(np.float32(scale)) * out["val"].reshape(-1)[inside]
+    return new.astype(np.float32)
+
+
 def reduce_workers_blocks(grads: list[np.ndarray], B: int, d: int, w: int, seed: int) -> dict:
     """Whole of Algorithm 1 with the block bitmap for W dense-stored worker gradients."""
     enc = [encode_blocks(g, B, d, w, seed) for g in grads]

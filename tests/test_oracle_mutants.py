@@ -37,6 +37,7 @@ def _some_pin_fails():
         (pins.test_topk_blocks_matches_pure_python, (16, 13)),
         (pins.test_topk_ties_go_to_the_lower_block_and_extremes, ()),
         (pins.test_topk_is_a_delta_approximate_compressor_and_loses_nothing, ()),
+        (pins.test_decode_blocks_update_against_pure_python_and_the_element_update, ()),
         (pins.test_topk_encode_blocks_matches_pure_python, (4, 3)),
         (pins.test_topk_encode_blocks_is_topk_then_encode_blocks_unless_a_kept_block_is_zero, ()),
         (pins.test_topk_encode_blocks_round_trip_without_collisions_returns_acc_in_the_kept_blocks, ()),
@@ -218,6 +219,19 @@ def _mut_fused_step_keeps_the_residual_of_sent_blocks(monkeypatch):
     monkeypatch.setattr(orc, "topk_encode_blocks", bad)
 
 
+def _mut_block_update_runs_past_the_end_of_the_block(monkeypatch):
+    real = orc.block_elements
+    def bad(blocks, B, n):
+        e = real(blocks, B, n)
+        return np.minimum(e + 1, n - 1)                                          # every element shifted by one
+    monkeypatch.setattr(orc, "block_elements", bad)
+
+
+def _mut_block_update_ignores_the_scale(monkeypatch):
+    real = orc.decode_blocks_update
+    monkeypatch.setattr(orc, "decode_blocks_update", lambda S, bm, n, B, seed, p, scale: real(S, bm, n, B, seed, p, 1.0))
+
+
 @pytest.mark.parametrize("mutant", [
     _mut_sign_dropped_in_query, _mut_msb_first_bitmap, _mut_median_off_by_one,
     _mut_low_bits_bucket, _mut_sign_uses_bucket_multiplier, _mut_merge_xor,
@@ -227,6 +241,7 @@ def _mut_fused_step_keeps_the_residual_of_sent_blocks(monkeypatch):
     _mut_topk_scores_by_abs_sum, _mut_topk_keeps_smallest, _mut_topk_residual_forgets_old_error,
     _mut_fused_step_marks_only_nonzero_blocks, _mut_fused_step_sketches_the_gradient_without_the_residual,
     _mut_fused_step_keeps_the_residual_of_sent_blocks,
+    _mut_block_update_runs_past_the_end_of_the_block, _mut_block_update_ignores_the_scale,
 ], ids=lambda f: f.__name__)
 def test_planted_mistake_is_caught(monkeypatch, mutant):
     mutant(monkeypatch)

@@ -506,6 +506,33 @@ def test_decode_update_is_an_sgd_step_when_recovery_is_exact():
     raise AssertionError("no collision-free seed")
 
 
+def test_decode_blocks_update_against_pure_python_and_the_element_update():
+    """Brute force: every element below n of every set block moves by scale times the
+    pure-Python median estimate, nothing else moves; with blocks of one element it is
+    decode_update; a ragged last block stops at n."""
+    from tests import bruteforce as bf
+    rng = np.random.default_rng(33)
+    n, B, d, w, seed = 203, 7, 3, 32, 6
+    gs = _tiny_grads(rng, 2, n, 0.06)
+    gs[0][n - 1] = np.float32(1.5)                                               # the ragged last block is set
+    res = orc.reduce_workers_blocks(gs, B, d, w, seed)
+    params = rng.normal(0, 1, n).astype(np.float32)
+    scale = -0.3
+    got = orc.decode_blocks_update(res["S"], res["bitmap"], n, B, seed, params, scale)
+    flags = [max(a, b) for a, b in zip(bf.block_flags(gs[0].tolist(), B), bf.block_flags(gs[1].tolist(), B))]
+    est = bf.decompress_blocks(flags, res["S"].tolist(), n, B, seed)
+    want = params.astype(np.float64)
+    for x, vals in est.items():
+        for o, v in enumerate(vals):
+            if x * B + o < n:
+                want[x * B + o] += float(np.float32(scale)) * v
+    assert np.array_equal(got, want.astype(np.float32))
+    one = orc.reduce_workers_blocks(gs, 1, d, w, seed)
+    el = orc.reduce_workers(gs, d, w, seed)
+    assert np.array_equal(orc.decode_blocks_update(one["S"], one["bitmap"], n, 1, seed, params, scale),
+                          orc.decode_update(el["S"], el["bitmap"], n, seed, params, scale))
+
+
 # ---------------------------------------------------------------- random tiny problems against the pure-Python loops
 def _hyp():
     import hypothesis
