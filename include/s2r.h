@@ -383,6 +383,27 @@ s2r_status s2r_decode_update(const float* sketch, const uint64_t* bitmap,
                              void* stream);
 
 /*
+ * The same with the block-granular bitmap: params[i] <- params[i] + scale *
+ * g_hat(i) at every element i < n of every block whose bit is set in
+ * block_bitmap (Section 3.1's bitmap over gradient blocks; Algorithm 1's
+ * decompress lines), however many blocks that is; other entries of params are
+ * not touched.  No values are returned; *nblk_out receives the number of set
+ * blocks.  The complete list of set blocks is built in the workspace:
+ * s2r_decode_blocks_update_workspace_bytes(n, block, d, w) bytes, 256-byte
+ * aligned.  params: dev, n float32, 4-byte aligned.  Other arguments, limits
+ * and errors as for s2r_decode_blocks.
+ */
+size_t s2r_decode_blocks_update_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w);
+
+s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_bitmap,
+                                    uint64_t n, uint32_t block,
+                                    uint32_t d, uint32_t w, uint64_t seed,
+                                    float* params, float scale,
+                                    uint64_t* nblk_out,
+                                    void* workspace, size_t workspace_bytes,
+                                    void* stream);
+
+/*
  * How s2r_encode carries out the insertion loops of Algorithm 1
  * (S[j, h_j(i)] += s_j(i) g(i)); the result is the same sketch either way.
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued

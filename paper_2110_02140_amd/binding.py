@@ -86,6 +86,9 @@ SIGNATURES = {
                                                ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p),
                                                ctypes.POINTER(c_void_p), c_uint64, c_void_p, c_void_p, c_size_t,
                                                c_void_p]),
+    "s2r_decode_blocks_update_workspace_bytes": (c_size_t, [c_uint64, c_uint32, c_uint32, c_uint32]),
+    "s2r_decode_blocks_update": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
+                                           c_void_p, ctypes.c_float, c_void_p, c_void_p, c_size_t, c_void_p]),
     "s2r_decode_blocks": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
                                     c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
@@ -298,6 +301,19 @@ def decode_update(sketch, bitmap, n, d, w, seed, params, scale, idx_out, val_out
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_decode_update")
+
+
+def decode_blocks_update_workspace_bytes(n: int, block: int, d: int, w: int) -> int:
+    return load().s2r_decode_blocks_update_workspace_bytes(n, block, d, w)
+
+
+def decode_blocks_update(sketch, block_bitmap, n, block, d, w, seed, params, scale, nblk_out, workspace, stream=None):
+    """s2r_decode_blocks_update: params float32[n] updated in place at every element of every set block."""
+    st = load().s2r_decode_blocks_update(_ptr(sketch), _ptr(block_bitmap), n, block, d, w, seed, _ptr(params),
+                                         float(scale), _ptr(nblk_out), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_decode_blocks_update")
 
 
 def set_insert_strategy(strategy: int):

@@ -1201,23 +1201,30 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const DecodeArgs 
   constexpr int kPer = 4;
   const uint64_t total = *count;
   const uint64_t have = (total < A.cap ? total : A.cap) * block;
-  const uint64_t t0 = (uint64_t)blockIdx.x * (kBlock * kPer) + threadIdx.x;
-  if ((uint64_t)blockIdx.x * (kBlock * kPer) >= have) return;
-  float g[kPer];
+  // (the grid is sized for the capacity of the list, capped; the listed blocks are usually fewer)
+  for (uint64_t wg = blockIdx.x; wg * (kBlock * kPer) < have; wg += gridDim.x) {
+    const uint64_t t0 = wg * (kBlock * kPer) + threadIdx.x;
+    float g[kPer];
 #pragma unroll
-  for (int u = 0; u < kPer; ++u) {
-    const uint64_t t = t0 + (uint64_t)u * kBlock;
-    g[u] = 0.0f;
-    if (t < have) {
-      const uint64_t q = t / block;
-      const uint64_t e = (uint64_t)blk_list[q] * block + (t - q * block);
-      if (e < A.n) g[u] = query<D>(A, hp, (uint32_t)e);
+    for (int u = 0; u < kPer; ++u) {
+      const uint64_t t = t0 + (uint64_t)u * kBlock;
+      g[u] = 0.0f;
+      if (t < have) {
+        const uint64_t q = t / block;
+        const uint64_t e = (uint64_t)blk_list[q] * block + (t - q * block);
+        if (e < A.n) {
+          g[u] = query<D>(A, hp, (uint32_t)e);
+          if (A.params != nullptr) A.params[e] = fmaf(A.scale, g[u], A.params[e]);
+        }
+      }
     }
-  }
+    if (A.val_out != nullptr) {
 #pragma unroll
-  for (int u = 0; u < kPer; ++u) {
-    const uint64_t t = t0 + (uint64_t)u * kBlock;
-    if (t < have) A.val_out[t] = g[u];
+      for (int u = 0; u < kPer; ++u) {
+        const uint64_t t = t0 + (uint64_t)u * kBlock;
+        if (t < have) A.val_out[t] = g[u];
+      }
+    }
   }
 }
 
@@ -1864,7 +1871,9 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
                               uint64_t* count_out, float* dense_out, void* workspace, size_t workspace_bytes,
                               void* stream, float* params = nullptr, float scale = 0.0f) {
   if (sketch == nullptr || bitmap == nullptr || count_out == nullptr) return S2R_ERR_NULL;
-  if ((idx_out == nullptr) != (val_out == nullptr)) return S2R_ERR_NULL;
+  // (a block-granular parameter update lists the blocks but returns no values)
+  if ((idx_out == nullptr) != (val_out == nullptr) && !(block != 0 && params != nullptr && val_out == nullptr))
+    return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
   const uint64_t elements = n;
@@ -2019,7 +2028,8 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     const uint32_t helpers = dense_grid(ntiles, 2048);
     hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, X, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    const dim3 bgrid((uint32_t)ceil_div(cap_items, (uint64_t)kBlock * 4)), bblock(kBlock);
+    const uint64_t bwgs = ceil_div(cap_items, (uint64_t)kBlock * 4);
+    const dim3 bgrid((uint32_t)(bwgs < 8192 ? bwgs : 8192)), bblock(kBlock);      // (the workgroups loop)
     switch (d) {
       case 1: hipLaunchKernelGGL(decode_blocks_kernel<1>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
       case 2: hipLaunchKernelGGL(decode_blocks_kernel<2>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
@@ -2136,6 +2146,29 @@ s2r_status s2r::encode_marked_blocks(const float* const* values, uint32_t W, uin
 }
 
 extern "C" {
+
+size_t s2r_decode_blocks_update_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w) {
+  if (check_sizes(n, d, w) != S2R_OK || !block_ok(n, block)) return 0;
+  const uint64_t nb = ceil_div(n, block);
+  return workspace_base(nb) + align256((size_t)nb * sizeof(uint32_t));
+}
+
+s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block,
+                                    uint32_t d, uint32_t w, uint64_t seed, float* params, float scale,
+                                    uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (params == nullptr) return S2R_ERR_NULL;
+  if (((uintptr_t)params & 3u) != 0) return S2R_ERR_ALIGN;
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  const s2r_status sz = check_sizes(n, d, w);
+  if (sz != S2R_OK) return sz;
+  const uint64_t nb = ceil_div(n, block);
+  if (workspace == nullptr || workspace_bytes < workspace_base(nb) + align256((size_t)nb * sizeof(uint32_t)))
+    return S2R_ERR_WORKSPACE;
+  // the complete list of set blocks goes to the workspace, behind the parts every decode uses
+  uint32_t* list = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + workspace_base(nb));
+  return decode_impl(sketch, block_bitmap, n, block, d, w, seed, list, nullptr, nb, nblk_out, nullptr, workspace,
+                     workspace_bytes, stream, params, scale);
+}
 
 s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block, uint32_t d,
                              uint32_t w, uint64_t seed, uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,

@@ -177,37 +177,58 @@ def u64(t: torch.Tensor) -> np.ndarray:
 class SparsifiedStep:
     """One data-parallel parameter update of W simulated workers, start to end in
     the library's kernels (Algorithm 1 with the block-wise Top-K sparsifier and
-    the error-feedback residual of Section 2.2 / Appendix A.2 in front of it):
+    the error-feedback residual of Section 2.2 / Appendix A.2 in front of it).
 
-        dense gradients g_k  ->  s2r_topk_blocks_batch   acc_k = g_k + e_k, keep K blocks, e_k <- rest
-                             ->  s2r_encode_batch        bitmap C_k, sketch S_k of the kept elements
-                             ->  s2r_merge               S = sum_k S_k, C = OR_k C_k  (stands in for AllReduce)
-                             ->  s2r_decode_update       params[i] += scale * median_j(...) at every bit of C
+    fused (default), block-granular bitmaps:
+        dense gradients g_k  ->  s2r_topk_encode_blocks_batch   acc_k = g_k + e_k, keep K blocks, e_k <- rest;
+                                                                 bitmap C_k of the kept blocks, sketch S_k
+                             ->  s2r_merge                      S = sum_k S_k, C = OR_k C_k  (stands in for AllReduce)
+                             ->  s2r_decode_blocks_update       params[i] += scale * median_j(...) in every block of C
+    not fused, element bitmaps:
+        s2r_topk_blocks_batch (sparse gradients materialised) -> s2r_encode_batch -> s2r_merge -> s2r_decode_update
 
     The caller owns the gradients and the parameters (float32[n] device tensors);
     this object owns the residuals and every intermediate buffer.
     """
 
-    def __init__(self, W: int, n: int, block: int, K: int, d: int, w: int, seed: int = 0, device="cuda:0"):
+    def __init__(self, W: int, n: int, block: int, K: int, d: int, w: int, seed: int = 0, device="cuda:0",
+                 fused: bool = True):
         nb = (n + block - 1) // block
         if not 0 < K <= nb:
             raise ValueError("K must be in 1..number of blocks")
-        self.block, self.K = block, K
-        cap = min(n, K * block)
-        self.codec = Buffers(W, n, d, w, seed, cap, 1, device)
-        dev = self.codec.device
+        self.block, self.K, self.fused = block, K, fused
+        if fused:
+            self.codec = BlockBuffers(W, n, block, d, w, seed, K, 1, device)
+            dev = self.codec.device
+            self.update_ws = torch.empty(binding.decode_blocks_update_workspace_bytes(n, block, d, w), dtype=torch.uint8,
+                                         device=dev)
+        else:
+            self.codec = Buffers(W, n, d, w, seed, min(n, K * block), 1, device)
+            dev = self.codec.device
+            self.codec.grads = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(W)]   # sparsified gradients
+            self.topk_ws = torch.empty(binding.topk_workspace_bytes(n, block) * W, dtype=torch.uint8, device=dev)
         self.residual = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(W)]
-        self.codec.grads = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(W)]    # sparsified gradients
-        self.topk_ws = torch.empty(binding.topk_workspace_bytes(n, block) * W, dtype=torch.uint8, device=dev)
 
     @property
     def sparse(self):
-        return self.codec.grads
+        """The sparsified gradients (only the not-fused path materialises them)."""
+        return None if self.fused else self.codec.grads
+
+    @property
+    def count(self):
+        """Device int64[1]: set blocks (fused) or union indices (not fused) of the last step."""
+        return self.codec.out_count
 
     def step(self, grads, params, scale: float, stream=None):
         """params += scale * (estimate of the sum over workers of their sparsified
         gradients); scale is typically -learning_rate / W."""
         c = self.codec
+        if self.fused:
+            c.topk_encode_all(grads, self.residual, self.K, stream)
+            c.merge(stream)
+            binding.decode_blocks_update(c.sketch_sum, c.bitmap_or, c.n, c.block, c.d, c.w, c.seed, params, scale,
+                                         c.out_count, self.update_ws, stream)
+            return
         binding.topk_blocks_batch(grads, self.residual, c.n, self.block, self.K, c.grads, None, self.topk_ws, stream)
         c.encode_all(stream)
         c.merge(stream)

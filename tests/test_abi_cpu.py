@@ -210,6 +210,20 @@ def test_topk_encode_blocks_argument_checks():
     assert call(one(0x1000), one(0x5000), None, 1 << 30) == b.S2R_ERR_WORKSPACE
 
 
+def test_decode_blocks_update_argument_checks():
+    lib = b.load()
+    n, B, d, w = 1 << 20, 256, 3, 1 << 14
+    need = b.decode_blocks_update_workspace_bytes(n, B, d, w)
+    assert need >= b.blocks_workspace_bytes(n, B, d, w) + 4 * (n // B) and need % 256 == 0
+    assert b.decode_blocks_update_workspace_bytes(n, 0, d, w) == 0
+    args = (0x1000, 0x2000, n, B, d, w, 0)
+    assert lib.s2r_decode_blocks_update(*args, None, 1.0, 0x4000, 0x10000, need, None) == b.S2R_ERR_NULL
+    assert lib.s2r_decode_blocks_update(*args, 0x3002, 1.0, 0x4000, 0x10000, need, None) == b.S2R_ERR_ALIGN
+    assert lib.s2r_decode_blocks_update(*args, 0x3000, 1.0, 0x4000, 0x10000, need - 256, None) == b.S2R_ERR_WORKSPACE
+    assert lib.s2r_decode_blocks_update(0x1000, 0x2000, n, 0, d, w, 0, 0x3000, 1.0, 0x4000, 0x10000, need, None) == b.S2R_ERR_SIZE
+    assert lib.s2r_decode_blocks_update(0x1000, 0x2000, n, B, d, 1000, 0, 0x3000, 1.0, 0x4000, 0x10000, need, None) == b.S2R_ERR_WIDTH
+
+
 def test_decode_update_argument_checks():
     lib = b.load()
     args = (0x1000, 0x2000, 1 << 20, 3, 1 << 14, 0)

@@ -776,6 +776,51 @@ def test_fused_topk_equals_the_two_calls():
         assert float((sa - sf).abs().max()) <= 2e-5 * float(sa.abs().max())
 
 
+def _block_update_check(gs, B, d, w, seed, scale):
+    W, n = len(gs), len(gs[0])
+    nb = (n + B - 1) // B
+    dev = "cuda"
+    print(f"[case] block update W={W} n={n} B={B} d={d} w={w}", flush=True)
+    res = orc.reduce_workers_blocks(gs, B, d, w, seed)
+    S = torch.from_numpy(res["S"].astype(np.float32).reshape(-1)).to(dev)          # the oracle's merged sketch, rounded
+    C = torch.from_numpy(res["bitmap"].view(np.int64)).to(dev)
+    rng = np.random.default_rng(n + B)
+    params0 = rng.normal(0, 1, n).astype(np.float32)
+    params = torch.from_numpy(params0.copy()).to(dev)
+    nblk = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws = torch.empty(binding.decode_blocks_update_workspace_bytes(n, B, d, w), dtype=torch.uint8, device=dev)
+    binding.decode_blocks_update(S, C, n, B, d, w, seed, params, scale, nblk, ws)
+    torch.cuda.synchronize()
+    blocks = orc.bitmap_indices(res["bitmap"], nb)
+    assert int(nblk.cpu()[0]) == len(blocks)
+    S32 = res["S"].astype(np.float32).astype(np.float64)
+    want = orc.decode_blocks_update(S32, res["bitmap"], n, B, seed, params0, scale).astype(np.float64)
+    elems = orc.block_elements(blocks, B, n)
+    got = params.cpu().numpy()
+    untouched = np.ones(n, dtype=bool)
+    untouched[elems] = False
+    assert np.array_equal(got[untouched], params0[untouched]), "entries outside the set blocks changed"
+    tol = np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+    tol[elems] += abs(scale) * (REL * orc.decode_tolerance_mass(res["M"], elems.astype(np.uint32), seed) + DENORM_SLACK)
+    err = np.abs(got.astype(np.float64) - want)
+    assert np.all(err <= tol), f"worst {err.max():.3e}"
+
+
+@pytest.mark.parametrize("cfg,B", [(2, 650), (3, 256), (4, 768), (1, 1), (5, 31)])
+def test_decode_blocks_update_matches_oracle(cfg, B):
+    wl = workloads.make_small(cfg)
+    _block_update_check([wl.dense(k) for k in range(wl.W)], B, wl.d, wl.w, wl.seed, -0.05 / wl.W)
+
+
+def test_decode_blocks_update_reaches_every_block_of_a_dense_gradient():
+    """Every block set, more list positions than one pass of the kernel's workgroups
+    covers (8192 workgroups x 1024 positions), a ragged last block."""
+    rng = np.random.default_rng(77)
+    n = 9_000_000 + 77
+    g = rng.normal(0, 1, n).astype(np.float32)
+    _block_update_check([g], 256, 2, 1 << 16, 3, 0.125)
+
+
 # ---------------------------------------------------------------- sizes at the limits, random shapes
 def test_maximum_length_gradient():
     """n = 2^32 (the limit: indices are uint32), non-zeros at both ends, across the 2^31

@@ -58,10 +58,54 @@ def _oracle_step(gs, es, params, B, K, d, w, seed, scale):
     return tk, union, M, new
 
 
+def _oracle_fused_step(gs, es, params, B, K, d, w, seed, scale):
+    enc = [orc.topk_encode_blocks(g, e, B, K, d, w, seed) for g, e in zip(gs, es)]
+    S, C = orc.merge([e["S"] for e in enc], [e["bitmap"] for e in enc])
+    M = np.sum([e["M"] for e in enc], axis=0)
+    n = params.shape[0]
+    blocks = orc.bitmap_indices(C, (n + B - 1) // B)
+    new = orc.decode_blocks_update(S, C, n, B, seed, params, scale)
+    return enc, blocks, orc.block_elements(blocks, B, n), M, new
+
+
+def test_fused_training_steps_match_the_oracle_chain():
+    """The one-call sparsifier + compress step, merge, and the block-granular update,
+    step by step against the oracle's chain run from the downloaded device state."""
+    W, n, m, B, K, d, w, seed = 3, 32768 + 40, 48, 64, 24, 3, 1 << 12, 5      # ragged last block; collisions
+    prob = LeastSquares(W, n, m, seed=3)
+    st = pipeline.SparsifiedStep(W, n, B, K, d, w, seed)
+    assert st.fused
+    x = torch.zeros(n, dtype=torch.float32, device="cuda")
+    scale = -0.5 / W
+    for it in range(4):
+        print(f"[case] fused training step {it}", flush=True)
+        grads = prob.grads(x)
+        gs = [g.cpu().numpy() for g in grads]
+        es = [e.cpu().numpy().copy() for e in st.residual]
+        x0 = x.cpu().numpy().copy()
+        st.step(grads, x, scale)
+        torch.cuda.synchronize()
+        enc, blocks, union, M, want = _oracle_fused_step(gs, es, x0, B, K, d, w, seed, scale)
+        for k in range(W):
+            assert np.array_equal(pipeline.u64(st.codec.bitmap[k]), enc[k]["bitmap"]), f"step {it}: bitmap of worker {k}"
+            assert np.array_equal(st.residual[k].cpu().numpy().view(np.uint32), enc[k]["residual"].view(np.uint32)), \
+                f"step {it}: residual of worker {k}"
+        assert int(st.count.cpu()[0]) == len(blocks)
+        got = x.cpu().numpy()
+        tol = np.zeros(n)
+        tol[union] = abs(scale) * (REL * orc.decode_tolerance_mass(M, union.astype(np.uint32), seed) + DENORM_SLACK)
+        tol += np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+        untouched = np.ones(n, dtype=bool)
+        untouched[union] = False
+        assert np.array_equal(got[untouched], x0[untouched]), f"step {it}: parameters outside the set blocks changed"
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        assert np.all(err <= tol), f"step {it}: worst parameter error {err.max():.3e}"
+
+
 def test_training_steps_match_the_oracle_chain():
     W, n, m, B, K, d, w, seed = 3, 32768 + 40, 48, 64, 24, 3, 1 << 12, 5      # ragged last block; w below the union: collisions
     prob = LeastSquares(W, n, m, seed=3)
-    st = pipeline.SparsifiedStep(W, n, B, K, d, w, seed)
+    st = pipeline.SparsifiedStep(W, n, B, K, d, w, seed, fused=False)
     x = torch.zeros(n, dtype=torch.float32, device="cuda")
     scale = -0.5 / W
     for it in range(4):
@@ -78,7 +122,7 @@ def test_training_steps_match_the_oracle_chain():
                 f"step {it}: residual of worker {k}"
             assert np.array_equal(st.sparse[k].cpu().numpy().view(np.uint32), tk[k]["sparse"].view(np.uint32)), \
                 f"step {it}: sparsified gradient of worker {k}"
-        assert int(st.codec.out_count.cpu()[0]) == len(union)
+        assert int(st.count.cpu()[0]) == len(union)
         got = x.cpu().numpy()
         tol = np.zeros(n)
         tol[union] = abs(scale) * (REL * orc.decode_tolerance_mass(M, union, seed) + DENORM_SLACK)
@@ -114,7 +158,10 @@ def test_sparsified_training_with_residuals_descends_like_dense_training():
     dense = _train(prob, steps, lr)
     wide = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 17))     # lambda = w / union >= 4 per row
     narrow = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 13))   # lambda <= 1: many collisions
-    print(f"[loss] start {start:.4e} dense {dense:.4e} sparsified(wide sketch) {wide:.4e} (narrow) {narrow:.4e}", flush=True)
+    two = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 17, fused=False))
+    print(f"[loss] start {start:.4e} dense {dense:.4e} sparsified(wide sketch) {wide:.4e} (narrow) {narrow:.4e} "
+          f"(not fused, wide) {two:.4e}", flush=True)
+    assert abs(two - wide) <= 0.05 * wide, "the fused and the two-call chains train alike"
     assert dense < 0.05 * start
     assert wide < 0.15 * start, "Top-K with residuals and a roomy sketch must follow dense training"
     assert wide < 6 * dense
