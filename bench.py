@@ -320,8 +320,8 @@ def main():
         if fused:       # g and e read once, e written once; no sparse gradient for a codec scan to read
             alg_bytes = wl.W * 12.0 * wl.n
             step_alg_bytes += wl.W * (12.0 - 4.0) * wl.n
-        elif topk:      # g and e read for the scores, read again and both written by the apply pass
-            step_alg_bytes += wl.W * 24.0 * wl.n
+        elif topk:      # g and e read and e <- g + e written by the scores' pass; e read and the sparse gradient written by the second
+            step_alg_bytes += wl.W * 20.0 * wl.n
     else:
         assert [int(x) for x in b.nnz.cpu().numpy()] == [len(i) for i in wl.idx], "encode counts differ from the generator's"
         alg_bytes = workers_per_launch * scan_kernel_bytes(wl.n, float(nnz.mean()), wl.d, atomic)

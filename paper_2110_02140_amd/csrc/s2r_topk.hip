@@ -317,7 +317,10 @@ __global__ __launch_bounds__(kHistBlock) void topk_pick_kernel(const TopkBatch B
 }
 
 // Four consecutive elements per thread.  `all` / `none` bypass the threshold
-// (K >= number of blocks, K = 0).
+// (K >= number of blocks, K = 0).  ACC_IN_E: the scores' pass has left acc in the
+// residual; the gradient is not read again and the residual is only written where
+// a block is kept.
+template <bool ACC_IN_E>
 __global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, uint32_t all, uint32_t none) {
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
@@ -329,9 +332,9 @@ __global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, u
   float a[kApplyPer];
   const bool whole = i0 + kApplyPer <= B.n;
   if (whole) {
-    const float4 g4 = *reinterpret_cast<const float4*>(P.grad + i0);
+    const float4 g4 = *reinterpret_cast<const float4*>((ACC_IN_E ? P.residual : P.grad) + i0);
     a[0] = g4.x; a[1] = g4.y; a[2] = g4.z; a[3] = g4.w;
-    if (P.residual != nullptr) {
+    if (!ACC_IN_E && P.residual != nullptr) {
       const float4 e4 = *reinterpret_cast<const float4*>(P.residual + i0);
       a[0] += e4.x; a[1] += e4.y; a[2] += e4.z; a[3] += e4.w;
     }
@@ -340,30 +343,33 @@ __global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, u
     for (int j = 0; j < kApplyPer; ++j) {
       a[j] = 0.0f;
       if (i0 + j < B.n) {
-        a[j] = P.grad[i0 + j];
-        if (P.residual != nullptr) a[j] += P.residual[i0 + j];
+        a[j] = ACC_IN_E ? P.residual[i0 + j] : P.grad[i0 + j];
+        if (!ACC_IN_E && P.residual != nullptr) a[j] += P.residual[i0 + j];
       }
     }
   }
   uint64_t x = i0 / B.block;
   uint32_t r = (uint32_t)(i0 - x * B.block);
   float s[kApplyPer], e[kApplyPer];
+  bool any_kept = false;
 #pragma unroll
   for (int j = 0; j < kApplyPer; ++j) {
     const bool kept = x < B.nb && keys[x] >= T;
+    any_kept |= kept;
     s[j] = kept ? a[j] : 0.0f;
     e[j] = kept ? 0.0f : a[j];
     if (++r == B.block) { r = 0; ++x; }
   }
+  const bool store_e = P.residual != nullptr && (!ACC_IN_E || any_kept);     // (elsewhere e already holds acc)
   if (whole) {
     *reinterpret_cast<float4*>(P.sparse + i0) = make_float4(s[0], s[1], s[2], s[3]);
-    if (P.residual != nullptr) *reinterpret_cast<float4*>(P.residual + i0) = make_float4(e[0], e[1], e[2], e[3]);
+    if (store_e) *reinterpret_cast<float4*>(P.residual + i0) = make_float4(e[0], e[1], e[2], e[3]);
   } else {
 #pragma unroll
     for (int j = 0; j < kApplyPer; ++j) {
       if (i0 + j < B.n) {
         P.sparse[i0 + j] = s[j];
-        if (P.residual != nullptr) P.residual[i0 + j] = e[j];
+        if (store_e) P.residual[i0 + j] = e[j];
       }
     }
   }
@@ -514,10 +520,15 @@ s2r_status s2r_topk_blocks_batch(const float* const* grads, float* const* residu
   s2r_status rc = fill_batch(B, grads, residuals, W, n, block, K, sparse_out, kept_bitmaps, workspace, workspace_bytes);
   if (rc != S2R_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
-  if ((rc = launch_selection(B, false, st)) != S2R_OK) return rc;
+  // with residuals the scores' pass leaves acc = g + e in them, and the second pass reads 4 bytes per element, not 8
+  const bool acc_in_e = residuals != nullptr;
+  if ((rc = launch_selection(B, acc_in_e, st)) != S2R_OK) return rc;
   const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
-  hipLaunchKernelGGL(topk_apply_kernel, dim3((uint32_t)ceil_div(n, (uint64_t)kBlock * kApplyPer), W), dim3(kBlock), 0, st,
-                     B, all, none);
+  const dim3 agrid((uint32_t)ceil_div(n, (uint64_t)kBlock * kApplyPer), W);
+  if (acc_in_e)
+    hipLaunchKernelGGL(topk_apply_kernel<true>, agrid, dim3(kBlock), 0, st, B, all, none);
+  else
+    hipLaunchKernelGGL(topk_apply_kernel<false>, agrid, dim3(kBlock), 0, st, B, all, none);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   return kept_bitmaps != nullptr ? launch_bitmaps(B, st) : S2R_OK;
 }
