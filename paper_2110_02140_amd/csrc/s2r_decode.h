@@ -1,0 +1,317 @@
+// Decompress (Algorithm 1, recovery line and query loops): the gather route and
+// the route that answers the queries from sketch slices held in LDS.
+// Included by s2r_kernels.hip only (one translation unit).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/s2r.h"
+#include "s2r_slices.h"
+
+namespace s2r {
+
+// ------------------------------------------------------------------ decode
+struct DecodeArgs {
+  const float* sketch;
+  const uint64_t* bitmap;
+  uint64_t n;
+  uint64_t nwords;
+  uint32_t d;
+  uint32_t log2w;
+  const uint64_t* prefix;    // [ntiles + 1]
+  const uint32_t* dense;     // dense-tile list: count, 64 words later the entries
+  uint32_t* idx_out;         // may be null
+  float* val_out;            // may be null
+  uint64_t cap;
+  float* dense_out;          // may be null
+  float* params;             // may be null; else params[i] += scale * estimate at every union index
+  float scale;
+};
+
+// Median of D values by a fully unrolled exchange network: every output is one
+// of the inputs (odd D); even D averages the two middle ones in float32.
+template <int D>
+__device__ __forceinline__ float median_fixed(float (&x)[D]) {
+#pragma unroll
+  for (int a = 0; a < D - 1; ++a) {
+#pragma unroll
+    for (int b = 0; b < D - 1 - a; ++b) {
+      const float lo = fminf(x[b], x[b + 1]);
+      const float hi = fmaxf(x[b], x[b + 1]);
+      x[b] = lo;
+      x[b + 1] = hi;
+    }
+  }
+  if constexpr ((D & 1) != 0) return x[D / 2];
+  else return 0.5f * (x[D / 2 - 1] + x[D / 2]);
+}
+
+template <int D>
+__device__ __forceinline__ float query(const DecodeArgs& A, const HashRows& hp, uint32_t i) {
+  float est[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) {
+    const uint32_t h = bucket_of(i, hp.a[j], hp.b[j], A.log2w);
+    const uint32_t raw = __float_as_uint(A.sketch[((uint64_t)j << A.log2w) + h]);
+    est[j] = __uint_as_float(raw ^ signbit_of(i, hp.c[j], hp.e[j]));
+  }
+  return median_fixed<D>(est);
+}
+
+// List positions [group * kGroupSlots, (group + 1) * kGroupSlots) of one tile, by
+// one workgroup of kBlock threads; group 0 also clears the tile's part of the
+// dense output first (the kernel that handles the further groups runs afterwards).
+template <int D>
+__device__ __forceinline__ void decode_group(const DecodeArgs& A, const HashRows& hp, TileBits& T, uint32_t tile,
+                                             uint32_t group) {
+  const uint64_t word0 = (uint64_t)tile * kTileWords;
+  uint64_t wd[kWordsPerThread];
+  read_tile_words<kBlock>(wd, A.bitmap, A.nwords, word0);      // in flight together with the two prefix loads
+  const uint64_t base = A.prefix[tile];
+  const uint32_t total = (uint32_t)(A.prefix[tile + 1] - base);
+
+  // dense output: group 0 owns the tile's elements; it clears them, and the estimates are
+  // written over the zeros after the barrier in scan_tile_words
+  if (group == 0 && A.dense_out != nullptr) {
+    const uint64_t e0 = word0 * 64;
+    const uint64_t e1 = min(A.n, e0 + (uint64_t)kTileElems);
+    float4* p4 = reinterpret_cast<float4*>(A.dense_out + e0);     // e0 is a multiple of 64 elements
+    const uint64_t n4 = (e1 - e0) / 4;
+    for (uint64_t q = threadIdx.x; q < n4; q += kBlock) p4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const uint64_t r = e0 + n4 * 4 + threadIdx.x;
+    if (r < e1) A.dense_out[r] = 0.0f;
+  }
+  const uint32_t first = group * kGroupSlots;
+  if (first >= total) return;                      // uniform over the workgroup
+  const uint32_t last = total - first > (uint32_t)kGroupSlots ? first + kGroupSlots : total;
+  scan_tile_words<kBlock>(T, wd);
+  // two list positions per thread and trip: 2 D bucket reads in flight
+  constexpr int kSlots = 2;
+  for (uint32_t t0 = first + threadIdx.x; t0 < last; t0 += kBlock * kSlots) {
+    uint32_t i[kSlots];
+    float g[kSlots];
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      const uint32_t t = t0 + u * kBlock;
+      i[u] = t < last ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) g[u] = t0 + u * kBlock < last ? query<D>(A, hp, i[u]) : 0.0f;
+#pragma unroll
+    for (int u = 0; u < kSlots; ++u) {
+      const uint32_t t = t0 + u * kBlock;
+      if (t >= last) continue;
+      const uint64_t pos = base + t;
+      if (A.idx_out != nullptr && pos < A.cap) {
+        A.idx_out[pos] = i[u];
+        A.val_out[pos] = g[u];
+      }
+      if (A.dense_out != nullptr) A.dense_out[i[u]] = g[u];
+      if (A.params != nullptr) A.params[i[u]] = fmaf(A.scale, g[u], A.params[i[u]]);   // union indices are distinct
+    }
+  }
+}
+
+// Workgroups below `helpers` take the further groups of the tiles in the
+// dense-tile list (A.dense: the entry count, 64 words later the entries), one
+// entry per trip; workgroup helpers + t takes group 0 of tile t.  With a dense output the two kinds must
+// not share a launch (group 0 clears the tile's part of it): the host then
+// launches the tiles alone (helpers = 0) and afterwards the helpers alone
+// (tiles = 0).
+template <int D>
+__global__ __launch_bounds__(kBlock) void decode_kernel(const DecodeArgs A, const HashRows hp, uint32_t helpers) {
+  __shared__ TileBits T;
+  if (blockIdx.x >= helpers) {
+    decode_group<D>(A, hp, T, blockIdx.x - helpers, 0u);
+    return;
+  }
+  const uint32_t entries = A.dense[0];
+  for (uint32_t e = blockIdx.x; e < entries; e += helpers) {
+    const uint32_t entry = A.dense[64 + e];
+    __syncthreads();                                     // T may still be read by the previous trip
+    decode_group<D>(A, hp, T, entry & 0xFFFFFu, entry >> 20);
+  }
+}
+
+// Block-granular decode by gathers: list position t is element t mod block of
+// the (t / block)-th listed block; every position gets its d bucket reads and
+// their median (0 for positions of the last block beyond the gradient).  One
+// thread per position and trip, kBlock * 4 positions per workgroup.
+template <int D>
+__global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const DecodeArgs A, const HashRows hp, uint32_t block,
+                                                               const uint32_t* __restrict__ blk_list,
+                                                               const uint64_t* __restrict__ count) {
+  constexpr int kPer = 4;
+  const uint64_t total = *count;
+  const uint64_t have = (total < A.cap ? total : A.cap) * block;
+  // (the grid is sized for the capacity of the list, capped; the listed blocks are usually fewer)
+  for (uint64_t wg = blockIdx.x; wg * (kBlock * kPer) < have; wg += gridDim.x) {
+    const uint64_t t0 = wg * (kBlock * kPer) + threadIdx.x;
+    float g[kPer];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const uint64_t t = t0 + (uint64_t)u * kBlock;
+      g[u] = 0.0f;
+      if (t < have) {
+        const uint64_t q = t / block;
+        const uint64_t e = (uint64_t)blk_list[q] * block + (t - q * block);
+        if (e < A.n) {
+          g[u] = query<D>(A, hp, (uint32_t)e);
+          if (A.params != nullptr) A.params[e] = fmaf(A.scale, g[u], A.params[e]);
+        }
+      }
+    }
+    if (A.val_out != nullptr) {
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const uint64_t t = t0 + (uint64_t)u * kBlock;
+        if (t < have) A.val_out[t] = g[u];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ decode by sketch slices
+// The bucket reads of decode_kernel each fetch a 128-byte line for 4 useful
+// bytes.  When the union list is long, s2r_decode instead partitions the
+// (list position, row) queries by sketch slice with the kernels of the encode's
+// slice strategy (records carry the list position instead of a value) and
+//   decode_slice_kernel   workgroup (j, s) loads slice s of row j into LDS with
+//                         coalesced loads, answers its bin's queries from LDS
+//                         and writes (estimate, position in chunk) into the
+//                         region of the query's chunk of kBinChunk list
+//                         positions: row j's answers of chunk c start at
+//                         (c * kBinChunk * d) + j * (items in c), and inside
+//                         them bin (j, s) starts where the prefix of the
+//                         chunk's histogram over the bins says
+//   decode_median_kernel  workgroup = chunk: row by row, the answers go through
+//                         LDS into the registers of the thread that owns the
+//                         list position; then the medians, stored coalesced
+struct DecodeSliceArgs {
+  const float* sketch;
+  const u32x2* rec;          // queries sorted by bin: (cell in slice | sign bit, list position)
+  uint2* answers;            // [nchunks][d][kBinChunk]-shaped regions, see above
+  const uint32_t* bin_start; // [nbins + 1]
+  const uint32_t* colpre;    // [nchunks][nbins]: queries of the bin in earlier chunks
+  const uint32_t* rowpre;    // [nchunks][nbins]: queries of the chunk in earlier bins
+  const uint64_t* count;     // the union count (device)
+  uint64_t cap;
+  float* val_out;
+  uint32_t nbins;
+  uint32_t slice_log2;
+  uint32_t d;
+  uint32_t block;            // block-granular codec: list positions are elements of listed blocks
+  uint64_t n;                //   (positions whose element is not below n get 0)
+  const uint32_t* blk_list;
+};
+
+constexpr int kBinChunkLog2 = 13;
+static_assert((1 << kBinChunkLog2) == kBinChunk, "list positions are split into chunk and offset by shifts");
+
+__global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeSliceArgs A) {
+  extern __shared__ float s_cells[];
+  constexpr int kAhead = 4;
+  const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
+  const uint32_t first = A.bin_start[bin], last = A.bin_start[bin + 1];
+  if (first == last) return;                              // uniform over the workgroup
+  const u32x2 none = {0u, 0u};
+  u32x2 x[kAhead];                                        // the first queries are requested together with the slice
+  uint64_t r0 = (uint64_t)first + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < kAhead; ++u)
+    x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r0 + u * kSliceBlock]) : none;
+  const uint32_t cells = 1u << A.slice_log2;
+  const float* src = A.sketch + (uint64_t)bin * cells;    // row-major sketch: slice s of row j starts at bin * cells
+  if (cells >= 4u * kSliceBlock) {                        // (the sketch and every slice of 4 cells or more are 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock)
+      reinterpret_cast<float4*>(s_cells)[c] = reinterpret_cast<const float4*>(src)[c];
+  } else {
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_cells[c] = src[c];
+  }
+  __syncthreads();
+  while (r0 < last) {                                     // x holds the queries r0 + u * kSliceBlock
+    const uint64_t r1 = r0 + kSliceBlock * kAhead;
+    u32x2 y[kAhead];
+    uint32_t colp[kAhead], rowp[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u)
+      y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r1 + u * kSliceBlock]) : none;
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const uint64_t at = (uint64_t)(x[u].y >> kBinChunkLog2) * A.nbins + bin;
+      const bool live = r0 + u * kSliceBlock < last;
+      colp[u] = live ? A.colpre[at] : 0u;
+      rowp[u] = live ? A.rowpre[at] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const uint64_t r = r0 + u * kSliceBlock;
+      if (r >= last) continue;
+      const uint32_t est = __float_as_uint(s_cells[x[u].x & 0x7FFFFFFFu]) ^ (x[u].x & 0x80000000u);
+      const uint64_t chunk = x[u].y >> kBinChunkLog2;
+      const uint64_t at = chunk * kBinChunk * A.d + rowp[u] + (uint32_t)(r - first - colp[u]);
+      A.answers[at] = make_uint2(est, x[u].y & (kBinChunk - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) x[u] = y[u];
+    r0 = r1;
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSliceArgs A) {
+  __shared__ float s_est[kBinChunk];
+  const uint32_t chunk = blockIdx.x;
+  const uint64_t total = *A.count;
+  const uint64_t listed = total < A.cap ? total : A.cap;
+  const uint64_t have = A.block != 0 ? listed * A.block : listed;
+  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
+  if (t0 >= have) return;                                 // uniform over the workgroup
+  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+  float est[kBinItems][D];
+  uint2 cur[kBinItems], nxt[kBinItems];                   // row j's answers, and row j + 1's on their way
+  const uint2* rows = A.answers + t0 * D;
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint32_t t = u * kBinBlock + threadIdx.x;
+    cur[u] = t < count ? rows[t] : make_uint2(0u, 0u);
+  }
+#pragma unroll
+  for (int j = 0; j < D; ++j) {
+    if (j + 1 < D) {
+#pragma unroll
+      for (int u = 0; u < kBinItems; ++u) {
+        const uint32_t t = u * kBinBlock + threadIdx.x;
+        nxt[u] = t < count ? rows[(uint64_t)(j + 1) * count + t] : make_uint2(0u, 0u);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (u * kBinBlock + threadIdx.x < count) s_est[cur[u].y] = __uint_as_float(cur[u].x);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      const uint32_t t = u * kBinBlock + threadIdx.x;
+      est[u][j] = t < count ? s_est[t] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) cur[u] = nxt[u];
+  }
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint32_t t = u * kBinBlock + threadIdx.x;
+    if (t >= count) continue;
+    float g = median_fixed<D>(est[u]);
+    if (A.block != 0) {                                   // the tail of the last block lies beyond the gradient
+      const uint64_t q = (t0 + t) / A.block;
+      if ((uint64_t)A.blk_list[q] * A.block + (t0 + t - q * A.block) >= A.n) g = 0.0f;
+    }
+    A.val_out[t0 + t] = g;
+  }
+}
+
+}  // namespace s2r

@@ -1,0 +1,437 @@
+// The insertions of Algorithm 1 without global atomics: a counting sort of
+// (item, row) records by sketch slice and the workgroups that own a slice in LDS.
+// Included by s2r_kernels.hip only (one translation unit).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/s2r.h"
+#include "s2r_tiles.h"
+#include "s2r_scan.h"
+
+namespace s2r {
+
+// ------------------------------------------------------------------ encode: sketch by LDS slices
+// The insertions S[j, h_j(i)] += s_j(i) g(i) without global atomics.  Row j of the
+// sketch is cut into slices of 2^slice_log2 cells (float64 accumulators in LDS); bin (j, s)
+// collects the pairs (item, row j) whose bucket falls in slice s.  A counting sort
+// over the listed items brings each bin's records together:
+//   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins
+//   bin_colscan_kernel, bin_start_kernel   offsets of every (chunk, bin) run and of every bin
+//   bin_scatter_kernel  writes each record (cell in the slice | sign bit, value)
+//                       into its run (order inside a run is arbitrary)
+//   sketch_slice_kernel workgroup (j, s) clears its slice in LDS, adds its bin's
+//                       records with LDS float64 atomics and stores the slice as float32
+// Work is O(items x rows), whatever the number of slices, and every cell of the
+// sketch is written exactly once by plain coalesced stores.
+constexpr int kBinBlock = 1024;
+constexpr int kBinItems = 8;                           // list items per thread
+constexpr int kBinChunk = kBinBlock * kBinItems;       // 8192 items per workgroup
+constexpr int kMaxBins = 8192;                         // d * slices per row that the LDS histograms hold
+constexpr size_t kSliceLdsMax = sizeof(double) << kSliceLog2Max;
+constexpr int kDecodeSliceLog2Max = 15;               // decode holds float32 cells: 2^15 of them are 128 KiB of LDS
+static_assert(kMaxBins <= (1 << 13) && kSliceLog2Max <= 15 && kDecodeSliceLog2Max <= 15,
+              "bin_scatter_kernel packs slice (bits 16..28) and cell (bits 0..14) into one word");
+
+// The items of the counting sort: the entries of the worker's list, or, in the
+// block-granular codec, the elements of the listed blocks (block by block).
+__device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t k) {
+  const uint64_t nnz = B.nnz_out[k];
+  const uint64_t listed = nnz < B.cap ? nnz : B.cap;
+  return B.block != 0 ? listed * B.block : listed;
+}
+
+// Item t (t < listed_items): its element index i and its payload v (the value's
+// bits, or the item's position t when B.payload_slot is set).  Returns whether
+// the item takes part: with blocks, elements beyond n never do, and elements
+// whose value is zero only when the payload is the position (a query), not when
+// it is the value (an insertion: zeros are inert).  An item that does not take
+// part in a query run is still given d answers (of element 0), which the median
+// kernel discards, so that every chunk holds the same number of answers per row.
+__device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs& P, uint64_t t, uint32_t& i, uint32_t& v) {
+  if (B.block == 0) {
+    i = P.nz_idx[t];
+    v = B.payload_slot != 0 ? (uint32_t)t : P.nz_val[t];
+    return true;
+  }
+  const uint32_t q = (uint32_t)t / B.block;                // (the sort's items are fewer than 2^32)
+  const uint64_t e = (uint64_t)P.nz_idx[q] * B.block + ((uint32_t)t - q * B.block);
+  const bool inside = e < B.n;
+  if (B.payload_slot != 0) {
+    i = inside ? (uint32_t)e : 0u;
+    v = (uint32_t)t;
+    return true;
+  }
+  i = (uint32_t)e;
+  v = inside ? P.grad[e] : 0u;
+  return inside && (v << 1) != 0u;
+}
+
+__global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
+  __shared__ uint32_t s_hist[kMaxBins];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const uint32_t chunk = blockIdx.x;
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
+  __syncthreads();
+  const uint64_t have = listed_items(B, k);
+  const WorkerPtrs P = B.w[k];
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;
+  uint32_t i[kBinItems], v[kBinItems];
+  bool ok[kBinItems];
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+    ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    if (ok[u]) {
+      for (uint32_t j = 0; j < B.d; ++j) {
+        const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
+        __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
+  if (B.rowpre_off == 0) return;                         // uniform over the workgroup
+  // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
+  constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
+  uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
+    sum += c[q];
+  }
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  __syncthreads();
+  uint32_t run = incl - sum;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
+  uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    if ((uint32_t)q < per && e < B.nbins) {
+      rowpre[e] = run;
+      run += c[q];
+    }
+  }
+}
+
+// Offsets of the counting sort, two kernels.
+// bin_colscan_kernel: workgroup = 64 adjacent bins of one worker (lane = bin, so a
+// chunk's counters are read as one 256-byte row); its 16 waves split the chunks
+// into 16 consecutive ranges.  In place, hist[c][b] becomes the number of records
+// of bin b in chunks before c: every wave sums its range, the waves' sums are
+// exchanged through LDS, then every wave walks its range again with its running
+// offset.  The bin's total goes to bin_start[b].
+// bin_start_kernel: one workgroup per worker turns the totals in bin_start[0..nbins)
+// into the number of records in bins before b (bin_start[nbins] = all records).
+__global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatch B) {
+  constexpr int kWaves = kBinBlock / kWave;              // 16
+  constexpr uint32_t kAhead = 8;                         // counters in flight per thread
+  __shared__ uint32_t s_part[kWaves][kWave];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t b = blockIdx.x * kWave + lane;
+  const bool live = b < B.nbins;
+  uint32_t* hist = ws_bin_hist(B, k);
+  const uint32_t per = (B.nchunks + kWaves - 1) / kWaves;
+  const uint32_t c_begin = wv * per < B.nchunks ? wv * per : B.nchunks;
+  const uint32_t c_end = c_begin + per < B.nchunks ? c_begin + per : B.nchunks;
+  uint32_t sum = 0;
+  for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
+    uint32_t v[kAhead];
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) v[q] = (live && c0 + q < c_end) ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) sum += v[q];
+  }
+  s_part[wv][lane] = sum;
+  __syncthreads();
+  uint32_t run = 0, total = 0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) {
+    const uint32_t x = s_part[q][lane];
+    if ((uint32_t)q < wv) run += x;
+    total += x;
+  }
+  for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
+    uint32_t v[kAhead];
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) v[q] = (live && c0 + q < c_end) ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) {
+      if (live && c0 + q < c_end) hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
+      run += v[q];
+    }
+  }
+  if (wv == 0 && live) ws_bin_start(B, k)[b] = total;
+}
+
+__global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch B) {
+  constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;           // 8
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  uint32_t* bin_start = ws_bin_start(B, k);
+  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;   // thread t owns bins t*per .. t*per + per - 1
+  uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    c[q] = ((uint32_t)q < per && e < B.nbins) ? bin_start[e] : 0u;
+    sum += c[q];
+  }
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  __syncthreads();
+  uint32_t run = incl - sum, all = 0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) {
+    const uint32_t x = s_wave[q];
+    if ((uint32_t)q < wv) run += x;
+    all += x;
+  }
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    if ((uint32_t)q < per && e < B.nbins) {
+      bin_start[e] = run;
+      run += c[q];
+    }
+  }
+  if (threadIdx.x == 0) bin_start[B.nbins] = all;
+}
+
+// One workgroup per chunk of kBinChunk list items, one pass per sketch row j.  The
+// chunk's records for row j are first sorted by slice inside LDS (a counting
+// sort: LDS counters give every record its rank in its slice, a scan of the
+// counters gives the start of every slice's run) and then copied out in sorted
+// order, so that consecutive lanes write consecutive records of the (chunk, bin)
+// run that the histogram pass reserved.  In LDS a record carries its slice number
+// in bits 16..28 of its first word (the cell takes bits 0..14, the sign bit 31).
+// Dynamic LDS: kBinChunk records, then two arrays of (slices per row) counters.
+__global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
+  extern __shared__ uint2 s_stage[];
+  constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;           // counters per thread in the scan, at most
+  __shared__ uint32_t s_wave[kWaves];
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;
+  const uint32_t chunk = blockIdx.x;
+  const uint64_t have = listed_items(B, k);
+  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
+  if (t0 >= have) return;                                 // uniform over the workgroup
+  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;
+  const uint32_t spr = 1u << spr_log2;                    // slices per row
+  uint32_t* s_loc = reinterpret_cast<uint32_t*>(s_stage + kBinChunk);
+  uint32_t* s_delta = s_loc + spr;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const WorkerPtrs P = B.w[k];
+  const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+  const uint32_t* bin_start = ws_bin_start(B, k);
+  uint2* __restrict__ rec = ws_records(B, k);
+  const uint32_t mask = (1u << B.slice_log2) - 1u;
+  const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan (<= kMaxPer)
+
+  uint32_t i[kBinItems], v[kBinItems];
+  bool ok[kBinItems];                                     // the item exists and takes part (see load_item)
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint32_t t = u * kBinBlock + threadIdx.x;
+    ok[u] = t < count && load_item(B, P, t0 + t, i[u], v[u]);
+  }
+  for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
+
+  for (uint32_t j = 0; j < B.d; ++j) {
+    // where the runs of this (chunk, row) start in the worker's records; needed after the scan
+    uint32_t gpos[kMaxPer];
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
+      const uint32_t e = threadIdx.x * per + q;
+      gpos[q] = ((uint32_t)q < per && e < spr) ? bin_start[(j << spr_log2) + e] + hist[(j << spr_log2) + e] : 0u;
+    }
+    __syncthreads();                                      // s_loc is zero, s_stage is free
+    uint32_t key[kBinItems], rank[kBinItems];
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (ok[u]) {
+        const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
+        const uint32_t sl = h >> B.slice_log2;
+        key[u] = (h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]) | (sl << 16);
+        rank[u] = __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    }
+    __syncthreads();
+    // exclusive scan of the counters; thread t owns counters t*per .. t*per + per - 1
+    uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
+      const uint32_t e = threadIdx.x * per + q;
+      c[q] = ((uint32_t)q < per && e < spr) ? s_loc[e] : 0u;
+      sum += c[q];
+    }
+    const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    uint32_t run = incl - sum, records = 0;               // records: the chunk's items that take part
+#pragma unroll
+    for (int q = 0; q < kWaves; ++q) {
+      const uint32_t x = s_wave[q];
+      if ((uint32_t)q < wv) run += x;
+      records += x;
+    }
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
+      const uint32_t e = threadIdx.x * per + q;
+      if ((uint32_t)q < per && e < spr) {
+        s_loc[e] = run;
+        s_delta[e] = gpos[q] - run;                       // sorted position p of slice e goes to record p + delta
+        run += c[q];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (ok[u]) s_stage[s_loc[(key[u] >> 16) & 0x1FFFu] + rank[u]] = make_uint2(key[u], v[u]);
+    }
+    __syncthreads();
+    for (uint32_t p = threadIdx.x; p < records; p += kBinBlock) {
+      const uint2 r = s_stage[p];
+      rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80007FFFu, r.y);
+    }
+    for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;      // for the next row; not read above
+  }
+}
+
+// Workgroup = bin (j, s) of worker blockIdx.y.  The slice is accumulated in
+// float64: the LDS float64 atomic add runs at full LDS rate on this chip (about
+// 1.7e12 per second over the chip at random addresses) while the float32 one
+// takes a slow path (0.2e12 per second, whatever the addresses); each cell is
+// rounded to float32 once, when the slice is stored.  The first records are
+// requested before the slice is cleared, and each later batch while the previous
+// one is added.
+__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B) {
+  extern __shared__ double s_slice[];
+  constexpr int kAhead = 4;                               // 8-byte record loads in flight per thread
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
+  const uint32_t cells = 1u << B.slice_log2;
+  const uint32_t* bin_start = ws_bin_start(B, k);
+  const uint32_t first = bin_start[bin], last = bin_start[bin + 1];
+  const u32x2* __restrict__ rec = reinterpret_cast<const u32x2*>(ws_records(B, k));
+  const u32x2 none = {0u, 0u};
+  u32x2 x[kAhead];
+  uint64_t r0 = (uint64_t)first + threadIdx.x;            // 64 bits: positions near 2^32 must not wrap
+#pragma unroll
+  for (int u = 0; u < kAhead; ++u)
+    x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&rec[r0 + u * kSliceBlock]) : none;
+
+  if (cells >= 2u * kSliceBlock) {                        // (the LDS array is 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 2; c += kSliceBlock)
+      reinterpret_cast<double2*>(s_slice)[c] = make_double2(0.0, 0.0);
+  } else {
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0;
+  }
+  __syncthreads();
+
+  while (r0 < last) {                                     // x holds the records r0 + u * kSliceBlock
+    const uint64_t r1 = r0 + kSliceBlock * kAhead;
+    u32x2 y[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u)
+      y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&rec[r1 + u * kSliceBlock]) : none;
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      if (r0 + u * kSliceBlock < last)
+        __hip_atomic_fetch_add(&s_slice[x[u].x & 0x7FFFFFFFu],
+                               (double)__uint_as_float(x[u].y ^ (x[u].x & 0x80000000u)),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) x[u] = y[u];
+    r0 = r1;
+  }
+  __syncthreads();
+  // bin = j * slices-per-row + s, so the slice starts at cell bin * cells of the row-major sketch
+  float* out = B.w[k].sketch + (uint64_t)bin * cells;
+  if (cells >= 4u * kSliceBlock) {                        // (every slice of 4 cells or more is 16-byte aligned)
+    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock) {
+      const double2 lo = reinterpret_cast<const double2*>(s_slice)[2 * c];
+      const double2 hi = reinterpret_cast<const double2*>(s_slice)[2 * c + 1];
+      f32x4 o;
+      o.x = (float)lo.x; o.y = (float)lo.y; o.z = (float)hi.x; o.w = (float)hi.y;
+      __builtin_nontemporal_store(o, &reinterpret_cast<f32x4*>(out)[c]);
+    }
+  } else {
+    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = (float)s_slice[c];
+  }
+}
+
+// Non-zeros at list positions >= cap are not in the caller's lists; this kernel
+// finds them in the bitmap and inserts them with atomics after the slices were
+// stored, so the sketch is complete whatever cap is.  Normally there are none:
+// each thread checks one tile's range of list positions and the workgroup leaves
+// unless one of its kBlock tiles reaches beyond cap.
+__global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBatch B, const HashRows hp) {
+  __shared__ TileBits T;
+  __shared__ uint32_t s_any;
+  const uint32_t k = blockIdx.y;
+  if (k >= B.nworkers) return;                           // uniform over the workgroup
+  const WorkerPtrs P = B.w[k];
+  const uint64_t* prefix = ws_prefix(B, k);
+  const uint32_t tile0 = blockIdx.x * kBlock;
+  if (threadIdx.x == 0) s_any = 0u;
+  __syncthreads();
+  const uint32_t mine = tile0 + threadIdx.x;
+  if (mine < B.ntiles && prefix[mine + 1] > B.cap) s_any = 1u;
+  __syncthreads();
+  if (s_any == 0u) return;                               // uniform over the workgroup
+  for (uint32_t tile = tile0; tile < tile0 + kBlock && tile < B.ntiles; ++tile) {
+    const uint64_t base = prefix[tile];
+    const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
+    if (base + total <= B.cap) continue;                 // uniform over the workgroup
+    const uint64_t word0 = (uint64_t)tile * kTileWords;
+    uint64_t wd[kWordsPerThread];
+    read_tile_words<kBlock>(wd, P.bitmap, B.nwords, word0);
+    __syncthreads();                                     // T may still be read by the previous tile's loop
+    scan_tile_words<kBlock>(T, wd);
+    const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
+    for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
+      const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
+      if (B.block == 0) {
+        sketch_insert(P.sketch, B.d, B.log2w, hp, i, P.grad[i]);
+      } else {                                           // an unlisted block: its non-zero elements
+        for (uint32_t o = 0; o < B.block; ++o) {
+          const uint64_t e = (uint64_t)i * B.block + o;
+          if (e >= B.n) break;
+          const uint32_t v = P.grad[e];
+          if ((v << 1) != 0u) sketch_insert(P.sketch, B.d, B.log2w, hp, (uint32_t)e, v);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace s2r
