@@ -27,6 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # scaled by what the same counters read for a plain 1 GiB copy (profiles/hbm_traffic_<workload>.txt):
 # (workload, insert strategy, workers per launch) -> bytes.  Other combinations have not been counted.
 MEASURED_SCAN_TRAFFIC = {("cfg5_large_zipf", "atomic", 1): 4.299e9, ("cfg5_large_zipf", "lds_slice", 1): 4.138e9}
+# the same for the scores kernel of s2r_topk_encode_blocks_batch: (workload, block, kept fraction) -> bytes per launch
+MEASURED_SCORES_TRAFFIC = {("cfg3_block_sparse", 256, 0.01): 2.464e9}
 
 
 def algorithmic_bytes(wl, nnz, union: int) -> float:
@@ -366,7 +368,8 @@ def main():
                           None if topk_ms is None else round(topk_ms, 4)},
         "roofline": {"kernel": "topk_score_kernel" if fused else "encode_scan_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None if args.block > 0 else
+                     "traffic": MEASURED_SCORES_TRAFFIC.get((wl.name, args.block, args.topk_frac)) if fused else
+                                None if args.block > 0 else
                                 MEASURED_SCAN_TRAFFIC.get((wl.name, "atomic" if atomic else "lds_slice", workers_per_launch)),
                      "algorithmic_bytes_per_launch": int(alg_bytes)},
         "setup_s": {"generate": round(t_gen, 1)},
