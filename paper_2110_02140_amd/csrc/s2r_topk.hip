@@ -4,18 +4,22 @@
 // Theorem 2: what is not sent stays in an error sequence added to the next
 // gradient).  See include/s2r.h for the contract.
 //
-//   topk_score_kernel   acc = g + e per element; per block the sum of squares
-//                       (float64 accumulation, one rounding to float32) packed
+//   topk_score_kernel,  acc = g + e per element; per block the sum of squares
+//   topk_score_vec_kernel (float64 accumulation, one rounding to float32) packed
 //                       with the block index into a 64-bit key, larger key =
-//                       kept first (higher score, then lower block)
+//                       kept first (higher score, then lower block).  STORE: acc
+//                       is written back over e on the way
 //   topk_hist_kernel,   radix select of the K-th largest key: six digits of 11
 //   topk_pick_kernel    or 10 bits from the top; per digit a histogram of the
-//                       keys that share the digits found so far, then one
-//                       workgroup picks the digit.  Keys are distinct, so the
-//                       result is the exact threshold
-//   topk_apply_kernel   second pass over g and e: kept blocks go to the sparse
-//                       gradient, the rest to the new residual
-//   topk_bitmap_kernel  optional bitmap of the kept blocks
+//                       keys that share the digits found so far.  The digit is
+//                       picked from the complete histogram by every workgroup of
+//                       the next pass (and by one last small launch).  Keys are
+//                       distinct, so the result is the exact threshold
+//   topk_apply_kernel   second pass: kept blocks go to the sparse gradient, the
+//                       rest to the new residual
+//   topk_bitmap_kernel  bitmap of the kept blocks, a wave ballot per word
+//   topk_clear_kept_kernel  (one-call sparsify + compress) the residual of the
+//                       kept blocks becomes zero once the codec has read acc there
 // No kernel waits for another workgroup.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -58,7 +62,7 @@ struct TopkWorker {
 
 struct TopkBatch {
   TopkWorker w[S2R_MAX_WORKERS];
-  char* workspace;           // W chunks of ws_stride bytes: keys u64[nb] | histogram u32[kBins] | TopkState
+  char* workspace;           // W chunks of ws_stride bytes: keys u64[nb] | histograms u32[kPasses][kBins] | TopkState[kPasses + 1]
   uint64_t ws_stride;
   uint64_t hist_off, state_off;
   uint64_t n;
@@ -94,10 +98,10 @@ __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
   const TopkWorker P = B.w[k];
   uint64_t* keys = ws_keys(B, k);
   if (blockIdx.x == 0) {
-    uint32_t* hist = ws_hist(B, k);
-    for (uint32_t b = threadIdx.x; b < kBins; b += kBlock) hist[b] = 0u;
+    uint32_t* hist = ws_hist(B, k);                         // one histogram per pass of the select
+    for (uint32_t b = threadIdx.x; b < kPasses * kBins; b += kBlock) hist[b] = 0u;
     if (threadIdx.x == 0) {
-      TopkState* st = ws_state(B, k);
+      TopkState* st = ws_state(B, k);                       // state[p]: after the digits of passes 0 .. p-1
       st->prefix = 0ull;
       st->remaining = B.K;
     }
@@ -177,10 +181,10 @@ __global__ __launch_bounds__(kBlock) void topk_score_vec_kernel(const TopkBatch 
   const TopkWorker P = B.w[k];
   uint64_t* keys = ws_keys(B, k);
   if (blockIdx.x == 0) {
-    uint32_t* hist = ws_hist(B, k);
-    for (uint32_t b = threadIdx.x; b < kBins; b += kBlock) hist[b] = 0u;
+    uint32_t* hist = ws_hist(B, k);                         // one histogram per pass of the select
+    for (uint32_t b = threadIdx.x; b < kPasses * kBins; b += kBlock) hist[b] = 0u;
     if (threadIdx.x == 0) {
-      TopkState* st = ws_state(B, k);
+      TopkState* st = ws_state(B, k);                       // state[p]: after the digits of passes 0 .. p-1
       st->prefix = 0ull;
       st->remaining = B.K;
     }
@@ -250,15 +254,63 @@ __global__ __launch_bounds__(kBlock) void topk_score_vec_kernel(const TopkBatch 
   }
 }
 
+// The digit of pass `pass` from that pass's complete histogram: the digit d with
+// (keys above d) < remaining <= (keys above d) + (keys in d), appended to the
+// state before the pass.  All kHistBlock threads of a workgroup call it (thread
+// t looks at bins 2t and 2t + 1); every thread gets the new state.  Keys are
+// distinct and remaining <= number of keys, so exactly one bin qualifies.
+__device__ __forceinline__ TopkState pick_digit(const uint32_t* __restrict__ hist, const TopkState prev, uint32_t pass,
+                                                uint32_t* s_wave, TopkState* s_out) {
+  constexpr int kWaves = kHistBlock / kWave;
+  const uint32_t lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+  const uint32_t c0 = hist[2 * threadIdx.x], c1 = hist[2 * threadIdx.x + 1];   // bins 2t, 2t + 1
+  const uint32_t sum = c0 + c1;
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  if (threadIdx.x == 0) *s_out = prev;                     // stays if there is nothing to find
+  __syncthreads();
+  uint32_t before = incl - sum, total = 0;                 // keys in bins below 2t; all keys counted
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) {
+    const uint32_t x = s_wave[q];
+    if ((uint32_t)q < wv) before += x;
+    total += x;
+  }
+  if (prev.remaining != 0 && prev.remaining <= total) {
+    const uint64_t above1 = total - before - sum;          // keys in bins above 2t + 1
+    const uint64_t above0 = above1 + c1;                   // keys in bins above 2t
+    if (above1 < prev.remaining && prev.remaining <= above1 + c1) {
+      s_out->prefix = prev.prefix | ((uint64_t)(2 * threadIdx.x + 1) << kShift[pass]);
+      s_out->remaining = prev.remaining - above1;
+    } else if (above0 < prev.remaining && prev.remaining <= above0 + c0) {
+      s_out->prefix = prev.prefix | ((uint64_t)(2 * threadIdx.x) << kShift[pass]);
+      s_out->remaining = prev.remaining - above0;
+    }
+  }
+  __syncthreads();
+  return *s_out;
+}
+
 // Histogram of digit `pass` over the keys that share the digits found so far.
+// Every workgroup first works out the digit of the pass before from that pass's
+// histogram (complete: it was another launch), which spares a launch per pass;
+// workgroup 0 also records the state for the next launch.
 __global__ __launch_bounds__(kHistBlock) void topk_hist_kernel(const TopkBatch B, uint32_t pass) {
   __shared__ uint32_t s_hist[kBins];
+  __shared__ uint32_t s_wave[kHistBlock / kWave];
+  __shared__ TopkState s_state;
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
   for (uint32_t b = threadIdx.x; b < kBins; b += kHistBlock) s_hist[b] = 0u;
+  TopkState* state = ws_state(B, k);
+  TopkState st = state[0];
+  if (pass > 0) {
+    st = pick_digit(ws_hist(B, k) + (size_t)(pass - 1) * kBins, state[pass - 1], pass - 1, s_wave, &s_state);
+    if (blockIdx.x == 0 && threadIdx.x == 0) state[pass] = st;
+  }
   __syncthreads();
   const uint64_t* __restrict__ keys = ws_keys(B, k);
-  const uint64_t prefix = ws_state(B, k)->prefix;
+  const uint64_t prefix = st.prefix;
   const uint32_t shift = kShift[pass], above = shift + kWidth[pass];
   const uint32_t mask = (1u << kWidth[pass]) - 1u;
   uint64_t key[kHistPer];
@@ -274,46 +326,22 @@ __global__ __launch_bounds__(kHistBlock) void topk_hist_kernel(const TopkBatch B
       __hip_atomic_fetch_add(&s_hist[(uint32_t)(key[u] >> shift) & mask], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
   __syncthreads();
-  uint32_t* hist = ws_hist(B, k);
+  uint32_t* hist = ws_hist(B, k) + (size_t)pass * kBins;
   for (uint32_t b = threadIdx.x; b < kBins; b += kHistBlock)
     if (s_hist[b] != 0u) atomicAdd(&hist[b], s_hist[b]);
 }
 
-// One workgroup per worker: the digit d with (keys above d) < remaining <= (keys
-// above d) + (keys in d); the histogram is cleared for the next pass.
-__global__ __launch_bounds__(kHistBlock) void topk_pick_kernel(const TopkBatch B, uint32_t pass) {
-  constexpr int kWaves = kHistBlock / kWave;
-  __shared__ uint32_t s_wave[kWaves];
+// One workgroup per worker, after the last pass: its digit completes the K-th
+// largest key, state[kPasses].prefix, the threshold the later kernels compare with.
+__global__ __launch_bounds__(kHistBlock) void topk_pick_kernel(const TopkBatch B) {
+  __shared__ uint32_t s_wave[kHistBlock / kWave];
+  __shared__ TopkState s_state;
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
-  const uint32_t lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-  uint32_t* hist = ws_hist(B, k);
-  TopkState* st = ws_state(B, k);
-  const uint64_t remaining = st->remaining;
-  const uint32_t c0 = hist[2 * threadIdx.x], c1 = hist[2 * threadIdx.x + 1];   // bins 2t, 2t + 1
-  const uint32_t sum = c0 + c1;
-  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
-  if (lane == kWave - 1) s_wave[wv] = incl;
-  __syncthreads();
-  uint32_t before = incl - sum, total = 0;                 // keys in bins below 2t; all keys counted
-#pragma unroll
-  for (int q = 0; q < kWaves; ++q) {
-    const uint32_t x = s_wave[q];
-    if ((uint32_t)q < wv) before += x;
-    total += x;
-  }
-  hist[2 * threadIdx.x] = 0u;
-  hist[2 * threadIdx.x + 1] = 0u;
-  if (remaining == 0 || remaining > total) return;         // nothing to find (the host does not launch such a case)
-  const uint64_t above1 = total - before - sum;            // keys in bins above 2t + 1
-  const uint64_t above0 = above1 + c1;                     // keys in bins above 2t
-  if (above1 < remaining && remaining <= above1 + c1) {
-    st->prefix |= (uint64_t)(2 * threadIdx.x + 1) << kShift[pass];
-    st->remaining = remaining - above1;
-  } else if (above0 < remaining && remaining <= above0 + c0) {
-    st->prefix |= (uint64_t)(2 * threadIdx.x) << kShift[pass];
-    st->remaining = remaining - above0;
-  }
+  TopkState* state = ws_state(B, k);
+  const TopkState st = pick_digit(ws_hist(B, k) + (size_t)(kPasses - 1) * kBins, state[kPasses - 1], kPasses - 1, s_wave,
+                                  &s_state);
+  if (threadIdx.x == 0) state[kPasses] = st;
 }
 
 // Four consecutive elements per thread.  `all` / `none` bypass the threshold
@@ -326,7 +354,7 @@ __global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, u
   if (k >= B.nworkers) return;
   const TopkWorker P = B.w[k];
   const uint64_t* __restrict__ keys = ws_keys(B, k);
-  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
+  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)[kPasses].prefix;
   const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * kApplyPer;
   if (i0 >= B.n) return;
   float a[kApplyPer];
@@ -379,7 +407,7 @@ __global__ __launch_bounds__(kBlock) void topk_apply_kernel(const TopkBatch B, u
 // and the ballot is the word.
 __device__ __forceinline__ uint64_t kept_word(const TopkBatch& B, uint32_t k, uint64_t wd, uint32_t all, uint32_t none) {
   const uint64_t* __restrict__ keys = ws_keys(B, k);
-  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)->prefix;
+  const uint64_t T = all ? 0ull : none ? ~0ull : ws_state(B, k)[kPasses].prefix;
   const uint64_t x = wd * 64 + (threadIdx.x & (kWave - 1));
   return __ballot(x < B.nb && keys[x] >= T);
 }
@@ -423,7 +451,9 @@ __global__ __launch_bounds__(kBlock) void topk_clear_kept_kernel(const TopkBatch
 }
 
 static inline size_t keys_bytes(uint64_t nb) { return align256((size_t)nb * sizeof(uint64_t)); }
-static inline size_t workspace_each(uint64_t nb) { return keys_bytes(nb) + align256(kBins * sizeof(uint32_t)) + 256; }
+static inline size_t hist_bytes() { return align256((size_t)kPasses * kBins * sizeof(uint32_t)); }
+static inline size_t workspace_each(uint64_t nb) { return keys_bytes(nb) + hist_bytes() + 256; }
+static_assert((kPasses + 1) * sizeof(TopkState) <= 256, "the states share one 256-byte part of the workspace");
 static inline bool sizes_ok(uint64_t n, uint32_t block) {
   return n >= 1 && n <= (1ull << 32) && block >= 1 && (uint64_t)block <= (1ull << 31);
 }
@@ -455,7 +485,7 @@ static s2r_status fill_batch(TopkBatch& B, const float* const* grads, float* con
   B.workspace = reinterpret_cast<char*>(workspace);
   B.ws_stride = ws_each;
   B.hist_off = keys_bytes(nb);
-  B.state_off = B.hist_off + align256(kBins * sizeof(uint32_t));
+  B.state_off = B.hist_off + hist_bytes();
   B.n = n;
   B.nb = nb;
   B.K = K > nb ? nb : K;
@@ -487,9 +517,9 @@ static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream
     for (uint32_t pass = 0; pass < (uint32_t)kPasses; ++pass) {
       hipLaunchKernelGGL(topk_hist_kernel, dim3(hist_blocks, W), dim3(kHistBlock), 0, st, B, pass);
       if (!launch_ok()) return S2R_ERR_LAUNCH;
-      hipLaunchKernelGGL(topk_pick_kernel, dim3(1, W), dim3(kHistBlock), 0, st, B, pass);
-      if (!launch_ok()) return S2R_ERR_LAUNCH;
     }
+    hipLaunchKernelGGL(topk_pick_kernel, dim3(1, W), dim3(kHistBlock), 0, st, B);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
   return S2R_OK;
 }
