@@ -673,6 +673,34 @@ def test_topk_error_feedback_over_steps_feeds_the_codec():
         assert np.array_equal(bb.out_blk[:cnt].cpu().numpy(), np.flatnonzero(union))
 
 
+def _check_fused_worker(k, g, e, B, K, d, w, seed, bitmap, blk, cap, nblk, sketch, resid):
+    """One worker's outputs of s2r_topk_encode_blocks_batch against the oracle (see _fused_topk_check)."""
+    n = len(g)
+    nb = (n + B - 1) // B
+    ref = orc.topk_encode_blocks(g, e, B, K, d, w, seed)
+    mask = orc.unpack_bitmap(pipeline.u64(bitmap), nb)
+    assert int(mask.sum()) == min(K, nb) == nblk, f"worker {k}: kept {int(mask.sum())} blocks"
+    got = np.flatnonzero(mask)
+    if np.array_equal(got, ref["blocks"]):
+        S, M, want_e = ref["S"], ref["M"], ref["residual"]
+        assert np.array_equal(pipeline.u64(bitmap), ref["bitmap"])
+    else:
+        acc = g if e is None else (g + e).astype(np.float32)
+        sc = orc.block_scores(acc, B).astype(np.float64)
+        lo, hi = sc[mask].min(), sc[~mask].max()
+        assert hi <= lo * (1 + 2.0 ** -22), f"worker {k}: a kept block scores {lo}, a dropped one {hi}"
+        elem = np.repeat(mask, B)[:n]
+        S, M = orc.insert(*orc.sparse_of(np.where(elem, acc, np.float32(0.0)).astype(np.float32)), d, w, seed)
+        want_e = np.where(elem, np.float32(0.0), acc).astype(np.float32)
+    if blk is not None:
+        m = min(cap, len(got))
+        assert np.array_equal(blk[:m].cpu().numpy().view(np.uint32), got[:m].astype(np.uint32)), f"worker {k} list"
+        assert (blk[m:].cpu().numpy() == -1).all(), "entries beyond the count are not written"
+    _check_sketch(sketch.cpu().numpy(), S, M, f"worker {k} sketch")
+    if e is not None:
+        assert np.array_equal(resid.cpu().numpy().view(np.uint32), want_e.view(np.uint32)), f"worker {k} residual"
+
+
 def _fused_topk_check(gs, es, B, K, d, w, seed=0, cap=None, lists=True):
     """Runs s2r_topk_encode_blocks_batch and checks bitmap, block list, sketch and residual
     against the oracle's pieces for the set of blocks the library kept (which must be the
@@ -693,29 +721,8 @@ def _fused_topk_check(gs, es, B, K, d, w, seed=0, cap=None, lists=True):
     binding.topk_encode_blocks_batch(grads, resid, n, B, K, d, w, seed, sketch, bitmap, blk, nblk, ws)
     torch.cuda.synchronize()
     for k in range(W):
-        ref = orc.topk_encode_blocks(gs[k], None if es is None else es[k], B, K, d, w, seed)
-        tk = orc.topk_blocks(gs[k], None if es is None else es[k], B, K)
-        mask = orc.unpack_bitmap(pipeline.u64(bitmap[k]), nb)
-        assert int(mask.sum()) == min(K, nb) == int(nblk[k].cpu()), f"worker {k}: kept {int(mask.sum())} blocks"
-        got = np.flatnonzero(mask)
-        acc = tk["acc"]
-        if np.array_equal(got, ref["blocks"]):
-            S, M, want_e = ref["S"], ref["M"], ref["residual"]
-            assert np.array_equal(pipeline.u64(bitmap[k]), ref["bitmap"])
-        else:
-            sc = tk["score"].astype(np.float64)
-            lo, hi = sc[mask].min(), sc[~mask].max()
-            assert hi <= lo * (1 + 2.0 ** -22), f"worker {k}: a kept block scores {lo}, a dropped one {hi}"
-            elem = np.repeat(mask, B)[:n]
-            S, M = orc.insert(*orc.sparse_of(np.where(elem, acc, np.float32(0.0)).astype(np.float32)), d, w, seed)
-            want_e = np.where(elem, np.float32(0.0), acc).astype(np.float32)
-        if lists:
-            m = min(cap, len(got))
-            assert np.array_equal(blk[k][:m].cpu().numpy().view(np.uint32), got[:m].astype(np.uint32)), f"worker {k} list"
-            assert (blk[k][m:].cpu().numpy() == -1).all(), "entries beyond the count are not written"
-        _check_sketch(sketch[k].cpu().numpy(), S, M, f"worker {k} sketch")
-        if es is not None:
-            assert np.array_equal(resid[k].cpu().numpy().view(np.uint32), want_e.view(np.uint32)), f"worker {k} residual"
+        _check_fused_worker(k, gs[k], None if es is None else es[k], B, K, d, w, seed, bitmap[k], blk[k] if lists else None,
+                            cap, int(nblk[k].cpu()), sketch[k], None if es is None else resid[k])
         assert np.array_equal(grads[k].cpu().numpy().view(np.uint32), gs[k].view(np.uint32)), "the gradient is an input"
 
 
@@ -743,6 +750,31 @@ def test_fused_topk_short_lists_no_lists_no_residual_and_zero_blocks(strategy):
     sparse[B * 40: B * 43] = rng.normal(0, 1, 3 * B).astype(np.float32)
     sparse[B * 41 + 5] = 0.0                                               # a zero inside a kept block is not inserted
     _fused_topk_check([sparse], [np.zeros(n, dtype=np.float32)], B, 9, 3, 1 << 12)   # six all-zero blocks kept and marked
+
+
+def test_fused_topk_full_size_in_the_benchmarked_configuration():
+    """The shape bench.py --workload cfg3 --block 256 --topk-frac 0.01 --fused-topk times
+    (W = 8 dense gradients of 25.6e6 elements, 1000 of 100000 blocks kept), second step
+    (residuals in place): two of the eight workers against the oracle."""
+    W, n, B, K, d, w, seed = 8, 25_600_000, 256, 1000, 3, 1 << 20, 0
+    nb = n // B
+    dev = "cuda"
+    gen = torch.Generator(device=dev).manual_seed(3998)
+    grads = [torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 0.01, generator=gen) for _ in range(W)]
+    resid = [torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 0.004, generator=gen) for _ in range(W)]
+    check = (0, 5)
+    gs = {k: grads[k].cpu().numpy() for k in check}
+    es = {k: resid[k].cpu().numpy().copy() for k in check}
+    bb = pipeline.BlockBuffers(W, n, B, d, w, seed, K, W * K)
+    for t in bb.blk_idx:
+        t.fill_(-1)
+    print(f"[case] fused top-k full size W={W} n={n} B={B} K={K}", flush=True)
+    bb.topk_encode_all(grads, resid, K)
+    torch.cuda.synchronize()
+    assert (bb.nblk.cpu().numpy() == K).all()
+    for k in check:
+        _check_fused_worker(k, gs[k], es[k], B, K, d, w, seed, bb.bitmap[k], bb.blk_idx[k], K, int(bb.nblk[k].cpu()),
+                            bb.sketch[k], resid[k])
 
 
 def test_fused_topk_equals_the_two_calls():
