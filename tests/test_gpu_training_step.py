@@ -166,3 +166,44 @@ def test_sparsified_training_with_residuals_descends_like_dense_training():
     assert wide < 0.15 * start, "Top-K with residuals and a roomy sketch must follow dense training"
     assert wide < 6 * dense
     assert narrow < 0.5 * start, "a sketch far below the union still descends"
+
+
+def test_fused_training_step_replays_from_a_captured_graph():
+    """sparsify + compress, merge and the block update only enqueue kernels, so a caller
+    can capture a whole parameter update into a HIP graph.  Two identical optimisers are
+    fed the same gradients, one stepping eagerly, one by graph replays (with eager work and
+    synchronisations in between): kept blocks and residuals must agree exactly, parameters
+    up to the summation order of the sketch cells."""
+    W, n, B, K, d, w = 3, 1 << 18, 128, 64, 3, 1 << 14
+    dev = "cuda"
+    eager = pipeline.SparsifiedStep(W, n, B, K, d, w, seed=1)
+    replayed = pipeline.SparsifiedStep(W, n, B, K, d, w, seed=1)
+    gen = torch.Generator(device=dev).manual_seed(5)
+    grads = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(W)]      # fixed addresses for the graph
+    x_e = torch.zeros(n, dtype=torch.float32, device=dev)
+    x_g = torch.zeros(n, dtype=torch.float32, device=dev)
+    scale = -0.1 / W
+    warm = pipeline.SparsifiedStep(W, n, B, K, d, w, seed=1)
+    warm.step(grads, torch.zeros(n, dtype=torch.float32, device=dev), scale)         # raises the LDS limits outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        replayed.step(grads, x_g, scale, torch.cuda.current_stream())
+    for r in replayed.residual:                      # (the capture itself runs nothing, but start both from the same state)
+        r.zero_()
+    x_g.zero_()
+    for it in range(4):
+        for g in grads:
+            g.normal_(0, 1, generator=gen)
+        torch.cuda.synchronize()
+        eager.step(grads, x_e, scale)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(eager.count, replayed.count), f"replay {it}: set blocks"
+        for k in range(W):
+            assert torch.equal(eager.codec.bitmap[k], replayed.codec.bitmap[k]), f"replay {it}: bitmap {k}"
+            assert torch.equal(eager.residual[k].view(torch.int32), replayed.residual[k].view(torch.int32)), \
+                f"replay {it}: residual {k}"
+        assert torch.allclose(x_e, x_g, rtol=1e-4, atol=1e-6), f"replay {it}: parameters"
+        assert float(x_e.abs().max()) > 0
