@@ -927,6 +927,33 @@ def test_random_shapes(case):
         binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
 
 
+@pytest.mark.parametrize("case", range(16))
+def test_random_shapes_sparsify_compress_update(case):
+    """Seeded random problems through the one-call sparsifier + compress step and the
+    block-granular update: length, block size (multiples of 4 and not, below and above a
+    wave), kept fraction, rows, width, workers, with and without residuals and lists, gradients
+    with many exact zeros."""
+    rng = np.random.default_rng(12000 + case)
+    n = int(rng.choice([rng.integers(1, 500), rng.integers(500, 60000), rng.integers(60000, 300000)]))
+    B = int(rng.choice([1, 3, 4, 31, 32, 36, 64, 100, 256, 1000, 4096]))
+    nb = (n + B - 1) // B
+    K = int(rng.choice([0, 1, max(1, nb // 50), max(1, nb // 4), nb, nb + 5]))
+    d = int(rng.integers(1, 9))
+    w = 1 << int(rng.integers(0, 17))
+    W = int(rng.integers(1, 5))
+    zeros = float(rng.choice([0.0, 0.5, 0.98]))
+    gs = [(rng.normal(0, 1, n) * (rng.random(n) >= zeros)).astype(np.float32) for _ in range(W)]
+    es = None if case % 4 == 3 else [(rng.normal(0, 0.3, n) * (rng.random(n) >= zeros)).astype(np.float32) for _ in range(W)]
+    seed = int(rng.integers(0, 1 << 40))
+    binding.set_insert_strategy(STRATEGIES[["atomic", "slice"][case % 2]])
+    try:
+        kept = min(K, nb)
+        _fused_topk_check(gs, es, B, K, d, w, seed=seed, cap=[None, max(kept // 2, 1)][(case // 2) % 2], lists=(case % 5 != 4))
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+    _block_update_check(gs, B, d, w, seed, -0.01 * (1 + case % 3))
+
+
 def test_very_sparse_gradient_with_dense_pockets(strategy):
     """Forty tiles with a handful of non-zeros per 2048-element piece, one piece of exactly
     8, one of 9 and one full piece, a ragged last tile, and a list capacity that ends inside
