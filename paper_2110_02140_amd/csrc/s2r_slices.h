@@ -223,16 +223,19 @@ __global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch 
 
 // One workgroup per chunk of kBinChunk list items, one pass per sketch row j.  The
 // chunk's records for row j are first sorted by slice inside LDS (a counting
-// sort: LDS counters give every record its rank in its slice, a scan of the
-// counters gives the start of every slice's run) and then copied out in sorted
+// sort in two sweeps over the items: LDS counters count every slice's records,
+// a scan turns them into the start of every slice's run, and a second sweep
+// takes a place in the run with a fetch-and-add) and then copied out in sorted
 // order, so that consecutive lanes write consecutive records of the (chunk, bin)
-// run that the histogram pass reserved.  In LDS a record carries its slice number
-// in bits 16..28 of its first word (the cell takes bits 0..14, the sign bit 31).
-// Dynamic LDS: kBinChunk records, then two arrays of (slices per row) counters.
-__global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
+// run that the histogram pass reserved.  The hashes are computed in both sweeps
+// rather than kept: with few registers two workgroups share a compute unit and
+// one's barriers hide behind the other's work.  In LDS a record carries its slice
+// number in bits 16..28 of its first word (the cell takes bits 0..14, the sign
+// bit 31).  Dynamic LDS: kBinChunk records, then two arrays of (slices per row)
+// counters.
+__global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
   extern __shared__ uint2 s_stage[];
   constexpr int kWaves = kBinBlock / kWave;
-  constexpr int kMaxPer = kMaxBins / kBinBlock;           // counters per thread in the scan, at most
   __shared__ uint32_t s_wave[kWaves];
   const uint32_t k = blockIdx.y;
   if (k >= B.nworkers) return;
@@ -252,45 +255,35 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
   const uint32_t* bin_start = ws_bin_start(B, k);
   uint2* __restrict__ rec = ws_records(B, k);
   const uint32_t mask = (1u << B.slice_log2) - 1u;
-  const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan (<= kMaxPer)
+  const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan: thread t owns t*per ..
 
   uint32_t i[kBinItems], v[kBinItems];
-  bool ok[kBinItems];                                     // the item exists and takes part (see load_item)
+  uint32_t ok = 0;                                        // bit u: item u exists and takes part (see load_item)
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
     const uint32_t t = u * kBinBlock + threadIdx.x;
-    ok[u] = t < count && load_item(B, P, t0 + t, i[u], v[u]);
+    if (t < count && load_item(B, P, t0 + t, i[u], v[u])) ok |= 1u << u;
   }
   for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
 
   for (uint32_t j = 0; j < B.d; ++j) {
-    // where the runs of this (chunk, row) start in the worker's records; needed after the scan
-    uint32_t gpos[kMaxPer];
-#pragma unroll
-    for (int q = 0; q < kMaxPer; ++q) {
-      const uint32_t e = threadIdx.x * per + q;
-      gpos[q] = ((uint32_t)q < per && e < spr) ? bin_start[(j << spr_log2) + e] + hist[(j << spr_log2) + e] : 0u;
-    }
+    // where this thread's first run of this (chunk, row) starts in the worker's records: wanted after the
+    // scan, requested now (with at most 1024 slices per row it is the thread's only run)
+    const uint32_t own = threadIdx.x * per;
+    const uint32_t gpos0 = own < spr ? bin_start[(j << spr_log2) + own] + hist[(j << spr_log2) + own] : 0u;
     __syncthreads();                                      // s_loc is zero, s_stage is free
-    uint32_t key[kBinItems], rank[kBinItems];
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
-      if (ok[u]) {
-        const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
-        const uint32_t sl = h >> B.slice_log2;
-        key[u] = (h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]) | (sl << 16);
-        rank[u] = __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (ok >> u & 1u) {
+        const uint32_t sl = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2;
+        __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
     __syncthreads();
-    // exclusive scan of the counters; thread t owns counters t*per .. t*per + per - 1
-    uint32_t c[kMaxPer], sum = 0;
-#pragma unroll
-    for (int q = 0; q < kMaxPer; ++q) {
-      const uint32_t e = threadIdx.x * per + q;
-      c[q] = ((uint32_t)q < per && e < spr) ? s_loc[e] : 0u;
-      sum += c[q];
-    }
+    // exclusive scan of the counters
+    uint32_t sum = 0;
+    for (uint32_t q = 0; q < per; ++q)
+      if (own + q < spr) sum += s_loc[own + q];
     const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
     if (lane == kWave - 1) s_wave[wv] = incl;
     __syncthreads();
@@ -301,19 +294,26 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(const EncodeBatc
       if ((uint32_t)q < wv) run += x;
       records += x;
     }
-#pragma unroll
-    for (int q = 0; q < kMaxPer; ++q) {
-      const uint32_t e = threadIdx.x * per + q;
-      if ((uint32_t)q < per && e < spr) {
-        s_loc[e] = run;
-        s_delta[e] = gpos[q] - run;                       // sorted position p of slice e goes to record p + delta
-        run += c[q];
+    for (uint32_t q = 0; q < per; ++q) {
+      const uint32_t e = own + q;
+      if (e < spr) {
+        const uint32_t c = s_loc[e];
+        const uint32_t gpos = q == 0 ? gpos0 : bin_start[(j << spr_log2) + e] + hist[(j << spr_log2) + e];
+        s_loc[e] = run;                                   // the next free place of slice e's run
+        s_delta[e] = gpos - run;                          // sorted position p of slice e goes to record p + delta
+        run += c;
       }
     }
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
-      if (ok[u]) s_stage[s_loc[(key[u] >> 16) & 0x1FFFu] + rank[u]] = make_uint2(key[u], v[u]);
+      if (ok >> u & 1u) {
+        const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
+        const uint32_t sl = h >> B.slice_log2;
+        const uint32_t key = (h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]) | (sl << 16);
+        const uint32_t place = __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        s_stage[place] = make_uint2(key, v[u]);
+      }
     }
     __syncthreads();
     for (uint32_t p = threadIdx.x; p < records; p += kBinBlock) {
