@@ -214,11 +214,16 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   extern __shared__ float s_cells[];
   constexpr int kAhead = 4;
   const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
-  const uint32_t first = A.bin_start[bin], last = A.bin_start[bin + 1];
-  if (first == last) return;                              // uniform over the workgroup
+  const uint32_t first = A.bin_start[bin], bin_last = A.bin_start[bin + 1];
+  // the bin's queries are shared out between the gridDim.y workgroups of the bin (each loads the slice):
+  // consecutive ranges of a multiple of kSliceBlock queries
+  const uint64_t share = ((((uint64_t)bin_last - first + gridDim.y - 1) / gridDim.y + kSliceBlock - 1) / kSliceBlock) * kSliceBlock;
+  const uint64_t mine = (uint64_t)first + blockIdx.y * share;
+  if (mine >= bin_last) return;                           // uniform over the workgroup (also: an empty bin)
+  const uint64_t last = mine + share < bin_last ? mine + share : bin_last;
   const u32x2 none = {0u, 0u};
   u32x2 x[kAhead];                                        // the first queries are requested together with the slice
-  uint64_t r0 = (uint64_t)first + threadIdx.x;
+  uint64_t r0 = mine + threadIdx.x;
 #pragma unroll
   for (int u = 0; u < kAhead; ++u)
     x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r0 + u * kSliceBlock]) : none;

@@ -658,7 +658,13 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (X.log2w - X.slice_log2));
     hipLaunchKernelGGL(bin_scatter_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), scatter_lds, st, X, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(decode_slice_kernel, dim3(L.nbins), dim3(kSliceBlock), sizeof(float) << L.slice_log2, st, Q);
+    // one workgroup per compute unit at a time (the slice fills its LDS): with few bins, several workgroups
+    // share a bin's queries so that the last round of workgroups is not mostly idle units
+    const uint64_t per_bin = cap_items * d / L.nbins;      // at most, on average
+    uint32_t parts = L.nbins >= 512 ? 1u : (uint32_t)ceil_div(768, L.nbins);   // (two rounds and more: no gain measured)
+    while (parts > 1 && per_bin / parts < 16384) --parts;
+    if (parts > 8) parts = 8;
+    hipLaunchKernelGGL(decode_slice_kernel, dim3(L.nbins, parts), dim3(kSliceBlock), sizeof(float) << L.slice_log2, st, Q);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const dim3 mgrid(L.nchunks), mblock(kBinBlock);
     switch (d) {
