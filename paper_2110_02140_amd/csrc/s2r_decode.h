@@ -194,8 +194,7 @@ struct DecodeSliceArgs {
   const u32x2* rec;          // queries sorted by bin: (cell in slice | sign bit, list position)
   uint2* answers;            // [nchunks][d][kBinChunk]-shaped regions, see above
   const uint32_t* bin_start; // [nbins + 1]
-  const uint32_t* colpre;    // [nchunks][nbins]: queries of the bin in earlier chunks
-  const uint32_t* rowpre;    // [nchunks][nbins]: queries of the chunk in earlier bins
+  const uint32_t* place;     // [nchunks][nbins]: rank in the bin + this = place of the answer (bin_colscan_kernel)
   const uint64_t* count;     // the union count (device)
   uint64_t cap;
   float* val_out;
@@ -239,24 +238,21 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   while (r0 < last) {                                     // x holds the queries r0 + u * kSliceBlock
     const uint64_t r1 = r0 + kSliceBlock * kAhead;
     u32x2 y[kAhead];
-    uint32_t colp[kAhead], rowp[kAhead];
+    uint32_t place[kAhead];
 #pragma unroll
     for (int u = 0; u < kAhead; ++u)
       y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r1 + u * kSliceBlock]) : none;
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
       const uint64_t at = (uint64_t)(x[u].y >> kBinChunkLog2) * A.nbins + bin;
-      const bool live = r0 + u * kSliceBlock < last;
-      colp[u] = live ? A.colpre[at] : 0u;
-      rowp[u] = live ? A.rowpre[at] : 0u;
+      place[u] = r0 + u * kSliceBlock < last ? A.place[at] : 0u;
     }
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
       const uint64_t r = r0 + u * kSliceBlock;
       if (r >= last) continue;
       const uint32_t est = __float_as_uint(s_cells[x[u].x & 0x7FFFFFFFu]) ^ (x[u].x & 0x80000000u);
-      const uint64_t chunk = x[u].y >> kBinChunkLog2;
-      const uint64_t at = chunk * kBinChunk * A.d + rowp[u] + (uint32_t)(r - first - colp[u]);
+      const uint32_t at = (uint32_t)(r - first) + place[u];          // modulo 2^32, see bin_colscan_kernel
       A.answers[at] = make_uint2(est, x[u].y & (kBinChunk - 1));
     }
 #pragma unroll

@@ -182,8 +182,8 @@ static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t c
   const uint32_t log2w = log2_of(w);
   L.slice_log2 = log2w < (uint32_t)kDecodeSliceLog2Max ? log2w : (uint32_t)kDecodeSliceLog2Max;
   const uint64_t nbins = (uint64_t)d << (log2w - L.slice_log2);
-  L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0 &&
-               d <= (uint32_t)kDecodeSliceMaxRows;
+  L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * (cap + kBinChunk) < (1ull << 32) && cap > 0 &&
+               d <= (uint32_t)kDecodeSliceMaxRows;                 // (places of answers are 32-bit)
   L.nbins = (uint32_t)(L.possible ? nbins : 0);
   L.nchunks = (uint32_t)(L.possible ? ceil_div(cap, kBinChunk) : 0);
   const size_t matrix = align256((size_t)L.nchunks * L.nbins * sizeof(uint32_t));
@@ -633,8 +633,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     Q.rec = reinterpret_cast<const u32x2*>(ws + L.rec_off);
     Q.answers = reinterpret_cast<uint2*>(ws + L.answers_off);
     Q.bin_start = reinterpret_cast<const uint32_t*>(ws + L.binstart_off);
-    Q.colpre = reinterpret_cast<const uint32_t*>(ws + L.hist_off);
-    Q.rowpre = reinterpret_cast<const uint32_t*>(ws + L.rowpre_off);
+    Q.place = reinterpret_cast<const uint32_t*>(ws + L.rowpre_off);
     Q.count = count_out;
     Q.cap = cap;
     Q.val_out = val_out;

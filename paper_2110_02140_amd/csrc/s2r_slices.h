@@ -170,13 +170,24 @@ __global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatc
     if ((uint32_t)q < wv) run += x;
     total += x;
   }
+  // decode: rowpre[c][b] (queries of chunk c in bins before b) becomes what decode_slice_kernel adds to a
+  // query's rank in its bin to get the place of its answer: the start of chunk c's answers, plus rowpre,
+  // minus the bin's queries in earlier chunks (modulo 2^32; the places themselves are below 2^32)
+  uint32_t* rowpre = B.rowpre_off != 0 ? reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) : nullptr;
   for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
-    uint32_t v[kAhead];
-#pragma unroll
-    for (uint32_t q = 0; q < kAhead; ++q) v[q] = (live && c0 + q < c_end) ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+    uint32_t v[kAhead], rp[kAhead];
 #pragma unroll
     for (uint32_t q = 0; q < kAhead; ++q) {
-      if (live && c0 + q < c_end) hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
+      const bool in = live && c0 + q < c_end;
+      v[q] = in ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+      rp[q] = in && rowpre != nullptr ? rowpre[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) {
+      if (live && c0 + q < c_end) {
+        hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
+        if (rowpre != nullptr) rowpre[(uint64_t)(c0 + q) * B.nbins + b] = (c0 + q) * (uint32_t)kBinChunk * B.d + rp[q] - run;
+      }
       run += v[q];
     }
   }
