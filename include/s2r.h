@@ -215,7 +215,7 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
  *
  * s2r_blocks_workspace_bytes: the least scratch for s2r_encode_blocks* and
  * s2r_decode_blocks; the other two: what lets them also use S2R_INSERT_SLICE /
- * S2R_DECODE_SLICE for lists of blk_cap blocks (needs d * blk_cap * block < 2^32).
+ * S2R_DECODE_SLICE for lists of blk_cap blocks (needs d * (blk_cap * block + 8192) < 2^32).
  * Host only; 0 outside the limits or if blk_cap > nb.
  */
 size_t s2r_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w);
@@ -434,7 +434,7 @@ s2r_status s2r_set_insert_strategy(int32_t strategy);
  *                      slice of one sketch row in LDS answer them; the answers
  *                      return to list order through LDS and meet in the median.
  *                      Needs idx_out / val_out, no dense_out, d <= 8,
- *                      d*w <= 2^27, d*cap < 2^32 and a workspace of
+ *                      d*w <= 2^27, d*(cap + 8192) < 2^32 and a workspace of
  *                      s2r_decode_workspace_bytes (otherwise s2r_decode gathers
  *                      whatever is set here)
  *   S2R_DECODE_AUTO    (default) chosen from d, w and cap, the capacity of the
