@@ -589,6 +589,8 @@ s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const*
     if (sketches[k] == nullptr || (blk_idx != nullptr && blk_idx[k] == nullptr)) return S2R_ERR_NULL;
     if (((uintptr_t)sketches[k] & 15u) || (blk_idx != nullptr && ((uintptr_t)blk_idx[k] & 3u))) return S2R_ERR_ALIGN;
   }
+  if (blk_idx == nullptr) blk_cap = 0;
+  if (blk_cap > ceil_div(n, block)) blk_cap = ceil_div(n, block);    // there cannot be more list entries than blocks
   const size_t select_each = s2r_topk_workspace_bytes(n, block);
   const size_t codec_each = s2r_encode_blocks_workspace_bytes(n, block, d, w, blk_cap);
   if (select_each == 0 || codec_each == 0) return S2R_ERR_SIZE;
