@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kBlock) void topk_score_kernel(const TopkBatch B) {
 // of a gradient whose length is not a multiple of 4 ends in a chunk that is read
 // and written element by element.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-constexpr int kVecTrips = 2;
+constexpr int kVecTrips = 1;
 
 template <bool STORE>
 __global__ __launch_bounds__(kBlock) void topk_score_vec_kernel(const TopkBatch B) {
