@@ -297,6 +297,24 @@ def test_estimate_is_unbiased_over_seeds():
     assert errs.std() > 0.0             # collisions do happen at this width
 
 
+def test_single_row_error_variance_is_the_others_energy_over_the_width():
+    """With one row the error of element j is sum_{i != j} Phi(i, j) g(i), and by the
+    proof of Theorem 1 Phi(i, j) is +1 or -1 with probability 0.5 / m each, independently
+    enough over pairs that the variance is sum_{i != j} g(i)^2 / m."""
+    rng = np.random.default_rng(51)
+    n, w, nseeds = 40, 8, 6000
+    g = rng.normal(0, 1.0, size=n).astype(np.float32)
+    errs = np.zeros((nseeds, n))
+    for s in range(nseeds):
+        enc = orc.encode(g, 1, w, s)
+        errs[s] = orc.decode(enc["S"], enc["bitmap"], n, s)["val"] - g.astype(np.float64)
+    energy = float(np.sum(g.astype(np.float64) ** 2))
+    want = (energy - g.astype(np.float64) ** 2) / w
+    got = errs.var(axis=0)
+    assert np.all(np.abs(got / want - 1.0) < 0.12), f"worst ratio {np.max(np.abs(got / want - 1.0)):.3f}"
+    assert abs(got.sum() / want.sum() - 1.0) < 0.03
+
+
 def test_collision_probabilities():
     """Two fixed distinct indices share a bucket with probability 1/m, and then
     agree / disagree in sign with probability 1/2 each (proof of Theorem 1)."""
