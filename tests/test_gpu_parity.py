@@ -344,6 +344,28 @@ def test_null_lists_and_in_place_merge():
     assert int(b.out_count.cpu()[0]) == len(dec["idx"])
 
 
+@pytest.mark.parametrize("cfg", [1, 3])
+def test_merge_with_bitmaps_at_8_byte_offsets_and_odd_word_counts(cfg):
+    """Bitmaps need 8-byte alignment only: s2r_merge on views that start 8 bytes into their
+    allocations, with an odd and an even number of words, writes exactly the words it owns."""
+    wl = workloads.make_small(cfg)
+    enc, S, C, M, dec = _oracle_for(wl)
+    nw = pipeline.words_of(wl.n)
+    b = pipeline.buffers_for(wl)
+    b.encode_all()
+    for shift in (0, 1):                                   # shift 1: views that start 8 bytes into an allocation
+        hold = [torch.zeros(nw + 2, dtype=torch.int64, device="cuda") for _ in range(wl.W + 1)]
+        views = [h[shift:shift + nw] for h in hold]
+        for k in range(wl.W):
+            views[k].copy_(b.bitmap[k])
+        assert all((v.data_ptr() % 16 == 8) == bool(shift) for v in views)
+        binding.merge(b.sketch, views[:wl.W], wl.n, wl.d, wl.w, wl.seed, b.sketch_sum, views[wl.W])
+        torch.cuda.synchronize()
+        assert np.array_equal(pipeline.u64(views[wl.W].contiguous()), C), f"shift {shift}, {nw} words"
+        for h in hold:                                     # nothing outside the nw words is written
+            assert int(h[:shift].abs().sum()) == 0 and int(h[shift + nw:].abs().sum()) == 0
+
+
 def test_linearity_on_device(strategy):
     """Sum of the workers' sketches == sketch of the summed gradient."""
     wl = workloads.make_small(2)
