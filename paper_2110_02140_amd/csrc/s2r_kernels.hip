@@ -257,7 +257,7 @@ using namespace s2r;
 
 extern "C" {
 
-int32_t s2r_version(void) { return 300; }
+int32_t s2r_version(void) { return 400; }
 
 const char* s2r_status_string(s2r_status status) {
   switch (status) {
