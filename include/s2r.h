@@ -299,10 +299,12 @@ s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap,
  *   kept_bitmap  dev, out   : ceil(ceil(n/block)/64) uint64 in the bitmap layout
  *                             of this file, bit x set iff block x is kept; or NULL
  *   workspace    dev scratch, 256-byte aligned, W * s2r_topk_workspace_bytes
- * The float64 sums are formed in an order of the library's choosing: two blocks
- * whose sums of squares differ by less than a float64 rounding may swap places
- * against another summation order; everything else is bit-exact.  Inputs are
- * expected to be finite.  Limits: 1 <= n <= 2^32, 1 <= block <= 2^31 (blocks of
+ * A score is the float64 sum rounded once to float32; equal scores are ordered by
+ * lower block index.  The float64 sum is formed in an order of the library's
+ * choosing, so against another summation order a score can differ by one
+ * float32 rounding where the sum lies at a rounding boundary: only a kept and
+ * a dropped block whose scores are within one float32 rounding of each other
+ * may swap; everything else is bit-exact.  Inputs are expected to be finite.  Limits: 1 <= n <= 2^32, 1 <= block <= 2^31 (blocks of
  * more than a few thousand elements are served by one wave each).  The batch
  * form takes host arrays of W device pointers (residuals and kept_bitmaps may be
  * NULL as a whole).  Enqueues on stream and returns; errors as for s2r_encode.

@@ -65,7 +65,9 @@ not fed back (a worker cannot see it: the decoder returns the sum over workers).
 
 Parity pins: see tests/test_oracle_*.py.  No function in this file is unpinned,
 but the hash family itself is a reading (the paper names none); it is pinned to a
-big-integer re-statement and to the published SplitMix64 reference outputs.
+big-integer re-statement and to the published SplitMix64 reference outputs.  The
+mass table M and decode_tolerance_mass, which only scale the tests' float32
+tolerances, are pinned cell by cell to pure-Python loops as well.
 """
 
 from __future__ import annotations

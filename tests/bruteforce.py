@@ -61,6 +61,26 @@ def compress(g, d, w, seed):
     return flags, S
 
 
+def mass_table(g, d, w, seed):
+    """M[j][b] = sum of |g(i)| over the non-zero elements i that row j sends to bucket b:
+    the insertion loops of Algorithm 1 with |g(i)| in place of s_j(i) g(i)."""
+    M = [[0.0] * w for _ in range(d)]
+    P = params(seed, d)
+    for i, x in enumerate(g):
+        if is_nonzero(x):
+            for j in range(d):
+                a, b, _c, _e = P[j]
+                M[j][h(i, a, b, w)] += abs(x)
+    return M
+
+
+def largest_mass_of(i, M, seed):
+    """max over the rows j of M[j][h_j(i)]: the largest bucket mass that index i reads."""
+    d, w = len(M), len(M[0])
+    P = params(seed, d)
+    return max(M[j][h(i, P[j][0], P[j][1], w)] for j in range(d))
+
+
 def words_of(flags):
     n = len(flags)
     out = []

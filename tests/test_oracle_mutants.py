@@ -31,6 +31,8 @@ def _some_pin_fails():
         (pins.test_merged_bitmap_popcount_is_union_size, ()),
         (pins.test_single_element_gradient, ()),
         (pins.test_hash_params_order_and_oddness, ()),
+        (pins.test_mass_table_and_decode_tolerance_mass_match_pure_python, (3, 16, 1)),
+        (pins.test_mass_table_and_decode_tolerance_mass_match_pure_python, (5, 4, 3)),
         (pins.test_single_row_error_variance_is_the_others_energy_over_the_width, ()),
         (pins.test_block_algorithm_matches_pure_python, (7, 4, 32, 2)),
         (pins.test_block_sketch_equals_element_sketch_and_values_agree_on_the_union, ()),
@@ -233,7 +235,40 @@ def _mut_block_update_ignores_the_scale(monkeypatch):
     monkeypatch.setattr(orc, "decode_blocks_update", lambda S, bm, n, B, seed, p, scale: real(S, bm, n, B, seed, p, 1.0))
 
 
+def _mut_mass_table_inflated(monkeypatch):
+    real = orc.insert
+
+    def bad(idx, val, d, w, seed):
+        S, M = real(idx, val, d, w, seed)
+        return S, 100.0 * M                                                     # every tolerance 100 times too wide
+    monkeypatch.setattr(orc, "insert", bad)
+
+
+def _mut_tolerance_mass_sums_the_rows(monkeypatch):
+    def bad(M, idx, seed):
+        d, w = M.shape
+        m = np.zeros(idx.shape[0])
+        for j, (a, b, _c, _e) in enumerate(orc.hash_params(seed, d)):
+            m = m + M[j, orc.bucket_hash(idx, a, b, w)]                        # sum over the rows, not the largest
+        return m
+    monkeypatch.setattr(orc, "decode_tolerance_mass", bad)
+
+
+def _mut_mass_table_signed(monkeypatch):
+    def bad(idx, val, d, w, seed):
+        S = np.zeros((d, w))
+        M = np.zeros((d, w))
+        v = val.astype(np.float64)
+        for j, (a, b, c, e) in enumerate(orc.hash_params(seed, d)):
+            h = orc.bucket_hash(idx, a, b, w)
+            np.add.at(S[j], h, orc.sign_hash(idx, c, e) * v)
+            np.add.at(M[j], h, v)                                               # signs cancel inside the mass
+        return S, np.abs(M)
+    monkeypatch.setattr(orc, "insert", bad)
+
+
 @pytest.mark.parametrize("mutant", [
+    _mut_mass_table_inflated, _mut_tolerance_mass_sums_the_rows, _mut_mass_table_signed,
     _mut_sign_dropped_in_query, _mut_msb_first_bitmap, _mut_median_off_by_one,
     _mut_low_bits_bucket, _mut_sign_uses_bucket_multiplier, _mut_merge_xor,
     _mut_merge_drops_last_worker, _mut_negative_zero_counts,

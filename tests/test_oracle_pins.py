@@ -345,6 +345,33 @@ def test_mass_table_bounds_sketch():
     assert np.all(m >= np.abs(res["val"]) - 1e-18)
 
 
+@pytest.mark.parametrize("d,w,seed", [(1, 8, 0), (3, 16, 1), (4, 32, 2), (5, 4, 3), (2, 1, 4)])
+def test_mass_table_and_decode_tolerance_mass_match_pure_python(d, w, seed):
+    """The scale of every float32 tolerance: M[j, b] is the sum of |g(i)| over the
+    insertions that land in the cell (per worker, and summed over the workers for the
+    aggregate), and a decoded value is judged against the largest of the d masses its
+    index reads.  Both against Python loops, cell by cell and index by index."""
+    rng = np.random.default_rng(100 + seed)
+    n, W = 200, 3
+    gs = _tiny_grads(rng, W, n, 0.2, specials=True)
+    res = orc.reduce_workers(gs, d, w, seed)
+    Ms = [bf.mass_table([float(x) for x in g], d, w, seed) for g in gs]
+    for k in range(W):
+        assert np.allclose(res["workers"][k]["M"], np.array(Ms[k]), rtol=1e-15, atol=0)
+        idx, val = orc.sparse_of(gs[k])
+        assert np.allclose(orc.insert(idx, val, d, w, seed)[1], np.array(Ms[k]), rtol=1e-15, atol=0)
+    total = [[math.fsum(Ms[k][j][b] for k in range(W)) for b in range(w)] for j in range(d)]
+    assert np.allclose(res["M"], np.array(total), rtol=1e-15, atol=0)
+    got = orc.decode_tolerance_mass(res["M"], res["idx"], seed)
+    want = [bf.largest_mass_of(int(i), total, seed) for i in res["idx"]]
+    assert np.allclose(got, np.array(want), rtol=1e-15, atol=0)
+    # an index that no worker inserted reads masses too (whatever its buckets hold), and an empty list is fine
+    probe = np.array([0, 1, n - 1], dtype=np.uint32)
+    assert np.allclose(orc.decode_tolerance_mass(res["M"], probe, seed),
+                       np.array([bf.largest_mass_of(int(i), total, seed) for i in probe]), rtol=1e-15, atol=0)
+    assert orc.decode_tolerance_mass(res["M"], np.zeros(0, dtype=np.uint32), seed).shape == (0,)
+
+
 # ---------------------------------------------------------------- block-granular variant
 @pytest.mark.parametrize("B,d,w,seed", [(1, 3, 16, 0), (4, 3, 16, 1), (7, 4, 32, 2), (64, 5, 8, 3), (250, 2, 4, 4)])
 def test_block_algorithm_matches_pure_python(B, d, w, seed):
