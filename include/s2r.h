@@ -202,6 +202,29 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
                       void* stream);
 
 /*
+ * s2r_decode for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and errors as s2r_decode, without the
+ * workspace: the scratch (counts per 2048 bitmap bits, their prefix sums, the
+ * dense-tile list; under 448 KiB) is a static array in device memory that every
+ * GPU the library runs on holds until the process ends.  The call allocates
+ * nothing and frees nothing.  The bucket reads are gathers (S2R_DECODE_GATHER).
+ *   - n <= S2R_DECODE_NOALLOC_MAX_N, else S2R_ERR_SIZE (nothing is enqueued).
+ *   - All calls on one GPU share the one array: calls that overlap in time on one
+ *     GPU (different streams, or different host threads) race and must be
+ *     serialised by the caller.  Nothing in it has to be cleared between calls:
+ *     every call writes all the entries it later reads.
+ *   - S2R_ERR_LAUNCH if the runtime cannot give the array's device address.
+ */
+#define S2R_DECODE_NOALLOC_MAX_N (1ull << 27)
+s2r_status s2r_decode_noalloc(const float* sketch, const uint64_t* bitmap,
+                              uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                              uint32_t* idx_out, float* val_out, uint64_t cap,
+                              uint64_t* count_out,
+                              float* dense_out,
+                              void* stream);
+
+/*
  * Block-granular codec: the bitmap as Section 3.1 sizes it, one bit per word
  * vector or gradient block that tells whether the block holds a non-zero
  * gradient (the bitmap line of Algorithm 1 is written per block).  Block x is

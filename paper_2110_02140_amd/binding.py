@@ -56,6 +56,8 @@ SIGNATURES = {
     "s2r_decode": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
                              c_void_p, c_void_p, c_uint64, c_void_p, c_void_p,
                              c_void_p, c_size_t, c_void_p]),
+    "s2r_decode_noalloc": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
+                                     c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_void_p]),
     "s2r_decode_update": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64, c_void_p, ctypes.c_float,
                                     c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "s2r_set_kernel_events": (c_int32, [c_int32, c_void_p, c_void_p]),
@@ -207,6 +209,18 @@ def decode(sketch, bitmap, n, d, w, seed, idx_out, val_out, count_out, dense_out
                            workspace.numel() * workspace.element_size(), _stream(stream))
     if st != S2R_OK:
         raise S2RError(st, "s2r_decode")
+
+
+S2R_DECODE_NOALLOC_MAX_N = 1 << 27
+
+
+def decode_noalloc(sketch, bitmap, n, d, w, seed, idx_out, val_out, count_out, dense_out, stream=None):
+    """s2r_decode_noalloc: s2r_decode without a workspace (the library's static device scratch)."""
+    cap = 0 if idx_out is None else idx_out.numel()
+    st = load().s2r_decode_noalloc(_ptr(sketch), _ptr(bitmap), n, d, w, seed, _ptr(idx_out), _ptr(val_out), cap,
+                                   _ptr(count_out), _ptr(dense_out), _stream(stream))
+    if st != S2R_OK:
+        raise S2RError(st, "s2r_decode_noalloc")
 
 
 def blocks_workspace_bytes(n: int, block: int, d: int, w: int) -> int:

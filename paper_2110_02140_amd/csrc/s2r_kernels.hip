@@ -47,6 +47,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "../../include/s2r.h"
 #include "s2r_device.h"
 #include "s2r_internal.h"
@@ -559,7 +561,7 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
 static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t block, uint32_t d,
                               uint32_t w, uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap,
                               uint64_t* count_out, float* dense_out, void* workspace, size_t workspace_bytes,
-                              void* stream, float* params = nullptr, float scale = 0.0f) {
+                              void* stream, float* params = nullptr, float scale = 0.0f, bool gather_only = false) {
   if (sketch == nullptr || bitmap == nullptr || count_out == nullptr) return S2R_ERR_NULL;
   // (a block-granular parameter update lists the blocks but returns no values)
   if ((idx_out == nullptr) != (val_out == nullptr) && !(block != 0 && params != nullptr && val_out == nullptr))
@@ -592,8 +594,9 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
   if (cap > n) cap = n;
   const uint64_t cap_items = block != 0 ? cap * block : cap;    // list positions that get a value, at most
   // (an update of parameters, like a dense output, must reach the union indices beyond the lists' capacity too)
-  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr || params != nullptr, idx_out ? cap_items : 0,
-                                         workspace_bytes);
+  const int32_t strategy = gather_only ? S2R_DECODE_GATHER :
+      choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr || params != nullptr, idx_out ? cap_items : 0,
+                    workspace_bytes);
   g_last_decode_strategy = strategy;
   if (strategy == S2R_DECODE_SLICE) {
     const DecodeLayout L = decode_layout(n, d, w, cap_items);
@@ -871,6 +874,41 @@ s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap, 
   if (!block_ok(n, block)) return S2R_ERR_SIZE;
   return decode_impl(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, blk_cap, nblk_out, nullptr,
                      workspace, workspace_bytes, stream);
+}
+
+// ---- s2r_decode without a workspace argument and without any allocation
+// The scratch that s2r_decode takes from its caller (piece counts, tile prefix, dense-tile list) lives in a
+// file-scope device array instead; every GPU the library runs on holds its own copy until the process ends.
+// Host code never uses the array's name as an address: the device address is asked for once per device.
+constexpr uint64_t kNoAllocMaxN = S2R_DECODE_NOALLOC_MAX_N;
+constexpr size_t kNoAllocScratchBytes = 448 * 1024;          // >= workspace_base(kNoAllocMaxN), checked at run time
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+static void* noalloc_scratch_ptr() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> ptr_of[kMaxDevices];              // zero-initialised; one address per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = ptr_of[dev].load(std::memory_order_acquire);
+  if (p != nullptr) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  ptr_of[dev].store(p, std::memory_order_release);            // (two threads may both ask: same answer)
+  return p;
+}
+
+s2r_status s2r_decode_noalloc(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
+                              uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out,
+                              float* dense_out, void* stream) {
+  const s2r_status sz = check_sizes(n, d, w);
+  if (sz != S2R_OK) return sz;
+  if (n > kNoAllocMaxN || workspace_base(n) > kNoAllocScratchBytes) return S2R_ERR_SIZE;
+  void* ws = noalloc_scratch_ptr();
+  if (ws == nullptr) return S2R_ERR_LAUNCH;
+  return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, dense_out, ws,
+                     kNoAllocScratchBytes, stream, nullptr, 0.0f, /*gather_only=*/true);
 }
 
 }  // extern "C"
