@@ -50,7 +50,7 @@
  *     from run to run.  A worker's sketch cell is a sum formed by hardware
  *     atomics in arbitrary order: float32 atomics in global memory (which may
  *     flush denormal operands and results to zero), or float64 atomics in LDS
- *     rounded to float32 once (see s2r_set_insert_strategy).  Cells, and the
+ *     rounded to float32 once (see s2r_options.insert_strategy).  Cells, and the
  *     decoded values that read them, are therefore reproducible only up to
  *     the summation order.
  *   - Workspace: s2r_encode and s2r_decode need a device scratch buffer of at
@@ -289,7 +289,7 @@ s2r_status s2r_encode_blocks_batch(const float* const* grads /* host array */, u
  *                or both non-NULL; nothing is written for list positions
  *                >= blk_cap.
  *   nblk_out     dev, out: one uint64, the true number of set blocks.  Required.
- * Routes and their conditions as for s2r_decode (s2r_set_decode_strategy), with
+ * Routes and their conditions as for s2r_decode (s2r_options.decode_strategy), with
  * cap = blk_cap * block; there is no dense output.
  */
 s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap,
@@ -429,8 +429,24 @@ s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_b
                                     void* stream);
 
 /*
- * How s2r_encode carries out the insertion loops of Algorithm 1
- * (S[j, h_j(i)] += s_j(i) g(i)); the result is the same sketch either way.
+ * Size query of s2r_decode's slice route (see s2r_options.decode_strategy): bytes of
+ * device scratch with which s2r_decode can also use S2R_DECODE_SLICE for lists of
+ * capacity cap (s2r_workspace_bytes plus 16*d bytes per list entry and two
+ * histograms).  With a smaller workspace (but at least s2r_workspace_bytes) it
+ * gathers.  Host only; returns 0 outside the limits or if cap > n.
+ */
+size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
+
+/* ------------------------------------------------------------------ per-call options
+ *
+ * Every entry point above that forms a sketch or reads one has a sibling with the
+ * suffix _ex and one more argument, a pointer to s2r_options.  The library keeps
+ * no state between calls: what steers a call travels with the call.  A NULL
+ * pointer, or a struct that is all zero except struct_bytes, gives exactly the
+ * plain entry point.
+ *
+ * insert_strategy: how the insertion loops of Algorithm 1 (S[j, h_j(i)] += s_j(i) g(i))
+ * are carried out; the sketch is the same either way.
  *   S2R_INSERT_ATOMIC  float32 atomics on the sketch in device memory, issued
  *                      from the dense scan (the sketch is zeroed first)
  *   S2R_INSERT_SLICE   workgroups that each own a slice of one sketch row in
@@ -438,20 +454,13 @@ s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_b
  *                      add the entries of Sparse(g), which a counting sort has
  *                      partitioned by slice; needs nz_idx / nz_val, a
  *                      workspace of s2r_encode_workspace_bytes, d*w <= 2^27 and
- *                      d*cap < 2^32 (otherwise s2r_encode uses atomics whatever
- *                      is set here)
- *   S2R_INSERT_AUTO    (default) chosen from n, d, w and cap, the caller's bound
- *                      on the number of non-zeros
- * State is per host thread.  Returns S2R_ERR_SIZE for any other value.
- */
-#define S2R_INSERT_AUTO   0
-#define S2R_INSERT_ATOMIC 1
-#define S2R_INSERT_SLICE  2
-s2r_status s2r_set_insert_strategy(int32_t strategy);
-
-/*
- * How s2r_decode carries out the query loops of Algorithm 1 (the d bucket reads
- * per union index); the result is the same either way, bit for bit.
+ *                      d*cap < 2^32 (otherwise the call uses atomics whatever
+ *                      is asked for)
+ *   S2R_INSERT_AUTO    (0, default) chosen from W, n, d, w and the expected number
+ *                      of non-zeros per worker
+ *
+ * decode_strategy: how the query loops of Algorithm 1 (the d bucket reads per union
+ * index) are carried out; the result is the same either way, bit for bit.
  *   S2R_DECODE_GATHER  every list position reads its d buckets from the sketch in
  *                      device memory (one 128-byte line fetched per 4-byte cell)
  *   S2R_DECODE_SLICE   the (position, row) queries are partitioned by sketch
@@ -460,72 +469,113 @@ s2r_status s2r_set_insert_strategy(int32_t strategy);
  *                      return to list order through LDS and meet in the median.
  *                      Needs idx_out / val_out, no dense_out, d <= 8,
  *                      d*w <= 2^27, d*(cap + 8192) < 2^32 and a workspace of
- *                      s2r_decode_workspace_bytes (otherwise s2r_decode gathers
- *                      whatever is set here)
- *   S2R_DECODE_AUTO    (default) chosen from d, w and cap, the capacity of the
- *                      caller's lists
- * State is per host thread.  Returns S2R_ERR_SIZE for any other value.
+ *                      s2r_decode_workspace_bytes (otherwise the call gathers
+ *                      whatever is asked for)
+ *   S2R_DECODE_AUTO    (0, default) chosen from d, w and the expected number of
+ *                      union indices
+ *
+ * expected_nnz: the caller's estimate of the number of non-zeros per worker (encode
+ * calls; non-zero blocks for the block codec) or of set bits of the aggregated bitmap
+ * (decode calls).  Only the AUTO choices and the way the work is cut into launches
+ * read it; results never depend on it.  0 = no estimate: the capacity of the caller's
+ * lists (cap) stands in for it, so a caller whose cap is a loose upper bound should
+ * give an estimate.
+ *
+ * report: NULL, or a host struct the call fills in before it returns: the strategies it
+ * used (S2R_INSERT_* / S2R_DECODE_*; AUTO when the call formed no sketch / read none) and
+ * the number of workers the last dense-scan launch covered.
+ *
+ * trace: NULL, or measurement hooks declared in s2r_bench.h.
+ *
+ * Errors: S2R_ERR_SIZE if struct_bytes is not sizeof(s2r_options), a strategy is not one of
+ * the three values, or flags is not 0.
  */
+#define S2R_INSERT_AUTO   0
+#define S2R_INSERT_ATOMIC 1
+#define S2R_INSERT_SLICE  2
 #define S2R_DECODE_AUTO   0
 #define S2R_DECODE_GATHER 1
 #define S2R_DECODE_SLICE  2
-s2r_status s2r_set_decode_strategy(int32_t strategy);
 
-/* S2R_DECODE_GATHER or S2R_DECODE_SLICE: what the calling thread's last
- * s2r_decode call used (S2R_DECODE_AUTO before any call, or when the call only
- * counted).  Host only. */
-int32_t s2r_last_decode_strategy(void);
+typedef struct s2r_report {
+  int32_t  insert_strategy;
+  int32_t  decode_strategy;
+  uint32_t scan_launch_workers;
+  uint32_t reserved;
+} s2r_report;
 
-/* Bytes of device scratch with which s2r_decode can also use S2R_DECODE_SLICE for
- * lists of capacity cap (s2r_workspace_bytes plus 16*d bytes per list entry and
- * two histograms).  With a smaller workspace (but at least s2r_workspace_bytes)
- * it gathers.  Host only; returns 0 outside the limits or if cap > n. */
-size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
+struct s2r_trace;
 
-/* S2R_INSERT_ATOMIC or S2R_INSERT_SLICE: what the calling thread's last
- * s2r_encode / s2r_encode_batch call used (S2R_INSERT_AUTO before any call).
- * Host only. */
-int32_t s2r_last_insert_strategy(void);
+typedef struct s2r_options {
+  uint32_t struct_bytes;            /* sizeof(s2r_options) */
+  int32_t  insert_strategy;
+  int32_t  decode_strategy;
+  uint32_t flags;                   /* must be 0 */
+  uint64_t expected_nnz;
+  s2r_report* report;               /* host, out */
+  const struct s2r_trace* trace;    /* host, in; see s2r_bench.h */
+} s2r_options;
 
-/*
- * Instrumentation for benchmarks.  While a pair of hipEvent_t is installed for
- * a slot, the corresponding kernel launch made by the calling thread is
- * bracketed by hipEventRecord(begin) / hipEventRecord(end) on the launch
- * stream.  Passing NULLs removes the pair.  State is per host thread.
- *   slot S2R_KERNEL_ENCODE_SCAN : the dense scan kernel of s2r_encode / s2r_encode_batch
- *                                 (see s2r_scan_launch_workers)
- *   slot S2R_KERNEL_MERGE       : the kernel of s2r_merge
- *   slot S2R_KERNEL_DECODE      : the expand-and-query kernel(s) of s2r_decode
- *   slot S2R_KERNEL_ENCODE_SLICE: the LDS-slice sketch kernel of s2r_encode
- *   slot S2R_KERNEL_TOPK_SCORES : the scores kernel (the pass over grad and residual)
- *                                 of s2r_topk_blocks* and s2r_topk_encode_blocks_batch
- */
-#define S2R_KERNEL_ENCODE_SCAN  0
-#define S2R_KERNEL_MERGE        1
-#define S2R_KERNEL_DECODE       2
-#define S2R_KERNEL_ENCODE_SLICE 3
-#define S2R_KERNEL_TOPK_SCORES  4
-#define S2R_KERNEL_SLOTS        5
-s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end);
+s2r_status s2r_encode_ex(const float* grad, uint64_t n,
+                         uint32_t d, uint32_t w, uint64_t seed,
+                         float* sketch, uint64_t* bitmap,
+                         uint32_t* nz_idx, float* nz_val, uint64_t cap,
+                         uint64_t* nnz_out,
+                         void* workspace, size_t workspace_bytes,
+                         void* stream, const s2r_options* options);
 
-/* Number of workers covered by the dense-scan launch that the
- * S2R_KERNEL_ENCODE_SCAN events of the calling thread's last encode call
- * bracketed (a batch may be scanned in one launch or worker by worker; in the
- * latter case the events bracket the last worker's launch).  Host only. */
-uint32_t s2r_scan_launch_workers(void);
+s2r_status s2r_encode_batch_ex(const float* const* grads, uint32_t W, uint64_t n,
+                               uint32_t d, uint32_t w, uint64_t seed,
+                               float* const* sketches, uint64_t* const* bitmaps,
+                               uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap,
+                               uint64_t* nnz_out,
+                               void* workspace, size_t workspace_bytes,
+                               void* stream, const s2r_options* options);
 
-/*
- * Measurement aid, no part of the method: one kernel that only reads the first
- * bytes/16 16-byte words of src with streaming loads, in the access pattern of
- * the dense scan of s2r_encode.  Timed by the caller, it gives the read rate the
- * memory system delivers on this device, the ceiling for the scan.
- *   src    dev, in : at least bytes bytes, 16-byte aligned; bytes >= 16
- *   sink   dev, out: one uint64, 8-byte aligned; written only if the XOR of all
- *                    words read equals an arbitrary constant (it keeps the loads
- *                    alive), so normally left untouched
- * Enqueues on stream and returns; S2R_ERR_NULL / _SIZE / _ALIGN / _LAUNCH as above.
- */
-s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* stream);
+s2r_status s2r_decode_ex(const float* sketch, const uint64_t* bitmap,
+                         uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                         uint32_t* idx_out, float* val_out, uint64_t cap,
+                         uint64_t* count_out,
+                         float* dense_out,
+                         void* workspace, size_t workspace_bytes,
+                         void* stream, const s2r_options* options);
+
+s2r_status s2r_encode_blocks_ex(const float* grad, uint64_t n, uint32_t block,
+                                uint32_t d, uint32_t w, uint64_t seed,
+                                float* sketch, uint64_t* block_bitmap,
+                                uint32_t* blk_idx, uint64_t blk_cap,
+                                uint64_t* nblk_out,
+                                void* workspace, size_t workspace_bytes,
+                                void* stream, const s2r_options* options);
+
+s2r_status s2r_encode_blocks_batch_ex(const float* const* grads /* host array */, uint32_t W,
+                                      uint64_t n, uint32_t block,
+                                      uint32_t d, uint32_t w, uint64_t seed,
+                                      float* const* sketches /* host array */,
+                                      uint64_t* const* block_bitmaps /* host array */,
+                                      uint32_t* const* blk_idx /* host array or NULL */, uint64_t blk_cap,
+                                      uint64_t* nblk_out /* dev, W entries */,
+                                      void* workspace, size_t workspace_bytes,
+                                      void* stream, const s2r_options* options);
+
+s2r_status s2r_decode_blocks_ex(const float* sketch, const uint64_t* block_bitmap,
+                                uint64_t n, uint32_t block,
+                                uint32_t d, uint32_t w, uint64_t seed,
+                                uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,
+                                uint64_t* nblk_out,
+                                void* workspace, size_t workspace_bytes,
+                                void* stream, const s2r_options* options);
+
+s2r_status s2r_topk_encode_blocks_batch_ex(const float* const* grads /* host array */,
+                                           float* const* residuals /* host array or NULL */, uint32_t W,
+                                           uint64_t n, uint32_t block, uint64_t K,
+                                           uint32_t d, uint32_t w, uint64_t seed,
+                                           float* const* sketches /* host array */,
+                                           uint64_t* const* block_bitmaps /* host array */,
+                                           uint32_t* const* blk_idx /* host array or NULL */, uint64_t blk_cap,
+                                           uint64_t* nblk_out /* dev, W entries */,
+                                           void* workspace, size_t workspace_bytes,
+                                           void* stream, const s2r_options* options);
 
 #ifdef __cplusplus
 }

@@ -62,14 +62,8 @@
 namespace s2r {
 
 // ------------------------------------------------------------------ host side
-struct EventPair { hipEvent_t begin, end; };
-static thread_local EventPair g_events[S2R_KERNEL_SLOTS] = {};
-static thread_local int32_t g_strategy = S2R_INSERT_AUTO;
-static thread_local int32_t g_last_strategy = S2R_INSERT_AUTO;   // what the last encode call used
-static thread_local int32_t g_decode_strategy = S2R_DECODE_AUTO;
-static thread_local int32_t g_last_decode_strategy = S2R_DECODE_AUTO;   // what the last decode call used
-static thread_local uint32_t g_scan_launch_workers = 0;     // workers covered by the scan launch the events bracket
-
+// The library keeps no state between calls: strategies, the second stream and the
+// measurement hooks of a call arrive in its s2r_options (resolved into an Exec).
 static inline uint64_t splitmix_next(uint64_t& state) {
   state += 0x9E3779B97F4A7C15ull;
   uint64_t z = state;
@@ -155,15 +149,15 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
 //  - slices: five more kernels, about 20 us of launches; 4 us per round of 256
 //    slice workgroups (each clears and stores 128 KiB of LDS); histogram, scatter
 //    and slice kernels together pass about 180e9 records per second.
-// `cap` is the caller's bound on the number of non-zeros.
+// `cap` is the capacity of the caller's lists, `expect` the number of items expected
+// (the caller's estimate, or cap when there is none); `asked` the caller's wish.
 static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap,
-                               size_t workspace_bytes) {
-  (void)n;
+                               uint64_t expect, size_t workspace_bytes, int32_t asked) {
   if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice strategy reads Sparse(g)
   const SliceLayout L = slice_layout(n, d, w, cap);
   if (!L.possible || workspace_bytes < L.total) return S2R_INSERT_ATOMIC;
-  if (g_strategy != S2R_INSERT_AUTO) return g_strategy;
-  const double records = (double)cap * d;
+  if (asked != S2R_INSERT_AUTO) return asked;
+  const double records = (double)expect * d;
   const double rounds = (double)ceil_div((uint64_t)W * L.nbins, 256);       // all workers' slices share the CUs
   const double t_slice = 20e-6 + rounds * 4e-6 + W * records / 180e9;
   const double t_atomic = W * (4.0 * d * w / 4.5e12 + 0.6 * records / 21e9);
@@ -202,28 +196,29 @@ static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t c
 // (4 MB per XCD) run at about 56e9 per second (each fetches a 128-byte line), from one of a few L2 sizes at
 // about 70e9, from one that fits at about 200e9; the slice route costs about 80 us of launches and latency
 // and passes about 110e9 queries per second.
-// `cap` (the capacity of the caller's lists) stands in for the number of union indices, which only the
-// device knows.
+// `cap` is the capacity of the caller's lists, `expect` the number of union indices expected (the caller's
+// estimate, or cap when there is none: only the device knows the true number); `asked` the caller's wish.
 static int32_t choose_decode(uint64_t n, uint32_t d, uint32_t w, bool have_lists, bool dense_out, uint64_t cap,
-                             size_t workspace_bytes) {
+                             uint64_t expect, size_t workspace_bytes, int32_t asked) {
   if (!have_lists || dense_out || cap == 0) return S2R_DECODE_GATHER;
   const DecodeLayout L = decode_layout(n, d, w, cap);
   if (!L.possible || workspace_bytes < L.total) return S2R_DECODE_GATHER;
-  if (g_decode_strategy != S2R_DECODE_AUTO) return g_decode_strategy;
-  const double queries = (double)cap * d;
+  if (asked != S2R_DECODE_AUTO) return asked;
+  const double queries = (double)expect * d;
   const double sketch_bytes = 4.0 * d * w;
   const double t_gather = queries / (sketch_bytes > 16e6 ? 56e9 : sketch_bytes > 4e6 ? 70e9 : 200e9);
   const double t_slice = 80e-6 + queries / 110e9;
   return t_slice < t_gather ? S2R_DECODE_SLICE : S2R_DECODE_GATHER;
 }
 
-// The slice kernels use more dynamic LDS than the default limit allows; raised once per host thread and device.
+// The slice kernels use more dynamic LDS than the default limit allows; the limit is a property of the
+// loaded kernel, raised once per device (asking again is harmless).
 static bool raise_lds_limits() {
   constexpr int kMaxDevices = 64;
-  static thread_local bool raised[kMaxDevices] = {};
+  static std::atomic<bool> raised[kMaxDevices];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0) return false;
-  if (dev < kMaxDevices && raised[dev]) return true;
+  if (dev < kMaxDevices && raised[dev].load(std::memory_order_acquire)) return true;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter_kernel),
@@ -232,12 +227,13 @@ static bool raise_lds_limits() {
       hipFuncSetAttribute(reinterpret_cast<const void*>(decode_slice_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kDecodeSliceLog2Max)) != hipSuccess)
     return false;
-  if (dev < kMaxDevices) raised[dev] = true;
+  if (dev < kMaxDevices) raised[dev].store(true, std::memory_order_release);
   return true;
 }
 
-static inline void record(int slot, bool end, hipStream_t st) {
-  hipEvent_t ev = end ? g_events[slot].end : g_events[slot].begin;
+static inline void record(const Exec& X, int slot, bool end, hipStream_t st) {
+  if (X.trace == nullptr) return;
+  hipEvent_t ev = (hipEvent_t)(end ? X.trace->end[slot] : X.trace->begin[slot]);
   if (ev != nullptr) (void)hipEventRecord(ev, st);
 }
 
@@ -259,7 +255,7 @@ using namespace s2r;
 
 extern "C" {
 
-int32_t s2r_version(void) { return 400; }
+int32_t s2r_version(void) { return 500; }
 
 const char* s2r_status_string(s2r_status status) {
   switch (status) {
@@ -299,29 +295,11 @@ s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out) {
   return S2R_OK;
 }
 
-s2r_status s2r_set_insert_strategy(int32_t strategy) {
-  if (strategy != S2R_INSERT_AUTO && strategy != S2R_INSERT_ATOMIC && strategy != S2R_INSERT_SLICE) return S2R_ERR_SIZE;
-  g_strategy = strategy;
-  return S2R_OK;
-}
-
-s2r_status s2r_set_decode_strategy(int32_t strategy) {
-  if (strategy != S2R_DECODE_AUTO && strategy != S2R_DECODE_GATHER && strategy != S2R_DECODE_SLICE) return S2R_ERR_SIZE;
-  g_decode_strategy = strategy;
-  return S2R_OK;
-}
-
-int32_t s2r_last_decode_strategy(void) { return g_last_decode_strategy; }
-
 size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   if (check_sizes(n, d, w) != S2R_OK || cap > n) return 0;
   const DecodeLayout L = decode_layout(n, d, w, cap);
   return L.possible ? L.total : workspace_base(n);
 }
-
-uint32_t s2r_scan_launch_workers(void) { return g_scan_launch_workers; }
-
-int32_t s2r_last_insert_strategy(void) { return g_last_strategy; }
 
 s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* stream) {
   if (src == nullptr || sink == nullptr) return S2R_ERR_NULL;
@@ -335,24 +313,108 @@ s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* s
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
-s2r_status s2r_set_kernel_events(int32_t slot, void* ev_begin, void* ev_end) {
-  if (slot < 0 || slot >= S2R_KERNEL_SLOTS) return S2R_ERR_SIZE;
-  if ((ev_begin == nullptr) != (ev_end == nullptr)) return S2R_ERR_NULL;
-  g_events[slot].begin = (hipEvent_t)ev_begin;
-  g_events[slot].end = (hipEvent_t)ev_end;
-  return S2R_OK;
-}
-
-// The encode of W workers (W = 1 for s2r_encode): every kernel is launched once
-// with the worker in blockIdx.y.  workspace_bytes is the size of the whole
-// workspace, split evenly between the workers.
+// The encode of W workers (W = 1 for s2r_encode): every kernel takes a group of
+// workers, the worker in first_worker + blockIdx.y.  workspace_bytes is the size of
+// the whole workspace, split evenly between the workers.
 // block = 0: the element codec (bitmaps of n bits, lists of non-zero elements with their values).
 // block >= 1: the block-granular codec (bitmaps of ceil(n / block) bits, lists of non-zero blocks, nz_val
 // unused, cap counted in blocks).
+struct EncodeLaunch {                      // what the launches of one call share
+  uint32_t ntiles, scan_blocks, scan_group;
+  uint64_t nvec, zb;
+  uint32_t ntail;
+  int32_t strategy;
+  bool lists, marked;
+  uint32_t log2w;
+};
+
+// Zeroing and the dense scan of workers first .. first + count - 1 on st (gradients of 1 GiB and more are
+// scanned worker by worker, smaller ones with one launch over the group).
+static s2r_status launch_scans(EncodeBatch& E, const HashRows& hp, const EncodeLaunch& L, uint32_t first,
+                               uint32_t count, bool traced, const Exec& X, hipStream_t st, uint32_t* last_launch) {
+  const bool atomics = L.strategy == S2R_INSERT_ATOMIC;
+  const uint32_t step = L.scan_group < count ? L.scan_group : count;
+  for (uint32_t k0 = first; k0 < first + count; k0 += step) {
+    const uint32_t gy = first + count - k0 < step ? first + count - k0 : step;
+    const bool last = traced && k0 + gy == first + count;    // the events bracket the call's last scan launch
+    E.first_worker = k0;
+    if (atomics || E.block != 0) {                            // the block bitmap is set bit by bit: zero it first
+      hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)L.zb, gy), dim3(kBlock), 0, st, E, atomics ? L.nvec : (uint64_t)0,
+                         atomics ? L.ntail : 0u, E.block != 0 ? E.nwords : (uint64_t)0);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+    }
+    if (last) record(X, S2R_KERNEL_ENCODE_SCAN, false, st);
+    const dim3 sgrid(L.scan_blocks, gy), sblock(kBlock);
+    if (E.block != 0 && atomics)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true, true>), sgrid, sblock, 0, st, E, hp);
+    else if (E.block != 0)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false, true>), sgrid, sblock, 0, st, E, hp);
+    else if (atomics)
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true, false>), sgrid, sblock, 0, st, E, hp);
+    else
+      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false, false>), sgrid, sblock, 0, st, E, hp);
+    if (last) record(X, S2R_KERNEL_ENCODE_SCAN, true, st);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    *last_launch = gy;
+  }
+  return S2R_OK;
+}
+
+// Everything after the scan for workers first .. first + count - 1, on st: counts of the block bitmap,
+// tile prefix, the lists, and the sketch by slices (or, for marked blocks under the atomic strategy, by the
+// overflow kernel from list position 0).
+static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const EncodeLaunch& L, uint32_t first,
+                                    uint32_t count, bool traced, const Exec& X, hipStream_t st) {
+  E.first_worker = first;
+  const uint32_t ntiles = L.ntiles;
+  if (E.block != 0) {                                        // the counts of the block bitmap's pieces
+    hipLaunchKernelGGL(bitmap_count_batch_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock), count), dim3(kBlock),
+                       0, st, E);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1, count), dim3(kPrefixBlock), 0, st, E.workspace + first * E.ws_stride,
+                     E.ws_stride, E.prefix_off, E.dense_off, ntiles, E.nnz_out + first);
+  if (!launch_ok()) return S2R_ERR_LAUNCH;
+
+  if (L.lists && E.cap > 0) {
+    const uint32_t helpers = dense_grid(ntiles, 512);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, count), dim3(kBlock), 0, st, E, helpers);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+
+  if (L.strategy == S2R_INSERT_SLICE) {
+    const size_t lds = sizeof(double) << E.slice_log2;
+    hipLaunchKernelGGL(bin_hist_kernel, dim3(E.nchunks, count), dim3(kBinBlock), 0, st, E, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(E.nbins, kWave), count), dim3(kBinBlock), 0, st, E);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    hipLaunchKernelGGL(bin_start_kernel, dim3(1, count), dim3(kBinBlock), 0, st, E);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (L.log2w - E.slice_log2));
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, count), dim3(kBinBlock), scatter_lds, st, E, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, false, st);
+    hipLaunchKernelGGL(sketch_slice_kernel, dim3(E.nbins, count), dim3(kSliceBlock), lds, st, E);
+    if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, true, st);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+
+    hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), count), dim3(kBlock), 0, st, E, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  } else if (L.marked) {
+    // no scan has inserted anything: every set block goes the way of the blocks beyond the lists
+    EncodeBatch A = E;
+    A.cap = 0;
+    hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), count), dim3(kBlock), 0, st, A, hp);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
+  return S2R_OK;
+}
+
 static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
                                  uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
                                  uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
-                                 void* workspace, size_t workspace_bytes, hipStream_t st, bool marked = false) {
+                                 void* workspace, size_t workspace_bytes, hipStream_t st, const Exec& X,
+                                 bool marked = false) {
   // marked: the (block) bitmaps are given; there is no scan, and grads[k] is read inside the set blocks only
   if (grads == nullptr || sketches == nullptr || bitmaps == nullptr || nnz_out == nullptr) return S2R_ERR_NULL;
   if (W == 0 || W > S2R_MAX_WORKERS || (marked && block == 0)) return S2R_ERR_SIZE;
@@ -380,16 +442,20 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   if (!lists) cap = 0;
   if (cap > nbits) cap = nbits;                               // there cannot be more list entries than bits
   const uint64_t cap_items = block != 0 ? cap * block : cap;  // elements the lists stand for, at most
+  uint64_t expect = X.expected_nnz != 0 && X.expected_nnz < cap ? X.expected_nnz : cap;
+  if (block != 0) expect *= block;                            // items the sort is expected to see
   const size_t ws_each = (workspace_bytes / W) & ~(size_t)255;
   if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || ws_each < workspace_base(nbits))
     return S2R_ERR_WORKSPACE;
 
   HashRows hp;
   make_hash_rows(seed, d, &hp);
-  const uint32_t ntiles = tiles_of(nbits);
-  const uint32_t log2w = log2_of(w);
-  const int32_t strategy = choose_strategy(W, nbits, d, w, lists, cap_items, ws_each);
-  g_last_strategy = strategy;
+  EncodeLaunch L;
+  L.ntiles = tiles_of(nbits);
+  L.log2w = log2_of(w);
+  L.strategy = choose_strategy(W, nbits, d, w, lists, cap_items, expect, ws_each, X.insert_strategy);
+  L.lists = lists;
+  L.marked = marked;
 
   E.nworkers = W;
   E.rowpre_off = 0;
@@ -400,124 +466,88 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.block = block;
   E.prefix_off = workspace_prefix_off(nbits);
   E.dense_off = workspace_dense_off(nbits);
-  const SliceLayout L = slice_layout(nbits, d, w, cap_items);
-  E.hist_off = L.hist_off;
-  E.binstart_off = L.binstart_off;
-  E.rec_off = L.rec_off;
-  E.nbins = L.nbins;
-  E.nchunks = L.nchunks;
+  const SliceLayout SL = slice_layout(nbits, d, w, cap_items);
+  E.hist_off = SL.hist_off;
+  E.binstart_off = SL.binstart_off;
+  E.rec_off = SL.rec_off;
+  E.nbins = SL.nbins;
+  E.nchunks = SL.nchunks;
   E.n = n;
   E.nwords = ceil_div(nbits, 64);
   E.cap = cap;
-  E.ntiles = ntiles;
+  E.ntiles = L.ntiles;
   E.d = d;
-  E.log2w = log2w;
-  E.slice_log2 = L.slice_log2;
+  E.log2w = L.log2w;
+  E.slice_log2 = SL.slice_log2;
+  E.first_worker = 0;
 
   // The scan, preceded by the zeroing of the sketch when the scan inserts into it with atomics.  Gradients
-  // of 1 GiB and more are scanned worker by worker, smaller ones with one launch over the whole batch.
+  // of 1 GiB and more are scanned worker by worker, smaller ones with one launch over a whole group.
   // Measured on config 5 (4 GB per worker, 84 MB sketches): one launch per worker takes 632 us per worker,
   // one launch over all workers 649 us; with atomics, a scan whose sketch was zeroed just before it takes
   // 760 us against 820 us when all 16 sketches were zeroed first.  Below 1 GiB the launches saved count more.
   const uint64_t cells = (uint64_t)d * w;
-  const bool atomics = strategy == S2R_INSERT_ATOMIC;
-  const uint64_t nvec = cells / 4;
-  const uint32_t ntail = (uint32_t)(cells - nvec * 4);
-  uint64_t zb = ceil_div(nvec > 0 ? nvec : 1, kBlock);
-  if (zb > 2048) zb = 2048;
-  const uint32_t group = n * sizeof(float) >= (1ull << 30) ? 1u : W;
+  const bool atomics = L.strategy == S2R_INSERT_ATOMIC;
+  L.nvec = cells / 4;
+  L.ntail = (uint32_t)(cells - L.nvec * 4);
+  L.zb = ceil_div(L.nvec > 0 ? L.nvec : 1, kBlock);
+  if (L.zb > 2048) L.zb = 2048;
+  L.scan_group = n * sizeof(float) >= (1ull << 30) ? 1u : W;
   // element codec: every piece of every tile gets its count; block codec: the pieces that hold elements
-  const uint32_t scan_blocks = block != 0 ? (uint32_t)ceil_div(ceil_div(n, 64), kScanWords) : ntiles * kScansPerTile;
-  uint32_t last_group = 0;
-  if (marked && atomics) {                                    // the sketches only: the bitmaps are the caller's
-    E.first_worker = 0;
-    hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, W), dim3(kBlock), 0, st, E, nvec, ntail, (uint64_t)0);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-  }
-  for (uint32_t k0 = 0; k0 < W && !marked; k0 += group) {
-    const uint32_t gy = W - k0 < group ? W - k0 : group;      // workers k0 .. k0 + gy - 1, all < W
-    const bool last = k0 + gy == W;                           // the events bracket the last scan launch
-    E.first_worker = k0;
-    if (atomics || block != 0) {                              // the block bitmap is set bit by bit: zero it first
-      hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)zb, gy), dim3(kBlock), 0, st, E, atomics ? nvec : (uint64_t)0,
-                         atomics ? ntail : 0u, block != 0 ? E.nwords : (uint64_t)0);
+  L.scan_blocks = block != 0 ? (uint32_t)ceil_div(ceil_div(n, 64), kScanWords) : L.ntiles * kScansPerTile;
+  if (L.strategy == S2R_INSERT_SLICE && !raise_lds_limits()) return S2R_ERR_LAUNCH;
+
+  if (X.report != nullptr) X.report->insert_strategy = L.strategy;
+  uint32_t last_launch = 0;
+  if (marked) {
+    if (atomics) {                                            // the sketches only: the bitmaps are the caller's
+      hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)L.zb, W), dim3(kBlock), 0, st, E, L.nvec, L.ntail, (uint64_t)0);
       if (!launch_ok()) return S2R_ERR_LAUNCH;
     }
-    if (last) record(S2R_KERNEL_ENCODE_SCAN, false, st);
-    const dim3 sgrid(scan_blocks, gy), sblock(kBlock);
-    if (block != 0 && atomics)
-      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true, true>), sgrid, sblock, 0, st, E, hp);
-    else if (block != 0)
-      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false, true>), sgrid, sblock, 0, st, E, hp);
-    else if (atomics)
-      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, true, false>), sgrid, sblock, 0, st, E, hp);
-    else
-      hipLaunchKernelGGL((encode_scan_kernel<kScanEPL, false, false>), sgrid, sblock, 0, st, E, hp);
-    if (last) record(S2R_KERNEL_ENCODE_SCAN, true, st);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    last_group = gy;
-  }
-  g_scan_launch_workers = last_group;
-  E.first_worker = 0;
-
-  if (block != 0) {                                          // the counts of the block bitmap's pieces
-    hipLaunchKernelGGL(bitmap_count_batch_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock), W), dim3(kBlock), 0,
-                       st, E);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-  }
-  hipLaunchKernelGGL(tile_prefix_kernel, dim3(1, W), dim3(kPrefixBlock), 0, st, E.workspace, E.ws_stride,
-                     E.prefix_off, E.dense_off, ntiles, nnz_out);
-  if (!launch_ok()) return S2R_ERR_LAUNCH;
-
-  if (lists && cap > 0) {
-    const uint32_t helpers = dense_grid(ntiles, 512);
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, W), dim3(kBlock), 0, st, E, helpers);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    return launch_after_scan(E, hp, L, 0, W, true, X, st);
   }
 
-  if (strategy == S2R_INSERT_SLICE) {
-    const size_t lds = sizeof(double) << E.slice_log2;
-    if (!raise_lds_limits()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_hist_kernel, dim3(E.nchunks, W), dim3(kBinBlock), 0, st, E, hp);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(E.nbins, kWave), W), dim3(kBinBlock), 0, st, E);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_start_kernel, dim3(1, W), dim3(kBinBlock), 0, st, E);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (log2w - E.slice_log2));
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, W), dim3(kBinBlock), scatter_lds, st, E, hp);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    record(S2R_KERNEL_ENCODE_SLICE, false, st);
-    hipLaunchKernelGGL(sketch_slice_kernel, dim3(E.nbins, W), dim3(kSliceBlock), lds, st, E);
-    record(S2R_KERNEL_ENCODE_SLICE, true, st);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-
-    hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), W), dim3(kBlock), 0, st, E, hp);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-  } else if (marked) {
-    // no scan has inserted anything: every set block goes the way of the blocks beyond the lists
-    EncodeBatch A = E;
-    A.cap = 0;
-    hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), W), dim3(kBlock), 0, st, A, hp);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-  }
+  s2r_status rc = launch_scans(E, hp, L, 0, W, true, X, st, &last_launch);
+  if (rc != S2R_OK) return rc;
+  rc = launch_after_scan(E, hp, L, 0, W, true, X, st);
+  if (rc != S2R_OK) return rc;
+  if (X.report != nullptr) X.report->scan_launch_workers = last_launch;
   return S2R_OK;
+}
+
+s2r_status s2r_encode_batch_ex(const float* const* grads, uint32_t W, uint64_t n, uint32_t d, uint32_t w,
+                               uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
+                               uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
+                               void* workspace, size_t workspace_bytes, void* stream, const s2r_options* options) {
+  Exec X;
+  const s2r_status rc = resolve_options(options, &X);
+  if (rc != S2R_OK) return rc;
+  return encode_workers(grads, W, n, 0u, d, w, seed, sketches, bitmaps, nz_idx, nz_val, cap, nnz_out, workspace,
+                        workspace_bytes, (hipStream_t)stream, X);
+}
+
+s2r_status s2r_encode_ex(const float* grad, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                         float* sketch, uint64_t* bitmap, uint32_t* nz_idx, float* nz_val, uint64_t cap,
+                         uint64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream,
+                         const s2r_options* options) {
+  if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
+  return s2r_encode_batch_ex(&grad, 1, n, d, w, seed, &sketch, &bitmap, nz_idx ? &nz_idx : nullptr,
+                             nz_val ? &nz_val : nullptr, cap, nnz_out, workspace, workspace_bytes, stream, options);
 }
 
 s2r_status s2r_encode(const float* grad, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
                       float* sketch, uint64_t* bitmap, uint32_t* nz_idx, float* nz_val, uint64_t cap,
                       uint64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream) {
-  if ((nz_idx == nullptr) != (nz_val == nullptr)) return S2R_ERR_NULL;
-  return encode_workers(&grad, 1, n, 0u, d, w, seed, &sketch, &bitmap, nz_idx ? &nz_idx : nullptr,
-                        nz_val ? &nz_val : nullptr, cap, nnz_out, workspace, workspace_bytes, (hipStream_t)stream);
+  return s2r_encode_ex(grad, n, d, w, seed, sketch, bitmap, nz_idx, nz_val, cap, nnz_out, workspace, workspace_bytes,
+                       stream, nullptr);
 }
 
 s2r_status s2r_encode_batch(const float* const* grads, uint32_t W, uint64_t n, uint32_t d, uint32_t w,
                             uint64_t seed, float* const* sketches, uint64_t* const* bitmaps,
                             uint32_t* const* nz_idx, float* const* nz_val, uint64_t cap, uint64_t* nnz_out,
                             void* workspace, size_t workspace_bytes, void* stream) {
-  return encode_workers(grads, W, n, 0u, d, w, seed, sketches, bitmaps, nz_idx, nz_val, cap, nnz_out, workspace,
-                        workspace_bytes, (hipStream_t)stream);
+  return s2r_encode_batch_ex(grads, W, n, d, w, seed, sketches, bitmaps, nz_idx, nz_val, cap, nnz_out, workspace,
+                             workspace_bytes, stream, nullptr);
 }
 
 s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
@@ -549,9 +579,7 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
   const uint64_t bb = ceil_div(A.nwords, kBlock);
   A.sketch_blocks = (uint32_t)sb;
   hipStream_t st = (hipStream_t)stream;
-  record(S2R_KERNEL_MERGE, false, st);
   hipLaunchKernelGGL(merge_kernel, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
-  record(S2R_KERNEL_MERGE, true, st);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
@@ -561,7 +589,7 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
 static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t block, uint32_t d,
                               uint32_t w, uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap,
                               uint64_t* count_out, float* dense_out, void* workspace, size_t workspace_bytes,
-                              void* stream, float* params = nullptr, float scale = 0.0f, bool gather_only = false) {
+                              void* stream, const Exec& X, float* params = nullptr, float scale = 0.0f) {
   if (sketch == nullptr || bitmap == nullptr || count_out == nullptr) return S2R_ERR_NULL;
   // (a block-granular parameter update lists the blocks but returns no values)
   if ((idx_out == nullptr) != (val_out == nullptr) && !(block != 0 && params != nullptr && val_out == nullptr))
@@ -594,42 +622,43 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
   if (cap > n) cap = n;
   const uint64_t cap_items = block != 0 ? cap * block : cap;    // list positions that get a value, at most
   // (an update of parameters, like a dense output, must reach the union indices beyond the lists' capacity too)
-  const int32_t strategy = gather_only ? S2R_DECODE_GATHER :
-      choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr || params != nullptr, idx_out ? cap_items : 0,
-                    workspace_bytes);
-  g_last_decode_strategy = strategy;
+  uint64_t expect = X.expected_nnz != 0 && X.expected_nnz < cap ? X.expected_nnz : cap;
+  if (block != 0) expect *= block;
+  const int32_t strategy = choose_decode(n, d, w, idx_out != nullptr, dense_out != nullptr || params != nullptr,
+                                         idx_out ? cap_items : 0, expect, workspace_bytes, X.decode_strategy);
+  if (X.report != nullptr) X.report->decode_strategy = strategy;
   if (strategy == S2R_DECODE_SLICE) {
     const DecodeLayout L = decode_layout(n, d, w, cap_items);
     if (!raise_lds_limits()) return S2R_ERR_LAUNCH;
     // the kernels of the encode's slice strategy, on one "worker" whose list is the union list
-    static thread_local EncodeBatch X;                     // (2.6 KB: not on the stack of every call)
-    X.w[0].grad = nullptr;                                 // expansion without values
-    X.w[0].sketch = nullptr;
-    X.w[0].bitmap = const_cast<uint64_t*>(bitmap);        // only read
-    X.w[0].nz_idx = idx_out;
-    X.w[0].nz_val = nullptr;
-    X.nnz_out = count_out;
-    X.workspace = reinterpret_cast<char*>(workspace);
-    X.ws_stride = 0;
-    X.prefix_off = workspace_prefix_off(n);
-    X.dense_off = workspace_dense_off(n);
-    X.hist_off = L.hist_off;
-    X.binstart_off = L.binstart_off;
-    X.rec_off = L.rec_off;
-    X.rowpre_off = L.rowpre_off;
-    X.payload_slot = 1;
-    X.block = block;
-    X.n = elements;
-    X.nwords = nwords;
-    X.cap = cap;
-    X.ntiles = ntiles;
-    X.d = d;
-    X.log2w = log2_of(w);
-    X.slice_log2 = L.slice_log2;
-    X.nbins = L.nbins;
-    X.nchunks = L.nchunks;
-    X.first_worker = 0;
-    X.nworkers = 1;
+    EncodeBatch B;
+    B.w[0].grad = nullptr;                                 // expansion without values
+    B.w[0].sketch = nullptr;
+    B.w[0].bitmap = const_cast<uint64_t*>(bitmap);        // only read
+    B.w[0].nz_idx = idx_out;
+    B.w[0].nz_val = nullptr;
+    B.nnz_out = count_out;
+    B.workspace = reinterpret_cast<char*>(workspace);
+    B.ws_stride = 0;
+    B.prefix_off = workspace_prefix_off(n);
+    B.dense_off = workspace_dense_off(n);
+    B.hist_off = L.hist_off;
+    B.binstart_off = L.binstart_off;
+    B.rec_off = L.rec_off;
+    B.rowpre_off = L.rowpre_off;
+    B.payload_slot = 1;
+    B.block = block;
+    B.n = elements;
+    B.nwords = nwords;
+    B.cap = cap;
+    B.ntiles = ntiles;
+    B.d = d;
+    B.log2w = log2_of(w);
+    B.slice_log2 = L.slice_log2;
+    B.nbins = L.nbins;
+    B.nchunks = L.nchunks;
+    B.first_worker = 0;
+    B.nworkers = 1;
     char* ws = reinterpret_cast<char*>(workspace);
     DecodeSliceArgs Q;
     Q.sketch = sketch;
@@ -647,18 +676,18 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     Q.n = elements;
     Q.blk_list = idx_out;
 
-    record(S2R_KERNEL_DECODE, false, st);
+    record(X, S2R_KERNEL_DECODE, false, st);
     const uint32_t helpers = dense_grid(ntiles, 2048);
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, X, helpers);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_hist_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), 0, st, X, hp);
+    hipLaunchKernelGGL(bin_hist_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), 0, st, B, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(L.nbins, kWave), 1), dim3(kBinBlock), 0, st, X);
+    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(L.nbins, kWave), 1), dim3(kBinBlock), 0, st, B);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_start_kernel, dim3(1, 1), dim3(kBinBlock), 0, st, X);
+    hipLaunchKernelGGL(bin_start_kernel, dim3(1, 1), dim3(kBinBlock), 0, st, B);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (X.log2w - X.slice_log2));
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), scatter_lds, st, X, hp);
+    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (B.log2w - B.slice_log2));
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), scatter_lds, st, B, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     // one workgroup per compute unit at a time (the slice fills its LDS): with few bins, several workgroups
     // share a bin's queries so that the last round of workgroups is not mostly idle units
@@ -679,7 +708,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
       case 7: hipLaunchKernelGGL(decode_median_kernel<7>, mgrid, mblock, 0, st, Q); break;
       default: hipLaunchKernelGGL(decode_median_kernel<8>, mgrid, mblock, 0, st, Q); break;
     }
-    record(S2R_KERNEL_DECODE, true, st);
+    record(X, S2R_KERNEL_DECODE, true, st);
     return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
   }
 
@@ -700,31 +729,31 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
   A.scale = scale;
 
   if (block != 0) {                                        // the block list, then one thread per element of a listed block
-    static thread_local EncodeBatch X;
-    X.w[0].grad = nullptr;
-    X.w[0].sketch = nullptr;
-    X.w[0].bitmap = const_cast<uint64_t*>(bitmap);        // only read
-    X.w[0].nz_idx = idx_out;
-    X.w[0].nz_val = nullptr;
-    X.nnz_out = count_out;
-    X.workspace = reinterpret_cast<char*>(workspace);
-    X.ws_stride = 0;
-    X.prefix_off = workspace_prefix_off(n);
-    X.dense_off = workspace_dense_off(n);
-    X.rowpre_off = 0;
-    X.payload_slot = 0;
-    X.block = block;
-    X.n = elements;
-    X.nwords = nwords;
-    X.cap = cap;
-    X.ntiles = ntiles;
-    X.d = d;
-    X.log2w = A.log2w;
-    X.first_worker = 0;
-    X.nworkers = 1;
-    record(S2R_KERNEL_DECODE, false, st);
+    EncodeBatch B;
+    B.w[0].grad = nullptr;
+    B.w[0].sketch = nullptr;
+    B.w[0].bitmap = const_cast<uint64_t*>(bitmap);        // only read
+    B.w[0].nz_idx = idx_out;
+    B.w[0].nz_val = nullptr;
+    B.nnz_out = count_out;
+    B.workspace = reinterpret_cast<char*>(workspace);
+    B.ws_stride = 0;
+    B.prefix_off = workspace_prefix_off(n);
+    B.dense_off = workspace_dense_off(n);
+    B.rowpre_off = 0;
+    B.payload_slot = 0;
+    B.block = block;
+    B.n = elements;
+    B.nwords = nwords;
+    B.cap = cap;
+    B.ntiles = ntiles;
+    B.d = d;
+    B.log2w = A.log2w;
+    B.first_worker = 0;
+    B.nworkers = 1;
+    record(X, S2R_KERNEL_DECODE, false, st);
     const uint32_t helpers = dense_grid(ntiles, 2048);
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, X, helpers);
+    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const uint64_t bwgs = ceil_div(cap_items, (uint64_t)kBlock * 4);
     const dim3 bgrid((uint32_t)(bwgs < 8192 ? bwgs : 8192)), bblock(kBlock);      // (the workgroups loop)
@@ -746,11 +775,11 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
       case 15: hipLaunchKernelGGL(decode_blocks_kernel<15>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
       default: hipLaunchKernelGGL(decode_blocks_kernel<16>, bgrid, bblock, 0, st, A, hp, block, idx_out, count_out); break;
     }
-    record(S2R_KERNEL_DECODE, true, st);
+    record(X, S2R_KERNEL_DECODE, true, st);
     return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
   }
 
-  record(S2R_KERNEL_DECODE, false, st);
+  record(X, S2R_KERNEL_DECODE, false, st);
   const uint32_t helpers = dense_grid(ntiles, 2048);
   switch (d) {
     case 1: launch_decode<1>(ntiles, helpers, st, A, hp); break;
@@ -770,16 +799,27 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     case 15: launch_decode<15>(ntiles, helpers, st, A, hp); break;
     default: launch_decode<16>(ntiles, helpers, st, A, hp); break;
   }
-  record(S2R_KERNEL_DECODE, true, st);
+  record(X, S2R_KERNEL_DECODE, true, st);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
 
+s2r_status s2r_decode_ex(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
+                         uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out,
+                         float* dense_out, void* workspace, size_t workspace_bytes, void* stream,
+                         const s2r_options* options) {
+  Exec X;
+  const s2r_status rc = resolve_options(options, &X);
+  if (rc != S2R_OK) return rc;
+  return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, dense_out, workspace,
+                     workspace_bytes, stream, X);
+}
+
 s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
                       uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out,
                       float* dense_out, void* workspace, size_t workspace_bytes, void* stream) {
-  return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, dense_out, workspace,
-                     workspace_bytes, stream);
+  return s2r_decode_ex(sketch, bitmap, n, d, w, seed, idx_out, val_out, cap, count_out, dense_out, workspace,
+                       workspace_bytes, stream, nullptr);
 }
 
 s2r_status s2r_decode_update(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
@@ -788,7 +828,7 @@ s2r_status s2r_decode_update(const float* sketch, const uint64_t* bitmap, uint64
   if (params == nullptr) return S2R_ERR_NULL;
   if (((uintptr_t)params & 3u) != 0) return S2R_ERR_ALIGN;
   return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, nullptr, workspace,
-                     workspace_bytes, stream, params, scale);
+                     workspace_bytes, stream, Exec(), params, scale);
 }
 
 // ---- block-granular codec
@@ -813,34 +853,84 @@ size_t s2r_decode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d,
   return L.possible ? L.total : workspace_base(nb);
 }
 
+s2r_status s2r_encode_blocks_batch_ex(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
+                                      uint32_t w, uint64_t seed, float* const* sketches,
+                                      uint64_t* const* block_bitmaps, uint32_t* const* blk_idx, uint64_t blk_cap,
+                                      uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream,
+                                      const s2r_options* options) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  Exec X;
+  const s2r_status rc = resolve_options(options, &X);
+  if (rc != S2R_OK) return rc;
+  return encode_workers(grads, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, nullptr, blk_cap, nblk_out,
+                        workspace, workspace_bytes, (hipStream_t)stream, X);
+}
+
+s2r_status s2r_encode_blocks_ex(const float* grad, uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t seed,
+                                float* sketch, uint64_t* block_bitmap, uint32_t* blk_idx, uint64_t blk_cap,
+                                uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream,
+                                const s2r_options* options) {
+  return s2r_encode_blocks_batch_ex(&grad, 1, n, block, d, w, seed, &sketch, &block_bitmap,
+                                    blk_idx ? &blk_idx : nullptr, blk_cap, nblk_out, workspace, workspace_bytes,
+                                    stream, options);
+}
+
 s2r_status s2r_encode_blocks_batch(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
                                    uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* block_bitmaps,
                                    uint32_t* const* blk_idx, uint64_t blk_cap, uint64_t* nblk_out, void* workspace,
                                    size_t workspace_bytes, void* stream) {
-  if (!block_ok(n, block)) return S2R_ERR_SIZE;
-  return encode_workers(grads, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, nullptr, blk_cap, nblk_out,
-                        workspace, workspace_bytes, (hipStream_t)stream);
+  return s2r_encode_blocks_batch_ex(grads, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, blk_cap,
+                                    nblk_out, workspace, workspace_bytes, stream, nullptr);
 }
 
 s2r_status s2r_encode_blocks(const float* grad, uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t seed,
                              float* sketch, uint64_t* block_bitmap, uint32_t* blk_idx, uint64_t blk_cap,
                              uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!block_ok(n, block)) return S2R_ERR_SIZE;
-  return encode_workers(&grad, 1, n, block, d, w, seed, &sketch, &block_bitmap, blk_idx ? &blk_idx : nullptr, nullptr,
-                        blk_cap, nblk_out, workspace, workspace_bytes, (hipStream_t)stream);
+  return s2r_encode_blocks_ex(grad, n, block, d, w, seed, sketch, block_bitmap, blk_idx, blk_cap, nblk_out, workspace,
+                              workspace_bytes, stream, nullptr);
 }
 
 }  // extern "C"
 
-void s2r::record_kernel_event(int slot, bool end, void* stream) { record(slot, end, (hipStream_t)stream); }
+void s2r::record_kernel_event(const Exec& X, int slot, bool end, void* stream) {
+  record(X, slot, end, (hipStream_t)stream);
+}
+
+s2r_status s2r::resolve_options(const s2r_options* options, Exec* X) {
+  *X = Exec();
+  if (options == nullptr) return S2R_OK;
+  if (options->struct_bytes != sizeof(s2r_options) || options->flags != 0) return S2R_ERR_SIZE;
+  if (options->insert_strategy != S2R_INSERT_AUTO && options->insert_strategy != S2R_INSERT_ATOMIC &&
+      options->insert_strategy != S2R_INSERT_SLICE)
+    return S2R_ERR_SIZE;
+  if (options->decode_strategy != S2R_DECODE_AUTO && options->decode_strategy != S2R_DECODE_GATHER &&
+      options->decode_strategy != S2R_DECODE_SLICE)
+    return S2R_ERR_SIZE;
+  if (options->trace != nullptr) {
+    for (int slot = 0; slot < S2R_KERNEL_SLOTS; ++slot)
+      if ((options->trace->begin[slot] == nullptr) != (options->trace->end[slot] == nullptr)) return S2R_ERR_NULL;
+  }
+  X->insert_strategy = options->insert_strategy;
+  X->decode_strategy = options->decode_strategy;
+  X->expected_nnz = options->expected_nnz;
+  X->report = options->report;
+  X->trace = options->trace;
+  if (X->report != nullptr) {
+    X->report->insert_strategy = S2R_INSERT_AUTO;
+    X->report->decode_strategy = S2R_DECODE_AUTO;
+    X->report->scan_launch_workers = 0;
+    X->report->reserved = 0;
+  }
+  return S2R_OK;
+}
 
 s2r_status s2r::encode_marked_blocks(const float* const* values, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
                                      uint32_t w, uint64_t seed, float* const* sketches, uint64_t* const* block_bitmaps,
                                      uint32_t* const* blk_idx, uint64_t cap, uint64_t* nblk_out, void* workspace,
-                                     size_t workspace_bytes, void* stream) {
+                                     size_t workspace_bytes, void* stream, const Exec& X) {
   if (!block_ok(n, block)) return S2R_ERR_SIZE;
   return encode_workers(values, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, nullptr, cap, nblk_out,
-                        workspace, workspace_bytes, (hipStream_t)stream, true);
+                        workspace, workspace_bytes, (hipStream_t)stream, X, true);
 }
 
 extern "C" {
@@ -865,15 +955,26 @@ s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_b
   // the complete list of set blocks goes to the workspace, behind the parts every decode uses
   uint32_t* list = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + workspace_base(nb));
   return decode_impl(sketch, block_bitmap, n, block, d, w, seed, list, nullptr, nb, nblk_out, nullptr, workspace,
-                     workspace_bytes, stream, params, scale);
+                     workspace_bytes, stream, Exec(), params, scale);
+}
+
+s2r_status s2r_decode_blocks_ex(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block,
+                                uint32_t d, uint32_t w, uint64_t seed, uint32_t* blk_idx_out, float* val_out,
+                                uint64_t blk_cap, uint64_t* nblk_out, void* workspace, size_t workspace_bytes,
+                                void* stream, const s2r_options* options) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  Exec X;
+  const s2r_status rc = resolve_options(options, &X);
+  if (rc != S2R_OK) return rc;
+  return decode_impl(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, blk_cap, nblk_out, nullptr,
+                     workspace, workspace_bytes, stream, X);
 }
 
 s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block, uint32_t d,
                              uint32_t w, uint64_t seed, uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,
                              uint64_t* nblk_out, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!block_ok(n, block)) return S2R_ERR_SIZE;
-  return decode_impl(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, blk_cap, nblk_out, nullptr,
-                     workspace, workspace_bytes, stream);
+  return s2r_decode_blocks_ex(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, blk_cap, nblk_out,
+                              workspace, workspace_bytes, stream, nullptr);
 }
 
 // ---- s2r_decode without a workspace argument and without any allocation
@@ -907,8 +1008,10 @@ s2r_status s2r_decode_noalloc(const float* sketch, const uint64_t* bitmap, uint6
   if (n > kNoAllocMaxN || workspace_base(n) > kNoAllocScratchBytes) return S2R_ERR_SIZE;
   void* ws = noalloc_scratch_ptr();
   if (ws == nullptr) return S2R_ERR_LAUNCH;
+  Exec X;
+  X.decode_strategy = S2R_DECODE_GATHER;     // (the slice route would want a workspace that grows with cap)
   return decode_impl(sketch, bitmap, n, 0u, d, w, seed, idx_out, val_out, cap, count_out, dense_out, ws,
-                     kNoAllocScratchBytes, stream, nullptr, 0.0f, /*gather_only=*/true);
+                     kNoAllocScratchBytes, stream, X);
 }
 
 }  // extern "C"

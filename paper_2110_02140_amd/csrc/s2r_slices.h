@@ -71,12 +71,15 @@ __device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs
 
 __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_hist[kMaxBins];
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const uint32_t chunk = blockIdx.x;
+  const uint64_t have = listed_items(B, k);
+  // the grid covers the lists' capacity; the chunks beyond the listed items leave at once, and no kernel
+  // reads their rows of the histogram
+  if ((uint64_t)chunk * kBinChunk >= have) return;       // uniform over the workgroup
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
   __syncthreads();
-  const uint64_t have = listed_items(B, k);
   const WorkerPtrs P = B.w[k];
   const uint32_t spr_log2 = B.log2w - B.slice_log2;
   uint32_t i[kBinItems], v[kBinItems];
@@ -143,16 +146,19 @@ __global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatc
   constexpr int kWaves = kBinBlock / kWave;              // 16
   constexpr uint32_t kAhead = 8;                         // counters in flight per thread
   __shared__ uint32_t s_part[kWaves][kWave];
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
   const uint32_t b = blockIdx.x * kWave + lane;
   const bool live = b < B.nbins;
   uint32_t* hist = ws_bin_hist(B, k);
-  const uint32_t per = (B.nchunks + kWaves - 1) / kWaves;
-  const uint32_t c_begin = wv * per < B.nchunks ? wv * per : B.nchunks;
-  const uint32_t c_end = c_begin + per < B.nchunks ? c_begin + per : B.nchunks;
+  // the chunks that hold listed items (the others' rows were not written)
+  const uint64_t filled = (listed_items(B, k) + kBinChunk - 1) / kBinChunk;
+  const uint32_t nchunks = filled < B.nchunks ? (uint32_t)filled : B.nchunks;
+  const uint32_t per = (nchunks + kWaves - 1) / kWaves;
+  const uint32_t c_begin = wv * per < nchunks ? wv * per : nchunks;
+  const uint32_t c_end = c_begin + per < nchunks ? c_begin + per : nchunks;
   uint32_t sum = 0;
   for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
     uint32_t v[kAhead];
@@ -198,7 +204,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch 
   constexpr int kWaves = kBinBlock / kWave;
   constexpr int kMaxPer = kMaxBins / kBinBlock;           // 8
   __shared__ uint32_t s_wave[kWaves];
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
@@ -248,7 +254,7 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
   extern __shared__ uint2 s_stage[];
   constexpr int kWaves = kBinBlock / kWave;
   __shared__ uint32_t s_wave[kWaves];
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   const uint32_t chunk = blockIdx.x;
   const uint64_t have = listed_items(B, k);
@@ -345,7 +351,7 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
 __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B) {
   extern __shared__ double s_slice[];
   constexpr int kAhead = 4;                               // 8-byte record loads in flight per thread
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
   const uint32_t cells = 1u << B.slice_log2;
@@ -408,7 +414,7 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
 __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ TileBits T;
   __shared__ uint32_t s_any;
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const WorkerPtrs P = B.w[k];
   const uint64_t* prefix = ws_prefix(B, k);

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kBlock) void bitmap_count_kernel(const uint64_t* __
 
 // The same for the (block) bitmaps of the workers of an encode batch.
 __global__ __launch_bounds__(kBlock) void bitmap_count_batch_kernel(const EncodeBatch B) {
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   count_tile_pieces(B.w[k].bitmap, B.nwords, B.ntiles, ws_piece_count(B, k));
 }
@@ -274,7 +274,7 @@ __device__ __forceinline__ void compact_group(const EncodeBatch& B, const Worker
 // of tile t.
 __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B, uint32_t helpers) {
   __shared__ TileBits T;
-  const uint32_t k = blockIdx.y;
+  const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   if (blockIdx.x >= helpers) {
     compact_group(B, B.w[k], ws_prefix(B, k), T, blockIdx.x - helpers, 0u);

@@ -496,12 +496,12 @@ static s2r_status fill_batch(TopkBatch& B, const float* const* grads, float* con
 
 // Scores (with acc written over the residuals if store_acc) and the radix select
 // of the K-th largest key; afterwards block x is kept iff keys[x] >= state.prefix.
-static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream_t st) {
+static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream_t st, const s2r::Exec& X) {
   const uint32_t W = B.nworkers;
   const uint64_t score_blocks =
       B.block >= 32u ? ceil_div(B.nb, (uint64_t)kWavesPerBlock * kScorePer) : ceil_div(B.nb, kBlock);
   const bool vec = B.block >= 32u && B.block % 4u == 0u;   // (gradients and residuals are 16-byte aligned)
-  s2r::record_kernel_event(S2R_KERNEL_TOPK_SCORES, false, st);
+  s2r::record_kernel_event(X, S2R_KERNEL_TOPK_SCORES, false, st);
   if (vec && store_acc)
     hipLaunchKernelGGL(topk_score_vec_kernel<true>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
   else if (vec)
@@ -510,7 +510,7 @@ static s2r_status launch_selection(const TopkBatch& B, bool store_acc, hipStream
     hipLaunchKernelGGL(topk_score_kernel<true>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
   else
     hipLaunchKernelGGL(topk_score_kernel<false>, dim3((uint32_t)score_blocks, W), dim3(kBlock), 0, st, B);
-  s2r::record_kernel_event(S2R_KERNEL_TOPK_SCORES, true, st);
+  s2r::record_kernel_event(X, S2R_KERNEL_TOPK_SCORES, true, st);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
   if (B.K != B.nb && B.K != 0) {
     const uint32_t hist_blocks = (uint32_t)ceil_div(B.nb, (uint64_t)kHistBlock * kHistPer);
@@ -552,7 +552,7 @@ s2r_status s2r_topk_blocks_batch(const float* const* grads, float* const* residu
   hipStream_t st = (hipStream_t)stream;
   // with residuals the scores' pass leaves acc = g + e in them, and the second pass reads 4 bytes per element, not 8
   const bool acc_in_e = residuals != nullptr;
-  if ((rc = launch_selection(B, acc_in_e, st)) != S2R_OK) return rc;
+  if ((rc = launch_selection(B, acc_in_e, st, s2r::Exec())) != S2R_OK) return rc;
   const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
   const dim3 agrid((uint32_t)ceil_div(n, (uint64_t)kBlock * kApplyPer), W);
   if (acc_in_e)
@@ -576,11 +576,15 @@ size_t s2r_topk_encode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32
   return select == 0 || codec == 0 ? 0 : select + codec;          // both are multiples of 256
 }
 
-s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
-                                        uint32_t block, uint64_t K, uint32_t d, uint32_t w, uint64_t seed,
-                                        float* const* sketches, uint64_t* const* block_bitmaps,
-                                        uint32_t* const* blk_idx, uint64_t blk_cap, uint64_t* nblk_out,
-                                        void* workspace, size_t workspace_bytes, void* stream) {
+s2r_status s2r_topk_encode_blocks_batch_ex(const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
+                                           uint32_t block, uint64_t K, uint32_t d, uint32_t w, uint64_t seed,
+                                           float* const* sketches, uint64_t* const* block_bitmaps,
+                                           uint32_t* const* blk_idx, uint64_t blk_cap, uint64_t* nblk_out,
+                                           void* workspace, size_t workspace_bytes, void* stream,
+                                           const s2r_options* options) {
+  s2r::Exec X;
+  const s2r_status orc = s2r::resolve_options(options, &X);
+  if (orc != S2R_OK) return orc;
   if (block_bitmaps == nullptr || sketches == nullptr || nblk_out == nullptr) return S2R_ERR_NULL;
   if (W == 0 || W > S2R_MAX_WORKERS || !sizes_ok(n, block)) return S2R_ERR_SIZE;
   // everything the compress step would refuse is refused here, before the residuals are touched
@@ -607,12 +611,12 @@ s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const*
   if (rc != S2R_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   // acc = g + e replaces e during the scores' pass; the kept blocks are read from there and cleared at the end
-  if ((rc = launch_selection(B, residuals != nullptr, st)) != S2R_OK) return rc;
+  if ((rc = launch_selection(B, residuals != nullptr, st, X)) != S2R_OK) return rc;
   if ((rc = launch_bitmaps(B, st)) != S2R_OK) return rc;
   const float* values[S2R_MAX_WORKERS];
   for (uint32_t k = 0; k < W; ++k) values[k] = residuals != nullptr ? residuals[k] : grads[k];
   rc = s2r::encode_marked_blocks(values, W, n, block, d, w, seed, sketches, block_bitmaps, blk_idx, blk_cap, nblk_out,
-                                 codec_ws, codec_bytes, stream);
+                                 codec_ws, codec_bytes, stream, X);
   if (rc != S2R_OK) return rc;
   if (residuals != nullptr) {
     const uint32_t all = B.K == B.nb ? 1u : 0u, none = B.K == 0 ? 1u : 0u;
@@ -621,6 +625,15 @@ s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const*
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
   return S2R_OK;
+}
+
+s2r_status s2r_topk_encode_blocks_batch(const float* const* grads, float* const* residuals, uint32_t W, uint64_t n,
+                                        uint32_t block, uint64_t K, uint32_t d, uint32_t w, uint64_t seed,
+                                        float* const* sketches, uint64_t* const* block_bitmaps,
+                                        uint32_t* const* blk_idx, uint64_t blk_cap, uint64_t* nblk_out,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  return s2r_topk_encode_blocks_batch_ex(grads, residuals, W, n, block, K, d, w, seed, sketches, block_bitmaps, blk_idx,
+                                         blk_cap, nblk_out, workspace, workspace_bytes, stream, nullptr);
 }
 
 }  // extern "C"

@@ -1,5 +1,5 @@
 """CPU-only checks of the C-ABI library: it loads, exports every symbol that
-include/s2r.h declares, and its host-only entry points and argument checks
+include/s2r.h and include/s2r_bench.h declare, and its host-only entry points and argument checks
 behave as documented.  No kernel is launched here."""
 
 import ctypes
@@ -16,9 +16,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "s2r.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(s2r_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in ("s2r.h", "s2r_bench.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(s2r_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -130,17 +133,66 @@ def test_encode_batch_rejects_bad_arguments():
     assert call(S=(ctypes.c_void_p * 2)(0x10000, 0x20004)) == b.S2R_ERR_ALIGN
 
 
-def test_set_insert_strategy_argument_checks():
-    assert b.load().s2r_set_insert_strategy(3) == b.S2R_ERR_SIZE
-    assert b.load().s2r_set_insert_strategy(-1) == b.S2R_ERR_SIZE
+def _options(**kw):
+    o = b.Options()
+    o.struct_bytes = ctypes.sizeof(b.Options)
+    for k, v in kw.items():
+        setattr(o, k, v)
+    return o
+
+
+def _call_encode_ex(opt, **kw):
+    lib = b.load()
+    a = dict(grad=0x1000, n=1000, d=3, w=64, seed=0, sketch=0x2000, bitmap=0x3000, idx=0x4000, val=0x5000,
+             cap=10, nnz=0x6000, ws=None, wsb=1 << 20, stream=None)
+    a.update(kw)
+    return lib.s2r_encode_ex(a["grad"], a["n"], a["d"], a["w"], a["seed"], a["sketch"], a["bitmap"], a["idx"],
+                             a["val"], a["cap"], a["nnz"], a["ws"], a["wsb"], a["stream"],
+                             None if opt is None else ctypes.byref(opt))
+
+
+def test_options_are_checked_before_anything_else():
+    # (every call below fails on its options, or, with good options, on the NULL workspace: nothing is enqueued)
+    assert ctypes.sizeof(b.Options) == 40 and ctypes.sizeof(b.Report) == 16
+    assert _call_encode_ex(None) == b.S2R_ERR_WORKSPACE
+    assert _call_encode_ex(_options()) == b.S2R_ERR_WORKSPACE
     for st in (b.S2R_INSERT_SLICE, b.S2R_INSERT_ATOMIC, b.S2R_INSERT_AUTO):
-        assert b.load().s2r_set_insert_strategy(st) == b.S2R_OK
+        assert _call_encode_ex(_options(insert_strategy=st)) == b.S2R_ERR_WORKSPACE
+    assert _call_encode_ex(_options(insert_strategy=3)) == b.S2R_ERR_SIZE
+    assert _call_encode_ex(_options(insert_strategy=-1)) == b.S2R_ERR_SIZE
+    assert _call_encode_ex(_options(decode_strategy=5)) == b.S2R_ERR_SIZE
+    assert _call_encode_ex(_options(flags=1)) == b.S2R_ERR_SIZE
+    assert _call_encode_ex(_options(struct_bytes=48)) == b.S2R_ERR_SIZE
+    tr = b.Trace()
+    tr.begin[b.S2R_KERNEL_ENCODE_SCAN] = 0x40                                         # begin without end
+    assert _call_encode_ex(_options(trace=ctypes.pointer(tr))) == b.S2R_ERR_NULL
+    tr.end[b.S2R_KERNEL_ENCODE_SCAN] = 0x50
+    assert _call_encode_ex(_options(trace=ctypes.pointer(tr))) == b.S2R_ERR_WORKSPACE
+    rep = b.Report(7, 7, 7, 7)
+    assert _call_encode_ex(_options(report=ctypes.pointer(rep))) == b.S2R_ERR_WORKSPACE
+    assert (rep.insert_strategy, rep.decode_strategy, rep.scan_launch_workers, rep.reserved) == (0, 0, 0, 0)
+    lib = b.load()
+    bad = _options(decode_strategy=9)
+    assert lib.s2r_decode_ex(0x1000, 0x2000, 1000, 3, 64, 0, None, None, 0, 0x3000, None, None, 0, None,
+                             ctypes.byref(bad)) == b.S2R_ERR_SIZE
+    assert lib.s2r_decode_blocks_ex(0x1000, 0x2000, 1000, 10, 3, 64, 0, None, None, 0, 0x3000, None, 0, None,
+                                    ctypes.byref(bad)) == b.S2R_ERR_SIZE
+    one = lambda v: (ctypes.c_void_p * 1)(v)
+    assert lib.s2r_encode_blocks_batch_ex(one(0x1000), 1, 1000, 10, 3, 64, 0, one(0x2000), one(0x3000), None, 0,
+                                          0x4000, None, 0, None, ctypes.byref(bad)) == b.S2R_ERR_SIZE
+    assert lib.s2r_topk_encode_blocks_batch_ex(one(0x1000), None, 1, 1000, 10, 5, 3, 64, 0, one(0x2000), one(0x3000),
+                                               None, 0, 0x4000, None, 0, None, ctypes.byref(bad)) == b.S2R_ERR_SIZE
 
 
-def test_set_kernel_events_argument_checks():
-    assert b.load().s2r_set_kernel_events(7, None, None) == b.S2R_ERR_SIZE
-    assert b.load().s2r_set_kernel_events(0, 0x10, None) == b.S2R_ERR_NULL
-    assert b.load().s2r_set_kernel_events(0, None, None) == b.S2R_OK
+def test_binding_side_defaults_are_checked():
+    with pytest.raises(b.S2RError):
+        b.set_insert_strategy(7)
+    with pytest.raises(b.S2RError):
+        b.set_decode_strategy(5)
+    with pytest.raises(b.S2RError):
+        b.set_kernel_events(b.S2R_KERNEL_SLOTS, None, None)
+    b.set_insert_strategy(b.S2R_INSERT_AUTO)
+    b.set_decode_strategy(b.S2R_DECODE_AUTO)
 
 
 def test_probe_read_argument_checks():
@@ -153,10 +205,6 @@ def test_probe_read_argument_checks():
 
 
 def test_decode_strategy_and_workspace_argument_checks():
-    lib = b.load()
-    assert lib.s2r_set_decode_strategy(5) == b.S2R_ERR_SIZE
-    for st in (b.S2R_DECODE_SLICE, b.S2R_DECODE_GATHER, b.S2R_DECODE_AUTO):
-        assert lib.s2r_set_decode_strategy(st) == b.S2R_OK
     base = b.workspace_bytes(1 << 20, 3, 1 << 14)
     assert b.decode_workspace_bytes(1 << 20, 3, 1 << 14, 50000) >= base + 16 * 3 * 50000
     assert b.decode_workspace_bytes(1 << 20, 9, 1 << 14, 50000) == base        # more than 8 rows: gather only

@@ -410,8 +410,9 @@ def test_auto_strategy_matches_oracle_on_every_small_recipe():
 
 
 def test_strategy_argument_check():
-    assert binding.load().s2r_set_insert_strategy(7) == binding.S2R_ERR_SIZE
-    assert binding.load().s2r_set_insert_strategy(binding.S2R_INSERT_AUTO) == binding.S2R_OK
+    with pytest.raises(binding.S2RError):
+        binding.set_insert_strategy(7)
+    binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
 
 
 def test_recipe5_full_size_in_the_benchmarked_configuration():
