@@ -394,7 +394,10 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
     hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, count), dim3(kBinBlock), scatter_lds, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, false, st);
-    hipLaunchKernelGGL(sketch_slice_kernel, dim3(E.nbins, count), dim3(kSliceBlock), lds, st, E);
+    // about one workgroup per compute unit, each walking `per` consecutive bins of one worker
+    const uint32_t per = (uint32_t)ceil_div((uint64_t)E.nbins * count, kSliceWorkgroups);
+    hipLaunchKernelGGL(sketch_slice_kernel, dim3((uint32_t)ceil_div(E.nbins, per), count), dim3(kSliceBlock), lds, st,
+                       E, per);
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, true, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
 

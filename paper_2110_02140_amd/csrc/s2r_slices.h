@@ -341,68 +341,105 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
   }
 }
 
-// Workgroup = bin (j, s) of worker blockIdx.y.  The slice is accumulated in
-// float64: the LDS float64 atomic add runs at full LDS rate on this chip (about
-// 1.7e12 per second over the chip at random addresses) while the float32 one
-// takes a slow path (0.2e12 per second, whatever the addresses); each cell is
-// rounded to float32 once, when the slice is stored.  The first records are
-// requested before the slice is cleared, and each later batch while the previous
-// one is added.
-__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B) {
+// A workgroup takes `per` consecutive bins (j, s) of one worker, one after the
+// other.  A slice is accumulated in float64: the LDS float64 atomic add runs at
+// full LDS rate on this chip (about 1.7e12 per second over the chip at random
+// addresses) while the float32 one takes a slow path (0.2e12 per second,
+// whatever the addresses); each cell is rounded to float32 once, when the slice
+// is stored.  With 128 KiB of accumulators a compute unit holds one workgroup,
+// and a workgroup that handled a single bin spent its life waiting: for its
+// launch, for its first records, for its stores to drain.  Walking several bins
+// hides all three: the first records of the next bin are requested before the
+// current slice is read out, the read-out leaves zeros behind (no separate
+// clearing pass), and the streaming stores of one slice drain while the next
+// is being accumulated.
+__global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B, uint32_t per) {
   extern __shared__ double s_slice[];
-  constexpr int kAhead = 4;                               // 8-byte record loads in flight per thread
+  constexpr int kAhead = 4;                               // 8-byte record loads per thread and batch
+  constexpr uint32_t kBatch = kSliceBlock * kAhead;       // records per batch; two batches are in flight
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
-  const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
+  const uint32_t bin0 = blockIdx.x * per;                 // bin = (j << log2(slices per row)) + s
+  if (bin0 >= B.nbins) return;                            // uniform over the workgroup
+  const uint32_t bin1 = bin0 + per < B.nbins ? bin0 + per : B.nbins;
   const uint32_t cells = 1u << B.slice_log2;
   const uint32_t* bin_start = ws_bin_start(B, k);
-  const uint32_t first = bin_start[bin], last = bin_start[bin + 1];
   const u32x2* __restrict__ rec = reinterpret_cast<const u32x2*>(ws_records(B, k));
   const u32x2 none = {0u, 0u};
-  u32x2 x[kAhead];
-  uint64_t r0 = (uint64_t)first + threadIdx.x;            // 64 bits: positions near 2^32 must not wrap
+  // The records of consecutive bins are consecutive in memory: the workgroup streams through those of its
+  // bins, batch after batch, whatever the bins' boundaries are; `base` is the position of the batch in x.
+  const uint64_t end = bin_start[bin1];                   // 64 bits: positions near 2^32 must not wrap
+  uint64_t base = bin_start[bin0];
+  u32x2 x[kAhead], y[kAhead];
 #pragma unroll
-  for (int u = 0; u < kAhead; ++u)
-    x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&rec[r0 + u * kSliceBlock]) : none;
-
+  for (int u = 0; u < kAhead; ++u) {
+    const uint64_t r = base + threadIdx.x + u * kSliceBlock;
+    x[u] = r < end ? __builtin_nontemporal_load(&rec[r]) : none;
+    y[u] = r + kBatch < end ? __builtin_nontemporal_load(&rec[r + kBatch]) : none;
+  }
   if (cells >= 2u * kSliceBlock) {                        // (the LDS array is 16-byte aligned)
     for (uint32_t c = threadIdx.x; c < cells / 2; c += kSliceBlock)
       reinterpret_cast<double2*>(s_slice)[c] = make_double2(0.0, 0.0);
   } else {
     for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_slice[c] = 0.0;
   }
-  __syncthreads();
-
-  while (r0 < last) {                                     // x holds the records r0 + u * kSliceBlock
-    const uint64_t r1 = r0 + kSliceBlock * kAhead;
-    u32x2 y[kAhead];
-#pragma unroll
-    for (int u = 0; u < kAhead; ++u)
-      y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&rec[r1 + u * kSliceBlock]) : none;
+  uint32_t bin = bin0;
+  uint64_t first = base, last = bin_start[bin0 + 1];      // the current bin's records are [first, last)
+  uint64_t next_last = bin0 + 1 < bin1 ? bin_start[bin0 + 2] : last;
+  __syncthreads();                                        // the slice is all zero
+  while (true) {
+    // the part of the batch that belongs to the current bin
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
-      if (r0 + u * kSliceBlock < last)
+      const uint64_t r = base + threadIdx.x + u * kSliceBlock;
+      if (r >= first && r < last)
         __hip_atomic_fetch_add(&s_slice[x[u].x & 0x7FFFFFFFu],
                                (double)__uint_as_float(x[u].y ^ (x[u].x & 0x80000000u)),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
+    if (base + kBatch < last) {                           // uniform: the bin goes on beyond this batch
+      base += kBatch;
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u) x[u] = y[u];
-    r0 = r1;
-  }
-  __syncthreads();
-  // bin = j * slices-per-row + s, so the slice starts at cell bin * cells of the row-major sketch
-  float* out = B.w[k].sketch + (uint64_t)bin * cells;
-  if (cells >= 4u * kSliceBlock) {                        // (every slice of 4 cells or more is 16-byte aligned)
-    for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock) {
-      const double2 lo = reinterpret_cast<const double2*>(s_slice)[2 * c];
-      const double2 hi = reinterpret_cast<const double2*>(s_slice)[2 * c + 1];
-      f32x4 o;
-      o.x = (float)lo.x; o.y = (float)lo.y; o.z = (float)hi.x; o.w = (float)hi.y;
-      __builtin_nontemporal_store(o, &reinterpret_cast<f32x4*>(out)[c]);
+      for (int u = 0; u < kAhead; ++u) {
+        x[u] = y[u];
+        const uint64_t r = base + kBatch + threadIdx.x + u * kSliceBlock;
+        y[u] = r < end ? __builtin_nontemporal_load(&rec[r]) : none;
+      }
+      continue;
     }
-  } else {
-    for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) out[c] = (float)s_slice[c];
+    __syncthreads();                                      // every record of the bin is in the slice
+    // the slice starts at cell bin * cells of the row-major sketch; every cell a thread reads it also clears
+    float* out = B.w[k].sketch + (uint64_t)bin * cells;
+    if (cells >= 4u * kSliceBlock) {                      // (every slice of 4 cells or more is 16-byte aligned)
+      for (uint32_t c = threadIdx.x; c < cells / 4; c += kSliceBlock) {
+        double2* cell = reinterpret_cast<double2*>(s_slice) + 2 * c;
+        const double2 lo = cell[0], hi = cell[1];
+        cell[0] = make_double2(0.0, 0.0);
+        cell[1] = make_double2(0.0, 0.0);
+        f32x4 o;
+        o.x = (float)lo.x; o.y = (float)lo.y; o.z = (float)hi.x; o.w = (float)hi.y;
+        __builtin_nontemporal_store(o, &reinterpret_cast<f32x4*>(out)[c]);
+      }
+    } else {
+      for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) {
+        out[c] = (float)s_slice[c];
+        s_slice[c] = 0.0;
+      }
+    }
+    if (++bin == bin1) break;                             // uniform
+    first = last;
+    last = next_last;
+    next_last = bin + 1 < bin1 ? bin_start[bin + 2] : last;
+    if (first >= base + kBatch) {                         // uniform: the bin ended with the batch
+      base += kBatch;
+#pragma unroll
+      for (int u = 0; u < kAhead; ++u) {
+        x[u] = y[u];
+        const uint64_t r = base + kBatch + threadIdx.x + u * kSliceBlock;
+        y[u] = r < end ? __builtin_nontemporal_load(&rec[r]) : none;
+      }
+    }
+    __syncthreads();                                      // the slice is all zero again
   }
 }
 
