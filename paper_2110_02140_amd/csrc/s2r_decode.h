@@ -264,12 +264,13 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
 template <int D>
 __global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSliceArgs A) {
   __shared__ float s_est[kBinChunk];
-  const uint32_t chunk = blockIdx.x;
   const uint64_t total = *A.count;
   const uint64_t listed = total < A.cap ? total : A.cap;
   const uint64_t have = A.block != 0 ? listed * A.block : listed;
+  // (the grid is sized for the number of positions expected: a workgroup takes the chunks blockIdx.x,
+  // blockIdx.x + gridDim.x, ... that hold list positions)
+  for (uint32_t chunk = blockIdx.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {     // uniform
   const uint64_t t0 = (uint64_t)chunk * kBinChunk;
-  if (t0 >= have) return;                                 // uniform over the workgroup
   const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
   float est[kBinItems][D];
   uint2 cur[kBinItems], nxt[kBinItems];                   // row j's answers, and row j + 1's on their way
@@ -312,6 +313,7 @@ __global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSl
       if ((uint64_t)A.blk_list[q] * A.block + (t0 + t - q * A.block) >= A.n) g = 0.0f;
     }
     A.val_out[t0 + t] = g;
+  }
   }
 }
 

@@ -321,6 +321,7 @@ s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* s
 // unused, cap counted in blocks).
 struct EncodeLaunch {                      // what the launches of one call share
   uint32_t ntiles, scan_blocks, scan_group;
+  uint32_t chunk_grid;                     // workgroups per worker of the kernels that walk the list chunks
   uint64_t nvec, zb;
   uint32_t ntail;
   int32_t strategy;
@@ -384,14 +385,14 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
 
   if (L.strategy == S2R_INSERT_SLICE) {
     const size_t lds = sizeof(double) << E.slice_log2;
-    hipLaunchKernelGGL(bin_hist_kernel, dim3(E.nchunks, count), dim3(kBinBlock), 0, st, E, hp);
+    hipLaunchKernelGGL(bin_hist_kernel, dim3(L.chunk_grid, count), dim3(kBinBlock), 0, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(E.nbins, kWave), count), dim3(kBinBlock), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_start_kernel, dim3(1, count), dim3(kBinBlock), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (L.log2w - E.slice_log2));
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3(E.nchunks, count), dim3(kBinBlock), scatter_lds, st, E, hp);
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(L.chunk_grid, count), dim3(kBinBlock), scatter_lds, st, E, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, false, st);
     // about one workgroup per compute unit, each walking `per` consecutive bins of one worker
@@ -459,6 +460,8 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   L.strategy = choose_strategy(W, nbits, d, w, lists, cap_items, expect, ws_each, X.insert_strategy);
   L.lists = lists;
   L.marked = marked;
+  // (the chunk kernels loop: a grid sized for the expected items serves any number of them)
+  L.chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);
 
   E.nworkers = W;
   E.rowpre_off = 0;
@@ -683,24 +686,25 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     const uint32_t helpers = dense_grid(ntiles, 2048);
     hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_hist_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), 0, st, B, hp);
+    const uint32_t chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);   // (the chunk kernels loop)
+    hipLaunchKernelGGL(bin_hist_kernel, dim3(chunk_grid, 1), dim3(kBinBlock), 0, st, B, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(L.nbins, kWave), 1), dim3(kBinBlock), 0, st, B);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_start_kernel, dim3(1, 1), dim3(kBinBlock), 0, st, B);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * ((size_t)1 << (B.log2w - B.slice_log2));
-    hipLaunchKernelGGL(bin_scatter_kernel, dim3(L.nchunks, 1), dim3(kBinBlock), scatter_lds, st, B, hp);
+    hipLaunchKernelGGL(bin_scatter_kernel, dim3(chunk_grid, 1), dim3(kBinBlock), scatter_lds, st, B, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     // one workgroup per compute unit at a time (the slice fills its LDS): with few bins, several workgroups
     // share a bin's queries so that the last round of workgroups is not mostly idle units
-    const uint64_t per_bin = cap_items * d / L.nbins;      // at most, on average
+    const uint64_t per_bin = expect * d / L.nbins;         // expected, on average
     uint32_t parts = L.nbins >= 512 ? 1u : (uint32_t)ceil_div(768, L.nbins);   // (two rounds and more: no gain measured)
     while (parts > 1 && per_bin / parts < 16384) --parts;
     if (parts > 8) parts = 8;
     hipLaunchKernelGGL(decode_slice_kernel, dim3(L.nbins, parts), dim3(kSliceBlock), sizeof(float) << L.slice_log2, st, Q);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    const dim3 mgrid(L.nchunks), mblock(kBinBlock);
+    const dim3 mgrid(chunk_grid), mblock(kBinBlock);
     switch (d) {
       case 1: hipLaunchKernelGGL(decode_median_kernel<1>, mgrid, mblock, 0, st, Q); break;
       case 2: hipLaunchKernelGGL(decode_median_kernel<2>, mgrid, mblock, 0, st, Q); break;

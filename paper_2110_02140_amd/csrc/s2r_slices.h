@@ -73,63 +73,65 @@ __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B
   __shared__ uint32_t s_hist[kMaxBins];
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
-  const uint32_t chunk = blockIdx.x;
   const uint64_t have = listed_items(B, k);
-  // the grid covers the lists' capacity; the chunks beyond the listed items leave at once, and no kernel
-  // reads their rows of the histogram
-  if ((uint64_t)chunk * kBinChunk >= have) return;       // uniform over the workgroup
-  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
-  __syncthreads();
   const WorkerPtrs P = B.w[k];
   const uint32_t spr_log2 = B.log2w - B.slice_log2;
-  uint32_t i[kBinItems], v[kBinItems];
-  bool ok[kBinItems];
-#pragma unroll
-  for (int u = 0; u < kBinItems; ++u) {
-    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-    ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
-  }
-#pragma unroll
-  for (int u = 0; u < kBinItems; ++u) {
-    if (ok[u]) {
-      for (uint32_t j = 0; j < B.d; ++j) {
-        const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
-        __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
-    }
-  }
-  __syncthreads();
-  uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
-  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
-  if (B.rowpre_off == 0) return;                         // uniform over the workgroup
-  // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
   constexpr int kWaves = kBinBlock / kWave;
   constexpr int kMaxPer = kMaxBins / kBinBlock;
   __shared__ uint32_t s_wave[kWaves];
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wv = threadIdx.x / kWave;
-  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
-  uint32_t c[kMaxPer], sum = 0;
+  // The grid is sized for the number of items expected; a workgroup takes the chunks blockIdx.x,
+  // blockIdx.x + gridDim.x, ... that hold listed items (no kernel reads the histogram rows of the others).
+  for (uint32_t chunk = blockIdx.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {   // uniform
+    for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
+    __syncthreads();
+    uint32_t i[kBinItems], v[kBinItems];
+    bool ok[kBinItems];
 #pragma unroll
-  for (int q = 0; q < kMaxPer; ++q) {
-    const uint32_t e = threadIdx.x * per + q;
-    c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
-    sum += c[q];
-  }
-  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
-  if (lane == kWave - 1) s_wave[wv] = incl;
-  __syncthreads();
-  uint32_t run = incl - sum;
-#pragma unroll
-  for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
-  uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
-#pragma unroll
-  for (int q = 0; q < kMaxPer; ++q) {
-    const uint32_t e = threadIdx.x * per + q;
-    if ((uint32_t)q < per && e < B.nbins) {
-      rowpre[e] = run;
-      run += c[q];
+    for (int u = 0; u < kBinItems; ++u) {
+      const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+      ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
     }
+#pragma unroll
+    for (int u = 0; u < kBinItems; ++u) {
+      if (ok[u]) {
+        for (uint32_t j = 0; j < B.d; ++j) {
+          const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
+          __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
+    }
+    __syncthreads();
+    uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+    for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
+    if (B.rowpre_off != 0) {                               // uniform over the workgroup
+      // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
+      const uint32_t lane = threadIdx.x & (kWave - 1);
+      const uint32_t wv = threadIdx.x / kWave;
+      const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
+      uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+      for (int q = 0; q < kMaxPer; ++q) {
+        const uint32_t e = threadIdx.x * per + q;
+        c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
+        sum += c[q];
+      }
+      const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+      if (lane == kWave - 1) s_wave[wv] = incl;
+      __syncthreads();
+      uint32_t run = incl - sum;
+#pragma unroll
+      for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
+      uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
+#pragma unroll
+      for (int q = 0; q < kMaxPer; ++q) {
+        const uint32_t e = threadIdx.x * per + q;
+        if ((uint32_t)q < per && e < B.nbins) {
+          rowpre[e] = run;
+          run += c[q];
+        }
+      }
+    }
+    __syncthreads();                                     // s_hist and s_wave are rewritten by the next chunk
   }
 }
 
@@ -256,11 +258,7 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
   __shared__ uint32_t s_wave[kWaves];
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
-  const uint32_t chunk = blockIdx.x;
   const uint64_t have = listed_items(B, k);
-  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
-  if (t0 >= have) return;                                 // uniform over the workgroup
-  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
   const uint32_t spr_log2 = B.log2w - B.slice_log2;
   const uint32_t spr = 1u << spr_log2;                    // slices per row
   uint32_t* s_loc = reinterpret_cast<uint32_t*>(s_stage + kBinChunk);
@@ -268,11 +266,17 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wv = threadIdx.x / kWave;
   const WorkerPtrs P = B.w[k];
-  const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
   const uint32_t* bin_start = ws_bin_start(B, k);
   uint2* __restrict__ rec = ws_records(B, k);
   const uint32_t mask = (1u << B.slice_log2) - 1u;
   const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan: thread t owns t*per ..
+  for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
+  // The grid is sized for the number of items expected; a workgroup takes the chunks blockIdx.x,
+  // blockIdx.x + gridDim.x, ... that hold listed items.
+  for (uint32_t chunk = blockIdx.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {   // uniform
+  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
+  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+  const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
 
   uint32_t i[kBinItems], v[kBinItems];
   uint32_t ok = 0;                                        // bit u: item u exists and takes part (see load_item)
@@ -281,7 +285,6 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
     const uint32_t t = u * kBinBlock + threadIdx.x;
     if (t < count && load_item(B, P, t0 + t, i[u], v[u])) ok |= 1u << u;
   }
-  for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
 
   for (uint32_t j = 0; j < B.d; ++j) {
     // where this thread's first run of this (chunk, row) starts in the worker's records: wanted after the
@@ -337,7 +340,8 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
       const uint2 r = s_stage[p];
       rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80007FFFu, r.y);
     }
-    for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;      // for the next row; not read above
+    for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;      // for the next row (or chunk); not read above
+  }
   }
 }
 
