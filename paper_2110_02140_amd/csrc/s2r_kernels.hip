@@ -585,7 +585,10 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
   const uint64_t bb = ceil_div(A.nwords, kBlock);
   A.sketch_blocks = (uint32_t)sb;
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(merge_kernel, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
+  if (W >= 16)
+    hipLaunchKernelGGL(merge_kernel<8>, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
+  else
+    hipLaunchKernelGGL(merge_kernel<4>, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
 
