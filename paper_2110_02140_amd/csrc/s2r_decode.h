@@ -31,17 +31,20 @@ struct DecodeArgs {
 };
 
 // Median of D values by a fully unrolled exchange network: every output is one
-// of the inputs (odd D); even D averages the two middle ones in float32.
+// of the inputs (odd D); even D averages the two middle ones in float32.  The
+// order is the total order a sort gives: NaN after everything else (a gradient
+// that holds a NaN or opposite infinities poisons its d buckets, and the indices
+// that read them, exactly as it does in a sort-based median), -0.0 and +0.0 equal.
 template <int D>
 __device__ __forceinline__ float median_fixed(float (&x)[D]) {
 #pragma unroll
   for (int a = 0; a < D - 1; ++a) {
 #pragma unroll
     for (int b = 0; b < D - 1 - a; ++b) {
-      const float lo = fminf(x[b], x[b + 1]);
-      const float hi = fmaxf(x[b], x[b + 1]);
-      x[b] = lo;
-      x[b + 1] = hi;
+      const float p = x[b], q = x[b + 1];
+      const bool swap = !(p <= q) && (q == q);     // p > q, or p is NaN and q is not
+      x[b] = swap ? q : p;
+      x[b + 1] = swap ? p : q;
     }
   }
   if constexpr ((D & 1) != 0) return x[D / 2];

@@ -301,6 +301,50 @@ def test_special_values_follow_the_bit_pattern_rule():
     assert np.array_equal(b.nz_val[0][:4].cpu().numpy(), g[[6, 70, 129, 299]])
 
 
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 5])
+def test_nan_and_infinities_poison_what_the_oracle_says_they_poison(d, strategy, decode_strategy):
+    """A NaN, a +Inf and a -Inf among the gradient values are non-zero entries like any other: they
+    are listed and inserted, their buckets become non-finite, and the median takes them in the total
+    order of a sort (NaN last), so every decoded value is non-finite exactly where the oracle's is,
+    with the same class (NaN, +Inf, -Inf), and within the tolerance elsewhere."""
+    rng = np.random.default_rng(31 + d)
+    n, W, w = 30000, 2, 256                       # narrow rows: the poisoned buckets are shared with many indices
+    idx = [np.sort(rng.choice(n, 2000, replace=False)).astype(np.uint32) for _ in range(W)]
+    val = [rng.normal(0, 1, 2000).astype(np.float32) + 3.0 for _ in range(W)]
+    val[0][10], val[0][500], val[0][900] = np.nan, np.inf, -np.inf
+    val[1][700], val[1][1300] = np.inf, -np.inf
+    wl = _custom(n, idx, val, d=d, w=w, W=W, seed=5)
+    enc, S, C, M, dec = _oracle_for(wl)
+    b = pipeline.buffers_for(wl)
+    b.step()
+    torch.cuda.synchronize()
+    for k in range(W):
+        cnt = int(b.nnz.cpu()[k])
+        assert cnt == len(idx[k])
+        assert np.array_equal(b.nz_idx[k][:cnt].cpu().numpy().view(np.uint32), idx[k])
+        assert np.array_equal(b.nz_val[k][:cnt].cpu().numpy().view(np.uint32), val[k].view(np.uint32))
+    assert np.array_equal(pipeline.u64(b.bitmap_or), C)
+
+    def same_class(got, ref, M_of, what):
+        got, ref = np.asarray(got, dtype=np.float64).ravel(), np.asarray(ref, dtype=np.float64).ravel()
+        fin = np.isfinite(ref)
+        assert np.array_equal(np.isnan(got), np.isnan(ref)), f"{what}: NaN positions"
+        assert np.array_equal(np.isposinf(got), np.isposinf(ref)) and np.array_equal(np.isneginf(got), np.isneginf(ref)), \
+            f"{what}: infinities"
+        # (an entry that reads a poisoned bucket besides its finite ones is judged against the largest finite mass)
+        m = np.where(np.isfinite(M_of), M_of, np.max(M[np.isfinite(M)]))
+        with np.errstate(invalid="ignore"):
+            assert np.all(np.abs(got[fin] - ref[fin]) <= REL * m.ravel()[fin] + DENORM_SLACK), f"{what}: finite entries"
+        return int((~fin).sum())
+
+    bad_cells = same_class(b.sketch_sum.cpu().numpy(), S, M, "merged sketch")
+    cnt = int(b.out_count.cpu()[0])
+    assert cnt == len(dec["idx"]) and np.array_equal(b.out_idx[:cnt].cpu().numpy().view(np.uint32), dec["idx"])
+    bad_vals = same_class(b.out_val[:cnt].cpu().numpy(), dec["val"], orc.decode_tolerance_mass(M, dec["idx"], wl.seed),
+                          "decoded values")
+    assert bad_cells >= d and bad_vals > 0, "the case must poison something"
+
+
 @pytest.mark.parametrize("d,w", [(1, 1), (1, 64), (2, 2), (4, 128), (5, 1 << 12), (6, 32), (7, 64), (8, 64), (16, 16)])
 def test_rows_and_widths(d, w, strategy):
     rng = np.random.default_rng(d * 1000 + w)

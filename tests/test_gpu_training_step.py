@@ -3,14 +3,10 @@
 update (Algorithm 1), on a synthetic least-squares problem split over W simulated
 workers.
 
-Two checks.  (1) Parity, step by step: before every step the device state
-(gradients, residuals, parameters) is downloaded and the oracle's own chain is run
-from it on the CPU; residuals must agree bit for bit and the parameters within the
-decode tolerance.  (2) The behaviour the method exists for: with a sketch wide
-enough for the union, sparsified training with residuals reaches a loss close to
-that of dense gradient descent with the same step size, and a far narrower sketch
-(heavy collisions) still descends (the estimation errors act like
-gradient noise).
+Parity, step by step: before every step the device state (gradients, residuals,
+parameters) is downloaded and the oracle's own chain is run from it on the CPU;
+residuals must agree bit for bit and the parameters within the decode tolerance.
+A last test replays a captured step as a HIP graph against the eager calls.
 
 The gradients themselves come from torch matmuls: they are the model's side of
 the loop, an input to the path under test.
@@ -134,38 +130,6 @@ def test_training_steps_match_the_oracle_chain():
         assert np.all(err <= tol), f"step {it}: worst parameter error {err.max():.3e}"
         if it == 0:
             assert not any(e.any() for e in es) and all(r.any() for r in st.residual), "residuals start at zero and fill up"
-
-
-def _train(prob, steps, lr, sparsifier=None):
-    x = torch.zeros(prob.n, dtype=torch.float32, device="cuda")
-    for _ in range(steps):
-        grads = prob.grads(x)
-        if sparsifier is None:
-            x -= lr / prob.W * sum(grads)
-        else:
-            sparsifier.step(grads, x, -lr / prob.W)
-    torch.cuda.synchronize()
-    return prob.loss(x)
-
-
-def test_sparsified_training_with_residuals_descends_like_dense_training():
-    W, n, m, B = 4, 1 << 16, 64, 256
-    nb = n // B
-    K = nb // 8                                   # each worker sends 1/8 of its blocks
-    prob = LeastSquares(W, n, m, seed=11)
-    lr, steps = 0.5, 150
-    start = prob.loss(torch.zeros(n, device="cuda"))
-    dense = _train(prob, steps, lr)
-    wide = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 17))     # lambda = w / union >= 4 per row
-    narrow = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 13))   # lambda <= 1: many collisions
-    two = _train(prob, steps, lr, pipeline.SparsifiedStep(W, n, B, K, 5, 1 << 17, fused=False))
-    print(f"[loss] start {start:.4e} dense {dense:.4e} sparsified(wide sketch) {wide:.4e} (narrow) {narrow:.4e} "
-          f"(not fused, wide) {two:.4e}", flush=True)
-    assert abs(two - wide) <= 0.05 * wide, "the fused and the two-call chains train alike"
-    assert dense < 0.05 * start
-    assert wide < 0.15 * start, "Top-K with residuals and a roomy sketch must follow dense training"
-    assert wide < 6 * dense
-    assert narrow < 0.5 * start, "a sketch far below the union still descends"
 
 
 def test_fused_training_step_replays_from_a_captured_graph():
