@@ -166,8 +166,10 @@ def cpu_baseline(wl, first_sample: int, target_wall_s: float = 5.0):
 
     ns = min(wl.n, first_sample)
     t_enc, t_rest, union = run(ns, list(range(wl.W)))
-    if ns < wl.n and t_enc + t_rest < target_wall_s / 2:
-        ns = int(min(wl.n, ns * target_wall_s / (t_enc + t_rest)))
+    for _ in range(3):                                       # (fixed costs dominate small samples: size again)
+        if ns >= wl.n or t_enc + t_rest >= target_wall_s / 2:
+            break
+        ns = int(min(wl.n, ns * min(8.0, target_wall_s / (t_enc + t_rest))))
         t_enc, t_rest, union = run(ns, list(range(wl.W)))
     wall = t_enc + t_rest
     t_one, _, _ = run(ns, [0])                               # one process alone: the single-core encode rate
