@@ -264,15 +264,9 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   }
 }
 
+// The medians of one chunk of list positions (all threads of the workgroup call it with the same arguments).
 template <int D>
-__global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSliceArgs A) {
-  __shared__ float s_est[kBinChunk];
-  const uint64_t total = *A.count;
-  const uint64_t listed = total < A.cap ? total : A.cap;
-  const uint64_t have = A.block != 0 ? listed * A.block : listed;
-  // (the grid is sized for the number of positions expected: a workgroup takes the chunks blockIdx.x,
-  // blockIdx.x + gridDim.x, ... that hold list positions)
-  for (uint32_t chunk = blockIdx.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {     // uniform
+__device__ __forceinline__ void median_chunk(const DecodeSliceArgs& A, uint32_t chunk, uint64_t have, float* s_est) {
   const uint64_t t0 = (uint64_t)chunk * kBinChunk;
   const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
   float est[kBinItems][D];
@@ -317,6 +311,22 @@ __global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSl
     }
     A.val_out[t0 + t] = g;
   }
+}
+
+// The grid is sized for the number of positions expected, which is normally all there are: a workgroup takes
+// chunk blockIdx.x, and only if the list holds more, the chunks blockIdx.x + gridDim.x, ... after it.
+template <int D>
+__global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSliceArgs A) {
+  __shared__ float s_est[kBinChunk];
+  const uint64_t total = *A.count;
+  const uint64_t listed = total < A.cap ? total : A.cap;
+  const uint64_t have = A.block != 0 ? listed * A.block : listed;
+  uint32_t chunk = blockIdx.x;
+  if ((uint64_t)chunk * kBinChunk >= have) return;        // uniform over the workgroup
+  median_chunk<D>(A, chunk, have, s_est);
+  for (chunk += gridDim.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {      // uniform
+    __syncthreads();                                      // s_est is rewritten
+    median_chunk<D>(A, chunk, have, s_est);
   }
 }
 

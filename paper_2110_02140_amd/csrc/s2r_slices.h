@@ -69,69 +69,78 @@ __device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs
   return inside && (v << 1) != 0u;
 }
 
+// The histogram of one chunk (all threads of the workgroup call it with the same arguments).
+__device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows& hp, uint32_t k, uint32_t chunk,
+                                           uint64_t have, uint32_t* s_hist, uint32_t* s_wave) {
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
+  __syncthreads();
+  const WorkerPtrs P = B.w[k];
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;
+  uint32_t i[kBinItems], v[kBinItems];
+  bool ok[kBinItems];
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
+    ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kBinItems; ++u) {
+    if (ok[u]) {
+      for (uint32_t j = 0; j < B.d; ++j) {
+        const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
+        __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+  for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
+  if (B.rowpre_off == 0) return;                         // uniform over the workgroup
+  // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
+  constexpr int kWaves = kBinBlock / kWave;
+  constexpr int kMaxPer = kMaxBins / kBinBlock;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
+  uint32_t c[kMaxPer], sum = 0;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
+    sum += c[q];
+  }
+  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
+  if (lane == kWave - 1) s_wave[wv] = incl;
+  __syncthreads();
+  uint32_t run = incl - sum;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
+  uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
+#pragma unroll
+  for (int q = 0; q < kMaxPer; ++q) {
+    const uint32_t e = threadIdx.x * per + q;
+    if ((uint32_t)q < per && e < B.nbins) {
+      rowpre[e] = run;
+      run += c[q];
+    }
+  }
+}
+
+// The grid is sized for the number of items expected, which is normally all there are: a workgroup takes
+// chunk blockIdx.x, and only if the lists hold more, the chunks blockIdx.x + gridDim.x, ... after it.  No
+// kernel reads the histogram rows of chunks without listed items.
 __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_hist[kMaxBins];
+  __shared__ uint32_t s_wave[kBinBlock / kWave];
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const uint64_t have = listed_items(B, k);
-  const WorkerPtrs P = B.w[k];
-  const uint32_t spr_log2 = B.log2w - B.slice_log2;
-  constexpr int kWaves = kBinBlock / kWave;
-  constexpr int kMaxPer = kMaxBins / kBinBlock;
-  __shared__ uint32_t s_wave[kWaves];
-  // The grid is sized for the number of items expected; a workgroup takes the chunks blockIdx.x,
-  // blockIdx.x + gridDim.x, ... that hold listed items (no kernel reads the histogram rows of the others).
-  for (uint32_t chunk = blockIdx.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {   // uniform
-    for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
-    __syncthreads();
-    uint32_t i[kBinItems], v[kBinItems];
-    bool ok[kBinItems];
-#pragma unroll
-    for (int u = 0; u < kBinItems; ++u) {
-      const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-      ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
-    }
-#pragma unroll
-    for (int u = 0; u < kBinItems; ++u) {
-      if (ok[u]) {
-        for (uint32_t j = 0; j < B.d; ++j) {
-          const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
-          __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-      }
-    }
-    __syncthreads();
-    uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
-    for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
-    if (B.rowpre_off != 0) {                               // uniform over the workgroup
-      // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
-      const uint32_t lane = threadIdx.x & (kWave - 1);
-      const uint32_t wv = threadIdx.x / kWave;
-      const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
-      uint32_t c[kMaxPer], sum = 0;
-#pragma unroll
-      for (int q = 0; q < kMaxPer; ++q) {
-        const uint32_t e = threadIdx.x * per + q;
-        c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
-        sum += c[q];
-      }
-      const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
-      if (lane == kWave - 1) s_wave[wv] = incl;
-      __syncthreads();
-      uint32_t run = incl - sum;
-#pragma unroll
-      for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
-      uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
-#pragma unroll
-      for (int q = 0; q < kMaxPer; ++q) {
-        const uint32_t e = threadIdx.x * per + q;
-        if ((uint32_t)q < per && e < B.nbins) {
-          rowpre[e] = run;
-          run += c[q];
-        }
-      }
-    }
-    __syncthreads();                                     // s_hist and s_wave are rewritten by the next chunk
+  uint32_t chunk = blockIdx.x;
+  if ((uint64_t)chunk * kBinChunk >= have) return;       // uniform over the workgroup
+  hist_chunk(B, hp, k, chunk, have, s_hist, s_wave);
+  for (chunk += gridDim.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {      // uniform
+    __syncthreads();                                     // s_hist and s_wave are rewritten
+    hist_chunk(B, hp, k, chunk, have, s_hist, s_wave);
   }
 }
 
