@@ -95,10 +95,14 @@ const char* s2r_status_string(s2r_status status);
  * larger of the two).  Host only; returns 0 for sizes outside the limits. */
 size_t s2r_workspace_bytes(uint64_t n, uint32_t d, uint32_t w);
 
-/* Bytes of device scratch with which s2r_encode can also use the LDS-slice
- * strategy for lists of capacity cap (s2r_workspace_bytes plus 8*d bytes per
- * list entry for the partitioned records, plus their histograms).  With a
- * smaller workspace (but at least s2r_workspace_bytes) it inserts with atomics.
+/* Bytes of device scratch with which the LDS-slice strategy of s2r_encode can
+ * take cap list entries per worker (s2r_workspace_bytes plus 8*d bytes per
+ * entry for the partitioned records, plus their histograms).  cap need not be the
+ * capacity of the lists: with a workspace for fewer entries than a worker lists,
+ * the strategy takes as many as fit and the call inserts the rest with atomics
+ * (so a caller with long lists sizes the workspace for what it expects, with
+ * some margin, and says so in s2r_options.expected_nnz); with no room for any
+ * (but at least s2r_workspace_bytes) the call inserts with atomics only.
  * Host only; returns 0 outside the limits or if cap > n. */
 size_t s2r_encode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
 
@@ -452,12 +456,15 @@ size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t c
  *   S2R_INSERT_SLICE   workgroups that each own a slice of one sketch row in
  *                      LDS (float64 accumulators, rounded to float32 once) and
  *                      add the entries of Sparse(g), which a counting sort has
- *                      partitioned by slice; needs nz_idx / nz_val, a
- *                      workspace of s2r_encode_workspace_bytes, d*w <= 2^27 and
- *                      d*cap < 2^32 (otherwise the call uses atomics whatever
- *                      is asked for)
+ *                      partitioned by slice; needs nz_idx / nz_val, d*w <= 2^27
+ *                      and a workspace with room for the sort of at least one
+ *                      list entry (s2r_encode_workspace_bytes; otherwise the
+ *                      call uses atomics whatever is asked for).  List entries
+ *                      beyond what the workspace holds, and beyond (2^32-1)/d,
+ *                      are inserted with atomics
  *   S2R_INSERT_AUTO    (0, default) chosen from W, n, d, w and the expected number
- *                      of non-zeros per worker
+ *                      of non-zeros per worker; slices only if the workspace holds
+ *                      the sort of that many entries
  *
  * decode_strategy: how the query loops of Algorithm 1 (the d bucket reads per union
  * index) are carried out; the result is the same either way, bit for bit.

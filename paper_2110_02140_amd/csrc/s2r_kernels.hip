@@ -149,14 +149,34 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
 //  - slices: five more kernels, about 20 us of launches; 4 us per round of 256
 //    slice workgroups (each clears and stores 128 KiB of LDS); histogram, scatter
 //    and slice kernels together pass about 180e9 records per second.
-// `cap` is the capacity of the caller's lists, `expect` the number of items expected
-// (the caller's estimate, or cap when there is none); `asked` the caller's wish.
-static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t cap,
-                               uint64_t expect, size_t workspace_bytes, int32_t asked) {
-  if (!have_lists || cap == 0) return S2R_INSERT_ATOMIC;     // the slice strategy reads Sparse(g)
-  const SliceLayout L = slice_layout(n, d, w, cap);
-  if (!L.possible || workspace_bytes < L.total) return S2R_INSERT_ATOMIC;
+// `sort_cap` is the number of list items whose counting sort the workspace holds (at most the lists'
+// capacity), `expect` the number of items expected (the caller's estimate, or the lists' capacity when
+// there is none); `asked` the caller's wish.
+// The largest number of list items (<= cap) whose counting sort fits a workspace share of `bytes`; 0 if none.
+static uint64_t sort_capacity(uint64_t n, uint32_t d, uint32_t w, uint64_t cap, size_t bytes) {
+  if (cap == 0) return 0;
+  uint64_t hi = cap;                                       // (record positions are 32-bit)
+  const uint64_t most = ((1ull << 32) - 1) / d;
+  if (hi > most) hi = most;
+  {
+    const SliceLayout L = slice_layout(n, d, w, hi);
+    if (!L.possible) return 0;
+    if (L.total <= bytes) return hi;
+  }
+  uint64_t lo = 0;                                         // total(lo) fits (or lo = 0), total(hi) does not
+  while (hi - lo > 1) {
+    const uint64_t mid = lo + (hi - lo) / 2;
+    if (slice_layout(n, d, w, mid).total <= bytes) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, bool have_lists, uint64_t sort_cap,
+                               uint64_t expect, int32_t asked) {
+  if (!have_lists || sort_cap == 0) return S2R_INSERT_ATOMIC;     // the slice strategy reads Sparse(g)
   if (asked != S2R_INSERT_AUTO) return asked;
+  if (sort_cap < expect) return S2R_INSERT_ATOMIC;           // most items would be inserted with atomics after all
+  const SliceLayout L = slice_layout(n, d, w, sort_cap);
   const double records = (double)expect * d;
   const double rounds = (double)ceil_div((uint64_t)W * L.nbins, 256);       // all workers' slices share the CUs
   const double t_slice = 20e-6 + rounds * 4e-6 + W * records / 180e9;
@@ -407,7 +427,7 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
   } else if (L.marked) {
     // no scan has inserted anything: every set block goes the way of the blocks beyond the lists
     EncodeBatch A = E;
-    A.cap = 0;
+    A.sort_cap = 0;
     hipLaunchKernelGGL(sketch_overflow_kernel, dim3((uint32_t)ceil_div(ntiles, kBlock), count), dim3(kBlock), 0, st, A, hp);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
@@ -457,7 +477,12 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   EncodeLaunch L;
   L.ntiles = tiles_of(nbits);
   L.log2w = log2_of(w);
-  L.strategy = choose_strategy(W, nbits, d, w, lists, cap_items, expect, ws_each, X.insert_strategy);
+  // what the counting sort can take: list items (elements of listed blocks in the block codec), whole list
+  // entries only
+  uint64_t sort_items = lists ? sort_capacity(nbits, d, w, cap_items, ws_each) : 0;
+  if (block != 0) sort_items -= sort_items % block;
+  L.strategy = choose_strategy(W, nbits, d, w, lists, sort_items, expect, X.insert_strategy);
+  if (L.strategy != S2R_INSERT_SLICE) sort_items = 0;
   L.lists = lists;
   L.marked = marked;
   // (the chunk kernels loop: a grid sized for the expected items serves any number of them)
@@ -472,7 +497,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.block = block;
   E.prefix_off = workspace_prefix_off(nbits);
   E.dense_off = workspace_dense_off(nbits);
-  const SliceLayout SL = slice_layout(nbits, d, w, cap_items);
+  const SliceLayout SL = slice_layout(nbits, d, w, sort_items);
   E.hist_off = SL.hist_off;
   E.binstart_off = SL.binstart_off;
   E.rec_off = SL.rec_off;
@@ -481,6 +506,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.n = n;
   E.nwords = ceil_div(nbits, 64);
   E.cap = cap;
+  E.sort_cap = block != 0 ? sort_items / block : sort_items;
   E.ntiles = L.ntiles;
   E.d = d;
   E.log2w = L.log2w;
@@ -660,6 +686,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.n = elements;
     B.nwords = nwords;
     B.cap = cap;
+    B.sort_cap = cap;
     B.ntiles = ntiles;
     B.d = d;
     B.log2w = log2_of(w);
@@ -756,6 +783,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.n = elements;
     B.nwords = nwords;
     B.cap = cap;
+    B.sort_cap = cap;
     B.ntiles = ntiles;
     B.d = d;
     B.log2w = A.log2w;

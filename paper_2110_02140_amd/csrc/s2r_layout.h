@@ -69,7 +69,9 @@ struct EncodeBatch {
                              //   bitmap / nwords / ntiles / cap describe the block bitmap.  0: one bit per element
   uint64_t n;
   uint64_t nwords;
-  uint64_t cap;
+  uint64_t cap;              // capacity of the caller's lists (entries; blocks in the block codec)
+  uint64_t sort_cap;         // list entries that take part in the counting sort (<= cap; 0: none): what the
+                             //   workspace's record area holds; entries beyond it are inserted with atomics
   uint32_t ntiles;
   uint32_t d;
   uint32_t log2w;

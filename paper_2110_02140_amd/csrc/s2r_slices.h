@@ -39,7 +39,7 @@ static_assert(kMaxBins <= (1 << 13) && kSliceLog2Max <= 15 && kDecodeSliceLog2Ma
 // block-granular codec, the elements of the listed blocks (block by block).
 __device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t k) {
   const uint64_t nnz = B.nnz_out[k];
-  const uint64_t listed = nnz < B.cap ? nnz : B.cap;
+  const uint64_t listed = nnz < B.sort_cap ? nnz : B.sort_cap;
   return B.block != 0 ? listed * B.block : listed;
 }
 
@@ -456,9 +456,10 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
   }
 }
 
-// Non-zeros at list positions >= cap are not in the caller's lists; this kernel
-// finds them in the bitmap and inserts them with atomics after the slices were
-// stored, so the sketch is complete whatever cap is.  Normally there are none:
+// Non-zeros at list positions >= sort_cap (beyond the caller's lists, or beyond
+// what the workspace's record area holds) took no part in the counting sort; this
+// kernel finds them in the bitmap and inserts them with atomics after the slices
+// were stored, so the sketch is complete whatever the capacities are.  Normally there are none:
 // each thread checks one tile's range of list positions and the workgroup leaves
 // unless one of its kBlock tiles reaches beyond cap.
 __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBatch B, const HashRows hp) {
@@ -472,19 +473,19 @@ __global__ __launch_bounds__(kBlock) void sketch_overflow_kernel(const EncodeBat
   if (threadIdx.x == 0) s_any = 0u;
   __syncthreads();
   const uint32_t mine = tile0 + threadIdx.x;
-  if (mine < B.ntiles && prefix[mine + 1] > B.cap) s_any = 1u;
+  if (mine < B.ntiles && prefix[mine + 1] > B.sort_cap) s_any = 1u;
   __syncthreads();
   if (s_any == 0u) return;                               // uniform over the workgroup
   for (uint32_t tile = tile0; tile < tile0 + kBlock && tile < B.ntiles; ++tile) {
     const uint64_t base = prefix[tile];
     const uint32_t total = (uint32_t)(prefix[tile + 1] - base);
-    if (base + total <= B.cap) continue;                 // uniform over the workgroup
+    if (base + total <= B.sort_cap) continue;            // uniform over the workgroup
     const uint64_t word0 = (uint64_t)tile * kTileWords;
     uint64_t wd[kWordsPerThread];
     read_tile_words<kBlock>(wd, P.bitmap, B.nwords, word0);
     __syncthreads();                                     // T may still be read by the previous tile's loop
     scan_tile_words<kBlock>(T, wd);
-    const uint32_t first = base >= B.cap ? 0u : (uint32_t)(B.cap - base);
+    const uint32_t first = base >= B.sort_cap ? 0u : (uint32_t)(B.sort_cap - base);
     for (uint32_t t = first + threadIdx.x; t < total; t += kBlock) {
       const uint32_t i = (uint32_t)(word0 * 64 + locate_set_bit(T, t));
       if (B.block == 0) {

@@ -32,7 +32,10 @@ class Buffers:
     """All device memory the path touches for a (W, n, d, w) problem."""
 
     def __init__(self, W: int, n: int, d: int, w: int, seed: int, nz_cap: int, union_cap: int,
-                 device="cuda:0", dense_out: bool = False):
+                 device="cuda:0", dense_out: bool = False, sort_cap: int | None = None):
+        """nz_cap / union_cap: capacity of the workers' lists and of the union list.  sort_cap: the
+        number of list entries the encode workspace is sized for (default: nz_cap); entries beyond it
+        are inserted with atomics."""
         self.W, self.n, self.d, self.w, self.seed = W, n, d, w, seed
         self.device = torch.device(device)
         dev = self.device
@@ -49,13 +52,19 @@ class Buffers:
         self.out_val = torch.empty(max(union_cap, 1), dtype=torch.float32, device=dev)
         self.out_count = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dense_out = torch.empty(n, dtype=torch.float32, device=dev) if dense_out else None
-        ws = binding.encode_workspace_bytes(n, d, w, min(max(nz_cap, 1), n))
+        ws = binding.encode_workspace_bytes(n, d, w, min(max(nz_cap if sort_cap is None else sort_cap, 1), n))
         ws_decode = binding.decode_workspace_bytes(n, d, w, min(max(union_cap, 1), n))
         if ws == 0 or ws_decode == 0:
             raise ValueError("sizes outside the library's limits")
-        # W shares for encode_batch; the same buffer serves s2r_decode afterwards
-        self.workspace = torch.empty(max(ws * W, ws_decode), dtype=torch.uint8, device=dev)
-        assert self.workspace.data_ptr() % 256 == 0
+        if sort_cap is None:
+            # W shares for encode_batch; the same buffer serves s2r_decode afterwards
+            self.workspace = torch.empty(max(ws * W, ws_decode), dtype=torch.uint8, device=dev)
+            self.decode_workspace = self.workspace
+        else:
+            # exactly what was asked for, so that the encode's sort capacity is what the caller chose
+            self.workspace = torch.empty(ws * W, dtype=torch.uint8, device=dev)
+            self.decode_workspace = torch.empty(ws_decode, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0 and self.decode_workspace.data_ptr() % 256 == 0
 
     # ------------------------------------------------------------ the path
     def encode(self, k: int, stream=None):
@@ -73,7 +82,7 @@ class Buffers:
 
     def decode(self, stream=None):
         binding.decode(self.sketch_sum, self.bitmap_or, self.n, self.d, self.w, self.seed,
-                       self.out_idx, self.out_val, self.out_count, self.dense_out, self.workspace, stream)
+                       self.out_idx, self.out_val, self.out_count, self.dense_out, self.decode_workspace, stream)
 
     def step(self, stream=None, batched: bool = True):
         """One pass of the whole hot path over the resident gradients: the W
@@ -87,11 +96,11 @@ class Buffers:
         self.decode(stream)
 
 
-def buffers_for(wl, device="cuda:0", dense_out: bool = False, slack: int = 0) -> Buffers:
+def buffers_for(wl, device="cuda:0", dense_out: bool = False, slack: int = 0, sort_cap: int | None = None) -> Buffers:
     """Buffers sized for a workloads.Workload, with its gradients uploaded."""
     nz_cap = max(len(i) for i in wl.idx) + slack
     union_cap = min(wl.n, sum(len(i) for i in wl.idx)) + slack
-    b = Buffers(wl.W, wl.n, wl.d, wl.w, wl.seed, nz_cap, union_cap, device, dense_out)
+    b = Buffers(wl.W, wl.n, wl.d, wl.w, wl.seed, nz_cap, union_cap, device, dense_out, sort_cap)
     for k in range(wl.W):
         b.grads.append(upload_dense(wl.idx[k], wl.val[k], wl.n, b.device))
     return b

@@ -87,10 +87,10 @@ def _check_sketch(got, S, M, what):
     assert np.all(got[M == 0] == 0.0), f"{what}: untouched cells must be zero"
 
 
-def _run_and_check(wl, dense_out=False, batched=True, slack=0):
-    print(f"[case] {wl.name} W={wl.W} n={wl.n} d={wl.d} w={wl.w} batched={batched} slack={slack}", flush=True)
+def _run_and_check(wl, dense_out=False, batched=True, slack=0, sort_cap=None):
+    print(f"[case] {wl.name} W={wl.W} n={wl.n} d={wl.d} w={wl.w} batched={batched} slack={slack} sort_cap={sort_cap}", flush=True)
     enc, S, C, M, dec = _oracle_for(wl)
-    b = pipeline.buffers_for(wl, dense_out=dense_out, slack=slack)
+    b = pipeline.buffers_for(wl, dense_out=dense_out, slack=slack, sort_cap=sort_cap)
     b.step(batched=batched)
     torch.cuda.synchronize()
     nnz = b.nnz.cpu().numpy()
@@ -489,6 +489,43 @@ def test_capacity_far_above_the_count_and_estimates_that_are_wrong(strategy, dec
         assert binding.last_decode_strategy() == DECODES[decode_strategy]
     finally:
         binding.set_expected_nnz(0, 0)
+
+
+@pytest.mark.parametrize("asked", ["auto", "slice"])
+@pytest.mark.parametrize("cfg", [2, 4, 5])
+def test_lists_as_long_as_the_gradient_with_a_workspace_for_the_expected_count(cfg, asked):
+    """A caller who cannot bound its non-zeros passes lists of n entries, says how many it expects, and sizes
+    the workspace for that: the slice strategy is still there to be taken (its sort takes what the workspace
+    holds; anything beyond would be inserted with atomics), and the library's own choice gives the same
+    outputs."""
+    wl = workloads.make_small(cfg)
+    most = max(len(i) for i in wl.idx)
+    binding.set_expected_nnz(most, 0)
+    binding.set_insert_strategy(STRATEGIES[asked])
+    binding.want_report(True)
+    try:
+        _run_and_check(wl, slack=wl.n - most, sort_cap=most + most // 4)
+        if asked == "slice":
+            assert binding.last_insert_strategy() == binding.S2R_INSERT_SLICE
+    finally:
+        binding.set_expected_nnz(0, 0)
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+        binding.want_report(False)
+
+
+@pytest.mark.parametrize("fraction", [0.001, 0.3, 0.999])
+def test_slice_strategy_with_a_workspace_for_a_part_of_the_lists(fraction):
+    """The slice strategy asked for, with a workspace whose record area holds only a part of the listed
+    non-zeros: the sort takes what fits, the rest is inserted with atomics after the slices are stored;
+    lists and sketches are as always."""
+    wl = workloads.make_small(4)
+    most = max(len(i) for i in wl.idx)
+    binding.set_insert_strategy(binding.S2R_INSERT_SLICE)
+    try:
+        _run_and_check(wl, sort_cap=max(1, int(fraction * most)))
+        assert binding.last_insert_strategy() == binding.S2R_INSERT_SLICE
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
 
 
 def test_auto_strategy_matches_oracle_on_every_small_recipe():
