@@ -363,7 +363,7 @@ def measure(args, workload: str, wl=None):
     insert = "atomic" if atomic else "lds_slice"
     if fused:
         traffic, step_traffic, traffic_file = profiled_traffic(f"{wl.name[:4]}_shape_topk_block{args.block}_fused",
-                                                               "topk_score_kernel", kept=args.topk_frac)
+                                                               "topk_score_kernel", kept=K)
     elif args.block > 0:
         traffic, step_traffic, traffic_file = None, None, None
     else:
