@@ -540,11 +540,14 @@ def test_strategy_argument_check():
     binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
 
 
-def test_recipe5_full_size_in_the_benchmarked_configuration():
-    """The workload bench.py times (W=16, n=1e9, 64 GB of dense input), default
-    strategy: every worker's count, bitmap, index list and sketch; the merged
-    bitmap and sketch; every decoded index and value."""
-    binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+@pytest.mark.parametrize("asked", ["auto", "atomic"])
+def test_recipe5_full_size_in_the_benchmarked_configuration(asked, request):
+    """The workload bench.py times (W=16, n=1e9, 64 GB of dense input), with the
+    library's own choice of strategy (the benchmarked one) and with atomics: every
+    worker's count, bitmap, index list and sketch; the merged bitmap and sketch;
+    every decoded index and value."""
+    binding.set_insert_strategy(STRATEGIES[asked])
+    request.addfinalizer(lambda: binding.set_insert_strategy(binding.S2R_INSERT_AUTO))
     wl = workloads.make(5)
     print(f"[case] {wl.name} full size", flush=True)
     b = pipeline.buffers_for(wl)
