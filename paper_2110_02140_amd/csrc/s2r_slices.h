@@ -18,7 +18,8 @@ namespace s2r {
 // sketch is cut into slices of 2^slice_log2 cells (float64 accumulators in LDS); bin (j, s)
 // collects the pairs (item, row j) whose bucket falls in slice s.  A counting sort
 // over the listed items brings each bin's records together:
-//   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins
+//   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins and, row by
+//                       row, its exclusive prefix over the row's slices
 //   bin_colscan_kernel, bin_start_kernel   offsets of every (chunk, bin) run and of every bin
 //   bin_scatter_kernel  writes each record (cell in the slice | sign bit, value)
 //                       into its run (order inside a run is arbitrary)
@@ -43,85 +44,91 @@ __device__ __forceinline__ uint64_t listed_items(const EncodeBatch& B, uint32_t 
   return B.block != 0 ? listed * B.block : listed;
 }
 
+// What the items of a sort are, fixed at compile time so that the element codec's kernels carry none of the
+// block codec's branches: BLOCKS (the items are the elements of the listed blocks) and QUERY (the payload of
+// a record is the item's position, for s2r_decode's queries, instead of its value).
+constexpr int kItemsElements = 0, kItemsBlocks = 1, kItemsQuery = 2;      // MODE = blocks | query
+__host__ __device__ constexpr bool mode_blocks(int mode) { return (mode & kItemsBlocks) != 0; }
+__host__ __device__ constexpr bool mode_query(int mode) { return (mode & kItemsQuery) != 0; }
+static inline int items_mode(const EncodeBatch& B) {
+  return (B.block != 0 ? kItemsBlocks : 0) | (B.payload_slot != 0 ? kItemsQuery : 0);
+}
+
 // Item t (t < listed_items): its element index i and its payload v (the value's
-// bits, or the item's position t when B.payload_slot is set).  Returns whether
+// bits, or the item's position t in a query run).  Returns whether
 // the item takes part: with blocks, elements beyond n never do, and elements
 // whose value is zero only when the payload is the position (a query), not when
 // it is the value (an insertion: zeros are inert).  An item that does not take
 // part in a query run is still given d answers (of element 0), which the median
 // kernel discards, so that every chunk holds the same number of answers per row.
+template <int MODE>
 __device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs& P, uint64_t t, uint32_t& i, uint32_t& v) {
-  if (B.block == 0) {
+  if constexpr (!mode_blocks(MODE)) {
     i = P.nz_idx[t];
-    v = B.payload_slot != 0 ? (uint32_t)t : P.nz_val[t];
+    if constexpr (mode_query(MODE)) v = (uint32_t)t; else v = P.nz_val[t];
     return true;
+  } else {
+    const uint32_t q = (uint32_t)t / B.block;              // (the sort's items are fewer than 2^32)
+    const uint64_t e = (uint64_t)P.nz_idx[q] * B.block + ((uint32_t)t - q * B.block);
+    const bool inside = e < B.n;
+    if constexpr (mode_query(MODE)) {
+      i = inside ? (uint32_t)e : 0u;
+      v = (uint32_t)t;
+      return true;
+    } else {
+      i = (uint32_t)e;
+      v = inside ? P.grad[e] : 0u;
+      return inside && (v << 1) != 0u;
+    }
   }
-  const uint32_t q = (uint32_t)t / B.block;                // (the sort's items are fewer than 2^32)
-  const uint64_t e = (uint64_t)P.nz_idx[q] * B.block + ((uint32_t)t - q * B.block);
-  const bool inside = e < B.n;
-  if (B.payload_slot != 0) {
-    i = inside ? (uint32_t)e : 0u;
-    v = (uint32_t)t;
-    return true;
-  }
-  i = (uint32_t)e;
-  v = inside ? P.grad[e] : 0u;
-  return inside && (v << 1) != 0u;
 }
 
-// The histogram of one chunk (all threads of the workgroup call it with the same arguments).
+// The histogram of one chunk (all threads of the workgroup call it with the same arguments).  The rows are
+// the outer loop: a row's hash parameters are fetched once (they are uniform) for the eight items of a thread.
+template <int MODE>
 __device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows& hp, uint32_t k, uint32_t chunk,
-                                           uint64_t have, uint32_t* s_hist, uint32_t* s_wave) {
+                                           uint64_t have, uint32_t* s_hist) {
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
-  __syncthreads();
   const WorkerPtrs P = B.w[k];
   const uint32_t spr_log2 = B.log2w - B.slice_log2;
-  uint32_t i[kBinItems], v[kBinItems];
-  bool ok[kBinItems];
+  uint32_t i[kBinItems];
+  uint32_t ok = 0;                                        // bit u: item u exists and takes part (see load_item)
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
     const uint64_t t = (uint64_t)chunk * kBinChunk + u * kBinBlock + threadIdx.x;
-    ok[u] = t < have && load_item(B, P, t, i[u], v[u]);
+    uint32_t v;
+    i[u] = 0u;
+    if (t < have && load_item<MODE>(B, P, t, i[u], v)) ok |= 1u << u;
   }
+  __syncthreads();                                        // s_hist is zero
+  for (uint32_t j = 0; j < B.d; ++j) {
+    const uint64_t a = hp.a[j], b = hp.b[j];
+    uint32_t* row = s_hist + (j << spr_log2);
 #pragma unroll
-  for (int u = 0; u < kBinItems; ++u) {
-    if (ok[u]) {
-      for (uint32_t j = 0; j < B.d; ++j) {
-        const uint32_t bin = (j << spr_log2) + (bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2);
-        __hip_atomic_fetch_add(&s_hist[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
+    for (int u = 0; u < kBinItems; ++u) {
+      if (ok >> u & 1u)
+        __hip_atomic_fetch_add(&row[bucket_of(i[u], a, b, B.log2w) >> B.slice_log2], 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
     }
   }
   __syncthreads();
   uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
-  if (B.rowpre_off == 0) return;                         // uniform over the workgroup
-  // exclusive prefix of this chunk's counts over the bins; thread t owns bins t*per .. t*per + per - 1
+  // row by row, the exclusive prefix of the chunk's counts over the row's slices: where, among the chunk's
+  // records of that row sorted by slice, each slice's run starts.  Wave wv takes the rows wv, wv + 16, ...
+  // 64 slices at a time.
   constexpr int kWaves = kBinBlock / kWave;
-  constexpr int kMaxPer = kMaxBins / kBinBlock;
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wv = threadIdx.x / kWave;
-  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;
-  uint32_t c[kMaxPer], sum = 0;
-#pragma unroll
-  for (int q = 0; q < kMaxPer; ++q) {
-    const uint32_t e = threadIdx.x * per + q;
-    c[q] = ((uint32_t)q < per && e < B.nbins) ? s_hist[e] : 0u;
-    sum += c[q];
-  }
-  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
-  if (lane == kWave - 1) s_wave[wv] = incl;
-  __syncthreads();
-  uint32_t run = incl - sum;
-#pragma unroll
-  for (int q = 0; q < kWaves; ++q) run += (uint32_t)q < wv ? s_wave[q] : 0u;
-  uint32_t* rowpre = reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) + (uint64_t)chunk * B.nbins;
-#pragma unroll
-  for (int q = 0; q < kMaxPer; ++q) {
-    const uint32_t e = threadIdx.x * per + q;
-    if ((uint32_t)q < per && e < B.nbins) {
-      rowpre[e] = run;
-      run += c[q];
+  const uint32_t spr = 1u << spr_log2;
+  uint32_t* pre = ws_slice_pre(B, k) + (uint64_t)chunk * B.nbins;
+  for (uint32_t j = threadIdx.x / kWave; j < B.d; j += kWaves) {                // uniform over the wave
+    uint32_t carry = 0;
+    for (uint32_t seg = 0; seg < spr; seg += kWave) {
+      const uint32_t e = seg + lane;
+      const uint32_t x = e < spr ? s_hist[(j << spr_log2) + e] : 0u;
+      const uint32_t incl = wave_inclusive_scan_u32(x, lane);
+      if (e < spr) pre[(j << spr_log2) + e] = carry + incl - x;
+      carry += __shfl(incl, kWave - 1, kWave);
     }
   }
 }
@@ -129,18 +136,18 @@ __device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows&
 // The grid is sized for the number of items expected, which is normally all there are: a workgroup takes
 // chunk blockIdx.x, and only if the lists hold more, the chunks blockIdx.x + gridDim.x, ... after it.  No
 // kernel reads the histogram rows of chunks without listed items.
+template <int MODE>
 __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_hist[kMaxBins];
-  __shared__ uint32_t s_wave[kBinBlock / kWave];
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const uint64_t have = listed_items(B, k);
   uint32_t chunk = blockIdx.x;
   if ((uint64_t)chunk * kBinChunk >= have) return;       // uniform over the workgroup
-  hist_chunk(B, hp, k, chunk, have, s_hist, s_wave);
+  hist_chunk<MODE>(B, hp, k, chunk, have, s_hist);
   for (chunk += gridDim.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {      // uniform
-    __syncthreads();                                     // s_hist and s_wave are rewritten
-    hist_chunk(B, hp, k, chunk, have, s_hist, s_wave);
+    __syncthreads();                                     // s_hist is rewritten
+    hist_chunk<MODE>(B, hp, k, chunk, have, s_hist);
   }
 }
 
@@ -187,23 +194,31 @@ __global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatc
     if ((uint32_t)q < wv) run += x;
     total += x;
   }
-  // decode: rowpre[c][b] (queries of chunk c in bins before b) becomes what decode_slice_kernel adds to a
-  // query's rank in its bin to get the place of its answer: the start of chunk c's answers, plus rowpre,
-  // minus the bin's queries in earlier chunks (modulo 2^32; the places themselves are below 2^32)
-  uint32_t* rowpre = B.rowpre_off != 0 ? reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.rowpre_off) : nullptr;
+  // decode: what decode_slice_kernel adds to a query's rank in its bin to get the place of its answer: the
+  // start of chunk c's answers, plus the chunk's queries in the rows before the bin's row j (every item of a
+  // chunk has a query in every row) and in the row's earlier slices, minus the bin's queries in earlier
+  // chunks (modulo 2^32; the places themselves are below 2^32)
+  const uint32_t* spre = ws_slice_pre(B, k);
+  uint32_t* place = B.place_off != 0 ? reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.place_off) : nullptr;
+  const uint64_t have = listed_items(B, k);
+  const uint32_t j = b >> (B.log2w - B.slice_log2);
   for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
     uint32_t v[kAhead], rp[kAhead];
 #pragma unroll
     for (uint32_t q = 0; q < kAhead; ++q) {
       const bool in = live && c0 + q < c_end;
       v[q] = in ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
-      rp[q] = in && rowpre != nullptr ? rowpre[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+      rp[q] = in && place != nullptr ? spre[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
     }
 #pragma unroll
     for (uint32_t q = 0; q < kAhead; ++q) {
       if (live && c0 + q < c_end) {
         hist[(uint64_t)(c0 + q) * B.nbins + b] = run;
-        if (rowpre != nullptr) rowpre[(uint64_t)(c0 + q) * B.nbins + b] = (c0 + q) * (uint32_t)kBinChunk * B.d + rp[q] - run;
+        if (place != nullptr) {
+          const uint64_t t0 = (uint64_t)(c0 + q) * kBinChunk;
+          const uint32_t items = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+          place[(uint64_t)(c0 + q) * B.nbins + b] = (c0 + q) * (uint32_t)kBinChunk * B.d + j * items + rp[q] - run;
+        }
       }
       run += v[q];
     }
@@ -250,107 +265,74 @@ __global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch 
 }
 
 // One workgroup per chunk of kBinChunk list items, one pass per sketch row j.  The
-// chunk's records for row j are first sorted by slice inside LDS (a counting
-// sort in two sweeps over the items: LDS counters count every slice's records,
-// a scan turns them into the start of every slice's run, and a second sweep
-// takes a place in the run with a fetch-and-add) and then copied out in sorted
-// order, so that consecutive lanes write consecutive records of the (chunk, bin)
-// run that the histogram pass reserved.  The hashes are computed in both sweeps
-// rather than kept: with few registers two workgroups share a compute unit and
-// one's barriers hide behind the other's work.  In LDS a record carries its slice
-// number in bits 16..28 of its first word (the cell takes bits 0..14, the sign
-// bit 31).  Dynamic LDS: kBinChunk records, then two arrays of (slices per row)
-// counters.
+// chunk's records for row j are first sorted by slice inside LDS (the histogram
+// pass left, for every row, where each slice's run starts among the chunk's
+// records of that row: a record takes its place in the run with a fetch-and-add)
+// and then copied out in sorted order, so that consecutive lanes write
+// consecutive records of the (chunk, bin) run that the histogram pass reserved.
+// In LDS a record carries its slice number in bits 16..28 of its first word (the
+// cell takes bits 0..14, the sign bit 31).  Dynamic LDS: kBinChunk records, then
+// two arrays of nbins counters: the next free place of every bin's run in the
+// sorted order of its row, and what turns such a place into the record's position
+// in the worker's records.
+template <int MODE>
 __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeBatch B, const HashRows hp) {
   extern __shared__ uint2 s_stage[];
-  constexpr int kWaves = kBinBlock / kWave;
-  __shared__ uint32_t s_wave[kWaves];
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   const uint64_t have = listed_items(B, k);
-  const uint32_t spr_log2 = B.log2w - B.slice_log2;
-  const uint32_t spr = 1u << spr_log2;                    // slices per row
-  uint32_t* s_loc = reinterpret_cast<uint32_t*>(s_stage + kBinChunk);
-  uint32_t* s_delta = s_loc + spr;
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wv = threadIdx.x / kWave;
+  const uint32_t spr_log2 = B.log2w - B.slice_log2;      // log2 of the slices per row
+  uint32_t* s_next = reinterpret_cast<uint32_t*>(s_stage + kBinChunk);
+  uint32_t* s_delta = s_next + B.nbins;
   const WorkerPtrs P = B.w[k];
   const uint32_t* bin_start = ws_bin_start(B, k);
   uint2* __restrict__ rec = ws_records(B, k);
   const uint32_t mask = (1u << B.slice_log2) - 1u;
-  const uint32_t per = (spr + kBinBlock - 1) / kBinBlock; // counters per thread in the scan: thread t owns t*per ..
-  for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;
   // The grid is sized for the number of items expected; a workgroup takes the chunks blockIdx.x,
   // blockIdx.x + gridDim.x, ... that hold listed items.
   for (uint32_t chunk = blockIdx.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {   // uniform
-  const uint64_t t0 = (uint64_t)chunk * kBinChunk;
-  const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
-  const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
+    const uint64_t t0 = (uint64_t)chunk * kBinChunk;
+    const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
+    const uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;      // the bin's records in earlier chunks
+    const uint32_t* pre = ws_slice_pre(B, k) + (uint64_t)chunk * B.nbins;
 
-  uint32_t i[kBinItems], v[kBinItems];
-  uint32_t ok = 0;                                        // bit u: item u exists and takes part (see load_item)
-#pragma unroll
-  for (int u = 0; u < kBinItems; ++u) {
-    const uint32_t t = u * kBinBlock + threadIdx.x;
-    if (t < count && load_item(B, P, t0 + t, i[u], v[u])) ok |= 1u << u;
-  }
-
-  for (uint32_t j = 0; j < B.d; ++j) {
-    // where this thread's first run of this (chunk, row) starts in the worker's records: wanted after the
-    // scan, requested now (with at most 1024 slices per row it is the thread's only run)
-    const uint32_t own = threadIdx.x * per;
-    const uint32_t gpos0 = own < spr ? bin_start[(j << spr_log2) + own] + hist[(j << spr_log2) + own] : 0u;
-    __syncthreads();                                      // s_loc is zero, s_stage is free
+    uint32_t i[kBinItems], v[kBinItems];
+    uint32_t ok = 0;                                      // bit u: item u exists and takes part (see load_item)
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
-      if (ok >> u & 1u) {
-        const uint32_t sl = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w) >> B.slice_log2;
-        __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
+      const uint32_t t = u * kBinBlock + threadIdx.x;
+      if (t < count && load_item<MODE>(B, P, t0 + t, i[u], v[u])) ok |= 1u << u;
+    }
+    for (uint32_t e = threadIdx.x; e < B.nbins; e += kBinBlock) {
+      const uint32_t at = pre[e];
+      s_next[e] = at;
+      s_delta[e] = bin_start[e] + hist[e] - at;
     }
     __syncthreads();
-    // exclusive scan of the counters
-    uint32_t sum = 0;
-    for (uint32_t q = 0; q < per; ++q)
-      if (own + q < spr) sum += s_loc[own + q];
-    const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
-    if (lane == kWave - 1) s_wave[wv] = incl;
-    __syncthreads();
-    uint32_t run = incl - sum, records = 0;               // records: the chunk's items that take part
+
+    for (uint32_t j = 0; j < B.d; ++j) {
+      const uint64_t a = hp.a[j], b = hp.b[j], c = hp.c[j], e = hp.e[j];
+      uint32_t* next = s_next + (j << spr_log2);
 #pragma unroll
-    for (int q = 0; q < kWaves; ++q) {
-      const uint32_t x = s_wave[q];
-      if ((uint32_t)q < wv) run += x;
-      records += x;
-    }
-    for (uint32_t q = 0; q < per; ++q) {
-      const uint32_t e = own + q;
-      if (e < spr) {
-        const uint32_t c = s_loc[e];
-        const uint32_t gpos = q == 0 ? gpos0 : bin_start[(j << spr_log2) + e] + hist[(j << spr_log2) + e];
-        s_loc[e] = run;                                   // the next free place of slice e's run
-        s_delta[e] = gpos - run;                          // sorted position p of slice e goes to record p + delta
-        run += c;
+      for (int u = 0; u < kBinItems; ++u) {
+        if (ok >> u & 1u) {
+          const uint32_t h = bucket_of(i[u], a, b, B.log2w);
+          const uint32_t sl = h >> B.slice_log2;
+          const uint32_t key = (h & mask) | signbit_of(i[u], c, e) | (sl << 16);
+          const uint32_t place = __hip_atomic_fetch_add(&next[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          s_stage[place] = make_uint2(key, v[u]);
+        }
       }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < kBinItems; ++u) {
-      if (ok >> u & 1u) {
-        const uint32_t h = bucket_of(i[u], hp.a[j], hp.b[j], B.log2w);
-        const uint32_t sl = h >> B.slice_log2;
-        const uint32_t key = (h & mask) | signbit_of(i[u], hp.c[j], hp.e[j]) | (sl << 16);
-        const uint32_t place = __hip_atomic_fetch_add(&s_loc[sl], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        s_stage[place] = make_uint2(key, v[u]);
+      __syncthreads();
+      // the last slice's run ends where the row's records end
+      const uint32_t records = s_next[((j + 1) << spr_log2) - 1];
+      const uint32_t* delta = s_delta + (j << spr_log2);
+      for (uint32_t p = threadIdx.x; p < records; p += kBinBlock) {
+        const uint2 r = s_stage[p];
+        rec[p + delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80007FFFu, r.y);
       }
+      __syncthreads();                                    // s_stage is free again (and, after the last row, the counters)
     }
-    __syncthreads();
-    for (uint32_t p = threadIdx.x; p < records; p += kBinBlock) {
-      const uint2 r = s_stage[p];
-      rec[p + s_delta[(r.x >> 16) & 0x1FFFu]] = make_uint2(r.x & 0x80007FFFu, r.y);
-    }
-    for (uint32_t e = threadIdx.x; e < spr; e += kBinBlock) s_loc[e] = 0u;      // for the next row (or chunk); not read above
-  }
   }
 }
 
