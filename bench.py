@@ -217,8 +217,7 @@ def measure(args, workload: str, wl=None):
         if args.fused_topk:
             def step():
                 b.topk_encode_all(dense, resid, K, stream)
-                b.merge(stream)
-                b.decode(stream)
+                b.merge_decode(stream)
         else:
             def step():
                 binding.topk_blocks_batch(dense, resid, wl.n, args.block, K, b.grads, None, ws_topk, stream)
@@ -264,9 +263,9 @@ def measure(args, workload: str, wl=None):
     value = wl.dense_bytes / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-kernel timing, same call sequence: HIP events the library records around its own launches
-    # (s2r_trace slots: scan, slice kernel, scores), and events around the merge and decode calls
+    # (s2r_trace slots: scan, slice kernel, scores, merge), and events around the encode and merge-decode calls
     reps = max(1, min(args.steps, 10))
-    timed = {k: [] for k in ("scan", "merge", "decode", "encode_call")}
+    timed = {k: [] for k in ("scan", "merge", "merge_decode_call", "encode_call")}
     slice_pairs = []
 
     def outside(name, call):
@@ -275,6 +274,13 @@ def measure(args, workload: str, wl=None):
         call()
         e1.record(stream)
         timed[name].append((e0, e1))
+
+    def traced_merge_decode():
+        m0, m1 = binding.HipEvent(), binding.HipEvent()
+        binding.set_kernel_events(binding.S2R_KERNEL_MERGE, m0.handle, m1.handle)
+        outside("merge_decode_call", lambda: b.merge_decode(stream))
+        binding.set_kernel_events(binding.S2R_KERNEL_MERGE, None, None)
+        timed["merge"].append((m0, m1))
 
     def traced_encode(call):
         e0, e1, s0, s1 = (binding.HipEvent() for _ in range(4))
@@ -299,8 +305,7 @@ def measure(args, workload: str, wl=None):
             tk_pairs.append((t_a, t_b))
             timed["scan"].append((c0, c1))
             slice_pairs.append((s0, s1))
-            outside("merge", lambda: b.merge(stream))
-            outside("decode", lambda: b.decode(stream))
+            traced_merge_decode()
             continue
         if topk:
             t_a, t_b = binding.HipEvent(), binding.HipEvent()
@@ -313,11 +318,11 @@ def measure(args, workload: str, wl=None):
         else:
             for k in range(wl.W):
                 traced_encode(lambda k=k: b.encode(k, stream))
-        outside("merge", lambda: b.merge(stream))
-        outside("decode", lambda: b.decode(stream))
+        traced_merge_decode()
     torch.cuda.synchronize()
-    scan_ms, merge_ms, decode_ms = (float(np.mean([a.elapsed_ms(c) for a, c in timed[k]]))
-                                    for k in ("scan", "merge", "decode"))
+    scan_ms, merge_ms, md_ms = (float(np.mean([a.elapsed_ms(c) for a, c in timed[k]]))
+                                for k in ("scan", "merge", "merge_decode_call"))
+    decode_ms = md_ms - merge_ms                               # everything of the call after the merge kernel
     encode_ms = float(np.mean([a.elapsed_ms(c) for a, c in timed["encode_call"]])) if timed["encode_call"] else None
     fused = topk and args.fused_topk
     workers_per_launch = wl.W if fused else binding.scan_launch_workers()

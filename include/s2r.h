@@ -206,6 +206,24 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap,
                       void* stream);
 
 /*
+ * Aggregate and decompress in one call (Algorithm 1 from AllReduce(S, C) to the
+ * median, on one GPU): exactly s2r_merge followed by s2r_decode of its outputs,
+ * arguments as for those two.  The aggregation kernel counts the set bits of the
+ * aggregated bitmap while it forms it, so the decompression starts without a
+ * pass of its own over that bitmap: one kernel launch fewer.  sketch_out and
+ * bitmap_out are written as by s2r_merge and are the sketch and bitmap the
+ * decompression reads.  All arguments are checked before anything is enqueued.
+ */
+s2r_status s2r_merge_decode(const float* const* sketches, const uint64_t* const* bitmaps,
+                            uint32_t W, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                            float* sketch_out, uint64_t* bitmap_out,
+                            uint32_t* idx_out, float* val_out, uint64_t cap,
+                            uint64_t* count_out,
+                            float* dense_out,
+                            void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
  * s2r_decode for callers that cannot allocate device memory or pass a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, results and errors as s2r_decode, without the
@@ -303,6 +321,19 @@ s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap,
                              uint64_t* nblk_out,
                              void* workspace, size_t workspace_bytes,
                              void* stream);
+
+/*
+ * s2r_merge followed by s2r_decode_blocks in one call, as s2r_merge_decode; the
+ * W inputs and bitmap_out are block bitmaps of ceil(ceil(n / block) / 64) words.
+ */
+s2r_status s2r_merge_decode_blocks(const float* const* sketches, const uint64_t* const* block_bitmaps,
+                                   uint32_t W, uint64_t n, uint32_t block,
+                                   uint32_t d, uint32_t w, uint64_t seed,
+                                   float* sketch_out, uint64_t* bitmap_out,
+                                   uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,
+                                   uint64_t* nblk_out,
+                                   void* workspace, size_t workspace_bytes,
+                                   void* stream);
 
 /*
  * Block-wise Top-K sparsifier with error feedback, the step the paper puts in
@@ -572,6 +603,26 @@ s2r_status s2r_decode_blocks_ex(const float* sketch, const uint64_t* block_bitma
                                 uint64_t* nblk_out,
                                 void* workspace, size_t workspace_bytes,
                                 void* stream, const s2r_options* options);
+
+s2r_status s2r_merge_decode_ex(const float* const* sketches /* host array */,
+                               const uint64_t* const* bitmaps /* host array */,
+                               uint32_t W, uint64_t n, uint32_t d, uint32_t w, uint64_t seed,
+                               float* sketch_out, uint64_t* bitmap_out,
+                               uint32_t* idx_out, float* val_out, uint64_t cap,
+                               uint64_t* count_out,
+                               float* dense_out,
+                               void* workspace, size_t workspace_bytes,
+                               void* stream, const s2r_options* options);
+
+s2r_status s2r_merge_decode_blocks_ex(const float* const* sketches /* host array */,
+                                      const uint64_t* const* block_bitmaps /* host array */,
+                                      uint32_t W, uint64_t n, uint32_t block,
+                                      uint32_t d, uint32_t w, uint64_t seed,
+                                      float* sketch_out, uint64_t* bitmap_out,
+                                      uint32_t* blk_idx_out, float* val_out, uint64_t blk_cap,
+                                      uint64_t* nblk_out,
+                                      void* workspace, size_t workspace_bytes,
+                                      void* stream, const s2r_options* options);
 
 s2r_status s2r_topk_encode_blocks_batch_ex(const float* const* grads /* host array */,
                                            float* const* residuals /* host array or NULL */, uint32_t W,

@@ -27,12 +27,14 @@ extern "C" {
  *   S2R_KERNEL_ENCODE_SLICE: the LDS-slice sketch kernel of the encode calls
  *   S2R_KERNEL_TOPK_SCORES : the scores kernel (the pass over gradient and residual)
  *                            of s2r_topk_encode_blocks_batch_ex
+ *   S2R_KERNEL_MERGE       : the aggregation kernel of the s2r_merge_decode calls
  */
 #define S2R_KERNEL_ENCODE_SCAN  0
 #define S2R_KERNEL_DECODE       1
 #define S2R_KERNEL_ENCODE_SLICE 2
 #define S2R_KERNEL_TOPK_SCORES  3
-#define S2R_KERNEL_SLOTS        4
+#define S2R_KERNEL_MERGE        4
+#define S2R_KERNEL_SLOTS        5
 
 struct s2r_trace {
   void* begin[S2R_KERNEL_SLOTS];

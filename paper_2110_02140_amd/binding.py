@@ -28,7 +28,8 @@ S2R_KERNEL_ENCODE_SCAN = 0
 S2R_KERNEL_DECODE = 1
 S2R_KERNEL_ENCODE_SLICE = 2
 S2R_KERNEL_TOPK_SCORES = 3
-S2R_KERNEL_SLOTS = 4
+S2R_KERNEL_MERGE = 4
+S2R_KERNEL_SLOTS = 5
 S2R_INSERT_AUTO = 0
 S2R_INSERT_ATOMIC = 1
 S2R_INSERT_SLICE = 2
@@ -67,6 +68,11 @@ _ENCODE_BATCH_ARGS = [ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32, c_
 _DECODE_ARGS = [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
                 c_void_p, c_void_p, c_uint64, c_void_p, c_void_p,
                 c_void_p, c_size_t, c_void_p]
+_MERGE_HEAD = [ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p), c_uint32]
+_MERGE_DECODE_ARGS = _MERGE_HEAD + [c_uint64, c_uint32, c_uint32, c_uint64, c_void_p, c_void_p,
+                                    c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+_MERGE_DECODE_BLOCKS_ARGS = _MERGE_HEAD + [c_uint64, c_uint32, c_uint32, c_uint32, c_uint64, c_void_p, c_void_p,
+                                           c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]
 _ENCODE_BLOCKS_ARGS = [c_void_p, c_uint64, c_uint32, c_uint32, c_uint32, c_uint64,
                        c_void_p, c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_size_t, c_void_p]
 _ENCODE_BLOCKS_BATCH_ARGS = [ctypes.POINTER(c_void_p), c_uint32, c_uint64, c_uint32, c_uint32, c_uint32,
@@ -96,6 +102,10 @@ SIGNATURES = {
                             c_void_p, c_void_p, c_void_p]),
     "s2r_decode": (c_int32, _DECODE_ARGS),
     "s2r_decode_ex": (c_int32, _DECODE_ARGS + [_OPT]),
+    "s2r_merge_decode": (c_int32, _MERGE_DECODE_ARGS),
+    "s2r_merge_decode_ex": (c_int32, _MERGE_DECODE_ARGS + [_OPT]),
+    "s2r_merge_decode_blocks": (c_int32, _MERGE_DECODE_BLOCKS_ARGS),
+    "s2r_merge_decode_blocks_ex": (c_int32, _MERGE_DECODE_BLOCKS_ARGS + [_OPT]),
     "s2r_decode_noalloc": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64,
                                      c_void_p, c_void_p, c_uint64, c_void_p, c_void_p, c_void_p]),
     "s2r_decode_update": (c_int32, [c_void_p, c_void_p, c_uint64, c_uint32, c_uint32, c_uint64, c_void_p, ctypes.c_float,
@@ -338,6 +348,28 @@ def decode(sketch, bitmap, n, d, w, seed, idx_out, val_out, count_out, dense_out
     _call("s2r_decode", (_ptr(sketch), _ptr(bitmap), n, d, w, seed, _ptr(idx_out), _ptr(val_out), cap,
                            _ptr(count_out), _ptr(dense_out), _ptr(workspace),
                            workspace.numel() * workspace.element_size(), _stream(stream)), decode=True)
+
+
+def merge_decode(sketches, bitmaps, n, d, w, seed, sketch_out, bitmap_out, idx_out, val_out, count_out, dense_out,
+                 workspace, stream=None):
+    """s2r_merge_decode: s2r_merge and s2r_decode of its outputs in one call."""
+    W = len(sketches)
+    cap = 0 if idx_out is None else idx_out.numel()
+    _call("s2r_merge_decode", (_ptr_array(sketches), _ptr_array(bitmaps), W, n, d, w, seed, _ptr(sketch_out),
+                                 _ptr(bitmap_out), _ptr(idx_out), _ptr(val_out), cap, _ptr(count_out), _ptr(dense_out),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+          decode=True)
+
+
+def merge_decode_blocks(sketches, block_bitmaps, n, block, d, w, seed, sketch_out, bitmap_out, blk_idx_out, val_out,
+                        nblk_out, workspace, stream=None):
+    """s2r_merge_decode_blocks: s2r_merge and s2r_decode_blocks of its outputs in one call."""
+    W = len(sketches)
+    cap = 0 if blk_idx_out is None else blk_idx_out.numel()
+    _call("s2r_merge_decode_blocks", (_ptr_array(sketches), _ptr_array(block_bitmaps), W, n, block, d, w, seed,
+                                        _ptr(sketch_out), _ptr(bitmap_out), _ptr(blk_idx_out), _ptr(val_out), cap,
+                                        _ptr(nblk_out), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)), decode=True)
 
 
 S2R_DECODE_NOALLOC_MAX_N = 1 << 27

@@ -284,7 +284,7 @@ using namespace s2r;
 
 extern "C" {
 
-int32_t s2r_version(void) { return 500; }
+int32_t s2r_version(void) { return 510; }
 
 const char* s2r_status_string(s2r_status status) {
   switch (status) {
@@ -610,10 +610,11 @@ s2r_status s2r_encode_batch(const float* const* grads, uint32_t W, uint64_t n, u
                              workspace_bytes, stream, nullptr);
 }
 
-s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
-                     uint32_t d, uint32_t w, uint64_t seed, float* sketch_out, uint64_t* bitmap_out,
-                     void* stream) {
-  (void)seed;
+// piece_count: NULL, or where the aggregated bitmap's set-bit counts per piece go (uint16[16 * tiles]: the
+// first part of a decode workspace).  launch = false only checks the arguments.
+static s2r_status merge_impl(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
+                             uint32_t d, uint32_t w, float* sketch_out, uint64_t* bitmap_out, uint16_t* piece_count,
+                             void* stream, const Exec& X, bool launch = true) {
   if (sketches == nullptr || bitmaps == nullptr || sketch_out == nullptr || bitmap_out == nullptr) return S2R_ERR_NULL;
   const s2r_status sz = check_sizes(n, d, w);
   if (sz != S2R_OK) return sz;
@@ -628,23 +629,44 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
     }
   }
   if (((uintptr_t)sketch_out & 15u) || ((uintptr_t)bitmap_out & 7u)) return S2R_ERR_ALIGN;
+  if (!launch) return S2R_OK;
   A.sketch_out = sketch_out;
   A.bitmap_out = bitmap_out;
   A.ncells = (uint64_t)d * w;
   A.ncell4 = A.ncells / 4;
   A.nwords = ceil_div(n, 64);
   A.W = W;
-  // one thread per 16 bytes of sketch / 8 bytes of bitmap (d*w <= 2^32 and n <= 2^32 keep the grid below 2^23)
+  A.piece_count = piece_count;
+  A.count_words = piece_count != nullptr ? (uint64_t)tiles_of(n) * kTileWords : 0;
+  // one thread per 16 bytes of sketch / 8 bytes of bitmap (d*w <= 2^32 and n <= 2^32 keep the grid below 2^23);
+  // with counts, the bitmap part covers every piece of every tile
   const uint64_t sb = ceil_div(A.ncell4 > 0 ? A.ncell4 : 1, kBlock);
-  const uint64_t bb = ceil_div(A.nwords, kBlock);
+  const uint64_t bb = ceil_div(piece_count != nullptr ? A.count_words : A.nwords, kBlock);
   A.sketch_blocks = (uint32_t)sb;
   hipStream_t st = (hipStream_t)stream;
-  if (W >= 16)
-    hipLaunchKernelGGL(merge_kernel<8>, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
-  else
-    hipLaunchKernelGGL(merge_kernel<4>, dim3((uint32_t)(sb + bb)), dim3(kBlock), 0, st, A);
+  const dim3 grid((uint32_t)(sb + bb)), block(kBlock);
+  record(X, S2R_KERNEL_MERGE, false, st);
+  if (W >= 16) {
+    if (piece_count != nullptr) hipLaunchKernelGGL((merge_kernel<8, true>), grid, block, 0, st, A);
+    else hipLaunchKernelGGL((merge_kernel<8, false>), grid, block, 0, st, A);
+  } else {
+    if (piece_count != nullptr) hipLaunchKernelGGL((merge_kernel<4, true>), grid, block, 0, st, A);
+    else hipLaunchKernelGGL((merge_kernel<4, false>), grid, block, 0, st, A);
+  }
+  record(X, S2R_KERNEL_MERGE, true, st);
   return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
 }
+
+s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
+                     uint32_t d, uint32_t w, uint64_t seed, float* sketch_out, uint64_t* bitmap_out,
+                     void* stream) {
+  (void)seed;
+  return merge_impl(sketches, bitmaps, W, n, d, w, sketch_out, bitmap_out, nullptr, stream, Exec());
+}
+
+// Where decode_impl takes the piece counts of the bitmap from: its own counting kernel, or the workspace, where
+// merge_impl has just put them; kCheckOnly: check the arguments and launch nothing.
+constexpr int kCountsFromBitmap = 0, kCountsInWorkspace = 1, kCheckOnly = 2;
 
 // block = 0: the element codec.  block >= 1: the block-granular codec: the bitmap has ceil(n / block) bits,
 // idx_out lists the set blocks (cap of them at most), val_out holds block values per listed block, and there
@@ -652,7 +674,8 @@ s2r_status s2r_merge(const float* const* sketches, const uint64_t* const* bitmap
 static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t block, uint32_t d,
                               uint32_t w, uint64_t seed, uint32_t* idx_out, float* val_out, uint64_t cap,
                               uint64_t* count_out, float* dense_out, void* workspace, size_t workspace_bytes,
-                              void* stream, const Exec& X, float* params = nullptr, float scale = 0.0f) {
+                              void* stream, const Exec& X, float* params = nullptr, float scale = 0.0f,
+                              int counts = kCountsFromBitmap) {
   if (sketch == nullptr || bitmap == nullptr || count_out == nullptr) return S2R_ERR_NULL;
   // (a block-granular parameter update lists the blocks but returns no values)
   if ((idx_out == nullptr) != (val_out == nullptr) && !(block != 0 && params != nullptr && val_out == nullptr))
@@ -665,6 +688,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     return S2R_ERR_WORKSPACE;
   if (((uintptr_t)sketch & 15u) || ((uintptr_t)bitmap & 7u) || ((uintptr_t)idx_out & 3u) ||
       ((uintptr_t)val_out & 3u) || ((uintptr_t)count_out & 7u) || ((uintptr_t)dense_out & 15u)) return S2R_ERR_ALIGN;
+  if (counts == kCheckOnly) return S2R_OK;
 
   hipStream_t st = (hipStream_t)stream;
   HashRows hp;
@@ -674,9 +698,11 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
 
   uint16_t* piece_count = reinterpret_cast<uint16_t*>(workspace);
   uint64_t* tile_prefix = reinterpret_cast<uint64_t*>((char*)workspace + workspace_prefix_off(n));
-  hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
-                     bitmap, nwords, ntiles, piece_count);
-  if (!launch_ok()) return S2R_ERR_LAUNCH;
+  if (counts == kCountsFromBitmap) {
+    hipLaunchKernelGGL(bitmap_count_kernel, dim3((uint32_t)ceil_div(ntiles, kWavesPerBlock)), dim3(kBlock), 0, st,
+                       bitmap, nwords, ntiles, piece_count);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+  }
   hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(kPrefixBlock), 0, st, (char*)workspace, (uint64_t)0,
                      (uint64_t)workspace_prefix_off(n), (uint64_t)workspace_dense_off(n), ntiles, count_out);
   if (!launch_ok()) return S2R_ERR_LAUNCH;
@@ -889,6 +915,48 @@ s2r_status s2r_decode(const float* sketch, const uint64_t* bitmap, uint64_t n, u
                        workspace_bytes, stream, nullptr);
 }
 
+// merge and decode in one call: the merge kernel counts the aggregated bitmap while it forms it
+static s2r_status merge_decode_impl(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W,
+                                    uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t seed,
+                                    float* sketch_out, uint64_t* bitmap_out, uint32_t* idx_out, float* val_out,
+                                    uint64_t cap, uint64_t* count_out, float* dense_out, void* workspace,
+                                    size_t workspace_bytes, void* stream, const s2r_options* options) {
+  Exec X;
+  s2r_status rc = resolve_options(options, &X);
+  if (rc != S2R_OK) return rc;
+  const s2r_status sz = check_sizes(n, d, w);
+  if (sz != S2R_OK) return sz;
+  const uint64_t nbits = block != 0 ? ceil_div(n, block) : n;
+  // both halves' arguments are checked before anything is launched
+  rc = merge_impl(sketches, bitmaps, W, nbits, d, w, sketch_out, bitmap_out, nullptr, stream, X, false);
+  if (rc != S2R_OK) return rc;
+  rc = decode_impl(sketch_out, bitmap_out, n, block, d, w, seed, idx_out, val_out, cap, count_out, dense_out,
+                   workspace, workspace_bytes, stream, X, nullptr, 0.0f, kCheckOnly);
+  if (rc != S2R_OK) return rc;
+  rc = merge_impl(sketches, bitmaps, W, nbits, d, w, sketch_out, bitmap_out, reinterpret_cast<uint16_t*>(workspace),
+                  stream, X);
+  if (rc != S2R_OK) return rc;
+  return decode_impl(sketch_out, bitmap_out, n, block, d, w, seed, idx_out, val_out, cap, count_out, dense_out,
+                     workspace, workspace_bytes, stream, X, nullptr, 0.0f, kCountsInWorkspace);
+}
+
+s2r_status s2r_merge_decode_ex(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
+                               uint32_t d, uint32_t w, uint64_t seed, float* sketch_out, uint64_t* bitmap_out,
+                               uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out,
+                               float* dense_out, void* workspace, size_t workspace_bytes, void* stream,
+                               const s2r_options* options) {
+  return merge_decode_impl(sketches, bitmaps, W, n, 0u, d, w, seed, sketch_out, bitmap_out, idx_out, val_out, cap,
+                           count_out, dense_out, workspace, workspace_bytes, stream, options);
+}
+
+s2r_status s2r_merge_decode(const float* const* sketches, const uint64_t* const* bitmaps, uint32_t W, uint64_t n,
+                            uint32_t d, uint32_t w, uint64_t seed, float* sketch_out, uint64_t* bitmap_out,
+                            uint32_t* idx_out, float* val_out, uint64_t cap, uint64_t* count_out, float* dense_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  return merge_decode_impl(sketches, bitmaps, W, n, 0u, d, w, seed, sketch_out, bitmap_out, idx_out, val_out, cap,
+                           count_out, dense_out, workspace, workspace_bytes, stream, nullptr);
+}
+
 s2r_status s2r_decode_update(const float* sketch, const uint64_t* bitmap, uint64_t n, uint32_t d, uint32_t w,
                              uint64_t seed, float* params, float scale, uint32_t* idx_out, float* val_out, uint64_t cap,
                              uint64_t* count_out, void* workspace, size_t workspace_bytes, void* stream) {
@@ -1035,6 +1103,26 @@ s2r_status s2r_decode_blocks_ex(const float* sketch, const uint64_t* block_bitma
   if (rc != S2R_OK) return rc;
   return decode_impl(sketch, block_bitmap, n, block, d, w, seed, blk_idx_out, val_out, blk_cap, nblk_out, nullptr,
                      workspace, workspace_bytes, stream, X);
+}
+
+s2r_status s2r_merge_decode_blocks_ex(const float* const* sketches, const uint64_t* const* block_bitmaps, uint32_t W,
+                                      uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t seed,
+                                      float* sketch_out, uint64_t* bitmap_out, uint32_t* blk_idx_out, float* val_out,
+                                      uint64_t blk_cap, uint64_t* nblk_out, void* workspace, size_t workspace_bytes,
+                                      void* stream, const s2r_options* options) {
+  if (!block_ok(n, block)) return S2R_ERR_SIZE;
+  return merge_decode_impl(sketches, block_bitmaps, W, n, block, d, w, seed, sketch_out, bitmap_out, blk_idx_out,
+                           val_out, blk_cap, nblk_out, nullptr, workspace, workspace_bytes, stream, options);
+}
+
+s2r_status s2r_merge_decode_blocks(const float* const* sketches, const uint64_t* const* block_bitmaps, uint32_t W,
+                                   uint64_t n, uint32_t block, uint32_t d, uint32_t w, uint64_t seed,
+                                   float* sketch_out, uint64_t* bitmap_out, uint32_t* blk_idx_out, float* val_out,
+                                   uint64_t blk_cap, uint64_t* nblk_out, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  return s2r_merge_decode_blocks_ex(sketches, block_bitmaps, W, n, block, d, w, seed, sketch_out, bitmap_out,
+                                    blk_idx_out, val_out, blk_cap, nblk_out, workspace, workspace_bytes, stream,
+                                    nullptr);
 }
 
 s2r_status s2r_decode_blocks(const float* sketch, const uint64_t* block_bitmap, uint64_t n, uint32_t block, uint32_t d,

@@ -23,6 +23,8 @@ struct MergeArgs {
   uint64_t nwords;
   uint32_t W;
   uint32_t sketch_blocks;   // blocks [0, sketch_blocks) sum the sketch, the rest OR the bitmap
+  uint16_t* piece_count;    // COUNTS: the aggregated bitmap's set bits per piece of kScanWords words, for every
+  uint64_t count_words;     //   piece of every tile: count_words = tiles * kTileWords words are covered
 };
 
 // One thread per 16 bytes of sketch (blocks [0, sketch_blocks)) or per bitmap word
@@ -32,7 +34,11 @@ struct MergeArgs {
 // 84 MB): with up to 8 workers 2 or 4 loads in flight per thread reach 5.9 to
 // 6.1 TB/s and 8 only 4.7 to 5.1; with 16 workers 8 in flight are the best
 // (6.1 against 5.7 TB/s): the host picks DEPTH = 4 below 16 workers, else 8.
-template <int DEPTH>
+// COUNTS: the bitmap part also leaves what the decompression step reads first, the
+// set-bit counts of the aggregated bitmap per piece (the pieces the dense scan
+// counts for a worker's bitmap): a piece is kScanWords = 32 consecutive words,
+// that is 32 consecutive lanes, whose popcounts meet in a butterfly.
+template <int DEPTH, bool COUNTS>
 __global__ __launch_bounds__(kBlock) void merge_kernel(const MergeArgs A) {
   constexpr uint32_t kDepth = DEPTH;
   if (blockIdx.x < A.sketch_blocks) {
@@ -60,8 +66,8 @@ __global__ __launch_bounds__(kBlock) void merge_kernel(const MergeArgs A) {
     }
   } else {
     const uint64_t i = (uint64_t)(blockIdx.x - A.sketch_blocks) * kBlock + threadIdx.x;
+    uint64_t acc = 0;
     if (i < A.nwords) {
-      uint64_t acc = 0;
       for (uint32_t k0 = 0; k0 < A.W; k0 += kDepth) {
         uint64_t x[kDepth];
 #pragma unroll
@@ -70,6 +76,13 @@ __global__ __launch_bounds__(kBlock) void merge_kernel(const MergeArgs A) {
         for (uint32_t u = 0; u < kDepth; ++u) acc |= x[u];
       }
       __builtin_nontemporal_store(acc, A.bitmap_out + i);
+    }
+    if (COUNTS) {                                          // (every lane of the wave is here: words beyond the end count 0)
+      static_assert(kScanWords == 32 && kBlock % kScanWords == 0, "a piece is one half of a wave");
+      uint32_t c = (uint32_t)__popcll(acc);
+#pragma unroll
+      for (int m = kScanWords / 2; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
+      if ((threadIdx.x & (kScanWords - 1)) == 0 && i < A.count_words) A.piece_count[i / kScanWords] = (uint16_t)c;
     }
   }
 }

@@ -122,6 +122,7 @@ __global__ __launch_bounds__(kPrefixBlock) void tile_prefix_kernel(char* __restr
 #pragma unroll
     for (int q = 0; q < kPrefixPer; ++q) {
       c[q] = sum_u16x8(lo16[q]) + sum_u16x8(hi16[q]);
+      if (c[q] > (uint32_t)kTileElems) c[q] = (uint32_t)kTileElems;   // (never, with counts this library wrote)
       if (c[q] > (uint32_t)kGroupSlots) {          // at most kGroupsPerTile - 1 further groups
         const uint32_t more = (c[q] - 1u) / kGroupSlots;
         const uint32_t at = __hip_atomic_fetch_add(&s_dense, more, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);

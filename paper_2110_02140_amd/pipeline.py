@@ -1,5 +1,6 @@
 """Device buffers for one workload and the call sequence of the hot path:
-W x s2r_encode -> s2r_merge -> s2r_decode, all on one stream.
+W x s2r_encode -> s2r_merge -> s2r_decode (the last two as one s2r_merge_decode
+call by default), all on one stream.
 
 torch is used for device memory only (allocation, host<->device copies of test
 data).  Every step of the path itself is a call into libs2r.so.
@@ -84,7 +85,13 @@ class Buffers:
         binding.decode(self.sketch_sum, self.bitmap_or, self.n, self.d, self.w, self.seed,
                        self.out_idx, self.out_val, self.out_count, self.dense_out, self.decode_workspace, stream)
 
-    def step(self, stream=None, batched: bool = True):
+    def merge_decode(self, stream=None):
+        """merge and decode as one s2r_merge_decode call."""
+        binding.merge_decode(self.sketch, self.bitmap, self.n, self.d, self.w, self.seed, self.sketch_sum,
+                             self.bitmap_or, self.out_idx, self.out_val, self.out_count, self.dense_out,
+                             self.decode_workspace, stream)
+
+    def step(self, stream=None, batched: bool = True, fused_merge_decode: bool = True):
         """One pass of the whole hot path over the resident gradients: the W
         encodes (one s2r_encode_batch call, or W s2r_encode calls), merge, decode."""
         if batched:
@@ -92,8 +99,11 @@ class Buffers:
         else:
             for k in range(self.W):
                 self.encode(k, stream)
-        self.merge(stream)
-        self.decode(stream)
+        if fused_merge_decode:
+            self.merge_decode(stream)
+        else:
+            self.merge(stream)
+            self.decode(stream)
 
 
 def buffers_for(wl, device="cuda:0", dense_out: bool = False, slack: int = 0, sort_cap: int | None = None) -> Buffers:
@@ -159,14 +169,22 @@ class BlockBuffers:
         binding.decode_blocks(self.sketch_sum, self.bitmap_or, self.n, self.block, self.d, self.w, self.seed,
                               self.out_blk, self.out_val, self.out_count, self.workspace, stream)
 
-    def step(self, stream=None, batched: bool = True):
+    def merge_decode(self, stream=None):
+        binding.merge_decode_blocks(self.sketch, self.bitmap, self.n, self.block, self.d, self.w, self.seed,
+                                    self.sketch_sum, self.bitmap_or, self.out_blk, self.out_val, self.out_count,
+                                    self.workspace, stream)
+
+    def step(self, stream=None, batched: bool = True, fused_merge_decode: bool = True):
         if batched:
             self.encode_all(stream)
         else:
             for k in range(self.W):
                 self.encode(k, stream)
-        self.merge(stream)
-        self.decode(stream)
+        if fused_merge_decode:
+            self.merge_decode(stream)
+        else:
+            self.merge(stream)
+            self.decode(stream)
 
 
 def block_buffers_for(wl, block: int, device="cuda:0", slack: int = 0) -> BlockBuffers:

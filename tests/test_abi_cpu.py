@@ -112,6 +112,39 @@ def test_merge_and_decode_reject_bad_arguments():
     assert dec(wsb=0) == b.S2R_ERR_WORKSPACE
 
 
+def test_merge_decode_checks_both_halves_before_it_launches():
+    """Every bad argument of either half is an error return (no GPU here: nothing may be enqueued)."""
+    lib = b.load()
+    two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    one_null = (ctypes.c_void_p * 2)(0x1000, None)
+    md = lambda **k: lib.s2r_merge_decode(k.get("S", two), k.get("C", two), k.get("W", 2), k.get("n", 100), k.get("d", 3),
+                                          k.get("w", 64), 0, k.get("So", 0x3000), k.get("Co", 0x4000),
+                                          k.get("idx", 0x5000), k.get("val", 0x6000), 10, k.get("cnt", 0x7000), None,
+                                          k.get("ws", 0x10000), k.get("wsb", 1 << 20), None)
+    assert md(S=None) == b.S2R_ERR_NULL
+    assert md(C=one_null) == b.S2R_ERR_NULL
+    assert md(W=0) == b.S2R_ERR_SIZE
+    assert md(W=65) == b.S2R_ERR_SIZE
+    assert md(So=None) == b.S2R_ERR_NULL
+    assert md(So=0x3004) == b.S2R_ERR_ALIGN
+    assert md(w=65) == b.S2R_ERR_WIDTH
+    assert md(n=0) == b.S2R_ERR_SIZE
+    assert md(cnt=None) == b.S2R_ERR_NULL               # the decode half
+    assert md(val=None) == b.S2R_ERR_NULL
+    assert md(wsb=0) == b.S2R_ERR_WORKSPACE
+    assert md(ws=0x10010) == b.S2R_ERR_WORKSPACE
+    bad = _options(decode_strategy=9)
+    assert lib.s2r_merge_decode_ex(two, two, 2, 100, 3, 64, 0, 0x3000, 0x4000, 0x5000, 0x6000, 10, 0x7000, None,
+                                   0x10000, 1 << 20, None, ctypes.byref(bad)) == b.S2R_ERR_SIZE
+    mdb = lambda **k: lib.s2r_merge_decode_blocks(two, two, 2, k.get("n", 1000), k.get("B", 10), 3, 64, 0, 0x3000,
+                                                  0x4000, 0x5000, k.get("val", 0x6000), 10, k.get("cnt", 0x7000),
+                                                  0x10000, k.get("wsb", 1 << 20), None)
+    assert mdb(B=0) == b.S2R_ERR_SIZE
+    assert mdb(cnt=None) == b.S2R_ERR_NULL
+    assert mdb(val=None) == b.S2R_ERR_NULL
+    assert mdb(wsb=16) == b.S2R_ERR_WORKSPACE
+
+
 def test_encode_batch_rejects_bad_arguments():
     lib = b.load()
     two = (ctypes.c_void_p * 2)(0x1000, 0x2000)

@@ -91,7 +91,7 @@ def _run_and_check(wl, dense_out=False, batched=True, slack=0, sort_cap=None):
     print(f"[case] {wl.name} W={wl.W} n={wl.n} d={wl.d} w={wl.w} batched={batched} slack={slack} sort_cap={sort_cap}", flush=True)
     enc, S, C, M, dec = _oracle_for(wl)
     b = pipeline.buffers_for(wl, dense_out=dense_out, slack=slack, sort_cap=sort_cap)
-    b.step(batched=batched)
+    b.step(batched=batched, fused_merge_decode=batched)   # (per-worker encodes go with separate merge and decode calls)
     torch.cuda.synchronize()
     nnz = b.nnz.cpu().numpy()
     for k in range(wl.W):
@@ -159,6 +159,55 @@ def test_ragged_lengths_dense_gradient(n, strategy):
     idx = [np.arange(n)]
     val = [rng.normal(0, 1, n).astype(np.float32) + 3.0]
     _run_and_check(_custom(n, idx, val, d=3, w=1 << 8), dense_out=True)
+
+
+@pytest.mark.parametrize("n,dense", [(1, True), (63, False), (2049, True), (32768, False), (32769, True), (100003, False),
+                                     (16 * 32768 + 5, True)])
+def test_merge_decode_is_merge_then_decode_bit_for_bit(n, dense, decode_strategy):
+    """s2r_merge_decode (the merge kernel counts the aggregated bitmap) against s2r_merge followed by
+    s2r_decode (which counts it itself) on the same encoded workers: every output identical, also for
+    lengths whose last piece, tile or word is ragged, for empty tiles in the middle, for a dense output."""
+    rng = np.random.default_rng(1000 + n)
+    W = 3
+    idx, val = [], []
+    for k in range(W):
+        m = min(n, max(1, n // (k + 2)))
+        i = np.sort(rng.choice(n, m, replace=False))
+        if n > 5 * 32768:                                  # leave tiles 2 and 3 empty
+            i = i[(i < 2 * 32768) | (i >= 4 * 32768)]
+        idx.append(i)
+        val.append(rng.normal(0, 1, len(i)).astype(np.float32) + 2.0)
+    wl = _custom(n, idx, val, d=3, w=1 << 9, W=W)
+    b = pipeline.buffers_for(wl, dense_out=dense)
+    names = ("sketch_sum", "bitmap_or", "out_idx", "out_val", "out_count") + (("dense_out",) if dense else ())
+    b.encode_all()                                         # (atomic insertions differ from run to run: encode once)
+    _same_outputs_from_both_call_sequences(b, names)
+    assert int(b.out_count.cpu()[0]) == len(np.unique(np.concatenate(idx)))
+
+
+def _same_outputs_from_both_call_sequences(b, names):
+    def run(call):
+        for name in names:
+            getattr(b, name).fill_(0)
+        call()
+        torch.cuda.synchronize()
+        return {name: getattr(b, name).cpu().numpy().copy() for name in names}
+    two_calls = run(lambda: (b.merge(), b.decode()))
+    one_call = run(b.merge_decode)
+    for name in names:
+        assert np.array_equal(two_calls[name].view(np.uint8), one_call[name].view(np.uint8)), name
+
+
+@pytest.mark.parametrize("n,B", [(1000, 7), (70000, 650), (200001, 64), (3 * 32768 * 16 + 11, 16)])
+def test_merge_decode_blocks_is_merge_then_decode_blocks_bit_for_bit(n, B, decode_strategy):
+    rng = np.random.default_rng(n + B)
+    W = 2
+    idx = [np.sort(rng.choice(n, max(1, n // 50), replace=False)) for _ in range(W)]
+    val = [rng.normal(0, 1, len(i)).astype(np.float32) + 2.0 for i in idx]
+    wl = _custom(n, idx, val, d=3, w=1 << 9, W=W)
+    b = pipeline.block_buffers_for(wl, B)
+    b.encode_all()
+    _same_outputs_from_both_call_sequences(b, ("sketch_sum", "bitmap_or", "out_blk", "out_val", "out_count"))
 
 
 @pytest.mark.parametrize("dense_out", [False, True], ids=["lists", "lists+dense"])
@@ -646,7 +695,7 @@ def _run_blocks_and_check(wl, B, batched=True):
     print(f"[case] blocks {wl.name} W={wl.W} n={wl.n} B={B} d={wl.d} w={wl.w} batched={batched}", flush=True)
     ref = _oracle_blocks(wl, B)
     b = pipeline.block_buffers_for(wl, B)
-    b.step(batched=batched)
+    b.step(batched=batched, fused_merge_decode=batched)   # (per-worker encodes go with separate merge and decode calls)
     torch.cuda.synchronize()
     nblk = b.nblk.cpu().numpy()
     for k in range(wl.W):
