@@ -397,7 +397,7 @@ def measure(args, workload: str, wl=None):
         "encode_calls": "s2r_topk_encode_blocks_batch_ex" if fused else
                         ("s2r_encode_blocks_batch_ex" if batched else "s2r_encode_blocks_ex x W") if args.block > 0
                         else ("s2r_encode_batch_ex" if batched else "s2r_encode_ex x W"),
-        "decode_route": "slice" if binding.last_decode_strategy() == binding.S2R_DECODE_SLICE else "gather",
+        "decode_route": {binding.S2R_DECODE_SLICE: "slice", binding.S2R_DECODE_ROWS: "rows"}.get(binding.last_decode_strategy(), "gather"),
         "insert_strategy": insert,
         "kernel_ms": {"topk_scores_per_launch" if fused else "encode_scan_per_launch": round(scan_ms, 4),
                       "workers_per_scan_launch": workers_per_launch,

@@ -509,6 +509,13 @@ size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t c
  *                      d*w <= 2^27, d*(cap + 8192) < 2^32 and a workspace of
  *                      s2r_decode_workspace_bytes (otherwise the call gathers
  *                      whatever is asked for)
+ *   S2R_DECODE_ROWS    gathers again, but a workgroup reads one sketch row only, and
+ *                      the rows are shared out between the chip's eight dies so that
+ *                      a row of up to 4 MB stays in the cache of the dies that read
+ *                      it; the estimates meet in the workspace and a second kernel
+ *                      takes the medians.  Needs idx_out / val_out, no dense_out,
+ *                      d <= 8 and a workspace of s2r_decode_workspace_bytes
+ *                      (otherwise the call gathers as S2R_DECODE_GATHER does)
  *   S2R_DECODE_AUTO    (0, default) chosen from d, w and the expected number of
  *                      union indices
  *
@@ -526,7 +533,7 @@ size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t c
  * trace: NULL, or measurement hooks declared in s2r_bench.h.
  *
  * Errors: S2R_ERR_SIZE if struct_bytes is not sizeof(s2r_options), a strategy is not one of
- * the three values, or flags is not 0.
+ * its values, or flags is not 0.
  */
 #define S2R_INSERT_AUTO   0
 #define S2R_INSERT_ATOMIC 1
@@ -534,6 +541,7 @@ size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t c
 #define S2R_DECODE_AUTO   0
 #define S2R_DECODE_GATHER 1
 #define S2R_DECODE_SLICE  2
+#define S2R_DECODE_ROWS   3
 
 typedef struct s2r_report {
   int32_t  insert_strategy;

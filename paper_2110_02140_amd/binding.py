@@ -36,6 +36,7 @@ S2R_INSERT_SLICE = 2
 S2R_DECODE_AUTO = 0
 S2R_DECODE_GATHER = 1
 S2R_DECODE_SLICE = 2
+S2R_DECODE_ROWS = 3
 
 
 
@@ -231,8 +232,9 @@ def set_insert_strategy(strategy: int):
 
 
 def set_decode_strategy(strategy: int):
-    """S2R_DECODE_AUTO / _GATHER / _SLICE for this module's following decode calls."""
-    _check_strategy(strategy, (S2R_DECODE_AUTO, S2R_DECODE_GATHER, S2R_DECODE_SLICE), "set_decode_strategy")
+    """S2R_DECODE_AUTO / _GATHER / _SLICE / _ROWS for this module's following decode calls."""
+    _check_strategy(strategy, (S2R_DECODE_AUTO, S2R_DECODE_GATHER, S2R_DECODE_SLICE, S2R_DECODE_ROWS),
+                    "set_decode_strategy")
     defaults.decode_strategy = strategy
 
 

@@ -216,6 +216,23 @@ static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t c
   return L;
 }
 
+// Workspace of s2r_decode's row route: the base parts, then the estimates, float32[d][stride], stride = the
+// list's capacity rounded up to 64 entries.
+constexpr uint32_t kRowsMaxRows = 8;                     // eight XCDs
+struct RowsLayout {
+  bool possible;
+  uint64_t stride;
+  size_t est_off, total;
+};
+static RowsLayout rows_layout(uint64_t n, uint32_t d, uint64_t cap) {
+  RowsLayout L;
+  L.possible = d <= kRowsMaxRows && cap > 0;
+  L.stride = ceil_div(cap, 64) * 64;
+  L.est_off = workspace_base(n);
+  L.total = L.est_off + (L.possible ? align256((size_t)d * L.stride * sizeof(float)) : 0);
+  return L;
+}
+
 // How s2r_decode reads the buckets.  Measured on MI355X: gathers from a sketch far larger than the L2
 // (4 MB per XCD) run at about 56e9 per second (each fetches a 128-byte line), from one of a few L2 sizes at
 // about 70e9, from one that fits at about 200e9; the slice route costs about 80 us of launches and latency
@@ -226,13 +243,24 @@ static int32_t choose_decode(uint64_t n, uint32_t d, uint32_t w, bool have_lists
                              uint64_t expect, size_t workspace_bytes, int32_t asked) {
   if (!have_lists || dense_out || cap == 0) return S2R_DECODE_GATHER;
   const DecodeLayout L = decode_layout(n, d, w, cap);
-  if (!L.possible || workspace_bytes < L.total) return S2R_DECODE_GATHER;
-  if (asked != S2R_DECODE_AUTO) return asked;
+  const RowsLayout R = rows_layout(n, d, cap);
+  const bool slice_ok = L.possible && workspace_bytes >= L.total;
+  const bool rows_ok = R.possible && workspace_bytes >= R.total;
+  if (asked == S2R_DECODE_SLICE) return slice_ok ? S2R_DECODE_SLICE : S2R_DECODE_GATHER;
+  if (asked == S2R_DECODE_ROWS) return rows_ok ? S2R_DECODE_ROWS : S2R_DECODE_GATHER;
+  if (asked == S2R_DECODE_GATHER) return S2R_DECODE_GATHER;
   const double queries = (double)expect * d;
   const double sketch_bytes = 4.0 * d * w;
-  const double t_gather = queries / (sketch_bytes > 16e6 ? 56e9 : sketch_bytes > 4e6 ? 70e9 : 200e9);
-  const double t_slice = 80e-6 + queries / 110e9;
-  return t_slice < t_gather ? S2R_DECODE_SLICE : S2R_DECODE_GATHER;
+  double best = queries / (sketch_bytes > 16e6 ? 56e9 : sketch_bytes > 4e6 ? 70e9 : 200e9);
+  int32_t choice = S2R_DECODE_GATHER;
+  // a row per XCD pays when a row fits an L2 (4 MB) and the whole sketch does not; it costs one more launch and
+  // a pass over the estimates
+  if (rows_ok && 4.0 * w <= 4.2e6 && sketch_bytes > 4.2e6 && 8e-6 + queries / 125e9 < best) {
+    best = 8e-6 + queries / 125e9;
+    choice = S2R_DECODE_ROWS;
+  }
+  if (slice_ok && 80e-6 + queries / 110e9 < best) choice = S2R_DECODE_SLICE;
+  return choice;
 }
 
 // The slice kernels use more dynamic LDS than the default limit allows; the limit is a property of the
@@ -267,6 +295,23 @@ static inline void record(const Exec& X, int slot, bool end, hipStream_t st) {
 }
 
 static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+static void launch_rows_median(uint32_t d, const float* est, uint64_t stride, const uint64_t* count, uint64_t cap,
+                               float* val_out, uint32_t block, uint64_t n, const uint32_t* blk_list, uint64_t expect,
+                               hipStream_t st) {
+  const uint64_t wgs = ceil_div(expect > 0 ? expect : 1, (uint64_t)kBlock * 2);        // (the threads loop)
+  const dim3 grid((uint32_t)(wgs < 16384 ? wgs : 16384)), blk(kBlock);
+  switch (d) {
+    case 1: hipLaunchKernelGGL(decode_rows_median_kernel<1>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    case 2: hipLaunchKernelGGL(decode_rows_median_kernel<2>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    case 3: hipLaunchKernelGGL(decode_rows_median_kernel<3>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    case 4: hipLaunchKernelGGL(decode_rows_median_kernel<4>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    case 5: hipLaunchKernelGGL(decode_rows_median_kernel<5>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    case 6: hipLaunchKernelGGL(decode_rows_median_kernel<6>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    case 7: hipLaunchKernelGGL(decode_rows_median_kernel<7>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+    default: hipLaunchKernelGGL(decode_rows_median_kernel<8>, grid, blk, 0, st, est, stride, count, cap, val_out, block, n, blk_list); break;
+  }
+}
 
 template <int D>
 static void launch_decode(uint32_t ntiles, uint32_t helpers, hipStream_t st, const DecodeArgs& A, const HashRows& hp) {
@@ -327,7 +372,8 @@ s2r_status s2r_hash_params(uint64_t seed, uint32_t d, uint64_t* params_out) {
 size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   if (check_sizes(n, d, w) != S2R_OK || cap > n) return 0;
   const DecodeLayout L = decode_layout(n, d, w, cap);
-  return L.possible ? L.total : workspace_base(n);
+  const RowsLayout R = rows_layout(n, d, cap);
+  return L.possible && L.total > R.total ? L.total : R.total;
 }
 
 s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* stream) {
@@ -848,6 +894,19 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     const uint32_t helpers = dense_grid(ntiles, 2048);
     hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
+    if (strategy == S2R_DECODE_ROWS) {
+      const RowsLayout R = rows_layout(n, d, cap_items);
+      float* est = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + R.est_off);
+      uint64_t units = ceil_div(expect > 0 ? expect : 1, (uint64_t)kBlock * kRowsBlockPer);   // (the units loop)
+      if (units > 16384) units = 16384;
+      const uint32_t groups = (uint32_t)ceil_div(units, 8u / d);
+      hipLaunchKernelGGL(decode_rows_blocks_kernel, dim3(8u * groups), dim3(kBlock), 0, st, A, hp, block, idx_out,
+                         count_out, est, R.stride, (uint32_t)units);
+      if (!launch_ok()) return S2R_ERR_LAUNCH;
+      launch_rows_median(d, est, R.stride, count_out, cap, val_out, block, elements, idx_out, expect, st);
+      record(X, S2R_KERNEL_DECODE, true, st);
+      return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+    }
     const uint64_t bwgs = ceil_div(cap_items, (uint64_t)kBlock * 4);
     const dim3 bgrid((uint32_t)(bwgs < 8192 ? bwgs : 8192)), bblock(kBlock);      // (the workgroups loop)
     switch (d) {
@@ -874,6 +933,16 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
 
   record(X, S2R_KERNEL_DECODE, false, st);
   const uint32_t helpers = dense_grid(ntiles, 2048);
+  if (strategy == S2R_DECODE_ROWS) {
+    const RowsLayout R = rows_layout(n, d, cap_items);
+    float* est = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + R.est_off);
+    const uint32_t groups = (uint32_t)ceil_div((uint64_t)ntiles + helpers, 8u / d);
+    hipLaunchKernelGGL(decode_rows_kernel, dim3(8u * groups), dim3(kBlock), 0, st, A, hp, est, R.stride, ntiles, helpers);
+    if (!launch_ok()) return S2R_ERR_LAUNCH;
+    launch_rows_median(d, est, R.stride, count_out, cap, val_out, 0u, elements, nullptr, expect, st);
+    record(X, S2R_KERNEL_DECODE, true, st);
+    return launch_ok() ? S2R_OK : S2R_ERR_LAUNCH;
+  }
   switch (d) {
     case 1: launch_decode<1>(ntiles, helpers, st, A, hp); break;
     case 2: launch_decode<2>(ntiles, helpers, st, A, hp); break;
@@ -985,7 +1054,8 @@ size_t s2r_decode_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d,
   if (check_sizes(n, d, w) != S2R_OK || !block_ok(n, block) || blk_cap > ceil_div(n, block)) return 0;
   const uint64_t nb = ceil_div(n, block);
   const DecodeLayout L = decode_layout(nb, d, w, blk_cap * block);
-  return L.possible ? L.total : workspace_base(nb);
+  const RowsLayout R = rows_layout(nb, d, blk_cap * block);
+  return L.possible && L.total > R.total ? L.total : R.total;
 }
 
 s2r_status s2r_encode_blocks_batch_ex(const float* const* grads, uint32_t W, uint64_t n, uint32_t block, uint32_t d,
@@ -1039,7 +1109,7 @@ s2r_status s2r::resolve_options(const s2r_options* options, Exec* X) {
       options->insert_strategy != S2R_INSERT_SLICE)
     return S2R_ERR_SIZE;
   if (options->decode_strategy != S2R_DECODE_AUTO && options->decode_strategy != S2R_DECODE_GATHER &&
-      options->decode_strategy != S2R_DECODE_SLICE)
+      options->decode_strategy != S2R_DECODE_SLICE && options->decode_strategy != S2R_DECODE_ROWS)
     return S2R_ERR_SIZE;
   if (options->trace != nullptr) {
     for (int slot = 0; slot < S2R_KERNEL_SLOTS; ++slot)

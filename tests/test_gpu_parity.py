@@ -32,10 +32,10 @@ def strategy(request):
     yield request.param
     binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
 
-DECODES = {"gather": binding.S2R_DECODE_GATHER, "slice": binding.S2R_DECODE_SLICE}
+DECODES = {"gather": binding.S2R_DECODE_GATHER, "slice": binding.S2R_DECODE_SLICE, "rows": binding.S2R_DECODE_ROWS}
 
 
-@pytest.fixture(params=["gather", "slice"])
+@pytest.fixture(params=["gather", "slice", "rows"])
 def decode_strategy(request):
     """Run the test once per way of reading the buckets in s2r_decode."""
     binding.set_decode_strategy(DECODES[request.param])
