@@ -115,9 +115,15 @@ static inline size_t workspace_dense_off(uint64_t n) {
 static inline size_t workspace_base(uint64_t n) {
   return workspace_dense_off(n) + 256 + align256((size_t)tiles_of(n) * kGroupsPerTile * sizeof(uint32_t));
 }
-// workgroups of the kernels that take the dense-tile list (per problem); each loops over the entries
-static inline uint32_t dense_grid(uint32_t ntiles, uint32_t most) {
-  const uint64_t entries = (uint64_t)ntiles * (kGroupsPerTile - 1);
+// Workgroups of the kernels that take the dense-tile list (per problem); each loops over the entries.  An
+// entry stands for kGroupSlots list positions beyond a tile's first kGroupSlots, so `positions` expected list
+// positions make at most positions / kGroupSlots entries: launching more helpers than that only fills the
+// chip with workgroups that read the entry count and leave (with 8 workers and 2048 helpers each, eight rounds
+// of them before the first tile was touched).
+static inline uint32_t dense_grid(uint32_t ntiles, uint64_t positions, uint32_t most) {
+  uint64_t entries = (uint64_t)ntiles * (kGroupsPerTile - 1);
+  const uint64_t expected = positions / kGroupSlots + 8;
+  if (entries > expected) entries = expected;
   return (uint32_t)(entries < most ? (entries > 0 ? entries : 1) : most);
 }
 struct SliceLayout {
@@ -415,6 +421,7 @@ static void launch_bin_scatter(const EncodeBatch& E, const HashRows& hp, dim3 gr
 struct EncodeLaunch {                      // what the launches of one call share
   uint32_t ntiles, scan_blocks, scan_group;
   uint32_t chunk_grid;                     // workgroups per worker of the kernels that walk the list chunks
+  uint64_t expect_bits;                    // set bits expected in a worker's bitmap
   uint64_t nvec, zb;
   uint32_t ntail;
   int32_t strategy;
@@ -471,7 +478,7 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
   if (!launch_ok()) return S2R_ERR_LAUNCH;
 
   if (L.lists && E.cap > 0) {
-    const uint32_t helpers = dense_grid(ntiles, 512);
+    const uint32_t helpers = dense_grid(ntiles, L.expect_bits, 512);
     hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, count), dim3(kBlock), 0, st, E, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
@@ -560,6 +567,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   L.marked = marked;
   // (the chunk kernels loop: a grid sized for the expected items serves any number of them)
   L.chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);
+  L.expect_bits = block != 0 ? expect / block : expect;
 
   E.nworkers = W;
   E.place_off = 0;
@@ -814,7 +822,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     Q.blk_list = idx_out;
 
     record(X, S2R_KERNEL_DECODE, false, st);
-    const uint32_t helpers = dense_grid(ntiles, 2048);
+    const uint32_t helpers = dense_grid(ntiles, block != 0 ? expect / block : expect, 2048);
     hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const uint32_t chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);   // (the chunk kernels loop)
@@ -891,7 +899,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.first_worker = 0;
     B.nworkers = 1;
     record(X, S2R_KERNEL_DECODE, false, st);
-    const uint32_t helpers = dense_grid(ntiles, 2048);
+    const uint32_t helpers = dense_grid(ntiles, block != 0 ? expect / block : expect, 2048);
     hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     if (strategy == S2R_DECODE_ROWS) {
@@ -932,7 +940,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
   }
 
   record(X, S2R_KERNEL_DECODE, false, st);
-  const uint32_t helpers = dense_grid(ntiles, 2048);
+  const uint32_t helpers = dense_grid(ntiles, block != 0 ? expect / block : expect, 2048);
   if (strategy == S2R_DECODE_ROWS) {
     const RowsLayout R = rows_layout(n, d, cap_items);
     float* est = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + R.est_off);
