@@ -260,7 +260,8 @@ s2r_status s2r_decode_noalloc(const float* sketch, const uint64_t* bitmap,
  *
  * s2r_blocks_workspace_bytes: the least scratch for s2r_encode_blocks* and
  * s2r_decode_blocks; the other two: what lets them also use S2R_INSERT_SLICE /
- * S2R_DECODE_SLICE for lists of blk_cap blocks (needs d * (blk_cap * block + 8192) < 2^32).
+ * S2R_DECODE_SLICE (needs d * (blk_cap * block + 8192) < 2^32) / S2R_DECODE_ROWS for
+ * lists of blk_cap blocks.
  * Host only; 0 outside the limits or if blk_cap > nb.
  */
 size_t s2r_blocks_workspace_bytes(uint64_t n, uint32_t block, uint32_t d, uint32_t w);
@@ -464,11 +465,13 @@ s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_b
                                     void* stream);
 
 /*
- * Size query of s2r_decode's slice route (see s2r_options.decode_strategy): bytes of
- * device scratch with which s2r_decode can also use S2R_DECODE_SLICE for lists of
- * capacity cap (s2r_workspace_bytes plus 16*d bytes per list entry and two
- * histograms).  With a smaller workspace (but at least s2r_workspace_bytes) it
- * gathers.  Host only; returns 0 outside the limits or if cap > n.
+ * Size query of s2r_decode's routes that need scratch of their own (see
+ * s2r_options.decode_strategy): bytes of device scratch with which s2r_decode can use
+ * any of them for lists of capacity cap: s2r_workspace_bytes plus, for
+ * S2R_DECODE_SLICE, 16*d bytes per list entry and three histograms, or, for
+ * S2R_DECODE_ROWS alone (where the slice route's limits are not met), 4*d bytes
+ * per list entry.  With a smaller workspace (but at least s2r_workspace_bytes) the
+ * call gathers.  Host only; returns 0 outside the limits or if cap > n.
  */
 size_t s2r_decode_workspace_bytes(uint64_t n, uint32_t d, uint32_t w, uint64_t cap);
 
