@@ -233,6 +233,20 @@ def test_tiles_around_the_expansion_group_size(strategy, dense_out):
     _run_and_check(_custom(n, idx, val, d=3, w=1 << 10, W=2), dense_out=dense_out)
 
 
+def test_dense_tiles_with_an_estimate_far_too_small(strategy, decode_strategy):
+    """Every element set (sixteen further groups per tile) while the caller expects one non-zero: the few
+    workgroups launched for the dense-tile list walk all of its entries."""
+    n = 20 * 32768 + 77
+    rng = np.random.default_rng(5)
+    idx = [np.arange(n)] * 2
+    val = [(rng.normal(0, 1, n) + 3.0).astype(np.float32) for _ in range(2)]
+    binding.set_expected_nnz(1, 1)
+    try:
+        _run_and_check(_custom(n, idx, val, d=3, w=1 << 10, W=2))
+    finally:
+        binding.set_expected_nnz(0, 0)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_small_recipes_both_decodes(cfg, decode_strategy):
     """Without a dense output the decode may take either route; with one (the
