@@ -546,7 +546,7 @@ s2r_status s2r_topk_blocks_batch(const float* const* grads, float* const* residu
                                  uint32_t block, uint64_t K, float* const* sparse_out, uint64_t* const* kept_bitmaps,
                                  void* workspace, size_t workspace_bytes, void* stream) {
   if (sparse_out == nullptr) return S2R_ERR_NULL;
-  static thread_local TopkBatch B;
+  TopkBatch B = {};
   s2r_status rc = fill_batch(B, grads, residuals, W, n, block, K, sparse_out, kept_bitmaps, workspace, workspace_bytes);
   if (rc != S2R_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
@@ -605,7 +605,7 @@ s2r_status s2r_topk_encode_blocks_batch_ex(const float* const* grads, float* con
   char* select_ws = reinterpret_cast<char*>(workspace);
   char* codec_ws = select_ws + (size_t)W * select_each;
   const size_t codec_bytes = workspace_bytes - (size_t)W * select_each;
-  static thread_local TopkBatch B;
+  TopkBatch B = {};
   s2r_status rc = fill_batch(B, grads, residuals, W, n, block, K, nullptr, block_bitmaps, select_ws,
                              (size_t)W * select_each);
   if (rc != S2R_OK) return rc;
