@@ -275,14 +275,19 @@ static bool raise_scatter_lds(const void* kernel) {
   return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)(kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * kMaxBins)) == hipSuccess;
 }
+static bool raise_slice_lds(const void* kernel) {
+  return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) == hipSuccess;
+}
 static bool raise_lds_limits() {
   constexpr int kMaxDevices = 64;
   static std::atomic<bool> raised[kMaxDevices];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0) return false;
   if (dev < kMaxDevices && raised[dev].load(std::memory_order_acquire)) return true;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(sketch_slice_kernel),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) != hipSuccess ||
+  if (!raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<true, true>)) ||
+      !raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<true, false>)) ||
+      !raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<false, true>)) ||
+      !raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<false, false>)) ||
       !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<0>)) ||
       !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<1>)) ||
       !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<2>)) ||
@@ -422,6 +427,7 @@ struct EncodeLaunch {                      // what the launches of one call shar
   uint32_t ntiles, scan_blocks, scan_group;
   uint32_t chunk_grid;                     // workgroups per worker of the kernels that walk the list chunks
   uint64_t expect_bits;                    // set bits expected in a worker's bitmap
+  uint64_t expect_items;                   // items expected in a worker's counting sort
   uint64_t nvec, zb;
   uint32_t ntail;
   int32_t strategy;
@@ -479,7 +485,10 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
 
   if (L.lists && E.cap > 0) {
     const uint32_t helpers = dense_grid(ntiles, L.expect_bits, 512);
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, count), dim3(kBlock), 0, st, E, helpers);
+    if (E.w[first].nz_val != nullptr)          // (all workers of a call have value lists, or none has)
+      hipLaunchKernelGGL(encode_compact_kernel<true>, dim3(helpers + ntiles, count), dim3(kBlock), 0, st, E, helpers);
+    else
+      hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(helpers + ntiles, count), dim3(kBlock), 0, st, E, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
   }
 
@@ -497,8 +506,14 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, false, st);
     // about one workgroup per compute unit, each walking `per` consecutive bins of one worker
     const uint32_t per = (uint32_t)ceil_div((uint64_t)E.nbins * count, kSliceWorkgroups);
-    hipLaunchKernelGGL(sketch_slice_kernel, dim3((uint32_t)ceil_div(E.nbins, per), count), dim3(kSliceBlock), lds, st,
-                       E, per);
+    // (streaming stores only when the call's sketches are more than the memory-side cache keeps)
+    const bool stream_out = ((uint64_t)E.nworkers * E.d << E.log2w) * sizeof(float) > (512ull << 20);
+    const bool stream_in = (uint64_t)E.nworkers * L.expect_items * E.d * 8 > (128ull << 20);
+    const dim3 sgrid((uint32_t)ceil_div(E.nbins, per), count), sblock(kSliceBlock);
+    if (stream_in && stream_out) hipLaunchKernelGGL((sketch_slice_kernel<true, true>), sgrid, sblock, lds, st, E, per);
+    else if (stream_in) hipLaunchKernelGGL((sketch_slice_kernel<true, false>), sgrid, sblock, lds, st, E, per);
+    else if (stream_out) hipLaunchKernelGGL((sketch_slice_kernel<false, true>), sgrid, sblock, lds, st, E, per);
+    else hipLaunchKernelGGL((sketch_slice_kernel<false, false>), sgrid, sblock, lds, st, E, per);
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, true, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
 
@@ -568,6 +583,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   // (the chunk kernels loop: a grid sized for the expected items serves any number of them)
   L.chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);
   L.expect_bits = block != 0 ? expect / block : expect;
+  L.expect_items = expect;
 
   E.nworkers = W;
   E.place_off = 0;
@@ -823,7 +839,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
 
     record(X, S2R_KERNEL_DECODE, false, st);
     const uint32_t helpers = dense_grid(ntiles, block != 0 ? expect / block : expect, 2048);
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
+    hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const uint32_t chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);   // (the chunk kernels loop)
     launch_bin_hist(B, hp, dim3(chunk_grid, 1), st);
@@ -900,7 +916,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.nworkers = 1;
     record(X, S2R_KERNEL_DECODE, false, st);
     const uint32_t helpers = dense_grid(ntiles, block != 0 ? expect / block : expect, 2048);
-    hipLaunchKernelGGL(encode_compact_kernel, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
+    hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     if (strategy == S2R_DECODE_ROWS) {
       const RowsLayout R = rows_layout(n, d, cap_items);

@@ -348,6 +348,21 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_scatter_kernel(const EncodeB
 // current slice is read out, the read-out leaves zeros behind (no separate
 // clearing pass), and the streaming stores of one slice drain while the next
 // is being accumulated.
+// STREAM_OUT: the slices leave with streaming stores.  Measured on MI355X: when the sketches of the launch
+// add up to more than the memory-side cache keeps (config 5: 1.3 GB), streaming stores are the faster ones
+// (410 against 442 us); when they do not (config 4: 336 MB; config 2: 25 MB), plain stores are (122 against
+// 136 us, 58 against 62 us) and the merge that reads the sketches next gains a little too (86 -> 83 us).
+// STREAM_IN: the records are read with streaming loads; the same kind of threshold from the other side: 49 MB
+// of records (config 3) are read faster with plain loads (26 against 30 us: the scatter kernel has just
+// written them), 253 MB (config 4) with streaming ones (123 against 136 us).
+// (Both are compile-time: as run-time flags inside the unrolled loops they cost the kernel 6 to 10 %.)
+template <bool STREAM_IN>
+__device__ __forceinline__ u32x2 load_record(const u32x2* p) {
+  if constexpr (STREAM_IN) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
+template <bool STREAM_IN, bool STREAM_OUT>
 __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeBatch B, uint32_t per) {
   extern __shared__ double s_slice[];
   constexpr int kAhead = 4;                               // 8-byte record loads per thread and batch
@@ -369,8 +384,8 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
 #pragma unroll
   for (int u = 0; u < kAhead; ++u) {
     const uint64_t r = base + threadIdx.x + u * kSliceBlock;
-    x[u] = r < end ? __builtin_nontemporal_load(&rec[r]) : none;
-    y[u] = r + kBatch < end ? __builtin_nontemporal_load(&rec[r + kBatch]) : none;
+    x[u] = r < end ? load_record<STREAM_IN>(&rec[r]) : none;
+    y[u] = r + kBatch < end ? load_record<STREAM_IN>(&rec[r + kBatch]) : none;
   }
   if (cells >= 2u * kSliceBlock) {                        // (the LDS array is 16-byte aligned)
     for (uint32_t c = threadIdx.x; c < cells / 2; c += kSliceBlock)
@@ -398,7 +413,7 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
       for (int u = 0; u < kAhead; ++u) {
         x[u] = y[u];
         const uint64_t r = base + kBatch + threadIdx.x + u * kSliceBlock;
-        y[u] = r < end ? __builtin_nontemporal_load(&rec[r]) : none;
+        y[u] = r < end ? load_record<STREAM_IN>(&rec[r]) : none;
       }
       continue;
     }
@@ -413,7 +428,8 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
         cell[1] = make_double2(0.0, 0.0);
         f32x4 o;
         o.x = (float)lo.x; o.y = (float)lo.y; o.z = (float)hi.x; o.w = (float)hi.y;
-        __builtin_nontemporal_store(o, &reinterpret_cast<f32x4*>(out)[c]);
+        if constexpr (STREAM_OUT) __builtin_nontemporal_store(o, &reinterpret_cast<f32x4*>(out)[c]);
+        else reinterpret_cast<f32x4*>(out)[c] = o;
       }
     } else {
       for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) {
@@ -431,7 +447,7 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
       for (int u = 0; u < kAhead; ++u) {
         x[u] = y[u];
         const uint64_t r = base + kBatch + threadIdx.x + u * kSliceBlock;
-        y[u] = r < end ? __builtin_nontemporal_load(&rec[r]) : none;
+        y[u] = r < end ? load_record<STREAM_IN>(&rec[r]) : none;
       }
     }
     __syncthreads();                                      // the slice is all zero again

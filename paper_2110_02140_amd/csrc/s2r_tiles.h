@@ -234,6 +234,8 @@ __device__ __forceinline__ uint32_t locate_set_bit(const TileBits& T, uint32_t t
 // ------------------------------------------------------------------ encode: Sparse(g)
 // List positions [group * kGroupSlots, (group + 1) * kGroupSlots) of one tile, by
 // one workgroup of kBlock threads.  All threads call it with the same arguments.
+// VALUES: the values at the set bits are gathered too (expansions of aggregated or block bitmaps carry none).
+template <bool VALUES>
 __device__ __forceinline__ void compact_group(const EncodeBatch& B, const WorkerPtrs& P, const uint64_t* prefix,
                                               TileBits& T, uint32_t tile, uint32_t group) {
   const uint64_t word0 = (uint64_t)tile * kTileWords;
@@ -256,15 +258,14 @@ __device__ __forceinline__ void compact_group(const EncodeBatch& B, const Worker
       live[u] = t < last && base + t < B.cap;
       i[u] = live[u] ? (uint32_t)(word0 * 64 + locate_set_bit(T, t)) : 0u;
     }
-    const bool values = P.nz_val != nullptr;             // expansions of aggregated or block bitmaps carry no values
 #pragma unroll
-    for (int u = 0; u < kSlots; ++u) v[u] = live[u] && values ? P.grad[i[u]] : 0u;
+    for (int u = 0; u < kSlots; ++u) v[u] = VALUES && live[u] ? P.grad[i[u]] : 0u;
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
       if (!live[u]) continue;
       const uint64_t pos = base + t0 + u * kBlock;
       P.nz_idx[pos] = i[u];
-      if (values) P.nz_val[pos] = v[u];
+      if (VALUES) P.nz_val[pos] = v[u];
     }
   }
 }
@@ -273,12 +274,13 @@ __device__ __forceinline__ void compact_group(const EncodeBatch& B, const Worker
 // in the dense-tile list, one entry per trip (they start first: theirs is the
 // longest work); workgroup helpers + t takes the first kGroupSlots list positions
 // of tile t.
+template <bool VALUES>
 __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatch B, uint32_t helpers) {
   __shared__ TileBits T;
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   if (blockIdx.x >= helpers) {
-    compact_group(B, B.w[k], ws_prefix(B, k), T, blockIdx.x - helpers, 0u);
+    compact_group<VALUES>(B, B.w[k], ws_prefix(B, k), T, blockIdx.x - helpers, 0u);
     return;
   }
   const uint32_t* dense = ws_dense_list(B, k);
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(kBlock) void encode_compact_kernel(const EncodeBatc
   for (uint32_t e = blockIdx.x; e < entries; e += helpers) {
     const uint32_t entry = dense[64 + e];
     __syncthreads();                                     // T may still be read by the previous trip
-    compact_group(B, B.w[k], ws_prefix(B, k), T, entry & 0xFFFFFu, entry >> 20);
+    compact_group<VALUES>(B, B.w[k], ws_prefix(B, k), T, entry & 0xFFFFFu, entry >> 20);
   }
 }
 
