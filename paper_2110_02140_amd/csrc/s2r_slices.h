@@ -26,7 +26,7 @@ namespace s2r {
 //   sketch_slice_kernel workgroup (j, s) clears its slice in LDS, adds its bin's
 //                       records with LDS float64 atomics and stores the slice as float32
 // Work is O(items x rows), whatever the number of slices, and every cell of the
-// sketch is written exactly once by plain coalesced stores.
+// sketch is written exactly once, by coalesced stores.
 constexpr int kBinBlock = 1024;
 constexpr int kBinItems = 8;                           // list items per thread
 constexpr int kBinChunk = kBinBlock * kBinItems;       // 8192 items per workgroup
