@@ -133,6 +133,45 @@ def test_recipe1_full_size(strategy):
     _run_and_check(workloads.make(1), dense_out=True)
 
 
+@pytest.mark.parametrize("case", range(36))
+def test_seeded_random_problems(case):
+    """Thirty-six problems drawn from a seeded generator: lengths from one word to a few tiles (ragged),
+    1 to 16 rows, 2^6 to 2^16 columns, 1 to 5 workers, isolated non-zeros, runs and fully dense stretches mixed,
+    list capacities from exact to generous, each of the insertion strategies and decode routes asked for in
+    turn (the library falls back where one does not apply), with and without a dense output."""
+    rng = np.random.default_rng(9000 + case)
+    n = int(rng.choice([rng.integers(1, 200), rng.integers(200, 70000), rng.integers(70000, 400000)]))
+    d = int(rng.integers(1, 17))
+    w = 1 << int(rng.integers(6, 17))
+    W = int(rng.integers(1, 6))
+    idx, val = [], []
+    for k in range(W):
+        kind = rng.integers(0, 3)
+        if kind == 0:                                      # isolated
+            m = int(rng.integers(0, max(1, n // 20) + 1))
+            i = rng.choice(n, size=min(m, n), replace=False)
+        elif kind == 1:                                    # runs of consecutive indices
+            starts = rng.choice(n, size=min(n, int(rng.integers(1, 12))), replace=False)
+            i = np.concatenate([np.arange(s0, min(n, s0 + int(rng.integers(1, 5000)))) for s0 in starts])
+        else:                                              # a dense stretch (tiles with more than 2048 set bits)
+            a = int(rng.integers(0, n))
+            i = np.arange(a, min(n, a + int(rng.integers(1, 40000))))
+        i = np.unique(i).astype(np.uint32)
+        idx.append(i)
+        v = rng.normal(0, 1, len(i)).astype(np.float32)
+        v[v == 0] = 1.0
+        val.append(v)
+    wl = _custom(n, idx, val, d=d, w=w, W=W, seed=int(rng.integers(0, 2**31)))
+    binding.set_insert_strategy([binding.S2R_INSERT_AUTO, binding.S2R_INSERT_ATOMIC, binding.S2R_INSERT_SLICE][case % 3])
+    binding.set_decode_strategy([binding.S2R_DECODE_AUTO, binding.S2R_DECODE_GATHER, binding.S2R_DECODE_SLICE,
+                                 binding.S2R_DECODE_ROWS][case % 4])
+    try:
+        _run_and_check(wl, dense_out=bool(case % 5 == 0), batched=bool(case % 2), slack=int(rng.choice([0, 1, 1000])))
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+        binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
 def test_recipe1_with_lds_sized_sketch(strategy, decode_strategy):
     """Recipe 1 with a 96 KB sketch (w = 2^13): the size at which the sketch is
     two LDS slices; heavy collisions (41 000 union items in 8192 columns)."""
