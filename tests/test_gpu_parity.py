@@ -786,6 +786,39 @@ def test_full_size_recipes_block_codec(cfg, B):
     _run_blocks_and_check(workloads.make(cfg), B)
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_block_codec_seeded_random_problems(case):
+    """Two dozen seeded problems for the block-granular codec: block sizes from 1 to beyond the gradient,
+    ragged last blocks, isolated non-zeros and runs, every strategy and route asked for in turn."""
+    rng = np.random.default_rng(7000 + case)
+    n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 60000), rng.integers(60000, 300000)]))
+    B = int(rng.choice([1, 2, 7, 64, 100, 256, 650, 1000, 4096, n + 5]))
+    d = int(rng.integers(1, 9))
+    w = 1 << int(rng.integers(6, 15))
+    W = int(rng.integers(1, 5))
+    idx, val = [], []
+    for k in range(W):
+        if rng.integers(0, 2) == 0:
+            i = rng.choice(n, size=min(n, int(rng.integers(0, max(1, n // 30) + 1))), replace=False)
+        else:
+            starts = rng.choice(n, size=min(n, int(rng.integers(1, 8))), replace=False)
+            i = np.concatenate([np.arange(s0, min(n, s0 + int(rng.integers(1, 3000)))) for s0 in starts])
+        i = np.unique(i).astype(np.uint32)
+        idx.append(i)
+        v = rng.normal(0, 1, len(i)).astype(np.float32)
+        v[v == 0] = 1.0
+        val.append(v)
+    wl = _custom(n, idx, val, d=d, w=w, W=W, seed=int(rng.integers(0, 2**31)))
+    binding.set_insert_strategy([binding.S2R_INSERT_AUTO, binding.S2R_INSERT_ATOMIC, binding.S2R_INSERT_SLICE][case % 3])
+    binding.set_decode_strategy([binding.S2R_DECODE_AUTO, binding.S2R_DECODE_GATHER, binding.S2R_DECODE_SLICE,
+                                 binding.S2R_DECODE_ROWS][case % 4])
+    try:
+        _run_blocks_and_check(wl, B, batched=bool(case % 2))
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+        binding.set_decode_strategy(binding.S2R_DECODE_AUTO)
+
+
 @pytest.mark.parametrize("n,B", [(1, 1), (63, 64), (64, 64), (65, 64), (1000, 7), (70000, 650), (200001, 4096), (5000, 9000)])
 def test_block_codec_dense_gradient_ragged(n, B, strategy, decode_strategy):
     """Every element set, lengths that are not multiples of the block, one block larger than n."""
