@@ -26,8 +26,8 @@
 //                                      extra workgroups through a dense-tile list
 //                bin_hist_kernel,      (slice variant) Sparse(g) x rows is partitioned by
 //                bin_colscan_kernel,   sketch slice (counting sort: histogram per chunk,
-//                bin_start_kernel,     offsets, scatter of (cell, signed value) records
-//                bin_scatter_kernel    sorted by slice inside LDS first)
+//                bin_scatter_kernel    offsets, scatter of (cell, signed value) records
+//                                      sorted by slice inside LDS first)
 //                sketch_slice_kernel   (slice variant) every workgroup owns a slice of
 //                                      one sketch row in LDS, adds the records of its
 //                                      bin and stores the slice: no global atomics, no
@@ -129,7 +129,7 @@ static inline uint32_t dense_grid(uint32_t ntiles, uint64_t positions, uint32_t 
 struct SliceLayout {
   bool possible;             // the bins fit the LDS histograms and record positions fit 32 bits
   uint32_t slice_log2, nbins, nchunks;
-  size_t hist_off, slicepre_off, binstart_off, rec_off, total;
+  size_t hist_off, slicepre_off, chunktotal_off, binstart_off, rec_off, total;
 };
 static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   SliceLayout L;
@@ -142,7 +142,8 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
   const size_t matrix = align256((size_t)L.nchunks * L.nbins * sizeof(uint32_t));
   L.hist_off = workspace_base(n);
   L.slicepre_off = L.hist_off + matrix;
-  L.binstart_off = L.slicepre_off + matrix;
+  L.chunktotal_off = L.slicepre_off + matrix;
+  L.binstart_off = L.chunktotal_off + align256((size_t)L.nchunks * sizeof(uint32_t));
   L.rec_off = L.binstart_off + align256(((size_t)L.nbins + 1) * sizeof(uint32_t));
   L.total = L.rec_off + align256((size_t)(L.possible ? d * cap : 0) * 8);
   return L;
@@ -200,7 +201,7 @@ constexpr int kDecodeSliceMaxRows = 8;                   // decode_median_kernel
 struct DecodeLayout {
   bool possible;
   uint32_t slice_log2, nbins, nchunks;
-  size_t hist_off, slicepre_off, place_off, binstart_off, rec_off, answers_off, total;
+  size_t hist_off, slicepre_off, place_off, chunktotal_off, binstart_off, rec_off, answers_off, total;
 };
 static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   DecodeLayout L;
@@ -215,7 +216,8 @@ static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t c
   L.hist_off = workspace_base(n);
   L.slicepre_off = L.hist_off + matrix;
   L.place_off = L.slicepre_off + matrix;
-  L.binstart_off = L.place_off + matrix;
+  L.chunktotal_off = L.place_off + matrix;
+  L.binstart_off = L.chunktotal_off + align256((size_t)L.nchunks * sizeof(uint32_t));
   L.rec_off = L.binstart_off + align256(((size_t)L.nbins + 1) * sizeof(uint32_t));
   L.answers_off = L.rec_off + align256((size_t)(L.possible ? d * cap : 0) * 8);
   L.total = L.answers_off + align256((size_t)L.nchunks * kBinChunk * d * 8);
@@ -498,8 +500,6 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(E.nbins, kWave), count), dim3(kBinBlock), 0, st, E);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_start_kernel, dim3(1, count), dim3(kBinBlock), 0, st, E);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
     const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * E.nbins;
     launch_bin_scatter(E, hp, dim3(L.chunk_grid, count), scatter_lds, st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
@@ -597,6 +597,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   const SliceLayout SL = slice_layout(nbits, d, w, sort_items);
   E.hist_off = SL.hist_off;
   E.slicepre_off = SL.slicepre_off;
+  E.chunktotal_off = SL.chunktotal_off;
   E.binstart_off = SL.binstart_off;
   E.rec_off = SL.rec_off;
   E.nbins = SL.nbins;
@@ -802,6 +803,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.prefix_off = workspace_prefix_off(n);
     B.dense_off = workspace_dense_off(n);
     B.hist_off = L.hist_off;
+    B.chunktotal_off = L.chunktotal_off;
     B.binstart_off = L.binstart_off;
     B.rec_off = L.rec_off;
     B.slicepre_off = L.slicepre_off;
@@ -845,8 +847,6 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     launch_bin_hist(B, hp, dim3(chunk_grid, 1), st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(L.nbins, kWave), 1), dim3(kBinBlock), 0, st, B);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_start_kernel, dim3(1, 1), dim3(kBinBlock), 0, st, B);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * B.nbins;
     launch_bin_scatter(B, hp, dim3(chunk_grid, 1), scatter_lds, st);

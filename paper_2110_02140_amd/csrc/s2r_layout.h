@@ -61,7 +61,8 @@ struct EncodeBatch {
   uint64_t dense_off;        // byte offset of the dense-tile list (count, then entries 256 bytes later)
   uint64_t hist_off;         // slice variant: byte offsets inside a chunk of the per-chunk bin histogram
   uint64_t slicepre_off;     //   [nchunks][nbins] u32, of each chunk's exclusive prefix of that histogram over the
-  uint64_t binstart_off;     //   slices of a row (same shape), of the bin starts [nbins + 1] u32,
+  uint64_t chunktotal_off;   //   slices of a row (same shape), of the chunks' item counts [nchunks] u32,
+  uint64_t binstart_off;     //   of the bin starts [nbins + 1] u32,
   uint64_t rec_off;          //   and of the binned records [d * cap] of 8 bytes
   uint64_t place_off;        // decode by slices: [nchunks][nbins] u32, what a query's rank in its bin is added to
                              //   to get the place of its answer; 0 when not wanted
@@ -97,6 +98,9 @@ __device__ __forceinline__ uint32_t* ws_bin_hist(const EncodeBatch& B, uint32_t 
 }
 __device__ __forceinline__ uint32_t* ws_slice_pre(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.slicepre_off);
+}
+__device__ __forceinline__ uint32_t* ws_chunk_total(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.chunktotal_off);
 }
 __device__ __forceinline__ uint32_t* ws_bin_start(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.binstart_off);

@@ -20,7 +20,7 @@ namespace s2r {
 // over the listed items brings each bin's records together:
 //   bin_hist_kernel     per chunk of kBinChunk items, a histogram over the bins and, row by
 //                       row, its exclusive prefix over the row's slices
-//   bin_colscan_kernel, bin_start_kernel   offsets of every (chunk, bin) run and of every bin
+//   bin_colscan_kernel  offsets of every (chunk, bin) run and of every bin
 //   bin_scatter_kernel  writes each record (cell in the slice | sign bit, value)
 //                       into its run (order inside a run is arbitrary)
 //   sketch_slice_kernel workgroup (j, s) clears its slice in LDS, adds its bin's
@@ -87,8 +87,9 @@ __device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs
 // the outer loop: a row's hash parameters are fetched once (they are uniform) for the eight items of a thread.
 template <int MODE>
 __device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows& hp, uint32_t k, uint32_t chunk,
-                                           uint64_t have, uint32_t* s_hist) {
+                                           uint64_t have, uint32_t* s_hist, uint32_t* s_total) {
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) s_hist[b] = 0u;
+  if (threadIdx.x == 0) *s_total = 0u;
   const WorkerPtrs P = B.w[k];
   const uint32_t spr_log2 = B.log2w - B.slice_log2;
   uint32_t i[kBinItems];
@@ -101,6 +102,12 @@ __device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows&
     if (t < have && load_item<MODE>(B, P, t, i[u], v)) ok |= 1u << u;
   }
   __syncthreads();                                        // s_hist is zero
+  {                                                       // the chunk's items that take part (the same in every row)
+    uint32_t mine = __popc(ok);
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) mine += __shfl_xor(mine, m, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) __hip_atomic_fetch_add(s_total, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
   for (uint32_t j = 0; j < B.d; ++j) {
     const uint64_t a = hp.a[j], b = hp.b[j];
     uint32_t* row = s_hist + (j << spr_log2);
@@ -114,6 +121,7 @@ __device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows&
   __syncthreads();
   uint32_t* hist = ws_bin_hist(B, k) + (uint64_t)chunk * B.nbins;
   for (uint32_t b = threadIdx.x; b < B.nbins; b += kBinBlock) hist[b] = s_hist[b];
+  if (threadIdx.x == 0) ws_chunk_total(B, k)[chunk] = *s_total;
   // row by row, the exclusive prefix of the chunk's counts over the row's slices: where, among the chunk's
   // records of that row sorted by slice, each slice's run starts.  Wave wv takes the rows wv, wv + 16, ...
   // 64 slices at a time.
@@ -139,31 +147,36 @@ __device__ __forceinline__ void hist_chunk(const EncodeBatch& B, const HashRows&
 template <int MODE>
 __global__ __launch_bounds__(kBinBlock) void bin_hist_kernel(const EncodeBatch B, const HashRows hp) {
   __shared__ uint32_t s_hist[kMaxBins];
+  __shared__ uint32_t s_total;
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;                           // uniform over the workgroup
   const uint64_t have = listed_items(B, k);
   uint32_t chunk = blockIdx.x;
   if ((uint64_t)chunk * kBinChunk >= have) return;       // uniform over the workgroup
-  hist_chunk<MODE>(B, hp, k, chunk, have, s_hist);
+  hist_chunk<MODE>(B, hp, k, chunk, have, s_hist, &s_total);
   for (chunk += gridDim.x; (uint64_t)chunk * kBinChunk < have; chunk += gridDim.x) {      // uniform
-    __syncthreads();                                     // s_hist is rewritten
-    hist_chunk<MODE>(B, hp, k, chunk, have, s_hist);
+    __syncthreads();                                     // s_hist and s_total are rewritten
+    hist_chunk<MODE>(B, hp, k, chunk, have, s_hist, &s_total);
   }
 }
 
-// Offsets of the counting sort, two kernels.
+// Offsets of the counting sort.
 // bin_colscan_kernel: workgroup = 64 adjacent bins of one worker (lane = bin, so a
 // chunk's counters are read as one 256-byte row); its 16 waves split the chunks
 // into 16 consecutive ranges.  In place, hist[c][b] becomes the number of records
 // of bin b in chunks before c: every wave sums its range, the waves' sums are
 // exchanged through LDS, then every wave walks its range again with its running
-// offset.  The bin's total goes to bin_start[b].
-// bin_start_kernel: one workgroup per worker turns the totals in bin_start[0..nbins)
-// into the number of records in bins before b (bin_start[nbins] = all records).
+// offset.  Where bin b = (row j, slice s) starts among the worker's records needs no
+// scan over the bins and so no kernel of its own: it is the records of the rows
+// before j, j times the items that take part (the sum of the chunks' totals), plus
+// the records of row j's earlier slices, the sum over the chunks of the slice prefix
+// at (chunk, b): two more column sums of the same walk.  bin_start[nbins] = all records.
 __global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatch B) {
   constexpr int kWaves = kBinBlock / kWave;              // 16
   constexpr uint32_t kAhead = 8;                         // counters in flight per thread
   __shared__ uint32_t s_part[kWaves][kWave];
+  __shared__ uint32_t s_before[kWaves][kWave];
+  __shared__ uint32_t s_items[kWaves];
   const uint32_t k = B.first_worker + blockIdx.y;
   if (k >= B.nworkers) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -171,34 +184,45 @@ __global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatc
   const uint32_t b = blockIdx.x * kWave + lane;
   const bool live = b < B.nbins;
   uint32_t* hist = ws_bin_hist(B, k);
+  const uint32_t* spre = ws_slice_pre(B, k);
   // the chunks that hold listed items (the others' rows were not written)
   const uint64_t filled = (listed_items(B, k) + kBinChunk - 1) / kBinChunk;
   const uint32_t nchunks = filled < B.nchunks ? (uint32_t)filled : B.nchunks;
   const uint32_t per = (nchunks + kWaves - 1) / kWaves;
   const uint32_t c_begin = wv * per < nchunks ? wv * per : nchunks;
   const uint32_t c_end = c_begin + per < nchunks ? c_begin + per : nchunks;
-  uint32_t sum = 0;
+  uint32_t sum = 0, before = 0;
   for (uint32_t c0 = c_begin; c0 < c_end; c0 += kAhead) {
-    uint32_t v[kAhead];
+    uint32_t v[kAhead], p[kAhead];
 #pragma unroll
-    for (uint32_t q = 0; q < kAhead; ++q) v[q] = (live && c0 + q < c_end) ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+    for (uint32_t q = 0; q < kAhead; ++q) {
+      const bool in = live && c0 + q < c_end;
+      v[q] = in ? hist[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+      p[q] = in ? spre[(uint64_t)(c0 + q) * B.nbins + b] : 0u;
+    }
 #pragma unroll
-    for (uint32_t q = 0; q < kAhead; ++q) sum += v[q];
+    for (uint32_t q = 0; q < kAhead; ++q) { sum += v[q]; before += p[q]; }
   }
+  uint32_t items = 0;                                     // the items of this wave's chunks that take part
+  for (uint32_t c = c_begin + lane; c < c_end; c += kWave) items += ws_chunk_total(B, k)[c];
+#pragma unroll
+  for (int m = kWave / 2; m >= 1; m >>= 1) items += __shfl_xor(items, m, kWave);
   s_part[wv][lane] = sum;
+  s_before[wv][lane] = before;
+  if (lane == 0) s_items[wv] = items;
   __syncthreads();
-  uint32_t run = 0, total = 0;
+  uint32_t run = 0, earlier_slices = 0, all_items = 0;
 #pragma unroll
   for (int q = 0; q < kWaves; ++q) {
     const uint32_t x = s_part[q][lane];
     if ((uint32_t)q < wv) run += x;
-    total += x;
+    earlier_slices += s_before[q][lane];
+    all_items += s_items[q];
   }
   // decode: what decode_slice_kernel adds to a query's rank in its bin to get the place of its answer: the
   // start of chunk c's answers, plus the chunk's queries in the rows before the bin's row j (every item of a
   // chunk has a query in every row) and in the row's earlier slices, minus the bin's queries in earlier
   // chunks (modulo 2^32; the places themselves are below 2^32)
-  const uint32_t* spre = ws_slice_pre(B, k);
   uint32_t* place = B.place_off != 0 ? reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.place_off) : nullptr;
   const uint64_t have = listed_items(B, k);
   const uint32_t j = b >> (B.log2w - B.slice_log2);
@@ -223,45 +247,8 @@ __global__ __launch_bounds__(kBinBlock) void bin_colscan_kernel(const EncodeBatc
       run += v[q];
     }
   }
-  if (wv == 0 && live) ws_bin_start(B, k)[b] = total;
-}
-
-__global__ __launch_bounds__(kBinBlock) void bin_start_kernel(const EncodeBatch B) {
-  constexpr int kWaves = kBinBlock / kWave;
-  constexpr int kMaxPer = kMaxBins / kBinBlock;           // 8
-  __shared__ uint32_t s_wave[kWaves];
-  const uint32_t k = B.first_worker + blockIdx.y;
-  if (k >= B.nworkers) return;
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wv = threadIdx.x / kWave;
-  uint32_t* bin_start = ws_bin_start(B, k);
-  const uint32_t per = (B.nbins + kBinBlock - 1) / kBinBlock;   // thread t owns bins t*per .. t*per + per - 1
-  uint32_t c[kMaxPer], sum = 0;
-#pragma unroll
-  for (int q = 0; q < kMaxPer; ++q) {
-    const uint32_t e = threadIdx.x * per + q;
-    c[q] = ((uint32_t)q < per && e < B.nbins) ? bin_start[e] : 0u;
-    sum += c[q];
-  }
-  const uint32_t incl = wave_inclusive_scan_u32(sum, lane);
-  if (lane == kWave - 1) s_wave[wv] = incl;
-  __syncthreads();
-  uint32_t run = incl - sum, all = 0;
-#pragma unroll
-  for (int q = 0; q < kWaves; ++q) {
-    const uint32_t x = s_wave[q];
-    if ((uint32_t)q < wv) run += x;
-    all += x;
-  }
-#pragma unroll
-  for (int q = 0; q < kMaxPer; ++q) {
-    const uint32_t e = threadIdx.x * per + q;
-    if ((uint32_t)q < per && e < B.nbins) {
-      bin_start[e] = run;
-      run += c[q];
-    }
-  }
-  if (threadIdx.x == 0) bin_start[B.nbins] = all;
+  if (wv == 0 && live) ws_bin_start(B, k)[b] = j * all_items + earlier_slices;
+  if (blockIdx.x == 0 && threadIdx.x == 0) ws_bin_start(B, k)[B.nbins] = B.d * all_items;
 }
 
 // One workgroup per chunk of kBinChunk list items, one pass per sketch row j.  The
