@@ -313,26 +313,25 @@ __global__ __launch_bounds__(kBlock) void decode_rows_median_kernel(const float*
 
 // ------------------------------------------------------------------ decode by sketch slices
 // The bucket reads of decode_kernel each fetch a 128-byte line for 4 useful
-// bytes.  When the union list is long, s2r_decode instead partitions the
-// (list position, row) queries by sketch slice with the kernels of the encode's
-// slice strategy (records carry the list position instead of a value) and
+// bytes.  When the union list is long, s2r_decode instead sorts the (list
+// position, row) queries of every chunk of kBinChunk list positions by sketch
+// slice with the kernel of the encode's slice strategy (bin_sort_kernel; a record
+// carries the list position instead of a value) and
 //   decode_slice_kernel   workgroup (j, s) loads slice s of row j into LDS with
-//                         coalesced loads, answers its bin's queries from LDS
-//                         and writes (estimate, position in chunk) into the
-//                         region of the query's chunk of kBinChunk list
-//                         positions: row j's answers of chunk c start at
-//                         (c * kBinChunk * d) + j * (items in c), and inside
-//                         them bin (j, s) starts where the prefix of the
-//                         chunk's histogram over the bins says
+//                         coalesced loads and answers its bin's queries, chunk by
+//                         chunk: the answer to the query at record r of a chunk's
+//                         region is (estimate, position in chunk) at the same place r
+//                         of the answers.  Every item of a chunk has a query in
+//                         every row, so row j's answers of chunk c are the count(c)
+//                         entries that start at c * kBinChunk * d + j * count(c)
 //   decode_median_kernel  workgroup = chunk: row by row, the answers go through
 //                         LDS into the registers of the thread that owns the
 //                         list position; then the medians, stored coalesced
 struct DecodeSliceArgs {
   const float* sketch;
-  const u32x2* rec;          // queries sorted by bin: (cell in slice | sign bit, list position)
-  uint2* answers;            // [nchunks][d][kBinChunk]-shaped regions, see above
-  const uint32_t* bin_start; // [nbins + 1]
-  const uint32_t* place;     // [nchunks][nbins]: rank in the bin + this = place of the answer (bin_colscan_kernel)
+  const u32x2* rec;          // queries, chunk by chunk, sorted by bin: (cell in slice | sign bit, list position)
+  uint2* answers;            // same shape as rec
+  const uint32_t* seg;       // [nchunks][nbins + 1]: the bins' segments in a chunk's region
   const uint64_t* count;     // the union count (device)
   uint64_t cap;
   float* val_out;
@@ -344,26 +343,56 @@ struct DecodeSliceArgs {
   const uint32_t* blk_list;
 };
 
-constexpr int kBinChunkLog2 = 13;
-static_assert((1 << kBinChunkLog2) == kBinChunk, "list positions are split into chunk and offset by shifts");
-
+// The bin's chunks are shared out between the gridDim.y workgroups of the bin (each loads the slice), a
+// workgroup's chunks between its waves, a wave's chunks between groups of its lanes (seg_lanes), eight
+// chunks or fewer to a pass; the first pass's queries are asked for before the slice is loaded, a pass's
+// segment places during the pass before.
 __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeSliceArgs A) {
   extern __shared__ float s_cells[];
-  constexpr int kAhead = 4;
+  constexpr int kWaves = kSliceBlock / kWave;
+  constexpr int kAhead = 8;
+  constexpr int kSets = 4;
   const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
-  const uint32_t first = A.bin_start[bin], bin_last = A.bin_start[bin + 1];
-  // the bin's queries are shared out between the gridDim.y workgroups of the bin (each loads the slice):
-  // consecutive ranges of a multiple of kSliceBlock queries
-  const uint64_t share = ((((uint64_t)bin_last - first + gridDim.y - 1) / gridDim.y + kSliceBlock - 1) / kSliceBlock) * kSliceBlock;
-  const uint64_t mine = (uint64_t)first + blockIdx.y * share;
-  if (mine >= bin_last) return;                           // uniform over the workgroup (also: an empty bin)
-  const uint64_t last = mine + share < bin_last ? mine + share : bin_last;
-  const u32x2 none = {0u, 0u};
-  u32x2 x[kAhead];                                        // the first queries are requested together with the slice
-  uint64_t r0 = mine + threadIdx.x;
+  const uint64_t total = *A.count;
+  const uint64_t listed = total < A.cap ? total : A.cap;
+  const uint64_t have = A.block != 0 ? listed * A.block : listed;
+  const uint32_t nchunks = (uint32_t)((have + kBinChunk - 1) / kBinChunk);
+  const uint32_t share = (nchunks + gridDim.y - 1) / gridDim.y;
+  const uint32_t c_begin = blockIdx.y * share;
+  if (c_begin >= nchunks) return;                         // uniform over the workgroup
+  const uint32_t c_end = c_begin + share < nchunks ? c_begin + share : nchunks;
+  const uint64_t stride = (uint64_t)kBinChunk * A.d;
+  const uint32_t row_len = A.nbins + 1;                   // of the segment table
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  // the workgroup's chunks are shared out between its waves in consecutive ranges
+  const uint32_t cpw = (c_end - c_begin + kWaves - 1) / kWaves;
+  const uint32_t w_begin = c_begin + wv * cpw < c_end ? c_begin + wv * cpw : c_end;
+  const uint32_t w_end = w_begin + cpw < c_end ? w_begin + cpw : c_end;
+  // a group's lanes: about a quarter of a full chunk's queries per bin, so that a pass has most segments
+  // in flight whole (kAhead times as many queries)
+  const uint32_t quarter = (uint32_t)kBinChunk * A.d / A.nbins / 4u;
+  uint32_t min_width = 8u;
+  while (min_width < quarter && min_width < (uint32_t)kWave) min_width <<= 1;
+  const SegLanes sl = seg_lanes(cpw, lane, min_width);
+  // a pass: kSets * groups chunks, the lane's are chunks cb + g + t * groups (t < kSets)
+  auto places = [&](uint32_t cb, uint32_t (&f)[kSets], uint32_t (&l)[kSets]) {
 #pragma unroll
-  for (int u = 0; u < kAhead; ++u)
-    x[u] = r0 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r0 + u * kSliceBlock]) : none;
+    for (int t = 0; t < kSets; ++t) {
+      const uint32_t c = cb + sl.g + t * sl.groups;
+      f[t] = l[t] = 0u;
+      if (c < w_end) {
+        f[t] = A.seg[(uint64_t)c * row_len + bin];
+        l[t] = A.seg[(uint64_t)c * row_len + bin + 1];
+      }
+    }
+  };
+  auto fetch = [&](uint32_t cb, const uint32_t (&f)[kSets], const uint32_t (&l)[kSets], u32x2 (&x)[kSets][kAhead]) {
+#pragma unroll
+    for (int t = 0; t < kSets; ++t) seg_fetch<true, kAhead>(A.rec + (uint64_t)(cb + sl.g + t * sl.groups) * stride, f[t], l[t], sl, x[t]);
+  };
+  uint32_t cb = w_begin, f[kSets], l[kSets];
+  places(cb, f, l);
   const uint32_t cells = 1u << A.slice_log2;
   const float* src = A.sketch + (uint64_t)bin * cells;    // row-major sketch: slice s of row j starts at bin * cells
   if (cells >= 4u * kSliceBlock) {                        // (the sketch and every slice of 4 cells or more are 16-byte aligned)
@@ -372,30 +401,37 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   } else {
     for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_cells[c] = src[c];
   }
+  u32x2 x[kSets][kAhead];
+  fetch(cb, f, l, x);
   __syncthreads();
-  while (r0 < last) {                                     // x holds the queries r0 + u * kSliceBlock
-    const uint64_t r1 = r0 + kSliceBlock * kAhead;
-    u32x2 y[kAhead];
-    uint32_t place[kAhead];
+  auto put = [&](uint2* to, const u32x2 q) {              // the answer goes where the query is
+    const uint32_t est = __float_as_uint(s_cells[q.x & 0x7FFFFFFFu]) ^ (q.x & 0x80000000u);
+    *to = make_uint2(est, q.y & (kBinChunk - 1));
+  };
+  while (true) {                                          // uniform over the wave
+    const uint32_t nb = cb + kSets * sl.groups;
+    uint32_t fn[kSets], ln[kSets];
+    if (nb < w_end) places(nb, fn, ln);
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u)
-      y[u] = r1 + u * kSliceBlock < last ? __builtin_nontemporal_load(&A.rec[r1 + u * kSliceBlock]) : none;
+    for (int t = 0; t < kSets; ++t) {
+      const uint64_t region = (uint64_t)(cb + sl.g + t * sl.groups) * stride;
+      const uint32_t start = seg_start(f[t], sl);
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u) {
-      const uint64_t at = (uint64_t)(x[u].y >> kBinChunkLog2) * A.nbins + bin;
-      place[u] = r0 + u * kSliceBlock < last ? A.place[at] : 0u;
+      for (int u = 0; u < kAhead; ++u) {
+        const uint32_t i = start + u * sl.width;
+        if (i >= f[t] && i < l[t]) put(A.answers + region + i, x[t][u]);
+      }
+      for (uint32_t i = start + kAhead * sl.width; i < l[t]; i += sl.width)      // the rest of a longer segment
+        put(A.answers + region + i, __builtin_nontemporal_load(A.rec + region + i));
     }
+    if (nb >= w_end) break;
+    cb = nb;
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u) {
-      const uint64_t r = r0 + u * kSliceBlock;
-      if (r >= last) continue;
-      const uint32_t est = __float_as_uint(s_cells[x[u].x & 0x7FFFFFFFu]) ^ (x[u].x & 0x80000000u);
-      const uint32_t at = (uint32_t)(r - first) + place[u];          // modulo 2^32, see bin_colscan_kernel
-      A.answers[at] = make_uint2(est, x[u].y & (kBinChunk - 1));
+    for (int t = 0; t < kSets; ++t) {
+      f[t] = fn[t];
+      l[t] = ln[t];
     }
-#pragma unroll
-    for (int u = 0; u < kAhead; ++u) x[u] = y[u];
-    r0 = r1;
+    fetch(cb, f, l, x);
   }
 }
 

@@ -24,10 +24,8 @@
 //                                      and gathers the values at the set bits; tiles
 //                                      with more than kGroupSlots set bits get
 //                                      extra workgroups through a dense-tile list
-//                bin_hist_kernel,      (slice variant) Sparse(g) x rows is partitioned by
-//                bin_colscan_kernel,   sketch slice (counting sort: histogram per chunk,
-//                bin_scatter_kernel    offsets, scatter of (cell, signed value) records
-//                                      sorted by slice inside LDS first)
+//                bin_sort_kernel       (slice variant) Sparse(g) x rows, chunk by chunk, sorted by
+//                                      sketch slice inside LDS into (cell, signed value) records
 //                sketch_slice_kernel   (slice variant) every workgroup owns a slice of
 //                                      one sketch row in LDS, adds the records of its
 //                                      bin and stores the slice: no global atomics, no
@@ -129,7 +127,7 @@ static inline uint32_t dense_grid(uint32_t ntiles, uint64_t positions, uint32_t 
 struct SliceLayout {
   bool possible;             // the bins fit the LDS histograms and record positions fit 32 bits
   uint32_t slice_log2, nbins, nchunks;
-  size_t hist_off, slicepre_off, chunktotal_off, binstart_off, rec_off, total;
+  size_t seg_off, rec_off, total;
 };
 static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   SliceLayout L;
@@ -139,12 +137,10 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
   L.possible = nbins <= (uint64_t)kMaxBins && (uint64_t)d * cap < (1ull << 32) && cap > 0;
   L.nbins = (uint32_t)(L.possible ? nbins : 0);
   L.nchunks = (uint32_t)(L.possible ? ceil_div(cap, kBinChunk) : 0);
-  const size_t matrix = align256((size_t)L.nchunks * L.nbins * sizeof(uint32_t));
-  L.hist_off = workspace_base(n);
-  L.slicepre_off = L.hist_off + matrix;
-  L.chunktotal_off = L.slicepre_off + matrix;
-  L.binstart_off = L.chunktotal_off + align256((size_t)L.nchunks * sizeof(uint32_t));
-  L.rec_off = L.binstart_off + align256(((size_t)L.nbins + 1) * sizeof(uint32_t));
+  // the segment offsets u32[nchunks][nbins + 1], then the records: a chunk's region holds kBinChunk * d of them
+  // (the last chunk's, d * what is left of cap)
+  L.seg_off = workspace_base(n);
+  L.rec_off = L.seg_off + align256((size_t)L.nchunks * ((size_t)L.nbins + 1) * sizeof(uint32_t));
   L.total = L.rec_off + align256((size_t)(L.possible ? d * cap : 0) * 8);
   return L;
 }
@@ -194,14 +190,13 @@ static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, b
 }
 
 // Workspace of s2r_decode when it partitions its queries by sketch slice: the base parts, then
-// [bin histogram u32[nchunks][nbins]] [its per-chunk, per-row prefix over the slices, same shape]
-// [the places' offsets, same shape] [bin starts u32[nbins + 1]]
-// [queries sorted by bin, 8 B x d*cap] [answers grouped by chunk, 8 B x d * nchunks * kBinChunk].
+// [segment offsets u32[nchunks][nbins + 1]] [queries, chunk by chunk, sorted by bin, 8 B x d * nchunks * kBinChunk]
+// [answers, same shape].
 constexpr int kDecodeSliceMaxRows = 8;                   // decode_median_kernel keeps 8 x d estimates per thread
 struct DecodeLayout {
   bool possible;
   uint32_t slice_log2, nbins, nchunks;
-  size_t hist_off, slicepre_off, place_off, chunktotal_off, binstart_off, rec_off, answers_off, total;
+  size_t seg_off, rec_off, answers_off, total;
 };
 static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap) {
   DecodeLayout L;
@@ -212,14 +207,9 @@ static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t c
                d <= (uint32_t)kDecodeSliceMaxRows;                 // (places of answers are 32-bit)
   L.nbins = (uint32_t)(L.possible ? nbins : 0);
   L.nchunks = (uint32_t)(L.possible ? ceil_div(cap, kBinChunk) : 0);
-  const size_t matrix = align256((size_t)L.nchunks * L.nbins * sizeof(uint32_t));
-  L.hist_off = workspace_base(n);
-  L.slicepre_off = L.hist_off + matrix;
-  L.place_off = L.slicepre_off + matrix;
-  L.chunktotal_off = L.place_off + matrix;
-  L.binstart_off = L.chunktotal_off + align256((size_t)L.nchunks * sizeof(uint32_t));
-  L.rec_off = L.binstart_off + align256(((size_t)L.nbins + 1) * sizeof(uint32_t));
-  L.answers_off = L.rec_off + align256((size_t)(L.possible ? d * cap : 0) * 8);
+  L.seg_off = workspace_base(n);
+  L.rec_off = L.seg_off + align256((size_t)L.nchunks * ((size_t)L.nbins + 1) * sizeof(uint32_t));
+  L.answers_off = L.rec_off + align256((size_t)L.nchunks * kBinChunk * d * 8);
   L.total = L.answers_off + align256((size_t)L.nchunks * kBinChunk * d * 8);
   return L;
 }
@@ -275,7 +265,7 @@ static int32_t choose_decode(uint64_t n, uint32_t d, uint32_t w, bool have_lists
 // loaded kernel, raised once per device (asking again is harmless).
 static bool raise_scatter_lds(const void* kernel) {
   return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)(kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * kMaxBins)) == hipSuccess;
+                             (int)(kBinChunk * sizeof(uint2) + sizeof(uint32_t) * kMaxBins)) == hipSuccess;
 }
 static bool raise_slice_lds(const void* kernel) {
   return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSliceLdsMax) == hipSuccess;
@@ -290,10 +280,10 @@ static bool raise_lds_limits() {
       !raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<true, false>)) ||
       !raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<false, true>)) ||
       !raise_slice_lds(reinterpret_cast<const void*>(sketch_slice_kernel<false, false>)) ||
-      !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<0>)) ||
-      !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<1>)) ||
-      !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<2>)) ||
-      !raise_scatter_lds(reinterpret_cast<const void*>(bin_scatter_kernel<3>)) ||
+      !raise_scatter_lds(reinterpret_cast<const void*>(bin_sort_kernel<0>)) ||
+      !raise_scatter_lds(reinterpret_cast<const void*>(bin_sort_kernel<1>)) ||
+      !raise_scatter_lds(reinterpret_cast<const void*>(bin_sort_kernel<2>)) ||
+      !raise_scatter_lds(reinterpret_cast<const void*>(bin_sort_kernel<3>)) ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(decode_slice_kernel),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) << kDecodeSliceLog2Max)) != hipSuccess)
     return false;
@@ -407,21 +397,14 @@ s2r_status s2r_probe_read(const void* src, size_t bytes, uint64_t* sink, void* s
 // block = 0: the element codec (bitmaps of n bits, lists of non-zero elements with their values).
 // block >= 1: the block-granular codec (bitmaps of ceil(n / block) bits, lists of non-zero blocks, nz_val
 // unused, cap counted in blocks).
-// The counting sort's two kernels that read the items, in the variant for what the items are.
-static void launch_bin_hist(const EncodeBatch& E, const HashRows& hp, dim3 grid, hipStream_t st) {
+// The chunk-local counting sort, in the variant for what the items are.
+static void launch_bin_sort(const EncodeBatch& E, const HashRows& hp, dim3 grid, hipStream_t st) {
+  const size_t lds = (size_t)kBinChunk * sizeof(uint2) + sizeof(uint32_t) * E.nbins;
   switch (items_mode(E)) {
-    case 0: hipLaunchKernelGGL(bin_hist_kernel<0>, grid, dim3(kBinBlock), 0, st, E, hp); break;
-    case 1: hipLaunchKernelGGL(bin_hist_kernel<1>, grid, dim3(kBinBlock), 0, st, E, hp); break;
-    case 2: hipLaunchKernelGGL(bin_hist_kernel<2>, grid, dim3(kBinBlock), 0, st, E, hp); break;
-    default: hipLaunchKernelGGL(bin_hist_kernel<3>, grid, dim3(kBinBlock), 0, st, E, hp); break;
-  }
-}
-static void launch_bin_scatter(const EncodeBatch& E, const HashRows& hp, dim3 grid, size_t lds, hipStream_t st) {
-  switch (items_mode(E)) {
-    case 0: hipLaunchKernelGGL(bin_scatter_kernel<0>, grid, dim3(kBinBlock), lds, st, E, hp); break;
-    case 1: hipLaunchKernelGGL(bin_scatter_kernel<1>, grid, dim3(kBinBlock), lds, st, E, hp); break;
-    case 2: hipLaunchKernelGGL(bin_scatter_kernel<2>, grid, dim3(kBinBlock), lds, st, E, hp); break;
-    default: hipLaunchKernelGGL(bin_scatter_kernel<3>, grid, dim3(kBinBlock), lds, st, E, hp); break;
+    case 0: hipLaunchKernelGGL(bin_sort_kernel<0>, grid, dim3(kBinBlock), lds, st, E, hp); break;
+    case 1: hipLaunchKernelGGL(bin_sort_kernel<1>, grid, dim3(kBinBlock), lds, st, E, hp); break;
+    case 2: hipLaunchKernelGGL(bin_sort_kernel<2>, grid, dim3(kBinBlock), lds, st, E, hp); break;
+    default: hipLaunchKernelGGL(bin_sort_kernel<3>, grid, dim3(kBinBlock), lds, st, E, hp); break;
   }
 }
 
@@ -496,12 +479,7 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
 
   if (L.strategy == S2R_INSERT_SLICE) {
     const size_t lds = sizeof(double) << E.slice_log2;
-    launch_bin_hist(E, hp, dim3(L.chunk_grid, count), st);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(E.nbins, kWave), count), dim3(kBinBlock), 0, st, E);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * E.nbins;
-    launch_bin_scatter(E, hp, dim3(L.chunk_grid, count), scatter_lds, st);
+    launch_bin_sort(E, hp, dim3(L.chunk_grid, count), st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, false, st);
     // about one workgroup per compute unit, each walking `per` consecutive bins of one worker
@@ -586,7 +564,6 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   L.expect_items = expect;
 
   E.nworkers = W;
-  E.place_off = 0;
   E.payload_slot = 0;
   E.nnz_out = nnz_out;
   E.workspace = reinterpret_cast<char*>(workspace);
@@ -595,10 +572,7 @@ static s2r_status encode_workers(const float* const* grads, uint32_t W, uint64_t
   E.prefix_off = workspace_prefix_off(nbits);
   E.dense_off = workspace_dense_off(nbits);
   const SliceLayout SL = slice_layout(nbits, d, w, sort_items);
-  E.hist_off = SL.hist_off;
-  E.slicepre_off = SL.slicepre_off;
-  E.chunktotal_off = SL.chunktotal_off;
-  E.binstart_off = SL.binstart_off;
+  E.seg_off = SL.seg_off;
   E.rec_off = SL.rec_off;
   E.nbins = SL.nbins;
   E.nchunks = SL.nchunks;
@@ -802,12 +776,8 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.ws_stride = 0;
     B.prefix_off = workspace_prefix_off(n);
     B.dense_off = workspace_dense_off(n);
-    B.hist_off = L.hist_off;
-    B.chunktotal_off = L.chunktotal_off;
-    B.binstart_off = L.binstart_off;
+    B.seg_off = L.seg_off;
     B.rec_off = L.rec_off;
-    B.slicepre_off = L.slicepre_off;
-    B.place_off = L.place_off;
     B.payload_slot = 1;
     B.block = block;
     B.n = elements;
@@ -827,8 +797,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     Q.sketch = sketch;
     Q.rec = reinterpret_cast<const u32x2*>(ws + L.rec_off);
     Q.answers = reinterpret_cast<uint2*>(ws + L.answers_off);
-    Q.bin_start = reinterpret_cast<const uint32_t*>(ws + L.binstart_off);
-    Q.place = reinterpret_cast<const uint32_t*>(ws + L.place_off);
+    Q.seg = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
     Q.count = count_out;
     Q.cap = cap;
     Q.val_out = val_out;
@@ -844,12 +813,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     hipLaunchKernelGGL(encode_compact_kernel<false>, dim3(helpers + ntiles, 1), dim3(kBlock), 0, st, B, helpers);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     const uint32_t chunk_grid = (uint32_t)ceil_div(expect > 0 ? expect : 1, kBinChunk);   // (the chunk kernels loop)
-    launch_bin_hist(B, hp, dim3(chunk_grid, 1), st);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    hipLaunchKernelGGL(bin_colscan_kernel, dim3((uint32_t)ceil_div(L.nbins, kWave), 1), dim3(kBinBlock), 0, st, B);
-    if (!launch_ok()) return S2R_ERR_LAUNCH;
-    const size_t scatter_lds = (size_t)kBinChunk * sizeof(uint2) + 2 * sizeof(uint32_t) * B.nbins;
-    launch_bin_scatter(B, hp, dim3(chunk_grid, 1), scatter_lds, st);
+    launch_bin_sort(B, hp, dim3(chunk_grid, 1), st);
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     // one workgroup per compute unit at a time (the slice fills its LDS): with few bins, several workgroups
     // share a bin's queries so that the last round of workgroups is not mostly idle units
@@ -902,7 +866,7 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     B.ws_stride = 0;
     B.prefix_off = workspace_prefix_off(n);
     B.dense_off = workspace_dense_off(n);
-    B.place_off = 0;
+
     B.payload_slot = 0;
     B.block = block;
     B.n = elements;

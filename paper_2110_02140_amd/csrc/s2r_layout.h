@@ -59,13 +59,8 @@ struct EncodeBatch {
   uint64_t ws_stride;
   uint64_t prefix_off;       // byte offset of the tile prefix inside a chunk
   uint64_t dense_off;        // byte offset of the dense-tile list (count, then entries 256 bytes later)
-  uint64_t hist_off;         // slice variant: byte offsets inside a chunk of the per-chunk bin histogram
-  uint64_t slicepre_off;     //   [nchunks][nbins] u32, of each chunk's exclusive prefix of that histogram over the
-  uint64_t chunktotal_off;   //   slices of a row (same shape), of the chunks' item counts [nchunks] u32,
-  uint64_t binstart_off;     //   of the bin starts [nbins + 1] u32,
-  uint64_t rec_off;          //   and of the binned records [d * cap] of 8 bytes
-  uint64_t place_off;        // decode by slices: [nchunks][nbins] u32, what a query's rank in its bin is added to
-                             //   to get the place of its answer; 0 when not wanted
+  uint64_t seg_off;          // slice variant: byte offsets inside a chunk of the segment offsets u32[nchunks][nbins + 1]
+  uint64_t rec_off;          //   and of the sorted records, 8 bytes each, kBinChunk * d per chunk of list items
   uint32_t payload_slot;     // non-zero: a record carries its item's list position instead of nz_val
   uint32_t block;            // block-granular codec: elements per bitmap bit; nz_idx then lists blocks, and
                              //   bitmap / nwords / ntiles / cap describe the block bitmap.  0: one bit per element
@@ -93,17 +88,8 @@ __device__ __forceinline__ uint64_t* ws_prefix(const EncodeBatch& B, uint32_t k)
 __device__ __forceinline__ const uint32_t* ws_dense_list(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<const uint32_t*>(B.workspace + k * B.ws_stride + B.dense_off);
 }
-__device__ __forceinline__ uint32_t* ws_bin_hist(const EncodeBatch& B, uint32_t k) {
-  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.hist_off);
-}
-__device__ __forceinline__ uint32_t* ws_slice_pre(const EncodeBatch& B, uint32_t k) {
-  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.slicepre_off);
-}
-__device__ __forceinline__ uint32_t* ws_chunk_total(const EncodeBatch& B, uint32_t k) {
-  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.chunktotal_off);
-}
-__device__ __forceinline__ uint32_t* ws_bin_start(const EncodeBatch& B, uint32_t k) {
-  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.binstart_off);
+__device__ __forceinline__ uint32_t* ws_seg(const EncodeBatch& B, uint32_t k) {
+  return reinterpret_cast<uint32_t*>(B.workspace + k * B.ws_stride + B.seg_off);
 }
 __device__ __forceinline__ uint2* ws_records(const EncodeBatch& B, uint32_t k) {
   return reinterpret_cast<uint2*>(B.workspace + k * B.ws_stride + B.rec_off);
