@@ -37,10 +37,13 @@
 //                tile_prefix_kernel
 //                decode_kernel         (gather variant) expands the bitmap; per index
 //                                      the d signed bucket reads and their median
-//                encode_compact_kernel, bin_*_kernel, decode_slice_kernel,
+//                encode_compact_kernel, bin_sort_kernel, decode_slice_kernel,
 //                decode_median_kernel  (slice variant) the union list, its queries
-//                                      partitioned by sketch slice, answered from
-//                                      LDS, brought back to list order, medians
+//                                      sorted by sketch slice chunk by chunk, answered
+//                                      from LDS in place, medians per chunk
+//                decode_rows_kernel, decode_rows_median_kernel
+//                                      (rows variant) one sketch row per XCD: the
+//                                      estimates row by row, then their medians
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -102,8 +105,8 @@ static inline uint32_t tiles_of(uint64_t n) { return (uint32_t)ceil_div(ceil_div
 
 // workspace of one worker: [piece counts u16[ntiles * 16]] [tile prefix u64[ntiles + 1]]
 // [dense-tile list: count u32, at +256 bytes entries u32[ntiles * 16]], and for the slice
-// strategy [bin histogram u32[nchunks][nbins]] [bin starts u32[nbins + 1]] [records 8 B x d*cap]; each part
-// 256-byte aligned.  The slice parts exist only when the caller's workspace is large enough for its cap.
+// strategy [segment table u32[nchunks][nbins + 1]] [records 8 B x d*cap, a region of d * kBinChunk per chunk];
+// each part 256-byte aligned.  The slice parts exist only when the caller's workspace is large enough for its cap.
 static inline size_t workspace_prefix_off(uint64_t n) {
   return align256((size_t)tiles_of(n) * kScansPerTile * sizeof(uint16_t));
 }
@@ -151,9 +154,9 @@ static SliceLayout slice_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t cap
 //    float32 atomics retire at about 21e9 per second over the whole chip whatever
 //    their scope, and when the dense scan issues them it hides about 40 % of that
 //    time (less when the non-zeros are clustered in few workgroups);
-//  - slices: five more kernels, about 20 us of launches; 4 us per round of 256
-//    slice workgroups (each clears and stores 128 KiB of LDS); histogram, scatter
-//    and slice kernels together pass about 180e9 records per second.
+//  - slices: three more kernels, about 13 us of launches; 4 us per round of 256
+//    slice workgroups (each clears and stores 128 KiB of LDS); sort and slice
+//    kernels together pass about 200e9 records per second.
 // `sort_cap` is the number of list items whose counting sort the workspace holds (at most the lists'
 // capacity), `expect` the number of items expected (the caller's estimate, or the lists' capacity when
 // there is none); `asked` the caller's wish.
