@@ -256,7 +256,17 @@ __device__ __forceinline__ void seg_add(const u32x2* __restrict__ at, uint32_t f
     const uint32_t i = start + u * s.width;
     if (i >= first && i < last) add_record(s_slice, x[u]);
   }
-  for (uint32_t i = start + AHEAD * s.width; i < last; i += s.width) add_record(s_slice, load_record<STREAM_IN>(at + i));
+  for (uint32_t i0 = start + AHEAD * s.width; i0 < last; i0 += AHEAD * s.width) {   // AHEAD loads in flight here too
+    u32x2 y[AHEAD];
+#pragma unroll
+    for (int u = 0; u < AHEAD; ++u) {
+      const uint32_t i = i0 + u * s.width;
+      y[u] = i < last ? load_record<STREAM_IN>(at + i) : u32x2{0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < AHEAD; ++u)
+      if (i0 + u * s.width < last) add_record(s_slice, y[u]);
+  }
 }
 
 // The slice goes to `out` as float32, and every cell a thread reads it also clears (no separate clearing pass).
@@ -295,7 +305,12 @@ __global__ __launch_bounds__(kSliceBlock) void sketch_slice_kernel(const EncodeB
   const uint32_t cpw = (nchunks + kWaves - 1) / kWaves;
   const uint32_t c_begin = wv * cpw < nchunks ? wv * cpw : nchunks;
   const uint32_t c_end = c_begin + cpw < nchunks ? c_begin + cpw : nchunks;
-  const SegLanes sl = seg_lanes(cpw, lane, 8u);
+  // a group's lanes: enough that kAhead trips take a segment of one and a half times a full chunk's share
+  // of a bin (a longer one goes on with loads that wait one for the other)
+  const uint32_t reach = (uint32_t)kBinChunk * B.d / B.nbins * 3u / 2u;
+  uint32_t min_width = 8u;
+  while (min_width * kAhead < reach && min_width < (uint32_t)kWave) min_width <<= 1;
+  const SegLanes sl = seg_lanes(cpw, lane, min_width);
   // The lane's chunk of the first pass.  Ahead of the bin whose records are being added: where that chunk
   // keeps the segments of the next two bins (fa, la and fb, lb take turns), and the next bin's first records
   // (x), asked for before the current bin's slice is read out.
