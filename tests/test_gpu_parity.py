@@ -191,6 +191,29 @@ def _custom(n, idx, val, d=3, w=64, W=1, seed=0):
     return wl
 
 
+@pytest.mark.parametrize("d,w", [(3, 1 << 14), (3, 1 << 20), (5, 1 << 17)], ids=["one_slice_per_row", "64_slices", "8_slices"])
+def test_long_lists_take_several_passes_per_bin(d, w, decode_strategy):
+    """Lists of 1.7 million entries per worker: 206 chunks of 8192, more than the lane groups of a slice
+    workgroup's waves take in one pass, so every bin is read in several passes; with one slice per row a
+    chunk's segment is the whole chunk (the loop over the rest of a long segment), with 64 slices it is
+    128 records."""
+    n = 1 << 23
+    rng = np.random.default_rng(77)
+    idx, val = [], []
+    for k in range(2):
+        i = np.flatnonzero(rng.random(n) < 0.2).astype(np.uint32)
+        idx.append(i)
+        val.append(rng.normal(0, 1, len(i)).astype(np.float32) + np.float32(2.0))
+    binding.set_insert_strategy(binding.S2R_INSERT_SLICE)
+    binding.want_report(True)
+    try:
+        _run_and_check(_custom(n, idx, val, d=d, w=w, W=2, seed=5))
+        assert binding.last_insert_strategy() == binding.S2R_INSERT_SLICE
+    finally:
+        binding.set_insert_strategy(binding.S2R_INSERT_AUTO)
+        binding.want_report(False)
+
+
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 2047, 2048, 2049, 4096 + 64, 32768, 32769, 100003])
 def test_ragged_lengths_dense_gradient(n, strategy):
     """Every element non-zero: maximal counts, every tile boundary crossed."""
