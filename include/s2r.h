@@ -468,7 +468,7 @@ s2r_status s2r_decode_blocks_update(const float* sketch, const uint64_t* block_b
  * Size query of s2r_decode's routes that need scratch of their own (see
  * s2r_options.decode_strategy): bytes of device scratch with which s2r_decode can use
  * any of them for lists of capacity cap: s2r_workspace_bytes plus, for
- * S2R_DECODE_SLICE, 16*d bytes per list entry and a table of segments, or, for
+ * S2R_DECODE_SLICE, 8*d bytes per list entry and a table of segments, or, for
  * S2R_DECODE_ROWS alone (where the slice route's limits are not met), 4*d bytes
  * per list entry.  With a smaller workspace (but at least s2r_workspace_bytes) the
  * call gathers.  Host only; returns 0 outside the limits or if cap > n.

@@ -316,21 +316,22 @@ __global__ __launch_bounds__(kBlock) void decode_rows_median_kernel(const float*
 // bytes.  When the union list is long, s2r_decode instead sorts the (list
 // position, row) queries of every chunk of kBinChunk list positions by sketch
 // slice with the kernel of the encode's slice strategy (bin_sort_kernel; a record
-// carries the list position instead of a value) and
+// is one word that carries the position in the chunk instead of a value) and
 //   decode_slice_kernel   workgroup (j, s) loads slice s of row j into LDS with
 //                         coalesced loads and answers its bin's queries, chunk by
 //                         chunk: the answer to the query at record r of a chunk's
-//                         region is (estimate, position in chunk) at the same place r
-//                         of the answers.  Every item of a chunk has a query in
+//                         region is the signed estimate at the same place r of the
+//                         answers (4 bytes each way: the query says whose it is).  Every item of a chunk has a query in
 //                         every row, so row j's answers of chunk c are the count(c)
 //                         entries that start at c * kBinChunk * d + j * count(c)
-//   decode_median_kernel  workgroup = chunk: row by row, the answers go through
-//                         LDS into the registers of the thread that owns the
-//                         list position; then the medians, stored coalesced
+//   decode_median_kernel  workgroup = chunk: row by row, the answers (with their
+//                         queries, for the positions) go through LDS into the
+//                         registers of the thread that owns the list position; then
+//                         the medians, stored coalesced
 struct DecodeSliceArgs {
   const float* sketch;
-  const u32x2* rec;          // queries, chunk by chunk, sorted by bin: (cell in slice | sign bit, list position)
-  uint2* answers;            // same shape as rec
+  const uint32_t* rec;       // queries, chunk by chunk, sorted by bin: cell in slice | position in chunk << slice_log2 | sign bit
+  uint32_t* answers;         // same shape as rec: the signed estimates (float32 bits)
   const uint32_t* seg;       // [nchunks][nbins + 1]: the bins' segments in a chunk's region
   const uint64_t* count;     // the union count (device)
   uint64_t cap;
@@ -370,9 +371,9 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   const uint32_t w_begin = c_begin + wv * cpw < c_end ? c_begin + wv * cpw : c_end;
   const uint32_t w_end = w_begin + cpw < c_end ? w_begin + cpw : c_end;
   // a group's lanes: about a quarter of a full chunk's queries per bin, so that a pass has most segments
-  // in flight whole (kAhead times as many queries)
+  // in flight whole (kAhead times as many queries), and 16 at least (64 contiguous bytes)
   const uint32_t quarter = (uint32_t)kBinChunk * A.d / A.nbins / 4u;
-  uint32_t min_width = 8u;
+  uint32_t min_width = 16u;
   while (min_width < quarter && min_width < (uint32_t)kWave) min_width <<= 1;
   const SegLanes sl = seg_lanes(cpw, lane, min_width);
   // a pass: kSets * groups chunks, the lane's are chunks cb + g + t * groups (t < kSets)
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
       }
     }
   };
-  auto fetch = [&](uint32_t cb, const uint32_t (&f)[kSets], const uint32_t (&l)[kSets], u32x2 (&x)[kSets][kAhead]) {
+  auto fetch = [&](uint32_t cb, const uint32_t (&f)[kSets], const uint32_t (&l)[kSets], uint32_t (&x)[kSets][kAhead]) {
 #pragma unroll
     for (int t = 0; t < kSets; ++t) seg_fetch<true, kAhead>(A.rec + (uint64_t)(cb + sl.g + t * sl.groups) * stride, f[t], l[t], sl, x[t]);
   };
@@ -401,12 +402,12 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   } else {
     for (uint32_t c = threadIdx.x; c < cells; c += kSliceBlock) s_cells[c] = src[c];
   }
-  u32x2 x[kSets][kAhead];
+  uint32_t x[kSets][kAhead];
   fetch(cb, f, l, x);
   __syncthreads();
-  auto put = [&](uint2* to, const u32x2 q) {              // the answer goes where the query is
-    const uint32_t est = __float_as_uint(s_cells[q.x & 0x7FFFFFFFu]) ^ (q.x & 0x80000000u);
-    *to = make_uint2(est, q.y & (kBinChunk - 1));
+  const uint32_t cell_mask = cells - 1u;
+  auto put = [&](uint32_t* to, const uint32_t q) {        // the answer goes where the query is
+    *to = __float_as_uint(s_cells[q & cell_mask]) ^ (q & 0x80000000u);
   };
   while (true) {                                          // uniform over the wave
     const uint32_t nb = cb + kSets * sl.groups;
@@ -441,12 +442,13 @@ __device__ __forceinline__ void median_chunk(const DecodeSliceArgs& A, uint32_t 
   const uint64_t t0 = (uint64_t)chunk * kBinChunk;
   const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
   float est[kBinItems][D];
-  uint2 cur[kBinItems], nxt[kBinItems];                   // row j's answers, and row j + 1's on their way
-  const uint2* rows = A.answers + t0 * D;
+  uint2 cur[kBinItems], nxt[kBinItems];                   // row j's (answer, query), and row j + 1's on their way
+  const uint32_t* rows = A.answers + t0 * D;
+  const uint32_t* asked = A.rec + t0 * D;                 // the query at the same place says whose answer it is
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
     const uint32_t t = u * kBinBlock + threadIdx.x;
-    cur[u] = t < count ? rows[t] : make_uint2(0u, 0u);
+    cur[u] = t < count ? make_uint2(rows[t], asked[t]) : make_uint2(0u, 0u);
   }
 #pragma unroll
   for (int j = 0; j < D; ++j) {
@@ -454,12 +456,12 @@ __device__ __forceinline__ void median_chunk(const DecodeSliceArgs& A, uint32_t 
 #pragma unroll
       for (int u = 0; u < kBinItems; ++u) {
         const uint32_t t = u * kBinBlock + threadIdx.x;
-        nxt[u] = t < count ? rows[(uint64_t)(j + 1) * count + t] : make_uint2(0u, 0u);
+        nxt[u] = t < count ? make_uint2(rows[(uint64_t)(j + 1) * count + t], asked[(uint64_t)(j + 1) * count + t]) : make_uint2(0u, 0u);
       }
     }
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
-      if (u * kBinBlock + threadIdx.x < count) s_est[cur[u].y] = __uint_as_float(cur[u].x);
+      if (u * kBinBlock + threadIdx.x < count) s_est[cur[u].y >> A.slice_log2 & (kBinChunk - 1)] = __uint_as_float(cur[u].x);
     }
     __syncthreads();
 #pragma unroll

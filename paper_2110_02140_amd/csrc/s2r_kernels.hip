@@ -193,7 +193,7 @@ static int32_t choose_strategy(uint32_t W, uint64_t n, uint32_t d, uint32_t w, b
 }
 
 // Workspace of s2r_decode when it partitions its queries by sketch slice: the base parts, then
-// [segment offsets u32[nchunks][nbins + 1]] [queries, chunk by chunk, sorted by bin, 8 B x d * nchunks * kBinChunk]
+// [segment offsets u32[nchunks][nbins + 1]] [queries, chunk by chunk, sorted by bin, 4 B x d * nchunks * kBinChunk]
 // [answers, same shape].
 constexpr int kDecodeSliceMaxRows = 8;                   // decode_median_kernel keeps 8 x d estimates per thread
 struct DecodeLayout {
@@ -212,8 +212,8 @@ static DecodeLayout decode_layout(uint64_t n, uint32_t d, uint32_t w, uint64_t c
   L.nchunks = (uint32_t)(L.possible ? ceil_div(cap, kBinChunk) : 0);
   L.seg_off = workspace_base(n);
   L.rec_off = L.seg_off + align256((size_t)L.nchunks * ((size_t)L.nbins + 1) * sizeof(uint32_t));
-  L.answers_off = L.rec_off + align256((size_t)L.nchunks * kBinChunk * d * 8);
-  L.total = L.answers_off + align256((size_t)L.nchunks * kBinChunk * d * 8);
+  L.answers_off = L.rec_off + align256((size_t)L.nchunks * kBinChunk * d * 4);
+  L.total = L.answers_off + align256((size_t)L.nchunks * kBinChunk * d * 4);
   return L;
 }
 
@@ -798,8 +798,8 @@ static s2r_status decode_impl(const float* sketch, const uint64_t* bitmap, uint6
     char* ws = reinterpret_cast<char*>(workspace);
     DecodeSliceArgs Q;
     Q.sketch = sketch;
-    Q.rec = reinterpret_cast<const u32x2*>(ws + L.rec_off);
-    Q.answers = reinterpret_cast<uint2*>(ws + L.answers_off);
+    Q.rec = reinterpret_cast<const uint32_t*>(ws + L.rec_off);
+    Q.answers = reinterpret_cast<uint32_t*>(ws + L.answers_off);
     Q.seg = reinterpret_cast<const uint32_t*>(ws + L.seg_off);
     Q.count = count_out;
     Q.cap = cap;

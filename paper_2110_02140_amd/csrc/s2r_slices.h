@@ -95,6 +95,10 @@ __device__ __forceinline__ bool load_item(const EncodeBatch& B, const WorkerPtrs
 //      row's T sorted records are copied out as one contiguous, coalesced run.
 // The hashes are computed in both sweeps rather than kept (registers).  Dynamic LDS: kBinChunk records, then
 // nbins counters.
+// A query's record (MODE with kItemsQuery) is one word: cell in the slice | position in the chunk <<
+// slice_log2 | sign bit; its answer will lie at the same place of an array of the same shape, so the
+// position inside the chunk (13 bits) is all that has to travel.  An insertion's record is (cell | sign bit,
+// value).
 template <int MODE>
 __global__ __launch_bounds__(kBinBlock, 8) void bin_sort_kernel(const EncodeBatch B, const HashRows hp) {
   extern __shared__ uint2 s_stage[];
@@ -162,6 +166,8 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_sort_kernel(const EncodeBatc
     if (threadIdx.x == 0) seg[B.nbins] = B.d * T;
     __syncthreads();
     uint2* __restrict__ out = ws_records(B, k) + (uint64_t)chunk * kBinChunk * B.d;
+    uint32_t* __restrict__ out_q = reinterpret_cast<uint32_t*>(ws_records(B, k)) + (uint64_t)chunk * kBinChunk * B.d;
+    uint32_t* s_stage_q = reinterpret_cast<uint32_t*>(s_stage);
     for (uint32_t j = 0; j < B.d; ++j) {
       const uint64_t a = hp.a[j], b = hp.b[j], c = hp.c[j], e = hp.e[j];
       uint32_t* next = s_next + (j << spr_log2);
@@ -171,11 +177,17 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_sort_kernel(const EncodeBatc
           const uint32_t h = bucket_of(i[u], a, b, B.log2w);
           const uint32_t place = __hip_atomic_fetch_add(&next[h >> B.slice_log2], 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_WORKGROUP);
-          s_stage[place] = make_uint2((h & mask) | signbit_of(i[u], c, e), v[u]);
+          const uint32_t word = (h & mask) | signbit_of(i[u], c, e);
+          if constexpr (mode_query(MODE)) s_stage_q[place] = word | ((u * kBinBlock + threadIdx.x) << B.slice_log2);
+          else s_stage[place] = make_uint2(word, v[u]);
         }
       }
       __syncthreads();
-      for (uint32_t p = threadIdx.x; p < T; p += kBinBlock) out[(uint64_t)j * T + p] = s_stage[p];
+      if constexpr (mode_query(MODE)) {
+        for (uint32_t p = threadIdx.x; p < T; p += kBinBlock) out_q[(uint64_t)j * T + p] = s_stage_q[p];
+      } else {
+        for (uint32_t p = threadIdx.x; p < T; p += kBinBlock) out[(uint64_t)j * T + p] = s_stage[p];
+      }
       __syncthreads();                                    // s_stage is free again (after the last row: the counters too)
     }
   }
@@ -197,8 +209,8 @@ __global__ __launch_bounds__(kBinBlock, 8) void bin_sort_kernel(const EncodeBatc
 // sketches next gains a little too.  STREAM_IN: the records are read with streaming loads; the same kind of
 // threshold from the other side.  (Both are compile-time: as run-time flags inside the unrolled loops they
 // cost the kernel 6 to 10 %.)
-template <bool STREAM_IN>
-__device__ __forceinline__ u32x2 load_record(const u32x2* p) {
+template <bool STREAM_IN, class REC>
+__device__ __forceinline__ REC load_record(const REC* p) {
   if constexpr (STREAM_IN) return __builtin_nontemporal_load(p);
   else return *p;
 }
@@ -234,15 +246,15 @@ __device__ __forceinline__ SegLanes seg_lanes(uint32_t chunks_per_wave, uint32_t
 // of a group reads one aligned piece of memory (8 lanes: the 64 bytes of one memory request).
 __device__ __forceinline__ uint32_t seg_start(uint32_t first, const SegLanes& s) { return (first & ~(s.width - 1u)) + s.p; }
 
-// Trips u < AHEAD: AHEAD loads of a lane in flight.
-template <bool STREAM_IN, int AHEAD>
-__device__ __forceinline__ void seg_fetch(const u32x2* __restrict__ at, uint32_t first, uint32_t last, const SegLanes& s,
-                                          u32x2 (&x)[AHEAD]) {
+// Trips u < AHEAD: AHEAD loads of a lane in flight.  REC: u32x2 (an insertion's record) or uint32_t (a query's).
+template <bool STREAM_IN, int AHEAD, class REC>
+__device__ __forceinline__ void seg_fetch(const REC* __restrict__ at, uint32_t first, uint32_t last, const SegLanes& s,
+                                          REC (&x)[AHEAD]) {
   const uint32_t start = seg_start(first, s);
 #pragma unroll
   for (int u = 0; u < AHEAD; ++u) {
     const uint32_t i = start + u * s.width;
-    x[u] = i >= first && i < last ? load_record<STREAM_IN>(at + i) : u32x2{0u, 0u};
+    x[u] = i >= first && i < last ? load_record<STREAM_IN>(at + i) : REC{};
   }
 }
 

@@ -239,7 +239,7 @@ def test_probe_read_argument_checks():
 
 def test_decode_strategy_and_workspace_argument_checks():
     base = b.workspace_bytes(1 << 20, 3, 1 << 14)
-    assert b.decode_workspace_bytes(1 << 20, 3, 1 << 14, 50000) >= base + 16 * 3 * 50000
+    assert b.decode_workspace_bytes(1 << 20, 3, 1 << 14, 50000) >= base + 8 * 3 * 50000
     assert b.decode_workspace_bytes(1 << 20, 9, 1 << 14, 50000) == base        # more than 8 rows: gather only
     assert b.decode_workspace_bytes(1 << 20, 3, 1 << 14, (1 << 20) + 1) == 0    # cap > n
     assert b.decode_workspace_bytes(0, 3, 1 << 14, 0) == 0
@@ -253,7 +253,7 @@ def test_block_codec_argument_checks():
     assert b.blocks_workspace_bytes(n, 256, d, w) <= b.workspace_bytes(n, d, w)
     assert b.encode_blocks_workspace_bytes(n, 256, d, w, 4097) == 0            # more blocks than the gradient has
     assert b.encode_blocks_workspace_bytes(n, 256, d, w, 100) >= b.blocks_workspace_bytes(n, 256, d, w) + 8 * d * 100 * 256
-    assert b.decode_blocks_workspace_bytes(n, 256, d, w, 100) >= b.blocks_workspace_bytes(n, 256, d, w) + 16 * d * 100 * 256
+    assert b.decode_blocks_workspace_bytes(n, 256, d, w, 100) >= b.blocks_workspace_bytes(n, 256, d, w) + 8 * d * 100 * 256
     assert lib.s2r_encode_blocks(0x1000, n, 0, d, w, 0, 0x2000, 0x3000, None, 0, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_SIZE
     assert lib.s2r_encode_blocks(None, n, 256, d, w, 0, 0x2000, 0x3000, None, 0, 0x4000, 0x5000, 1 << 20, None) == b.S2R_ERR_NULL
     assert lib.s2r_encode_blocks(0x1000, n, 256, d, w, 0, 0x2000, 0x3000, None, 0, 0x4000, None, 1 << 20, None) == b.S2R_ERR_WORKSPACE
