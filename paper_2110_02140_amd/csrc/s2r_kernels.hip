@@ -486,7 +486,14 @@ static s2r_status launch_after_scan(EncodeBatch& E, const HashRows& hp, const En
     if (!launch_ok()) return S2R_ERR_LAUNCH;
     if (traced) record(X, S2R_KERNEL_ENCODE_SLICE, false, st);
     // about one workgroup per compute unit, each walking `per` consecutive bins of one worker
-    const uint32_t per = (uint32_t)ceil_div((uint64_t)E.nbins * count, kSliceWorkgroups);
+    // One workgroup is resident per compute unit (its slice fills the LDS).  Two rounds of workgroups with half
+    // the bins each beat one round when a workgroup still walks enough bins to spread its start-up (clearing
+    // 128 KiB of LDS, the first loads), or when one round would leave units idle anyway.  Measured (us): 5120
+    // (bin, worker) pairs 135 -> 129, 384 pairs of 67 K records 66 -> 57, 20480 pairs 465 -> 467; 1536 pairs
+    // (6 or 3 bins per workgroup) 27.5 -> 29, which therefore stay one round.
+    const uint64_t pairs = (uint64_t)E.nbins * count;
+    uint32_t per = (uint32_t)ceil_div(pairs, 2 * kSliceWorkgroups);
+    if (per < 4 && ceil_div(pairs, kSliceWorkgroups) > 2) per = (uint32_t)ceil_div(pairs, kSliceWorkgroups);
     // (streaming stores only when the call's sketches are more than the memory-side cache keeps)
     const bool stream_out = ((uint64_t)E.nworkers * E.d << E.log2w) * sizeof(float) > (512ull << 20);
     const bool stream_in = (uint64_t)E.nworkers * L.expect_items * E.d * 8 > (128ull << 20);

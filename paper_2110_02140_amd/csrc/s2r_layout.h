@@ -27,7 +27,7 @@ constexpr int kGroupsPerTile = kTileElems / kGroupSlots;     // 16
 constexpr int kPrefixBlock = 1024;                // threads of the single prefix workgroup
 constexpr int kPrefixPer = 8;                     // tiles per thread per round
 constexpr int kSliceBlock = 1024;                 // threads of a sketch-slice workgroup
-constexpr int kSliceWorkgroups = 256;             // slice workgroups per launch, about: one per compute unit
+constexpr int kSliceWorkgroups = 256;             // slice workgroups that are resident at a time: one per compute unit
 constexpr int kSliceLog2Max = 14;                 // 2^14 cells = 128 KiB of float64 accumulators in LDS (smaller slices
                                                   // with smaller workgroups measured slower in total: more bins)
 static_assert(kTileWords % kScanWords == 0, "scan workgroups must not straddle tiles");
