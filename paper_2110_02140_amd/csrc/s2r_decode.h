@@ -442,22 +442,15 @@ __device__ __forceinline__ void median_chunk(const DecodeSliceArgs& A, uint32_t 
   const uint64_t t0 = (uint64_t)chunk * kBinChunk;
   const uint32_t count = have - t0 < (uint64_t)kBinChunk ? (uint32_t)(have - t0) : (uint32_t)kBinChunk;
   float est[kBinItems][D];
-  uint2 cur[kBinItems], nxt[kBinItems];                   // row j's (answer, query), and row j + 1's on their way
+  uint2 cur[kBinItems];                                   // row j's (answer, query)
   const uint32_t* rows = A.answers + t0 * D;
   const uint32_t* asked = A.rec + t0 * D;                 // the query at the same place says whose answer it is
 #pragma unroll
-  for (int u = 0; u < kBinItems; ++u) {
-    const uint32_t t = u * kBinBlock + threadIdx.x;
-    cur[u] = t < count ? make_uint2(rows[t], asked[t]) : make_uint2(0u, 0u);
-  }
-#pragma unroll
   for (int j = 0; j < D; ++j) {
-    if (j + 1 < D) {
 #pragma unroll
-      for (int u = 0; u < kBinItems; ++u) {
-        const uint32_t t = u * kBinBlock + threadIdx.x;
-        nxt[u] = t < count ? make_uint2(rows[(uint64_t)(j + 1) * count + t], asked[(uint64_t)(j + 1) * count + t]) : make_uint2(0u, 0u);
-      }
+    for (int u = 0; u < kBinItems; ++u) {
+      const uint32_t t = u * kBinBlock + threadIdx.x;
+      cur[u] = t < count ? make_uint2(rows[(uint64_t)j * count + t], asked[(uint64_t)j * count + t]) : make_uint2(0u, 0u);
     }
 #pragma unroll
     for (int u = 0; u < kBinItems; ++u) {
@@ -470,8 +463,6 @@ __device__ __forceinline__ void median_chunk(const DecodeSliceArgs& A, uint32_t 
       est[u][j] = t < count ? s_est[t] : 0.0f;
     }
     __syncthreads();
-#pragma unroll
-    for (int u = 0; u < kBinItems; ++u) cur[u] = nxt[u];
   }
 #pragma unroll
   for (int u = 0; u < kBinItems; ++u) {
@@ -489,7 +480,7 @@ __device__ __forceinline__ void median_chunk(const DecodeSliceArgs& A, uint32_t 
 // The grid is sized for the number of positions expected, which is normally all there are: a workgroup takes
 // chunk blockIdx.x, and only if the list holds more, the chunks blockIdx.x + gridDim.x, ... after it.
 template <int D>
-__global__ __launch_bounds__(kBinBlock) void decode_median_kernel(const DecodeSliceArgs A) {
+__global__ __launch_bounds__(kBinBlock, D <= 5 ? 8 : 4) void decode_median_kernel(const DecodeSliceArgs A) {
   __shared__ float s_est[kBinChunk];
   const uint64_t total = *A.count;
   const uint64_t listed = total < A.cap ? total : A.cap;
