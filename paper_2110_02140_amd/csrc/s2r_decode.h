@@ -352,7 +352,7 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   extern __shared__ float s_cells[];
   constexpr int kWaves = kSliceBlock / kWave;
   constexpr int kAhead = 8;
-  constexpr int kSets = 4;
+  constexpr int kSets = 8;                                // chunks of a lane in a pass, at most
   const uint32_t bin = blockIdx.x;                        // = (j << log2(slices per row)) + s
   const uint64_t total = *A.count;
   const uint64_t listed = total < A.cap ? total : A.cap;
@@ -376,13 +376,19 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
   uint32_t min_width = 16u;
   while (min_width < quarter && min_width < (uint32_t)kWave) min_width <<= 1;
   const SegLanes sl = seg_lanes(cpw, lane, min_width);
-  // a pass: kSets * groups chunks, the lane's are chunks cb + g + t * groups (t < kSets)
+  // A pass: sets * groups chunks, the lane's are chunks cb + g + t * groups (t < sets).  The more segments a
+  // wave has in flight the better (measured with 4, 6 and 8 chunks per lane: config 4 78, 66, 70 us, config 5
+  // 208, 190, 182 us), and a last pass with little in it costs as much as a full one: so as few passes as
+  // kSets allows, all equally full (config 4: 33 chunks per wave, 4 groups: passes of 5 + 4, not 8 + 1).
+  const uint32_t all_sets = (cpw + sl.groups - 1) / sl.groups;
+  const uint32_t passes = (all_sets + kSets - 1) / kSets;
+  const uint32_t sets = passes != 0 ? (all_sets + passes - 1) / passes : 1u;     // uniform over the workgroup
   auto places = [&](uint32_t cb, uint32_t (&f)[kSets], uint32_t (&l)[kSets]) {
 #pragma unroll
     for (int t = 0; t < kSets; ++t) {
       const uint32_t c = cb + sl.g + t * sl.groups;
       f[t] = l[t] = 0u;
-      if (c < w_end) {
+      if ((uint32_t)t < sets && c < w_end) {
         f[t] = A.seg[(uint64_t)c * row_len + bin];
         l[t] = A.seg[(uint64_t)c * row_len + bin + 1];
       }
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(kSliceBlock) void decode_slice_kernel(const DecodeS
     *to = __float_as_uint(s_cells[q & cell_mask]) ^ (q & 0x80000000u);
   };
   while (true) {                                          // uniform over the wave
-    const uint32_t nb = cb + kSets * sl.groups;
+    const uint32_t nb = cb + sets * sl.groups;
     uint32_t fn[kSets], ln[kSets];
     if (nb < w_end) places(nb, fn, ln);
 #pragma unroll
